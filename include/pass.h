@@ -1,0 +1,165 @@
+/*
+ * pass.h -- C ABI of the MI355X (gfx950) hot path of PaSS, parallel speculative sampling.
+ *
+ * The library runs the (1+k)-row decode step that the method calls twice per iteration
+ * (Section 2.2 of the paper): a drafting call on the last token plus k look-ahead embeddings
+ * (Section 2.2.1), and a validation call on the drafted block followed by the accept / reject
+ * chain of Algorithm 1.  Every step of that path runs in HIP kernels; there is no CPU fallback.
+ *
+ * Conventions
+ *   - Every function returns PASS_OK (0) or a negative pass_status; nothing throws or aborts.
+ *     pass_last_error() gives a message for the last failure on that context.
+ *   - "host" / "device" on a pointer says where the memory lives.  Pointers are borrowed for
+ *     the duration of the call only, except the arena given to pass_create, which the caller
+ *     owns and must keep alive (and not touch) until pass_destroy.
+ *   - The library allocates no device memory: K/V pages, packed weights, workspaces and
+ *     per-slot state all live in the caller's arena (pass_arena_bytes tells how large).
+ *   - All work is issued on the HIP stream given to pass_create.  Calls that return results to
+ *     host memory synchronise that stream before returning.
+ *   - One context may be used from one thread at a time.
+ *
+ * Per-slot invariant between calls:  kv_len == (#tokens of the sequence) - 1;  the last token
+ * is "pending": its K/V are computed by the next call.  K/V rows beyond kv_len are dead and are
+ * overwritten by the next call; rolling the cache back after a rejection is not advancing
+ * kv_len (the paper's Baselines paragraph: the cache is updated after every call according to
+ * the number of drafted and accepted tokens).
+ *
+ * Notation: k is the number of look-ahead embeddings (L in Algorithm 1); p_t is the target
+ * distribution of the validation call, d_t the draft distribution of the drafting call, both
+ * softmax(logits / temperature).
+ */
+#ifndef PASS_H_
+#define PASS_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pass_ctx pass_ctx;
+
+typedef enum {
+  PASS_OK = 0,
+  PASS_EINVAL = -1,    /* bad argument, bad slot, unsupported shape                         */
+  PASS_ESTATE = -2,    /* call out of order (draft needs a prefilled slot, verify a drafted) */
+  PASS_ECAPACITY = -3, /* kv_len + 1 + k would exceed max_seq_len, or the page pool is empty */
+  PASS_EDEVICE = -4    /* a HIP call failed                                                  */
+} pass_status;
+
+enum { PASS_F32 = 0, PASS_BF16 = 1 };
+enum { PASS_MAX_K = 15, PASS_MAX_ROWS = 64 };
+
+/* Shape of a LLaMA-style decoder (pre-norm RMSNorm, rotary embedding on interleaved pairs,
+ * SwiGLU, multi-head attention with n_heads * head_dim projection width, untied LM head) --
+ * the paper's Experiments section runs a re-implementation of LLaMA-7B in bfloat16. */
+typedef struct {
+  int32_t n_layers, d_model, n_heads, head_dim, d_ffn, vocab;
+  float rms_eps, rope_base;
+  int32_t dtype;       /* PASS_F32 / PASS_BF16: storage type of every model tensor and of K/V  */
+  int32_t k;           /* look-ahead embeddings per drafting call, 0 .. PASS_MAX_K             */
+  int32_t max_slots;   /* concurrent sequences; (1+k) * max_slots <= PASS_MAX_ROWS             */
+  int32_t max_seq_len; /* per-sequence limit on cached positions                               */
+  int32_t page_size;   /* positions per K/V page (power of two, >= 16)                         */
+  int32_t n_pages;     /* pages in the pool; 0 = max_slots * ceil(max_seq_len / page_size)     */
+} pass_config;
+
+typedef struct {
+  float temperature;   /* 0 = greedy (every sample is an argmax, lowest index on ties)         */
+  int32_t top_k;       /* must be 0 (reserved for the top-k filter)                            */
+  uint64_t seed;       /* Philox4x32-10 key; streams are separated by sequence id, iteration,
+                          row and purpose, so results do not depend on batch composition      */
+} pass_sampling;
+
+typedef struct {
+  int64_t iterations;       /* PaSS iterations (draft + verify), summed over slots            */
+  int64_t drafts_proposed;  /* k per iteration and slot                                       */
+  int64_t drafts_accepted;
+  int64_t tokens_out;       /* tokens written to out_tokens                                   */
+  double draft_ms, verify_ms; /* device time of the two calls, summed over iterations         */
+} pass_stats;
+
+/* Model tensors in their plain layout: matrices are [out_features, in_features] row-major,
+ * element type config.dtype.  Arrays of per-layer pointers live in host memory. */
+typedef struct {
+  const void *tok_emb;    /* [vocab, d_model]                                                */
+  const void *lm_head;    /* [vocab, d_model]                                                */
+  const void *final_norm; /* [d_model]                                                       */
+  const void *lookahead;  /* [k, d_model] look-ahead embeddings (Section 2.2.1); NULL if k==0 */
+  const void *const *attn_norm, *const *wq, *const *wk, *const *wv, *const *wo;
+  const void *const *ffn_norm, *const *w_gate, *const *w_up, *const *w_down;
+} pass_weights;
+
+/* Bytes of device memory pass_create needs for this configuration (0 if it is invalid). */
+size_t pass_arena_bytes(const pass_config *cfg);
+
+/* Create a context.  hip_stream: a hipStream_t (NULL = the null stream).  device_arena:
+ * device memory of at least pass_arena_bytes(cfg) bytes, 256-byte aligned, owned by the caller.
+ * Errors: PASS_EINVAL (shape not supported, arena too small or misaligned), PASS_EDEVICE. */
+int pass_create(const pass_config *cfg, void *hip_stream, void *device_arena, size_t arena_bytes,
+                pass_ctx **out);
+
+/* Copy the model into the arena, repacking matrices into the layout the kernels stream
+ * (tiles of 16 rows x 32 columns for the bf16 matrix-core path).  on_device = 0: tensor
+ * pointers are host memory; 1: device memory.  The caller may free its tensors afterwards. */
+int pass_load_weights(pass_ctx *ctx, const pass_weights *w, int on_device);
+
+/* Start a sequence in `slot` (frees what the slot held).  prompt: host, n >= 1 token ids.
+ * Computes K/V of prompt[0..n-2]; prompt[n-1] becomes the pending token, so the first
+ * drafting call is already a parallel one (Algorithm 1 starts from the prompt x_0..x_t).
+ * seq_id selects the sequence's random streams. */
+int pass_prefill(pass_ctx *ctx, int slot, uint32_t seq_id, const int32_t *prompt, int n);
+
+/* Release a slot's pages. */
+int pass_release(pass_ctx *ctx, int slot);
+
+/* Drafting phase (Algorithm 1, first step of the loop; Section 2.2): one model call on
+ * (pending, [LA]_1..[LA]_k) per slot; samples x_{n+1} from row 0 and draft t from row t, in
+ * parallel.  Afterwards kv_len += 1 and pending = x_{n+1}.  slots: host, n_slots distinct
+ * slot numbers, all prefilled / verified.  out_first: host [n_slots]; out_drafts: host
+ * [n_slots * k] or NULL. */
+int pass_draft(pass_ctx *ctx, const int32_t *slots, int n_slots, const pass_sampling *sp,
+               int32_t *out_first, int32_t *out_drafts);
+
+/* Validation phase (Algorithm 1, second model call and the for-loop): one call on
+ * (x_{n+1}, drafts); draft t is accepted iff r_t < min(1, p_t(x)/d_t(x)), in order, until the
+ * first reject, which is replaced by a sample from the normalised (p_t - d_t)_+; if all k are
+ * accepted one more token is sampled from the last row.  Afterwards kv_len += 1 + a and
+ * pending = the final token.  out_n_accepted: host [n_slots]; out_tokens: host
+ * [n_slots * (k+1)], per slot the a accepted drafts followed by the final token. */
+int pass_verify(pass_ctx *ctx, const int32_t *slots, int n_slots, const pass_sampling *sp,
+                int32_t *out_n_accepted, int32_t *out_tokens);
+
+/* Algorithm 1's while loop for a batch of prefilled slots: draft + verify until every slot has
+ * produced at least max_new tokens; out_tokens: host [n_slots * max_new], the first max_new
+ * tokens of each.  out_stats may be NULL.  Slots that finish early keep stepping with the
+ * batch (their extra tokens are dropped) so the launch shape stays fixed. */
+int pass_generate(pass_ctx *ctx, const int32_t *slots, int n_slots, int max_new,
+                  const pass_sampling *sp, int32_t *out_tokens, pass_stats *out_stats);
+
+/* Parity hook: fp32 logits [(1+k) * vocab] of the slot's last drafting (which = 0) or
+ * validation (which = 1) call, copied to host memory. */
+int pass_get_logits(pass_ctx *ctx, int slot, int which, float *out);
+
+/* kv_len and number of generated tokens of a slot (either pointer may be NULL). */
+int pass_seq_len(pass_ctx *ctx, int slot, int32_t *kv_len, int32_t *n_generated);
+
+/* Options: "graph" (1 = replay the step as a HIP graph, default 0 until captured paths are
+ * enabled), "path" (0 = auto, 1 = force the generic kernels).  Unknown names: PASS_EINVAL. */
+int pass_set_option(pass_ctx *ctx, const char *name, int value);
+
+/* Timed replay of one drafting-shaped step on the given slots without changing any sequence
+ * state (no sampling state is committed): returns the mean device milliseconds of `iters`
+ * steps after `warmup`.  Used by the benchmark to time the dominant kernels in isolation. */
+int pass_time_step(pass_ctx *ctx, const int32_t *slots, int n_slots, int warmup, int iters,
+                   double *out_ms);
+
+/* Message of the last failure on ctx; ctx == NULL: of the last failed pass_create. */
+const char *pass_last_error(pass_ctx *ctx);
+void pass_destroy(pass_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PASS_H_ */

@@ -1,0 +1,222 @@
+"""Thin ctypes binding of libpass_hip.so (include/pass.h).  Argument marshalling only.
+
+PyTorch supplies device memory (the arena) and the HIP stream; every step of the decode path runs
+in the library's kernels.  There is no CPU fallback: a missing library or GPU raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpass_hip.so")
+
+PASS_F32, PASS_BF16 = 0, 1
+MAX_K, MAX_ROWS = 15, 64
+
+SYMBOLS = ["pass_arena_bytes", "pass_create", "pass_load_weights", "pass_prefill", "pass_release",
+           "pass_draft", "pass_verify", "pass_generate", "pass_get_logits", "pass_seq_len",
+           "pass_set_option", "pass_time_step", "pass_last_error", "pass_destroy"]
+
+
+class PassConfig(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
+                ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32),
+                ("k", C.c_int32), ("max_slots", C.c_int32), ("max_seq_len", C.c_int32),
+                ("page_size", C.c_int32), ("n_pages", C.c_int32)]
+
+
+class PassSampling(C.Structure):
+    _fields_ = [("temperature", C.c_float), ("top_k", C.c_int32), ("seed", C.c_uint64)]
+
+
+class PassStats(C.Structure):
+    _fields_ = [("iterations", C.c_int64), ("drafts_proposed", C.c_int64), ("drafts_accepted", C.c_int64),
+                ("tokens_out", C.c_int64), ("draft_ms", C.c_double), ("verify_ms", C.c_double)]
+
+
+_PP = C.POINTER(C.c_void_p)
+
+
+class PassWeights(C.Structure):
+    _fields_ = [("tok_emb", C.c_void_p), ("lm_head", C.c_void_p), ("final_norm", C.c_void_p),
+                ("lookahead", C.c_void_p),
+                ("attn_norm", _PP), ("wq", _PP), ("wk", _PP), ("wv", _PP), ("wo", _PP),
+                ("ffn_norm", _PP), ("w_gate", _PP), ("w_up", _PP), ("w_down", _PP)]
+
+
+class PassError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"pass error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library():
+    """Load libpass_hip.so (built by paper_2311_13581_amd/build.py).  Raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is not built: run `python -m paper_2311_13581_amd.build` "
+                                "(there is no fallback path)")
+    # PyTorch ships its own HIP runtime under the same soname as the system one; whichever is
+    # loaded first serves the whole process.  Import torch first so that the arena it allocates
+    # and the kernels launched here share one runtime.
+    import torch  # noqa: F401
+    L = C.CDLL(LIB_PATH)
+    ip = C.POINTER(C.c_int32)
+    L.pass_arena_bytes.restype = C.c_size_t
+    L.pass_arena_bytes.argtypes = [C.POINTER(PassConfig)]
+    L.pass_create.argtypes = [C.POINTER(PassConfig), C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]
+    L.pass_load_weights.argtypes = [C.c_void_p, C.POINTER(PassWeights), C.c_int]
+    L.pass_prefill.argtypes = [C.c_void_p, C.c_int, C.c_uint32, ip, C.c_int]
+    L.pass_release.argtypes = [C.c_void_p, C.c_int]
+    L.pass_draft.argtypes = [C.c_void_p, ip, C.c_int, C.POINTER(PassSampling), ip, ip]
+    L.pass_verify.argtypes = [C.c_void_p, ip, C.c_int, C.POINTER(PassSampling), ip, ip]
+    L.pass_generate.argtypes = [C.c_void_p, ip, C.c_int, C.c_int, C.POINTER(PassSampling), ip, C.POINTER(PassStats)]
+    L.pass_get_logits.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_float)]
+    L.pass_seq_len.argtypes = [C.c_void_p, C.c_int, ip, ip]
+    L.pass_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int]
+    L.pass_time_step.argtypes = [C.c_void_p, ip, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double)]
+    L.pass_last_error.restype = C.c_char_p
+    L.pass_last_error.argtypes = [C.c_void_p]
+    L.pass_destroy.argtypes = [C.c_void_p]
+    _lib = L
+    return L
+
+
+def _ip(a):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def make_config(shape, k, max_slots, max_seq_len, page_size=64, n_pages=0) -> PassConfig:
+    return PassConfig(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn, shape.vocab,
+                      shape.rms_eps, shape.rope_base, shape.dtype, k, max_slots, max_seq_len, page_size, n_pages)
+
+
+class Pass:
+    """One model instance on the current CUDA(HIP) device.  Methods mirror the C entry points."""
+
+    def __init__(self, cfg: PassConfig, options: dict | None = None):
+        import torch
+        if not torch.cuda.is_available():
+            raise RuntimeError("no GPU: the PaSS decode path has no CPU fallback")
+        self._torch = torch
+        self.lib = load_library()
+        self.cfg = cfg
+        self.k = cfg.k
+        self.vocab = cfg.vocab
+        nbytes = self.lib.pass_arena_bytes(C.byref(cfg))
+        if nbytes == 0:
+            raise PassError(-1, "configuration not supported")
+        self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
+        base = (self.arena.data_ptr() + 255) & ~255
+        self.stream = torch.cuda.current_stream()
+        h = C.c_void_p()
+        rc = self.lib.pass_create(C.byref(cfg), C.c_void_p(self.stream.cuda_stream), C.c_void_p(base), nbytes,
+                                  C.byref(h))
+        if rc != 0:
+            raise PassError(rc, self.lib.pass_last_error(None).decode())
+        self.h = h
+        for name, val in (options or {}).items():
+            self.set_option(name, val)
+
+    def _check(self, rc):
+        if rc != 0:
+            raise PassError(rc, self.lib.pass_last_error(self.h).decode())
+
+    def close(self):
+        if getattr(self, "h", None):
+            self.lib.pass_destroy(self.h)
+            self.h = None
+            self.arena = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_option(self, name: str, value: int):
+        self._check(self.lib.pass_set_option(self.h, name.encode(), int(value)))
+
+    def load_weights(self, weights: dict):
+        """weights: dict of numpy arrays (host) or torch CUDA tensors (device), plain layout."""
+        torch = self._torch
+        sample = weights["tok_emb"]
+        on_device = isinstance(sample, torch.Tensor)
+
+        def ptr(a):
+            if a is None:
+                return None
+            if on_device:
+                assert a.is_cuda and a.is_contiguous()
+                return a.data_ptr()
+            assert a.flags["C_CONTIGUOUS"] or a.size == 0
+            return a.ctypes.data
+
+        w = PassWeights()
+        keep = []
+        for name in ("tok_emb", "lm_head", "final_norm"):
+            setattr(w, name, ptr(weights[name]))
+        w.lookahead = ptr(weights["lookahead"]) if self.k > 0 else None
+        for name in ("attn_norm", "wq", "wk", "wv", "wo", "ffn_norm", "w_gate", "w_up", "w_down"):
+            lst = weights[name]
+            arr = (C.c_void_p * len(lst))(*[ptr(a) for a in lst])
+            keep.append(arr)
+            setattr(w, name, C.cast(arr, _PP))
+        self._check(self.lib.pass_load_weights(self.h, C.byref(w), int(on_device)))
+
+    def prefill(self, slot: int, prompt, seq_id: int = 0):
+        p = np.ascontiguousarray(prompt, dtype=np.int32)
+        self._check(self.lib.pass_prefill(self.h, slot, seq_id, _ip(p), p.size))
+
+    def release(self, slot: int):
+        self._check(self.lib.pass_release(self.h, slot))
+
+    def draft(self, slots, temperature: float, seed: int):
+        s = np.ascontiguousarray(slots, dtype=np.int32)
+        sp = PassSampling(temperature, 0, seed)
+        first = np.zeros(s.size, dtype=np.int32)
+        drafts = np.zeros(max(1, s.size * self.k), dtype=np.int32)
+        self._check(self.lib.pass_draft(self.h, _ip(s), s.size, C.byref(sp), _ip(first), _ip(drafts)))
+        return first, drafts[:s.size * self.k].reshape(s.size, self.k)
+
+    def verify(self, slots, temperature: float, seed: int):
+        s = np.ascontiguousarray(slots, dtype=np.int32)
+        sp = PassSampling(temperature, 0, seed)
+        n_acc = np.zeros(s.size, dtype=np.int32)
+        toks = np.zeros(s.size * (self.k + 1), dtype=np.int32)
+        self._check(self.lib.pass_verify(self.h, _ip(s), s.size, C.byref(sp), _ip(n_acc), _ip(toks)))
+        return n_acc, toks.reshape(s.size, self.k + 1)
+
+    def generate(self, slots, max_new: int, temperature: float, seed: int):
+        s = np.ascontiguousarray(slots, dtype=np.int32)
+        sp = PassSampling(temperature, 0, seed)
+        out = np.zeros(max(1, s.size * max_new), dtype=np.int32)
+        st = PassStats()
+        self._check(self.lib.pass_generate(self.h, _ip(s), s.size, max_new, C.byref(sp), _ip(out), C.byref(st)))
+        stats = {f: getattr(st, f) for f, _ in PassStats._fields_}
+        return out[:s.size * max_new].reshape(s.size, max_new), stats
+
+    def get_logits(self, slot: int, which: int) -> np.ndarray:
+        out = np.empty((self.k + 1, self.vocab), dtype=np.float32)
+        self._check(self.lib.pass_get_logits(self.h, slot, which, out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
+
+    def seq_len(self, slot: int):
+        a, b = C.c_int32(0), C.c_int32(0)
+        self._check(self.lib.pass_seq_len(self.h, slot, C.byref(a), C.byref(b)))
+        return a.value, b.value
+
+    def time_step(self, slots, warmup: int, iters: int) -> float:
+        s = np.ascontiguousarray(slots, dtype=np.int32)
+        ms = C.c_double(0)
+        self._check(self.lib.pass_time_step(self.h, _ip(s), s.size, warmup, iters, C.byref(ms)))
+        return ms.value

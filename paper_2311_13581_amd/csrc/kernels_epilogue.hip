@@ -1,0 +1,290 @@
+// Sampling epilogues of the two model calls of Algorithm 1, on fp32 logits.
+//
+// Drafting call: row 0 gives x_{n+1} (an ordinary sample, not part of the draft), row t gives
+// draft t; the rows' ln-sum-exp is kept so that the validation call can evaluate d_t(x).
+// Validation call: accept draft t iff  ln r_t + ln d_t(x) < ln p_t(x)  (r < min(1, p/d)), in
+// order; the first reject is replaced by a draw from the normalised (p_t - d_t)_+; if all k are
+// accepted one more token is drawn from the last row.  Then kv_len += 1 + a: rows of rejected
+// drafts stay in the cache as dead entries.
+//
+// Every "draw" is a Gumbel-max: argmax_j (score_j - ln(-ln u_j)), u_j from Philox4x32-10 with
+// key = seed and counter = (j/4, iteration, row | purpose << 8, sequence id); an argmax is
+// independent of reduction order, so wavefront reductions give the same winner as a serial loop.
+// Ties go to the lowest index.  temperature == 0 is greedy (argmax of the logits).
+#include "pass_internal.h"
+
+namespace pass {
+
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3, uint32_t k0,
+                                              uint32_t k1, uint32_t (&out)[4]) {
+#pragma unroll
+  for (int i = 0; i < 10; ++i) {
+    uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    k0 += 0x9E3779B9u;
+    k1 += 0xBB67AE85u;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+// top 23 bits -> (bits + 0.5) * 2^-23, in (0,1), exact in fp32
+__device__ __forceinline__ float u01(uint32_t x) { return ((float)(x >> 9) + 0.5f) * (1.0f / 8388608.0f); }
+__device__ __forceinline__ float gumbel(float u) { return -logf(-logf(u)); }
+
+struct Best {
+  float s;
+  int idx;
+};
+__device__ __forceinline__ Best better(Best a, Best b) {
+  // larger score wins; equal scores: lower index; idx < 0 means "no candidate"
+  if (b.idx < 0) return a;
+  if (a.idx < 0) return b;
+  if (b.s > a.s || (b.s == a.s && b.idx < a.idx)) return b;
+  return a;
+}
+__device__ __forceinline__ Best wave_best(Best v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    Best t;
+    t.s = __shfl_xor(v.s, o);
+    t.idx = __shfl_xor(v.idx, o);
+    v = better(v, t);
+  }
+  return v;
+}
+
+struct MaxSum {
+  float m, s;  // running max and sum of exp(a - m)
+};
+__device__ __forceinline__ MaxSum ms_merge(MaxSum a, MaxSum b) {
+  if (b.m == -INFINITY) return a;
+  if (a.m == -INFINITY) return b;
+  MaxSum r;
+  r.m = fmaxf(a.m, b.m);
+  r.s = a.s * expf(a.m - r.m) + b.s * expf(b.m - r.m);
+  return r;
+}
+__device__ __forceinline__ MaxSum wave_ms(MaxSum v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    MaxSum t;
+    t.m = __shfl_xor(v.m, o);
+    t.s = __shfl_xor(v.s, o);
+    v = ms_merge(v, t);
+  }
+  return v;
+}
+
+constexpr int kEpiThreads = 512;
+constexpr int kEpiWaves = kEpiThreads / 64;
+
+__device__ Best block_best(Best v, Best *sh) {
+  v = wave_best(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  Best r = sh[0];
+  for (int w = 1; w < kEpiWaves; ++w) r = better(r, sh[w]);
+  return r;
+}
+__device__ MaxSum block_ms(MaxSum v, MaxSum *sh) {
+  v = wave_ms(v);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = v;
+  __syncthreads();
+  MaxSum r = sh[0];
+  for (int w = 1; w < kEpiWaves; ++w) r = ms_merge(r, sh[w]);
+  return r;
+}
+
+// Gumbel-max over softmax(logits * inv_t) (or plain argmax when greedy) fused with ln-sum-exp.
+__device__ void sample_row(const float *logits, int V, bool greedy, float inv_t, uint32_t k0, uint32_t k1,
+                           uint32_t c1, uint32_t c2, uint32_t c3, Best &best, MaxSum &ms) {
+  best.s = -INFINITY;
+  best.idx = -1;
+  ms.m = -INFINITY;
+  ms.s = 0.f;
+  for (int q4 = threadIdx.x; q4 * 4 < V; q4 += kEpiThreads) {
+    uint32_t rnd[4] = {0, 0, 0, 0};
+    if (!greedy) philox4x32_10((uint32_t)q4, c1, c2, c3, k0, k1, rnd);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      int j = q4 * 4 + e;
+      if (j < V) {
+        float l = logits[j];
+        float a = l * inv_t;
+        if (a > ms.m) {
+          ms.s = (ms.m == -INFINITY) ? 1.f : ms.s * expf(ms.m - a) + 1.f;
+          ms.m = a;
+        } else {
+          ms.s += expf(a - ms.m);
+        }
+        Best c;
+        c.s = greedy ? l : a + gumbel(u01(rnd[e]));
+        c.idx = j;
+        best = better(best, c);
+      }
+    }
+  }
+}
+
+__global__ __launch_bounds__(kEpiThreads) void draft_epilogue_kernel(Params p, SampleArgs a, int R) {
+  __shared__ Best sh_b[kEpiWaves];
+  __shared__ MaxSum sh_m[kEpiWaves];
+  int m = blockIdx.x, b = m / R, r = m % R;
+  int slot = p.step_slots[b];
+  const float *logits = p.draft_logits + ((size_t)slot * (1 + p.k) + r) * p.V;
+  bool greedy = a.temperature == 0.f;
+  float inv_t = greedy ? 1.f : 1.f / a.temperature;
+  Best best;
+  MaxSum ms;
+  sample_row(logits, p.V, greedy, inv_t, a.seed_lo, a.seed_hi, p.iter[slot], (uint32_t)r | (PURPOSE_DRAFT << 8),
+             p.seq_id[slot], best, ms);
+  best = block_best(best, sh_b);
+  ms = block_ms(ms, sh_m);
+  if (threadIdx.x == 0) {
+    p.logz_d[slot * (kMaxK + 1) + r] = ms.m + logf(ms.s);
+    if (r > 0) {
+      p.drafts[slot * kMaxK + (r - 1)] = best.idx;
+    } else {
+      p.first[slot] = best.idx;
+      int ng = p.n_gen[slot];
+      int frozen = ng >= p.gen_limit[slot];
+      p.frozen[slot] = frozen;
+      if (a.commit && !frozen) {
+        // x_{n+1} is accepted unconditionally: it joins the sequence, its predecessor's K/V stay
+        p.kv_len[slot] += 1;
+        p.pending[slot] = best.idx;
+        if (ng < p.gen_cap) p.gen[(size_t)slot * p.gen_cap + ng] = best.idx;
+        p.n_gen[slot] = ng + 1;
+      }
+    }
+  }
+}
+
+// ln-sum-exp and argmax of every validation row
+__global__ __launch_bounds__(kEpiThreads) void verify_stats_kernel(Params p, SampleArgs a, int R) {
+  __shared__ Best sh_b[kEpiWaves];
+  __shared__ MaxSum sh_m[kEpiWaves];
+  int m = blockIdx.x, b = m / R, r = m % R;
+  int slot = p.step_slots[b];
+  const float *logits = p.verify_logits + ((size_t)slot * (1 + p.k) + r) * p.V;
+  bool greedy = a.temperature == 0.f;
+  float inv_t = greedy ? 1.f : 1.f / a.temperature;
+  Best best;
+  MaxSum ms;
+  sample_row(logits, p.V, true, inv_t, 0, 0, 0, 0, 0, best, ms);
+  best = block_best(best, sh_b);
+  ms = block_ms(ms, sh_m);
+  if (threadIdx.x == 0) {
+    p.logz_p[slot * (kMaxK + 1) + r] = ms.m + logf(ms.s);
+    p.argmax_p[slot * (kMaxK + 1) + r] = best.idx;
+  }
+}
+
+__global__ __launch_bounds__(kEpiThreads) void verify_decide_kernel(Params p, SampleArgs a) {
+  __shared__ Best sh_b[kEpiWaves];
+  __shared__ int sh_a;
+  const int slot = p.step_slots[blockIdx.x];
+  const int k = p.k, V = p.V;
+  const bool greedy = a.temperature == 0.f;
+  const float inv_t = greedy ? 1.f : 1.f / a.temperature;
+  const float *P = p.verify_logits + (size_t)slot * (1 + k) * V;
+  const float *Dl = p.draft_logits + (size_t)slot * (1 + k) * V;
+  const float *zp = p.logz_p + slot * (kMaxK + 1), *zd = p.logz_d + slot * (kMaxK + 1);
+  const int32_t *drafts = p.drafts + slot * kMaxK;
+  const uint32_t it = p.iter[slot], sid = p.seq_id[slot];
+
+  if (threadIdx.x == 0) {
+    int acc = 0;
+    for (int t = 1; t <= k; ++t) {
+      int x = drafts[t - 1];
+      bool ok;
+      if (greedy) {
+        ok = x == p.argmax_p[slot * (kMaxK + 1) + (t - 1)];
+      } else {
+        float lp = P[(size_t)(t - 1) * V + x] * inv_t - zp[t - 1];
+        float ld = Dl[(size_t)t * V + x] * inv_t - zd[t];
+        uint32_t rnd[4];
+        philox4x32_10(0u, it, (uint32_t)t | (PURPOSE_ACCEPT << 8), sid, a.seed_lo, a.seed_hi, rnd);
+        ok = logf(u01(rnd[0])) + ld < lp;
+      }
+      if (!ok) break;
+      acc += 1;
+    }
+    sh_a = acc;
+  }
+  __syncthreads();
+  const int acc = sh_a;
+  int y;
+  if (greedy) {
+    y = p.argmax_p[slot * (kMaxK + 1) + acc];
+  } else if (acc == k) {
+    Best best;
+    MaxSum ms;
+    sample_row(P + (size_t)k * V, V, false, inv_t, a.seed_lo, a.seed_hi, it, (uint32_t)(k + 1) | (PURPOSE_BONUS << 8),
+               sid, best, ms);
+    y = block_best(best, sh_b).idx;
+  } else {
+    const float *pr = P + (size_t)acc * V, *dr = Dl + (size_t)(acc + 1) * V;
+    const float z_p = zp[acc], z_d = zd[acc + 1];
+    const uint32_t c2 = (uint32_t)(acc + 1) | (PURPOSE_RESIDUAL << 8);
+    Best best;
+    best.s = -INFINITY;
+    best.idx = -1;
+    for (int q4 = threadIdx.x; q4 * 4 < V; q4 += kEpiThreads) {
+      uint32_t rnd[4];
+      philox4x32_10((uint32_t)q4, it, c2, sid, a.seed_lo, a.seed_hi, rnd);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        int j = q4 * 4 + e;
+        if (j < V) {
+          float w = expf(pr[j] * inv_t - z_p) - expf(dr[j] * inv_t - z_d);
+          if (w > 0.f) {
+            Best c;
+            c.s = logf(w) + gumbel(u01(rnd[e]));
+            c.idx = j;
+            best = better(best, c);
+          }
+        }
+      }
+    }
+    best = block_best(best, sh_b);
+    if (best.idx < 0) {
+      // residual empty through rounding: draw from p_t with the same counters
+      MaxSum ms;
+      sample_row(pr, V, false, inv_t, a.seed_lo, a.seed_hi, it, c2, sid, best, ms);
+      best = block_best(best, sh_b);
+      if (threadIdx.x == 0) atomicAdd(p.fallbacks, 1);
+    }
+    y = best.idx;
+  }
+  if (threadIdx.x == 0) {
+    int32_t *lo = p.last_out + slot * (kMaxK + 1);
+    for (int t = 0; t < acc; ++t) lo[t] = drafts[t];
+    lo[acc] = y;
+    p.n_acc[slot] = acc;
+    if (a.commit && !p.frozen[slot]) {
+      int ng = p.n_gen[slot];
+      for (int t = 0; t <= acc; ++t)
+        if (ng + t < p.gen_cap) p.gen[(size_t)slot * p.gen_cap + ng + t] = lo[t];
+      p.n_gen[slot] = ng + acc + 1;
+      p.kv_len[slot] += 1 + acc;  // K/V of x_{n+1} and of the accepted drafts are kept
+      p.pending[slot] = y;
+      p.iter[slot] = it + 1;
+    }
+  }
+}
+
+void launch_draft_epilogue(const Params &p, const SampleArgs &a, int B, int R, hipStream_t s) {
+  draft_epilogue_kernel<<<B * R, kEpiThreads, 0, s>>>(p, a, R);
+}
+
+void launch_verify_epilogue(const Params &p, const SampleArgs &a, int B, int R, hipStream_t s) {
+  verify_stats_kernel<<<B * R, kEpiThreads, 0, s>>>(p, a, R);
+  verify_decide_kernel<<<B, kEpiThreads, 0, s>>>(p, a);
+}
+
+}  // namespace pass

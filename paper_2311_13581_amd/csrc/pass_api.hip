@@ -1,0 +1,655 @@
+// C ABI of libpass_hip.so: context, arena layout, paged K/V bookkeeping, the step schedule and
+// Algorithm 1's loop.  All arithmetic of the method runs in the kernels this file launches.
+#include <limits.h>
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <string>
+#include <vector>
+
+#include "pass_internal.h"
+
+using namespace pass;
+
+namespace {
+
+struct Arena {
+  char *base;
+  size_t off;
+  template <typename T>
+  T *take(size_t n) {
+    off = (off + 255) & ~(size_t)255;
+    T *p = base ? (T *)(base + off) : nullptr;
+    off += n * sizeof(T);
+    return p;
+  }
+};
+
+struct LayerW {
+  void *attn_norm, *wqkv, *wo, *ffn_norm, *wgu, *wdown;
+};
+
+struct Slot {
+  int state = 0;  // 0 empty, 1 ready for draft, 2 ready for verify
+  int kv_len = 0, n_gen = 0;
+  uint32_t seq_id = 0;
+  std::vector<int> pages;
+};
+
+constexpr int kReportStride = 4 + kMaxK + kMaxK + 1;
+
+}  // namespace
+
+struct pass_ctx {
+  pass_config cfg;
+  hipStream_t stream;
+  Params P;
+  size_t esz;  // bytes per model element
+  // weights (arena)
+  void *tok_emb, *lm_head, *final_norm, *lookahead, *staging;
+  size_t staging_bytes;
+  std::vector<LayerW> layers;
+  bool weights_loaded = false;
+  bool use_mfma = false;  // matrix-core path active (set by pass_load_weights)
+  int opt_graph = 0, opt_path = 0;
+  // device scratch
+  int32_t *prompt_buf, *report_dev;
+  // host
+  std::vector<Slot> slots;
+  std::vector<int> free_pages;
+  int32_t *report_host = nullptr;       // pinned
+  int32_t *block_table_host = nullptr;  // pinned mirror of P.block_table
+  hipEvent_t ev[3];
+  std::string err;
+};
+
+namespace {
+
+std::string g_create_error;  // message of the last failed pass_create (no context exists yet)
+
+int fail(pass_ctx *c, int code, const char *fmt, ...) {
+  if (c) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    c->err = buf;
+  }
+  return code;
+}
+
+#define HIP_TRY(c, call)                                                                         \
+  do {                                                                                           \
+    hipError_t e_ = (call);                                                                      \
+    if (e_ != hipSuccess) return fail((c), PASS_EDEVICE, "%s: %s", #call, hipGetErrorString(e_)); \
+  } while (0)
+
+bool config_ok(const pass_config *c, std::string *why) {
+  auto bad = [&](const char *m) { if (why) *why = m; return false; };
+  if (!c) return bad("null config");
+  if (c->n_layers < 1 || c->d_model < 8 || c->n_heads < 1 || c->d_ffn < 8 || c->vocab < 2) return bad("bad shape");
+  if (c->head_dim != 64 && c->head_dim != 128) return bad("head_dim must be 64 or 128");
+  if (c->d_model % 8 || c->d_ffn % 8) return bad("d_model and d_ffn must be multiples of 8");
+  if (c->dtype != PASS_F32 && c->dtype != PASS_BF16) return bad("dtype must be PASS_F32 or PASS_BF16");
+  if (c->k < 0 || c->k > kMaxK) return bad("k out of range");
+  if (c->max_slots < 1 || (1 + c->k) * c->max_slots > kMaxRows) return bad("(1+k)*max_slots exceeds PASS_MAX_ROWS");
+  if (c->max_seq_len < 2 + c->k) return bad("max_seq_len too small");
+  if (c->page_size < 16 || (c->page_size & (c->page_size - 1))) return bad("page_size must be a power of two >= 16");
+  if (c->n_pages < 0) return bad("n_pages negative");
+  if (!(c->rms_eps > 0) || !(c->rope_base > 1)) return bad("rms_eps / rope_base");
+  return true;
+}
+
+int pages_per_seq(const pass_config &c) { return (c.max_seq_len + c.page_size - 1) / c.page_size; }
+int pool_pages(const pass_config &c) { return c.n_pages ? c.n_pages : c.max_slots * pages_per_seq(c); }
+
+// Carve the arena.  With base == nullptr only the size is computed.
+size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
+  Arena A{base, 0};
+  const size_t esz = c.dtype == PASS_F32 ? 4 : 2;
+  const size_t d = c.d_model, D = (size_t)c.n_heads * c.head_dim, F = c.d_ffn, V = c.vocab, S = c.max_slots;
+  const size_t M = kMaxRows;
+  const int pps = pages_per_seq(c);
+  const int np = pool_pages(c);
+  Params P;
+  memset(&P, 0, sizeof P);
+  P.L = c.n_layers; P.d = c.d_model; P.H = c.n_heads; P.hd = c.head_dim; P.D = (int)D; P.F = c.d_ffn; P.V = c.vocab;
+  P.k = c.k; P.max_slots = c.max_slots; P.max_seq_len = c.max_seq_len; P.page_size = c.page_size;
+  P.page_shift = __builtin_ctz(c.page_size); P.n_pages = np; P.pages_per_seq = pps;
+  P.gen_cap = c.max_seq_len + kMaxK + 2;
+  P.eps = c.rms_eps; P.rope_base = c.rope_base;
+
+  P.kv_len = A.take<int32_t>(S); P.pending = A.take<int32_t>(S); P.first = A.take<int32_t>(S);
+  P.drafts = A.take<int32_t>(S * kMaxK); P.n_gen = A.take<int32_t>(S); P.n_acc = A.take<int32_t>(S);
+  P.frozen = A.take<int32_t>(S); P.gen_limit = A.take<int32_t>(S);
+  P.iter = A.take<uint32_t>(S); P.seq_id = A.take<uint32_t>(S);
+  P.last_out = A.take<int32_t>(S * (kMaxK + 1));
+  P.gen = A.take<int32_t>(S * P.gen_cap);
+  P.logz_d = A.take<float>(S * (kMaxK + 1)); P.logz_p = A.take<float>(S * (kMaxK + 1));
+  P.argmax_p = A.take<int32_t>(S * (kMaxK + 1));
+  P.fallbacks = A.take<int32_t>(1);
+  P.block_table = A.take<int32_t>(S * pps);
+  P.draft_logits = A.take<float>(S * (1 + c.k) * V);
+  P.verify_logits = A.take<float>(S * (1 + c.k) * V);
+  P.step_slots = A.take<int32_t>(M);
+  P.row_pos = A.take<int32_t>(M); P.row_slot = A.take<int32_t>(M); P.row_out = A.take<int32_t>(M);
+  P.rope_cos = A.take<float>(M * c.head_dim / 2); P.rope_sin = A.take<float>(M * c.head_dim / 2);
+  P.h = A.take<float>(M * d); P.xn = A.take<float>(M * d); P.qkv = A.take<float>(M * 3 * D);
+  P.attn = A.take<float>(M * D); P.gu = A.take<float>(M * 2 * F); P.act = A.take<float>(M * F);
+  P.attn_bf16 = A.take<uint16_t>(M * D); P.act_bf16 = A.take<uint16_t>(M * F);
+  P.part_acc = A.take<float>(M * c.n_heads * kMaxSplits * c.head_dim);
+  P.part_m = A.take<float>(M * c.n_heads * kMaxSplits); P.part_l = A.take<float>(M * c.n_heads * kMaxSplits);
+  size_t pool_elems = (size_t)c.n_layers * np * c.n_heads * c.page_size * c.head_dim;
+  P.k_pool = A.take<char>(pool_elems * esz); P.v_pool = A.take<char>(pool_elems * esz);
+  int32_t *prompt_buf = A.take<int32_t>(c.max_seq_len);
+  int32_t *report_dev = A.take<int32_t>(S * kReportStride);
+
+  void *tok_emb = A.take<char>(V * d * esz), *lm_head = A.take<char>(V * d * esz);
+  void *final_norm = A.take<char>(d * esz), *lookahead = A.take<char>((size_t)(c.k ? c.k : 1) * d * esz);
+  std::vector<LayerW> layers(c.n_layers);
+  for (auto &l : layers) {
+    l.attn_norm = A.take<char>(d * esz); l.ffn_norm = A.take<char>(d * esz);
+    l.wqkv = A.take<char>(3 * D * d * esz); l.wo = A.take<char>(d * D * esz);
+    l.wgu = A.take<char>(2 * F * d * esz); l.wdown = A.take<char>(d * F * esz);
+  }
+  size_t stage = V * d;
+  if (F * d > stage) stage = F * d;
+  if (D * d > stage) stage = D * d;
+  void *staging = A.take<char>(stage * esz);
+  if (ctx) {
+    ctx->P = P; ctx->esz = esz; ctx->prompt_buf = prompt_buf; ctx->report_dev = report_dev;
+    ctx->tok_emb = tok_emb; ctx->lm_head = lm_head; ctx->final_norm = final_norm; ctx->lookahead = lookahead;
+    ctx->layers = layers; ctx->staging = staging; ctx->staging_bytes = stage * esz;
+  }
+  return (A.off + 255) & ~(size_t)255;
+}
+
+__global__ void gather_report_kernel(Params p, int B, int32_t *out) {
+  int b = threadIdx.x;
+  if (b >= B) return;
+  int slot = p.step_slots[b];
+  int32_t *o = out + b * kReportStride;
+  o[0] = p.kv_len[slot]; o[1] = p.n_gen[slot]; o[2] = p.n_acc[slot]; o[3] = p.first[slot];
+  for (int t = 0; t < kMaxK; ++t) o[4 + t] = p.drafts[slot * kMaxK + t];
+  for (int t = 0; t <= kMaxK; ++t) o[4 + kMaxK + t] = p.last_out[slot * (kMaxK + 1) + t];
+}
+
+int poke(pass_ctx *c, std::vector<int32_t *> &ptrs, std::vector<int32_t> &vals) {
+  for (size_t i = 0; i < ptrs.size(); i += 16) {
+    int n = (int)std::min<size_t>(16, ptrs.size() - i);
+    launch_poke(ptrs.data() + i, vals.data() + i, n, c->stream);
+  }
+  ptrs.clear();
+  vals.clear();
+  HIP_TRY(c, hipGetLastError());
+  return PASS_OK;
+}
+
+void release_pages(pass_ctx *c, int slot) {
+  Slot &s = c->slots[slot];
+  for (int pg : s.pages) c->free_pages.push_back(pg);
+  s.pages.clear();
+}
+
+// Make sure `slot` has pages for positions [0, n_pos).
+int ensure_pages(pass_ctx *c, int slot, int n_pos) {
+  Slot &s = c->slots[slot];
+  const int ps = c->cfg.page_size, pps = c->P.pages_per_seq;
+  int need = (n_pos + ps - 1) / ps;
+  if (need > pps) return fail(c, PASS_ECAPACITY, "slot %d: %d positions exceed max_seq_len", slot, n_pos);
+  int have = (int)s.pages.size();
+  if (need <= have) return PASS_OK;
+  if ((int)c->free_pages.size() < need - have) return fail(c, PASS_ECAPACITY, "K/V page pool exhausted");
+  for (int i = have; i < need; ++i) {
+    int pg = c->free_pages.back();
+    c->free_pages.pop_back();
+    s.pages.push_back(pg);
+    c->block_table_host[(size_t)slot * pps + i] = pg;
+  }
+  // entries are only ever appended while a sequence lives, so an in-flight copy of this row can
+  // at worst see a newer value of an entry no running kernel reads
+  HIP_TRY(c, hipMemcpyAsync(c->P.block_table + (size_t)slot * pps + have, c->block_table_host + (size_t)slot * pps + have,
+                            sizeof(int32_t) * (need - have), hipMemcpyHostToDevice, c->stream));
+  return PASS_OK;
+}
+
+int set_step_slots(pass_ctx *c, const int32_t *slots, int B) {
+  std::vector<int32_t *> ptrs;
+  std::vector<int32_t> vals;
+  for (int b = 0; b < B; ++b) { ptrs.push_back(c->P.step_slots + b); vals.push_back(slots[b]); }
+  return poke(c, ptrs, vals);
+}
+
+int choose_splits(const pass_ctx *c, int B, int R, int max_keys) {
+  int groups = B * ((R + kAttnRowsPerGroup - 1) / kAttnRowsPerGroup);
+  int by_fill = (1024 + groups * c->P.H - 1) / (groups * c->P.H);
+  int by_len = (max_keys + 63) / 64;
+  int s = std::min(by_fill, by_len);
+  return std::max(1, std::min(kMaxSplits, s));
+}
+
+// One model call on B*R rows.  logits_base == nullptr: no LM head (prefill).
+int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_keys, const int32_t *prefill_ids) {
+  Params P = c->P;
+  P.prefill_ids = const_cast<int32_t *>(prefill_ids);
+  const int dt = c->cfg.dtype, M = B * R;
+  hipStream_t s = c->stream;
+  const int S = choose_splits(c, B, R, max_keys);
+  launch_assemble(P, dt, c->tok_emb, c->lookahead, mode, B, R, s);
+  for (int l = 0; l < P.L; ++l) {
+    const LayerW &w = c->layers[l];
+    launch_rmsnorm(P, dt, P.h, w.attn_norm, P.xn, M, s);
+    launch_gemm_generic(dt, P.xn, w.wqkv, P.qkv, M, 3 * P.D, P.d, 3 * P.D, nullptr, 0, s);
+    launch_rope_kv(P, dt, l, M, s);
+    launch_attention(P, dt, l, B, R, S, 0, s);
+    launch_gemm_generic(dt, P.attn, w.wo, P.h, M, P.d, P.D, P.d, nullptr, 1, s);
+    launch_rmsnorm(P, dt, P.h, w.ffn_norm, P.xn, M, s);
+    launch_gemm_generic(dt, P.xn, w.wgu, P.gu, M, 2 * P.F, P.d, 2 * P.F, nullptr, 0, s);
+    launch_silu_mul(P, M, s);
+    launch_gemm_generic(dt, P.act, w.wdown, P.h, M, P.d, P.F, P.d, nullptr, 1, s);
+  }
+  if (logits_base) {
+    launch_rmsnorm(P, dt, P.h, c->final_norm, P.xn, M, s);
+    launch_gemm_generic(dt, P.xn, c->lm_head, logits_base, M, P.V, P.d, P.V, P.row_out, 0, s);
+  }
+  HIP_TRY(c, hipGetLastError());
+  return PASS_OK;
+}
+
+int check_slots(pass_ctx *c, const int32_t *slots, int n_slots, int want_state) {
+  if (!slots || n_slots < 1 || n_slots > c->cfg.max_slots) return fail(c, PASS_EINVAL, "bad slot list");
+  for (int i = 0; i < n_slots; ++i) {
+    int s = slots[i];
+    if (s < 0 || s >= c->cfg.max_slots) return fail(c, PASS_EINVAL, "slot %d out of range", s);
+    for (int j = 0; j < i; ++j)
+      if (slots[j] == s) return fail(c, PASS_EINVAL, "slot %d listed twice", s);
+    if (c->slots[s].state != want_state)
+      return fail(c, PASS_ESTATE, "slot %d is in state %d, call needs state %d", s, c->slots[s].state, want_state);
+  }
+  return PASS_OK;
+}
+
+int check_sampling(pass_ctx *c, const pass_sampling *sp) {
+  if (!sp) return fail(c, PASS_EINVAL, "null sampling parameters");
+  if (!(sp->temperature >= 0.f) || !isfinite(sp->temperature)) return fail(c, PASS_EINVAL, "temperature must be >= 0");
+  if (sp->top_k != 0) return fail(c, PASS_EINVAL, "top_k is reserved and must be 0");
+  return PASS_OK;
+}
+
+SampleArgs sample_args(const pass_sampling *sp, int commit) {
+  SampleArgs a;
+  a.temperature = sp->temperature;
+  a.seed_lo = (uint32_t)sp->seed;
+  a.seed_hi = (uint32_t)(sp->seed >> 32);
+  a.commit = commit;
+  return a;
+}
+
+int fetch_report(pass_ctx *c, int B) {
+  gather_report_kernel<<<1, 64, 0, c->stream>>>(c->P, B, c->report_dev);
+  HIP_TRY(c, hipGetLastError());
+  HIP_TRY(c, hipMemcpyAsync(c->report_host, c->report_dev, sizeof(int32_t) * B * kReportStride, hipMemcpyDeviceToHost,
+                            c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PASS_OK;
+}
+
+int max_keys_of(pass_ctx *c, const int32_t *slots, int B, int extra) {
+  int mk = 1;
+  for (int b = 0; b < B; ++b) mk = std::max(mk, c->slots[slots[b]].kv_len + extra);
+  return mk;
+}
+
+// the two halves of an iteration, without host synchronisation
+int issue_draft(pass_ctx *c, const int32_t *slots, int B, const pass_sampling *sp, int commit) {
+  const int R = 1 + c->cfg.k;
+  int rc = run_step(c, MODE_DRAFT, B, R, c->P.draft_logits, max_keys_of(c, slots, B, R), nullptr);
+  if (rc) return rc;
+  launch_draft_epilogue(c->P, sample_args(sp, commit), B, R, c->stream);
+  HIP_TRY(c, hipGetLastError());
+  return PASS_OK;
+}
+
+int issue_verify(pass_ctx *c, const int32_t *slots, int B, const pass_sampling *sp, int commit) {
+  const int R = 1 + c->cfg.k;
+  int rc = run_step(c, MODE_VERIFY, B, R, c->P.verify_logits, max_keys_of(c, slots, B, R + 1), nullptr);
+  if (rc) return rc;
+  launch_verify_epilogue(c->P, sample_args(sp, commit), B, R, c->stream);
+  HIP_TRY(c, hipGetLastError());
+  return PASS_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+extern "C" {
+
+size_t pass_arena_bytes(const pass_config *cfg) {
+  if (!config_ok(cfg, nullptr)) return 0;
+  return carve(*cfg, nullptr, nullptr);
+}
+
+int pass_create(const pass_config *cfg, void *hip_stream, void *device_arena, size_t arena_bytes, pass_ctx **out) {
+  if (!out) return PASS_EINVAL;
+  *out = nullptr;
+  std::string why;
+  if (!config_ok(cfg, &why)) { g_create_error = "pass_create: " + why; return PASS_EINVAL; }
+  if (!device_arena || ((uintptr_t)device_arena & 255)) { g_create_error = "pass_create: arena null or misaligned"; return PASS_EINVAL; }
+  if (arena_bytes < carve(*cfg, nullptr, nullptr)) { g_create_error = "pass_create: arena too small"; return PASS_EINVAL; }
+  pass_ctx *c = new pass_ctx();
+  c->cfg = *cfg;
+  c->stream = (hipStream_t)hip_stream;
+  carve(*cfg, (char *)device_arena, c);
+  c->slots.resize(cfg->max_slots);
+  for (int i = pool_pages(*cfg) - 1; i >= 0; --i) c->free_pages.push_back(i);
+  const size_t S = cfg->max_slots;
+  auto die = [&](hipError_t e) {
+    g_create_error = std::string("pass_create: ") + hipGetErrorString(e);
+    if (c->report_host) (void)hipHostFree(c->report_host);
+    if (c->block_table_host) (void)hipHostFree(c->block_table_host);
+    delete c;
+    return PASS_EDEVICE;
+  };
+  hipError_t e = hipHostMalloc((void **)&c->report_host, sizeof(int32_t) * S * kReportStride, hipHostMallocDefault);
+  if (e != hipSuccess) return die(e);
+  e = hipHostMalloc((void **)&c->block_table_host, sizeof(int32_t) * S * c->P.pages_per_seq, hipHostMallocDefault);
+  if (e != hipSuccess) return die(e);
+  memset(c->block_table_host, 0, sizeof(int32_t) * S * c->P.pages_per_seq);
+  for (auto &ev : c->ev) {
+    e = hipEventCreate(&ev);
+    if (e != hipSuccess) return die(e);
+  }
+  // per-slot state starts at zero; block table at page 0 (valid memory, never read before set)
+  size_t state_ints = (size_t)((char *)c->P.gen - (char *)c->P.kv_len) / 4;
+  launch_fill_i32(c->P.kv_len, 0, state_ints, c->stream);
+  launch_fill_i32(c->P.block_table, 0, S * c->P.pages_per_seq, c->stream);
+  launch_fill_i32(c->P.fallbacks, 0, 1, c->stream);
+  launch_fill_i32(c->P.gen_limit, INT_MAX, S, c->stream);
+  launch_fill_i32(c->P.step_slots, 0, kMaxRows, c->stream);
+  e = hipGetLastError();
+  if (e != hipSuccess) return die(e);
+  e = hipStreamSynchronize(c->stream);
+  if (e != hipSuccess) return die(e);
+  *out = c;
+  return PASS_OK;
+}
+
+int pass_load_weights(pass_ctx *c, const pass_weights *w, int on_device) {
+  if (!c) return PASS_EINVAL;
+  if (!w || !w->tok_emb || !w->lm_head || !w->final_norm || (c->cfg.k > 0 && !w->lookahead) || !w->attn_norm ||
+      !w->wq || !w->wk || !w->wv || !w->wo || !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down)
+    return fail(c, PASS_EINVAL, "null weight pointer");
+  const size_t e = c->esz, d = c->P.d, D = c->P.D, F = c->P.F, V = c->P.V;
+  const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
+  auto cp = [&](void *dst, const void *src, size_t elems) -> int {
+    if (!src) return fail(c, PASS_EINVAL, "null weight pointer");
+    HIP_TRY(c, hipMemcpyAsync(dst, src, elems * e, kind, c->stream));
+    return PASS_OK;
+  };
+  int rc;
+  if ((rc = cp(c->tok_emb, w->tok_emb, V * d))) return rc;
+  if ((rc = cp(c->lm_head, w->lm_head, V * d))) return rc;
+  if ((rc = cp(c->final_norm, w->final_norm, d))) return rc;
+  if (c->cfg.k > 0 && (rc = cp(c->lookahead, w->lookahead, (size_t)c->cfg.k * d))) return rc;
+  for (int l = 0; l < c->P.L; ++l) {
+    LayerW &lw = c->layers[l];
+    if ((rc = cp(lw.attn_norm, w->attn_norm[l], d))) return rc;
+    if ((rc = cp(lw.ffn_norm, w->ffn_norm[l], d))) return rc;
+    if ((rc = cp(lw.wqkv, w->wq[l], D * d))) return rc;
+    if ((rc = cp((char *)lw.wqkv + D * d * e, w->wk[l], D * d))) return rc;
+    if ((rc = cp((char *)lw.wqkv + 2 * D * d * e, w->wv[l], D * d))) return rc;
+    if ((rc = cp(lw.wo, w->wo[l], d * D))) return rc;
+    if ((rc = cp(lw.wgu, w->w_gate[l], F * d))) return rc;
+    if ((rc = cp((char *)lw.wgu + F * d * e, w->w_up[l], F * d))) return rc;
+    if ((rc = cp(lw.wdown, w->w_down[l], d * F))) return rc;
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  c->weights_loaded = true;
+  return PASS_OK;
+}
+
+int pass_release(pass_ctx *c, int slot) {
+  if (!c) return PASS_EINVAL;
+  if (slot < 0 || slot >= c->cfg.max_slots) return fail(c, PASS_EINVAL, "slot %d out of range", slot);
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  release_pages(c, slot);
+  c->slots[slot] = Slot();
+  return PASS_OK;
+}
+
+int pass_prefill(pass_ctx *c, int slot, uint32_t seq_id, const int32_t *prompt, int n) {
+  if (!c) return PASS_EINVAL;
+  if (!c->weights_loaded) return fail(c, PASS_ESTATE, "weights not loaded");
+  if (slot < 0 || slot >= c->cfg.max_slots) return fail(c, PASS_EINVAL, "slot %d out of range", slot);
+  if (!prompt || n < 1) return fail(c, PASS_EINVAL, "prompt must hold at least one token");
+  for (int i = 0; i < n; ++i)
+    if (prompt[i] < 0 || prompt[i] >= c->cfg.vocab) return fail(c, PASS_EINVAL, "prompt[%d] = %d outside the vocabulary", i, prompt[i]);
+  if (n - 1 + 1 + c->cfg.k > c->cfg.max_seq_len) return fail(c, PASS_ECAPACITY, "prompt of %d tokens does not fit max_seq_len", n);
+  int rc = pass_release(c, slot);
+  if (rc) return rc;
+  if ((rc = ensure_pages(c, slot, n - 1 + 1 + c->cfg.k))) return rc;
+  Slot &s = c->slots[slot];
+  s.seq_id = seq_id;
+  const Params &P = c->P;
+  std::vector<int32_t *> ptrs = {P.kv_len + slot, P.pending + slot, P.n_gen + slot, (int32_t *)P.iter + slot,
+                                 (int32_t *)P.seq_id + slot, P.gen_limit + slot, P.frozen + slot, P.n_acc + slot,
+                                 P.step_slots};
+  std::vector<int32_t> vals = {0, prompt[n - 1], 0, 0, (int32_t)seq_id, INT_MAX, 0, 0, slot};
+  if ((rc = poke(c, ptrs, vals))) return rc;
+  if (n > 1) {
+    HIP_TRY(c, hipMemcpyAsync(c->prompt_buf, prompt, sizeof(int32_t) * (n - 1), hipMemcpyHostToDevice, c->stream));
+    const int chunk = 32;
+    for (int done = 0; done < n - 1; done += chunk) {
+      int R = std::min(chunk, n - 1 - done);
+      ptrs = {P.kv_len + slot};
+      vals = {done};
+      if ((rc = poke(c, ptrs, vals))) return rc;
+      if ((rc = run_step(c, MODE_PREFILL, 1, R, nullptr, done + R, c->prompt_buf + done))) return rc;
+    }
+    ptrs = {P.kv_len + slot};
+    vals = {n - 1};
+    if ((rc = poke(c, ptrs, vals))) return rc;
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  s.kv_len = n - 1;
+  s.n_gen = 0;
+  s.state = 1;
+  return PASS_OK;
+}
+
+int pass_draft(pass_ctx *c, const int32_t *slots, int n_slots, const pass_sampling *sp, int32_t *out_first,
+               int32_t *out_drafts) {
+  if (!c) return PASS_EINVAL;
+  int rc;
+  if ((rc = check_slots(c, slots, n_slots, 1))) return rc;
+  if ((rc = check_sampling(c, sp))) return rc;
+  const int k = c->cfg.k;
+  for (int b = 0; b < n_slots; ++b) {
+    if (c->slots[slots[b]].kv_len + 1 + k > c->cfg.max_seq_len) return fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]);
+    if ((rc = ensure_pages(c, slots[b], c->slots[slots[b]].kv_len + 1 + k))) return rc;
+  }
+  if ((rc = set_step_slots(c, slots, n_slots))) return rc;
+  if ((rc = issue_draft(c, slots, n_slots, sp, 1))) return rc;
+  if ((rc = fetch_report(c, n_slots))) return rc;
+  for (int b = 0; b < n_slots; ++b) {
+    const int32_t *r = c->report_host + b * kReportStride;
+    Slot &s = c->slots[slots[b]];
+    s.kv_len = r[0];
+    s.n_gen = r[1];
+    s.state = 2;
+    if (out_first) out_first[b] = r[3];
+    if (out_drafts)
+      for (int t = 0; t < k; ++t) out_drafts[b * k + t] = r[4 + t];
+  }
+  return PASS_OK;
+}
+
+int pass_verify(pass_ctx *c, const int32_t *slots, int n_slots, const pass_sampling *sp, int32_t *out_n_accepted,
+                int32_t *out_tokens) {
+  if (!c) return PASS_EINVAL;
+  int rc;
+  if ((rc = check_slots(c, slots, n_slots, 2))) return rc;
+  if ((rc = check_sampling(c, sp))) return rc;
+  const int k = c->cfg.k;
+  for (int b = 0; b < n_slots; ++b) {
+    if (c->slots[slots[b]].kv_len + 1 + k > c->cfg.max_seq_len) return fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]);
+    if ((rc = ensure_pages(c, slots[b], c->slots[slots[b]].kv_len + 1 + k))) return rc;
+  }
+  if ((rc = set_step_slots(c, slots, n_slots))) return rc;
+  if ((rc = issue_verify(c, slots, n_slots, sp, 1))) return rc;
+  if ((rc = fetch_report(c, n_slots))) return rc;
+  for (int b = 0; b < n_slots; ++b) {
+    const int32_t *r = c->report_host + b * kReportStride;
+    Slot &s = c->slots[slots[b]];
+    s.kv_len = r[0];
+    s.n_gen = r[1];
+    s.state = 1;
+    int a = r[2];
+    if (out_n_accepted) out_n_accepted[b] = a;
+    if (out_tokens)
+      for (int t = 0; t <= k; ++t) out_tokens[b * (k + 1) + t] = t <= a ? r[4 + kMaxK + t] : -1;
+  }
+  return PASS_OK;
+}
+
+int pass_generate(pass_ctx *c, const int32_t *slots, int n_slots, int max_new, const pass_sampling *sp,
+                  int32_t *out_tokens, pass_stats *out_stats) {
+  if (!c) return PASS_EINVAL;
+  int rc;
+  if ((rc = check_slots(c, slots, n_slots, 1))) return rc;
+  if ((rc = check_sampling(c, sp))) return rc;
+  if (max_new < 0 || (max_new > 0 && !out_tokens)) return fail(c, PASS_EINVAL, "bad max_new / out_tokens");
+  const int k = c->cfg.k;
+  pass_stats st;
+  memset(&st, 0, sizeof st);
+  std::vector<int> start(n_slots);
+  std::vector<int32_t *> ptrs;
+  std::vector<int32_t> vals;
+  for (int b = 0; b < n_slots; ++b) {
+    start[b] = c->slots[slots[b]].n_gen;
+    if (start[b] + max_new + k + 1 > c->P.gen_cap) return fail(c, PASS_ECAPACITY, "slot %d: token buffer too small", slots[b]);
+    ptrs.push_back(c->P.gen_limit + slots[b]);
+    vals.push_back(start[b] + max_new);
+  }
+  if ((rc = poke(c, ptrs, vals))) return rc;
+  if ((rc = set_step_slots(c, slots, n_slots))) return rc;
+  auto finish = [&](int code) {
+    for (int b = 0; b < n_slots; ++b) { ptrs.push_back(c->P.gen_limit + slots[b]); vals.push_back(INT_MAX); }
+    int r2 = poke(c, ptrs, vals);
+    (void)hipStreamSynchronize(c->stream);
+    return code ? code : r2;
+  };
+  for (;;) {
+    bool all_done = true;
+    for (int b = 0; b < n_slots; ++b) {
+      Slot &s = c->slots[slots[b]];
+      bool done = s.n_gen - start[b] >= max_new;
+      all_done &= done;
+      if (!done && s.kv_len + 2 + k > c->cfg.max_seq_len) return finish(fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]));
+      int want = std::min(s.kv_len + 2 + k, c->cfg.max_seq_len);
+      if ((rc = ensure_pages(c, slots[b], want))) return finish(rc);
+    }
+    if (all_done) break;
+    HIP_TRY(c, hipEventRecord(c->ev[0], c->stream));
+    if ((rc = issue_draft(c, slots, n_slots, sp, 1))) return finish(rc);
+    HIP_TRY(c, hipEventRecord(c->ev[1], c->stream));
+    if ((rc = issue_verify(c, slots, n_slots, sp, 1))) return finish(rc);
+    HIP_TRY(c, hipEventRecord(c->ev[2], c->stream));
+    if ((rc = fetch_report(c, n_slots))) return finish(rc);
+    float ms_d = 0, ms_v = 0;
+    HIP_TRY(c, hipEventElapsedTime(&ms_d, c->ev[0], c->ev[1]));
+    HIP_TRY(c, hipEventElapsedTime(&ms_v, c->ev[1], c->ev[2]));
+    st.draft_ms += ms_d;
+    st.verify_ms += ms_v;
+    for (int b = 0; b < n_slots; ++b) {
+      const int32_t *r = c->report_host + b * kReportStride;
+      Slot &s = c->slots[slots[b]];
+      if (r[1] != s.n_gen) {  // the slot was live in this iteration
+        st.iterations += 1;
+        st.drafts_proposed += k;
+        st.drafts_accepted += r[2];
+      }
+      s.kv_len = r[0];
+      s.n_gen = r[1];
+    }
+  }
+  for (int b = 0; b < n_slots; ++b) {
+    if (max_new > 0)
+      HIP_TRY(c, hipMemcpyAsync(out_tokens + (size_t)b * max_new, c->P.gen + (size_t)slots[b] * c->P.gen_cap + start[b],
+                                sizeof(int32_t) * max_new, hipMemcpyDeviceToHost, c->stream));
+    st.tokens_out += max_new;
+  }
+  rc = finish(PASS_OK);
+  if (out_stats) *out_stats = st;
+  return rc;
+}
+
+int pass_get_logits(pass_ctx *c, int slot, int which, float *out) {
+  if (!c) return PASS_EINVAL;
+  if (slot < 0 || slot >= c->cfg.max_slots || !out || (which != 0 && which != 1)) return fail(c, PASS_EINVAL, "bad argument");
+  size_t n = (size_t)(1 + c->cfg.k) * c->cfg.vocab;
+  const float *src = (which ? c->P.verify_logits : c->P.draft_logits) + (size_t)slot * n;
+  HIP_TRY(c, hipMemcpyAsync(out, src, n * sizeof(float), hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PASS_OK;
+}
+
+int pass_seq_len(pass_ctx *c, int slot, int32_t *kv_len, int32_t *n_generated) {
+  if (!c) return PASS_EINVAL;
+  if (slot < 0 || slot >= c->cfg.max_slots) return fail(c, PASS_EINVAL, "slot %d out of range", slot);
+  if (c->slots[slot].state == 0) return fail(c, PASS_ESTATE, "slot %d is empty", slot);
+  if (kv_len) *kv_len = c->slots[slot].kv_len;
+  if (n_generated) *n_generated = c->slots[slot].n_gen;
+  return PASS_OK;
+}
+
+int pass_set_option(pass_ctx *c, const char *name, int value) {
+  if (!c || !name) return PASS_EINVAL;
+  if (!strcmp(name, "graph")) { c->opt_graph = value; return PASS_OK; }
+  if (!strcmp(name, "path")) {
+    if (c->weights_loaded) return fail(c, PASS_ESTATE, "\"path\" must be set before pass_load_weights");
+    c->opt_path = value;
+    return PASS_OK;
+  }
+  return fail(c, PASS_EINVAL, "unknown option %s", name);
+}
+
+int pass_time_step(pass_ctx *c, const int32_t *slots, int n_slots, int warmup, int iters, double *out_ms) {
+  if (!c) return PASS_EINVAL;
+  int rc;
+  if ((rc = check_slots(c, slots, n_slots, 1))) return rc;
+  if (iters < 1 || warmup < 0 || !out_ms) return fail(c, PASS_EINVAL, "bad argument");
+  const int k = c->cfg.k;
+  for (int b = 0; b < n_slots; ++b) {
+    if (c->slots[slots[b]].kv_len + 1 + k > c->cfg.max_seq_len) return fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]);
+    if ((rc = ensure_pages(c, slots[b], c->slots[slots[b]].kv_len + 1 + k))) return rc;
+  }
+  if ((rc = set_step_slots(c, slots, n_slots))) return rc;
+  pass_sampling sp = {0.f, 0, 0};
+  for (int i = 0; i < warmup + iters; ++i) {
+    if (i == warmup) HIP_TRY(c, hipEventRecord(c->ev[0], c->stream));
+    if ((rc = issue_draft(c, slots, n_slots, &sp, 0))) return rc;
+  }
+  HIP_TRY(c, hipEventRecord(c->ev[1], c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  float ms = 0;
+  HIP_TRY(c, hipEventElapsedTime(&ms, c->ev[0], c->ev[1]));
+  *out_ms = (double)ms / iters;
+  return PASS_OK;
+}
+
+const char *pass_last_error(pass_ctx *c) { return c ? c->err.c_str() : g_create_error.c_str(); }
+
+void pass_destroy(pass_ctx *c) {
+  if (!c) return;
+  (void)hipStreamSynchronize(c->stream);
+  for (auto &ev : c->ev) (void)hipEventDestroy(ev);
+  if (c->report_host) (void)hipHostFree(c->report_host);
+  if (c->block_table_host) (void)hipHostFree(c->block_table_host);
+  delete c;
+}
+
+}  // extern "C"

@@ -1,0 +1,104 @@
+// Internal declarations shared by the HIP translation units of libpass_hip.so (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pass.h"
+
+namespace pass {
+
+enum StepMode { MODE_PREFILL = 0, MODE_DRAFT = 1, MODE_VERIFY = 2 };
+enum Purpose { PURPOSE_DRAFT = 0, PURPOSE_ACCEPT = 1, PURPOSE_RESIDUAL = 2, PURPOSE_BONUS = 3 };
+
+constexpr int kMaxK = PASS_MAX_K;
+constexpr int kMaxRows = PASS_MAX_ROWS;
+constexpr int kAttnRowsPerGroup = 8;  // queries one attention workgroup carries in registers
+constexpr int kMaxSplits = 32;
+
+// bfloat16 storage type: raw bits, converted with shifts (round-to-nearest-even on store)
+struct bf16_t {
+  uint16_t bits;
+};
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float load_f(const float *p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_f(const bf16_t *p, size_t i) { return bf16_to_f32(p[i].bits); }
+__device__ __forceinline__ void store_f(float *p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_f(bf16_t *p, size_t i, float v) { p[i].bits = f32_to_bf16(v); }
+
+// Everything a kernel needs to find its way around the arena.  Passed by value.
+struct Params {
+  // shape
+  int L, d, H, hd, D, F, V, k;
+  int max_slots, max_seq_len, page_size, page_shift, n_pages, pages_per_seq;
+  int gen_cap;
+  float eps, rope_base;
+  // per-slot state (device), indexed by slot
+  int32_t *kv_len, *pending, *first, *drafts /*[slot][kMaxK]*/, *n_gen, *n_acc, *frozen, *gen_limit;
+  uint32_t *iter, *seq_id;
+  int32_t *last_out;  // [slot][kMaxK+1]: accepted drafts then the final token of the last verify
+  int32_t *gen;       // [slot][gen_cap]: every generated token since the prefill
+  float *logz_d, *logz_p;  // [slot][kMaxK+1]: ln sum exp(logit/T) of each draft / verify row
+  int32_t *argmax_p;       // [slot][kMaxK+1]
+  int32_t *fallbacks;      // [1]: residual numerically empty after a reject
+  int32_t *block_table;    // [slot][pages_per_seq]
+  float *draft_logits, *verify_logits;  // [slot][1+k][V]
+  // per-step tables (device)
+  int32_t *step_slots;   // [B]
+  int32_t *prefill_ids;  // [R]
+  int32_t *row_pos, *row_slot, *row_out;  // [M]
+  float *rope_cos, *rope_sin;             // [M][hd/2]
+  // workspaces
+  float *h;        // [M][d]   residual stream
+  float *xn;       // [M][d]
+  float *qkv;      // [M][3D]  q | k | v
+  float *attn;     // [M][D]
+  float *gu;       // [M][2F]  gate | up
+  float *act;      // [M][F]
+  uint16_t *attn_bf16;  // [M][D]   matrix-core path
+  uint16_t *act_bf16;   // [M][F]
+  float *part_acc, *part_m, *part_l;  // attention partials [M][H][S][hd], [M][H][S]
+  // K/V pools: [layer][page][head][page_size][hd] in the model's storage type
+  void *k_pool, *v_pool;
+};
+
+__device__ __forceinline__ size_t kv_offset(const Params &p, int layer, int slot, int pos, int head) {
+  int page = p.block_table[(size_t)slot * p.pages_per_seq + (pos >> p.page_shift)];
+  int off = pos & (p.page_size - 1);
+  return ((((size_t)layer * p.n_pages + page) * p.H + head) * p.page_size + off) * (size_t)p.hd;
+}
+
+struct SampleArgs {
+  float temperature;
+  uint32_t seed_lo, seed_hi;
+  int commit;  // 0: compute but leave the sequence state untouched (timing replays)
+};
+
+// ---- launchers (each checks nothing but launches; shapes are validated by the caller) ----
+// generic path (any storage type, fp32 activations)
+void launch_assemble(const Params &p, int dtype, const void *tok_emb, const void *lookahead, int mode, int B,
+                     int R, hipStream_t s);
+void launch_rmsnorm(const Params &p, int dtype, const float *x, const void *gain, float *out, int M, hipStream_t s);
+void launch_gemm_generic(int dtype, const float *X, const void *W, float *out, int M, int N, int K, int ldc,
+                         const int32_t *rowmap, int accumulate, hipStream_t s);
+void launch_rope_kv(const Params &p, int dtype, int layer, int M, hipStream_t s);
+void launch_silu_mul(const Params &p, int M, hipStream_t s);
+// attention (both paths).  out_bf16 != 0 writes p.attn_bf16, else p.attn
+void launch_attention(const Params &p, int dtype, int layer, int B, int R, int n_splits, int out_bf16,
+                      hipStream_t s);
+// sampling epilogues (both paths)
+void launch_draft_epilogue(const Params &p, const SampleArgs &a, int B, int R, hipStream_t s);
+void launch_verify_epilogue(const Params &p, const SampleArgs &a, int B, int R, hipStream_t s);
+void launch_poke(int32_t *const *ptrs, const int32_t *vals, int n, hipStream_t s);
+void launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t s);
+
+// matrix-core path (bf16, 16x32 weight tiles)
+void launch_pack_tiles(const uint16_t *src, uint16_t *dst, int N, int K, int n_src_rows_offset, hipStream_t s);
+
+}  // namespace pass

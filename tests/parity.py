@@ -1,0 +1,146 @@
+"""Helpers that compare the HIP path with the CPU oracle on the same seeded inputs.
+
+Decisions (token ids, accept bits) are compared bit-exactly wherever the oracle's decision is
+stable under the measured logit difference: for a step whose GPU logits differ from the
+oracle's by at most e per element, every score of the samplers moves by at most e/T (plus a few
+fp32 rounding steps of the exp/log the kernels evaluate), and the oracle reports whether its
+winner can change under such a move.  Unstable decisions are counted, never silently passed.
+"""
+import numpy as np
+
+import pass_oracle as O
+
+F32_ARITH = 3e-5  # fp32 exp/log/ln-sum-exp noise on scores of magnitude <~ 30
+
+LOGIT_TOL = {0: 1e-4, 1: 2e-2}  # per row: max|diff| / max|logit|, fp32 / bf16 models
+
+
+def logits_error(gpu, ref, tol, what=""):
+    """Assert per-row max|diff| <= tol * max|ref| and return the largest absolute difference."""
+    gpu = np.asarray(gpu, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert gpu.shape == ref.shape
+    assert np.all(np.isfinite(gpu)), f"{what}: non-finite logits"
+    worst = 0.0
+    for r in range(ref.shape[0]):
+        diff = np.abs(gpu[r] - ref[r]).max()
+        scale = np.abs(ref[r]).max()
+        assert diff <= tol * scale, f"{what} row {r}: max|diff| {diff:.3e} > {tol:g} * {scale:.3e}"
+        worst = max(worst, diff)
+    return worst
+
+
+class StepStats:
+    def __init__(self):
+        self.compared = 0
+        self.unstable = 0
+        self.iterations = 0
+        self.accepted = 0
+        self.diverged = False
+        self.max_rel_err = 0.0
+
+    def __repr__(self):
+        return (f"iters={self.iterations} decisions={self.compared} unstable={self.unstable} "
+                f"accepted={self.accepted} diverged={self.diverged} max_rel_err={self.max_rel_err:.2e}")
+
+
+def stepwise_parity(gpu, oseq, slot, seq_id, n_iters, temp, seed, tol, stats=None):
+    """Drive one sequence through draft/verify on both sides, comparing logits and decisions.
+
+    Stops (stats.diverged) when an unstable decision differs; any difference on a stable decision
+    fails.  Returns the stats."""
+    st = stats or StepStats()
+    k = gpu.k
+    inv_t = 1.0 if temp == 0 else 1.0 / temp
+    for it in range(n_iters):
+        kv0 = oseq.kv_len
+        o_first, o_drafts = oseq.draft(temp, seed)
+        g_first, g_drafts = gpu.draft([slot], temp, seed)
+        ol, gl = oseq.logits(0), gpu.get_logits(slot, 0)
+        err_d = logits_error(gl, ol, tol, f"draft it={it}")
+        st.max_rel_err = max(st.max_rel_err, err_d / np.abs(ol).max())
+        tau = err_d * inv_t * 1.01 + (0.0 if temp == 0 else F32_ARITH)
+        if temp == 0 and err_d == 0:
+            tau = 0.0
+        same = True
+        for t in range(k + 1):
+            tok, stable = O.sample_softmax(ol[t], temp, seed, seq_id, it, t, O.DRAFT, tau)
+            o_tok = o_first if t == 0 else o_drafts[t - 1]
+            g_tok = g_first[0] if t == 0 else g_drafts[0, t - 1]
+            assert tok == o_tok
+            st.compared += 1
+            if stable:
+                assert g_tok == tok, f"draft it={it} row {t}: gpu {g_tok} != oracle {tok} on a stable decision"
+            else:
+                st.unstable += 1
+                same &= g_tok == tok
+        assert gpu.seq_len(slot)[0] == kv0 + 1 == oseq.kv_len
+        if not same:
+            st.diverged = True
+            return st
+        o_a, o_out = oseq.verify(temp, seed)
+        g_a, g_out = gpu.verify([slot], temp, seed)
+        pl, gpl = oseq.logits(1), gpu.get_logits(slot, 1)
+        err_v = logits_error(gpl, pl, tol, f"verify it={it}")
+        st.max_rel_err = max(st.max_rel_err, err_v / np.abs(pl).max())
+        tau = max(err_d, err_v) * inv_t * 1.01 + (0.0 if temp == 0 else F32_ARITH)
+        if temp == 0 and err_d == 0 and err_v == 0:
+            tau = 0.0
+        # replay the accept chain with stability flags
+        a = 0
+        ok_so_far = True
+        for t in range(1, k + 1):
+            acc, stable = O.accept(pl[t - 1], ol[t], o_drafts[t - 1], temp, seed, seq_id, it, t, tau)
+            st.compared += 1
+            if not stable:
+                st.unstable += 1
+                ok_so_far = False
+            if not acc:
+                break
+            a += 1
+        assert a == o_a
+        if ok_so_far:
+            assert g_a[0] == a, f"verify it={it}: gpu accepted {g_a[0]}, oracle {a}"
+        elif g_a[0] != a:
+            st.diverged = True
+            return st
+        if a < k:
+            y, stable, _ = O.sample_residual(pl[a], ol[a + 1], temp, seed, seq_id, it, a + 1, tau)
+        else:
+            y, stable = O.sample_softmax(pl[k], temp, seed, seq_id, it, k + 1, O.BONUS, tau)
+        assert y == o_out[-1]
+        st.compared += 1
+        assert np.array_equal(g_out[0, :a], o_out[:a])
+        if stable:
+            assert g_out[0, a] == y, f"verify it={it}: final token gpu {g_out[0, a]} != oracle {y} (a={a})"
+        else:
+            st.unstable += 1
+            if g_out[0, a] != y:
+                st.diverged = True
+                return st
+        assert np.all(g_out[0, a + 1:] == -1)
+        assert gpu.seq_len(slot)[0] == kv0 + 2 + a == oseq.kv_len
+        st.iterations += 1
+        st.accepted += a
+    return st
+
+
+def generate_parity(gpu_tokens, oracle_tokens, oracle_acc, oracle_stable):
+    """Free-running comparison.  Returns the identical prefix length; a mismatch inside an
+    iteration whose decisions the oracle reports stable (and with no unstable iteration before
+    it) fails."""
+    n = len(oracle_tokens)
+    assert len(gpu_tokens) == n
+    if np.array_equal(gpu_tokens, oracle_tokens):
+        return n
+    first_bad = int(np.nonzero(np.asarray(gpu_tokens) != np.asarray(oracle_tokens))[0][0])
+    pos = 0
+    for it, a in enumerate(oracle_acc):
+        end = pos + a + 2
+        if not oracle_stable[it]:
+            return first_bad  # an unstable decision at or before the mismatch: allowed to part ways
+        if first_bad < end:
+            raise AssertionError(f"token {first_bad} differs inside iteration {it}, "
+                                 "all of whose decisions are stable")
+        pos = end
+    raise AssertionError("mismatch beyond the recorded iterations")

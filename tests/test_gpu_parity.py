@@ -1,0 +1,169 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+import parity
+import pass_oracle as O
+from paper_2311_13581_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TINY = synth.WORKLOADS["tiny_fp32_greedy"]
+TINY_BF16 = synth.scaled(TINY, dtype=synth.BF16)
+
+
+def _gpu(shape, W, k, max_slots=1, max_seq_len=256, page_size=16, options=None):
+    from paper_2311_13581_amd import binding
+    g = binding.Pass(binding.make_config(shape, k, max_slots, max_seq_len, page_size), options)
+    g.load_weights(W)
+    return g
+
+
+def _both(w, k, seed=None, scale=None, **kw):
+    seed = w.seed if seed is None else seed
+    W = synth.make_weights(w.shape, seed, max(k, 1), w.lm_head_scale if scale is None else scale)
+    return _gpu(w.shape, W, k, **kw), O.Model(w.shape, W, k), W
+
+
+@pytest.mark.parametrize("w,temp", [(TINY, 0.0), (TINY, 1.0), (TINY_BF16, 0.0), (TINY_BF16, 1.0)],
+                         ids=["fp32-greedy", "fp32-t1", "bf16-greedy", "bf16-t1"])
+def test_tiny_stepwise(w, temp):
+    """Configuration 1 (and its bf16 twin): logits of every call and every decision, 24 iterations."""
+    g, m, _ = _both(w, w.k)
+    prompt = synth.make_prompts(w)[0]
+    seed = synth.sampling_seed(w)
+    g.prefill(0, prompt, seq_id=7)
+    s = m.sequence(256, seq_id=7)
+    s.prefill(prompt)
+    st = parity.stepwise_parity(g, s, 0, 7, 24, temp, seed, parity.LOGIT_TOL[w.shape.dtype])
+    print(st)
+    assert st.iterations >= (24 if w.shape.dtype == synth.F32 else 6)
+    if w.shape.dtype == synth.F32:
+        assert st.max_rel_err < 1e-5 and st.unstable <= 1
+    g.close()
+
+
+@pytest.mark.parametrize("w,temp", [(TINY, 0.0), (TINY, 1.0)], ids=["greedy", "t1"])
+def test_tiny_generate(w, temp):
+    """Configuration 1 end to end: 64 tokens, free running."""
+    g, m, _ = _both(w, w.k)
+    prompt = synth.make_prompts(w)[0]
+    seed = synth.sampling_seed(w)
+    g.prefill(0, prompt, seq_id=0)
+    toks, stats = g.generate([0], 64, temp, seed)
+    s = m.sequence(256, seq_id=0)
+    s.prefill(prompt)
+    tau = 1e-4 * 40.0 / max(temp, 1.0) + parity.F32_ARITH
+    ref, acc, stable = s.generate(64, temp, seed, tau=tau)
+    n_same = parity.generate_parity(toks[0], ref, acc, stable)
+    print("identical prefix", n_same, stats)
+    assert n_same == 64 or not stable.all()
+    assert stats["tokens_out"] == 64 and 2 * stats["iterations"] <= 64 + w.k + 1
+    assert stats["drafts_proposed"] == w.k * stats["iterations"]
+    kv, ng = g.seq_len(0)
+    assert kv == len(prompt) - 1 + ng and ng >= 64
+    g.close()
+
+
+@pytest.mark.parametrize("k", [0, 1, 4, 6])
+def test_lookahead_counts_and_paging(k):
+    """k sweep on the tiny model with 16-position pages and a prompt that is not a multiple of the
+    page, the attention row group or the prefill chunk."""
+    w = synth.scaled(TINY, k=k)
+    g, m, _ = _both(w, k, seed=11)
+    prompt = np.random.default_rng(k).integers(0, w.shape.vocab, 75).astype(np.int32)
+    g.prefill(0, prompt, seq_id=3)
+    s = m.sequence(256, seq_id=3)
+    s.prefill(prompt)
+    st = parity.stepwise_parity(g, s, 0, 3, 10, 0.7, 99, 1e-4)
+    print(st)
+    assert st.iterations == 10
+    g.close()
+
+
+def test_high_temperature_accepts_drafts():
+    """Flat distributions (high temperature) make drafts get accepted: the accept, partial-accept
+    and all-accepted (extra token) branches all run under bit-exact comparison."""
+    w = synth.scaled(TINY, k=3)
+    g, m, _ = _both(w, 3, seed=5, scale=1.0)
+    total = parity.StepStats()
+    for sid in range(4):
+        prompt = np.random.default_rng(sid).integers(0, w.shape.vocab, 9 + sid).astype(np.int32)
+        g.prefill(0, prompt, seq_id=sid)
+        s = m.sequence(256, seq_id=sid)
+        s.prefill(prompt)
+        parity.stepwise_parity(g, s, 0, sid, 12, 3.0, 1234, 1e-4, total)
+    print(total)
+    assert total.accepted >= 10 and total.iterations >= 40
+
+
+def test_batch_of_ragged_slots_matches_single_runs():
+    """Results of a slot do not depend on which other slots share the batch (per-sequence
+    counters), with ragged prompt lengths; and they match the oracle."""
+    w = synth.scaled(TINY, k=2)
+    W = synth.make_weights(w.shape, 21, 2, 6.0)
+    lens = [5, 37, 18]
+    prompts = [np.random.default_rng(i).integers(0, w.shape.vocab, n).astype(np.int32) for i, n in enumerate(lens)]
+    g = _gpu(w.shape, W, 2, max_slots=3)
+    for i, p in enumerate(prompts):
+        g.prefill(i, p, seq_id=100 + i)
+    toks, stats = g.generate([0, 1, 2], 30, 1.0, 555)
+    for i, p in enumerate(prompts):
+        g.prefill(i, p, seq_id=100 + i)
+        single, _ = g.generate([i], 30, 1.0, 555)
+        assert np.array_equal(single[0], toks[i]), f"slot {i} depends on its batch"
+    m = O.Model(w.shape, W, 2)
+    for i, p in enumerate(prompts):
+        s = m.sequence(256, seq_id=100 + i)
+        s.prefill(p)
+        ref, acc, stable = s.generate(30, 1.0, 555, tau=1e-4 * 40 + parity.F32_ARITH)
+        parity.generate_parity(toks[i], ref, acc, stable)
+    g.close()
+
+
+def test_gpu_greedy_pass_equals_gpu_autoregressive():
+    """Property that holds at any size: greedy PaSS (k=4) and greedy k=0 decoding give the same
+    tokens on the GPU path."""
+    w = synth.scaled(TINY_BF16, k=4)
+    W = synth.make_weights(w.shape, 8, 4, 8.0)
+    prompt = np.random.default_rng(3).integers(0, w.shape.vocab, 40).astype(np.int32)
+    outs = []
+    for k in (4, 0):
+        g = _gpu(w.shape, W, k)
+        g.prefill(0, prompt)
+        outs.append(g.generate([0], 48, 0.0, 0)[0][0])
+        g.close()
+    assert np.array_equal(outs[0], outs[1])
+
+
+def test_error_paths():
+    from paper_2311_13581_amd import binding
+    w = synth.scaled(TINY, k=2)
+    W = synth.make_weights(w.shape, 1, 2, 1.0)
+    g = _gpu(w.shape, W, 2, max_slots=2, max_seq_len=32)
+    with pytest.raises(binding.PassError) as e:
+        g.draft([0], 1.0, 1)  # not prefilled
+    assert e.value.code == -2
+    with pytest.raises(binding.PassError) as e:
+        g.prefill(5, [1, 2, 3])
+    assert e.value.code == -1
+    with pytest.raises(binding.PassError) as e:
+        g.prefill(0, [1, 2, 9999])
+    assert e.value.code == -1
+    with pytest.raises(binding.PassError) as e:
+        g.prefill(0, np.arange(40) % 100)  # longer than max_seq_len
+    assert e.value.code == -3
+    g.prefill(0, [1, 2, 3])
+    with pytest.raises(binding.PassError) as e:
+        g.verify([0], 1.0, 1)  # verify before draft
+    assert e.value.code == -2
+    with pytest.raises(binding.PassError) as e:
+        g.draft([0, 0], 1.0, 1)
+    assert e.value.code == -1
+    with pytest.raises(binding.PassError) as e:
+        g.generate([0], 64, 1.0, 1)  # runs out of positions
+    assert e.value.code == -3
+    g.prefill(0, [1, 2, 3])  # the slot is usable again after the failure
+    g.draft([0], 0.0, 1)
+    g.verify([0], 0.0, 1)
+    g.close()
