@@ -36,92 +36,103 @@ class StepStats:
         self.unstable = 0
         self.iterations = 0
         self.accepted = 0
-        self.diverged = False
+        self.resyncs = 0
         self.max_rel_err = 0.0
 
     def __repr__(self):
         return (f"iters={self.iterations} decisions={self.compared} unstable={self.unstable} "
-                f"accepted={self.accepted} diverged={self.diverged} max_rel_err={self.max_rel_err:.2e}")
+                f"accepted={self.accepted} resyncs={self.resyncs} max_rel_err={self.max_rel_err:.2e}")
 
 
-def stepwise_parity(gpu, oseq, slot, seq_id, n_iters, temp, seed, tol, stats=None):
-    """Drive one sequence through draft/verify on both sides, comparing logits and decisions.
-
-    Stops (stats.diverged) when an unstable decision differs; any difference on a stable decision
-    fails.  Returns the stats."""
-    st = stats or StepStats()
+def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st):
+    """One draft + verify on both sides.  Returns (tokens the oracle added, in_sync)."""
     k = gpu.k
     inv_t = 1.0 if temp == 0 else 1.0 / temp
-    for it in range(n_iters):
-        kv0 = oseq.kv_len
-        o_first, o_drafts = oseq.draft(temp, seed)
-        g_first, g_drafts = gpu.draft([slot], temp, seed)
-        ol, gl = oseq.logits(0), gpu.get_logits(slot, 0)
-        err_d = logits_error(gl, ol, tol, f"draft it={it}")
-        st.max_rel_err = max(st.max_rel_err, err_d / np.abs(ol).max())
-        tau = err_d * inv_t * 1.01 + (0.0 if temp == 0 else F32_ARITH)
-        if temp == 0 and err_d == 0:
-            tau = 0.0
-        same = True
-        for t in range(k + 1):
-            tok, stable = O.sample_softmax(ol[t], temp, seed, seq_id, it, t, O.DRAFT, tau)
-            o_tok = o_first if t == 0 else o_drafts[t - 1]
-            g_tok = g_first[0] if t == 0 else g_drafts[0, t - 1]
-            assert tok == o_tok
-            st.compared += 1
-            if stable:
-                assert g_tok == tok, f"draft it={it} row {t}: gpu {g_tok} != oracle {tok} on a stable decision"
-            else:
-                st.unstable += 1
-                same &= g_tok == tok
-        assert gpu.seq_len(slot)[0] == kv0 + 1 == oseq.kv_len
-        if not same:
-            st.diverged = True
-            return st
-        o_a, o_out = oseq.verify(temp, seed)
-        g_a, g_out = gpu.verify([slot], temp, seed)
-        pl, gpl = oseq.logits(1), gpu.get_logits(slot, 1)
-        err_v = logits_error(gpl, pl, tol, f"verify it={it}")
-        st.max_rel_err = max(st.max_rel_err, err_v / np.abs(pl).max())
-        tau = max(err_d, err_v) * inv_t * 1.01 + (0.0 if temp == 0 else F32_ARITH)
-        if temp == 0 and err_d == 0 and err_v == 0:
-            tau = 0.0
-        # replay the accept chain with stability flags
-        a = 0
-        ok_so_far = True
-        for t in range(1, k + 1):
-            acc, stable = O.accept(pl[t - 1], ol[t], o_drafts[t - 1], temp, seed, seq_id, it, t, tau)
-            st.compared += 1
-            if not stable:
-                st.unstable += 1
-                ok_so_far = False
-            if not acc:
-                break
-            a += 1
-        assert a == o_a
-        if ok_so_far:
-            assert g_a[0] == a, f"verify it={it}: gpu accepted {g_a[0]}, oracle {a}"
-        elif g_a[0] != a:
-            st.diverged = True
-            return st
-        if a < k:
-            y, stable, _ = O.sample_residual(pl[a], ol[a + 1], temp, seed, seq_id, it, a + 1, tau)
-        else:
-            y, stable = O.sample_softmax(pl[k], temp, seed, seq_id, it, k + 1, O.BONUS, tau)
-        assert y == o_out[-1]
+    kv0 = oseq.kv_len
+    o_first, o_drafts = oseq.draft(temp, seed)
+    g_first, g_drafts = gpu.draft([slot], temp, seed)
+    ol, gl = oseq.logits(0), gpu.get_logits(slot, 0)
+    err_d = logits_error(gl, ol, tol, f"draft it={it}")
+    st.max_rel_err = max(st.max_rel_err, err_d / np.abs(ol).max())
+    tau = err_d * inv_t * 1.01 + (0.0 if temp == 0 else F32_ARITH)
+    same = True
+    for t in range(k + 1):
+        tok, stable = O.sample_softmax(ol[t], temp, seed, seq_id, it, t, O.DRAFT, tau)
+        o_tok = o_first if t == 0 else o_drafts[t - 1]
+        g_tok = g_first[0] if t == 0 else g_drafts[0, t - 1]
+        assert tok == o_tok
         st.compared += 1
-        assert np.array_equal(g_out[0, :a], o_out[:a])
         if stable:
-            assert g_out[0, a] == y, f"verify it={it}: final token gpu {g_out[0, a]} != oracle {y} (a={a})"
+            assert g_tok == tok, f"draft it={it} row {t}: gpu {g_tok} != oracle {tok} on a stable decision"
         else:
             st.unstable += 1
-            if g_out[0, a] != y:
-                st.diverged = True
-                return st
-        assert np.all(g_out[0, a + 1:] == -1)
-        assert gpu.seq_len(slot)[0] == kv0 + 2 + a == oseq.kv_len
-        st.iterations += 1
-        st.accepted += a
+            same &= g_tok == tok
+    assert gpu.seq_len(slot)[0] == kv0 + 1 == oseq.kv_len
+    o_a, o_out = oseq.verify(temp, seed)
+    added = [o_first] + [int(x) for x in o_out]
+    if not same:
+        return added, False
+    g_a, g_out = gpu.verify([slot], temp, seed)
+    pl, gpl = oseq.logits(1), gpu.get_logits(slot, 1)
+    err_v = logits_error(gpl, pl, tol, f"verify it={it}")
+    st.max_rel_err = max(st.max_rel_err, err_v / np.abs(pl).max())
+    tau = max(err_d, err_v) * inv_t * 1.01 + (0.0 if temp == 0 else F32_ARITH)
+    a = 0
+    chain_stable = True
+    for t in range(1, k + 1):  # replay the accept chain with stability flags
+        acc, stable = O.accept(pl[t - 1], ol[t], o_drafts[t - 1], temp, seed, seq_id, it, t, tau)
+        st.compared += 1
+        if not stable:
+            st.unstable += 1
+            chain_stable = False
+        if not acc:
+            break
+        a += 1
+    assert a == o_a
+    if chain_stable:
+        assert g_a[0] == a, f"verify it={it}: gpu accepted {g_a[0]}, oracle {a}"
+    elif g_a[0] != a:
+        return added, False
+    if a < k:
+        y, stable, _ = O.sample_residual(pl[a], ol[a + 1], temp, seed, seq_id, it, a + 1, tau)
+    else:
+        y, stable = O.sample_softmax(pl[k], temp, seed, seq_id, it, k + 1, O.BONUS, tau)
+    assert y == o_out[-1]
+    st.compared += 1
+    assert np.array_equal(g_out[0, :a], o_out[:a])
+    if stable:
+        assert g_out[0, a] == y, f"verify it={it}: final token gpu {g_out[0, a]} != oracle {y} (a={a})"
+    else:
+        st.unstable += 1
+        if g_out[0, a] != y:
+            return added, False
+    assert np.all(g_out[0, a + 1:] == -1)
+    assert gpu.seq_len(slot)[0] == kv0 + 2 + a == oseq.kv_len
+    st.accepted += a
+    return added, True
+
+
+def stepwise_parity(gpu, omodel, slot, seq_id, prompt, n_iters, temp, seed, tol, max_len=256, stats=None):
+    """Drive one sequence through draft / verify on both sides, comparing the logits of every
+    call and every decision.  A difference on a stable decision fails.  When an unstable decision
+    differs, both sides restart from the oracle's token history (a resync, counted)."""
+    st = stats or StepStats()
+    hist = [int(t) for t in prompt]
+    done = 0
+    while done < n_iters:
+        gpu.prefill(slot, hist, seq_id=seq_id)
+        oseq = omodel.sequence(max_len, seq_id=seq_id)
+        oseq.prefill(hist)
+        it = 0
+        while done < n_iters:
+            added, in_sync = _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st)
+            hist += added
+            done += 1
+            it += 1
+            st.iterations += 1
+            if not in_sync:
+                st.resyncs += 1
+                break
     return st
 
 

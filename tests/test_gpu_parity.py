@@ -32,14 +32,13 @@ def test_tiny_stepwise(w, temp):
     g, m, _ = _both(w, w.k)
     prompt = synth.make_prompts(w)[0]
     seed = synth.sampling_seed(w)
-    g.prefill(0, prompt, seq_id=7)
-    s = m.sequence(256, seq_id=7)
-    s.prefill(prompt)
-    st = parity.stepwise_parity(g, s, 0, 7, 24, temp, seed, parity.LOGIT_TOL[w.shape.dtype])
+    st = parity.stepwise_parity(g, m, 0, 7, prompt, 24, temp, seed, parity.LOGIT_TOL[w.shape.dtype])
     print(st)
-    assert st.iterations >= (24 if w.shape.dtype == synth.F32 else 6)
+    assert st.iterations == 24
     if w.shape.dtype == synth.F32:
-        assert st.max_rel_err < 1e-5 and st.unstable <= 1
+        assert st.max_rel_err < 1e-5 and st.unstable <= 1 and st.resyncs == 0
+    else:
+        assert st.resyncs <= 12
     g.close()
 
 
@@ -72,12 +71,9 @@ def test_lookahead_counts_and_paging(k):
     w = synth.scaled(TINY, k=k)
     g, m, _ = _both(w, k, seed=11)
     prompt = np.random.default_rng(k).integers(0, w.shape.vocab, 75).astype(np.int32)
-    g.prefill(0, prompt, seq_id=3)
-    s = m.sequence(256, seq_id=3)
-    s.prefill(prompt)
-    st = parity.stepwise_parity(g, s, 0, 3, 10, 0.7, 99, 1e-4)
+    st = parity.stepwise_parity(g, m, 0, 3, prompt, 10, 0.7, 99, 1e-4)
     print(st)
-    assert st.iterations == 10
+    assert st.iterations == 10 and st.resyncs == 0
     g.close()
 
 
@@ -89,12 +85,9 @@ def test_high_temperature_accepts_drafts():
     total = parity.StepStats()
     for sid in range(4):
         prompt = np.random.default_rng(sid).integers(0, w.shape.vocab, 9 + sid).astype(np.int32)
-        g.prefill(0, prompt, seq_id=sid)
-        s = m.sequence(256, seq_id=sid)
-        s.prefill(prompt)
-        parity.stepwise_parity(g, s, 0, sid, 12, 3.0, 1234, 1e-4, total)
+        parity.stepwise_parity(g, m, 0, sid, prompt, 12, 3.0, 1234, 1e-4, stats=total)
     print(total)
-    assert total.accepted >= 10 and total.iterations >= 40
+    assert total.accepted >= 10 and total.iterations == 48 and total.resyncs <= 1
 
 
 def test_batch_of_ragged_slots_matches_single_runs():
