@@ -1,0 +1,196 @@
+#!/usr/bin/env python3
+"""Benchmark of the PaSS decode path on one MI355X.
+
+A "step" is one iteration of Algorithm 1: a drafting call on (last token, k look-ahead rows), its
+sampling epilogue, a validation call on the drafted block and the accept / reject epilogue, for
+every sequence of the batch.  Inputs (weights, prompts' K/V) are resident in HBM before the timed
+region starts.  Prints ONE JSON line.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--k K] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes_per_call(shape, k, ctx_lens):
+    """Bytes one (1+k)-row model call must move: every streamed parameter once, the cached K/V of
+    every sequence once, the K/V rows written, the fp32 logits."""
+    esz = 2 if shape.dtype == 1 else 4
+    M = (1 + k) * len(ctx_lens)
+    kv_tok = 2 * shape.n_layers * shape.n_heads * shape.head_dim * esz
+    return shape.n_params_streamed * esz + kv_tok * sum(ctx_lens) + kv_tok * M + 4 * M * shape.vocab
+
+
+def gate_up_kernel_bytes(shape, M):
+    """Algorithmic bytes of one launch of the dominant kernel (gate/up GEMM + SiLU*mul): both
+    weight matrices once, the M input rows (bf16), the M activation rows written (bf16)."""
+    esz = 2 if shape.dtype == 1 else 4
+    return 2 * shape.d_ffn * shape.d_model * esz + M * shape.d_model * 2 + M * shape.d_ffn * 2
+
+
+def device_weights(torch, shape, k, lm_head_scale, seed):
+    """Random-init N(0, 0.02) model generated on the device (same recipe as the synthetic
+    generator, different random stream): keeps the 13 GB off the host."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    dt = torch.bfloat16 if shape.dtype == 1 else torch.float32
+
+    def normal(rows, cols, scale=1.0):
+        return (torch.randn(rows, cols, generator=g, device="cuda", dtype=torch.float32) * (0.02 * scale)).to(dt)
+
+    d, f, v, hd = shape.d_model, shape.d_ffn, shape.vocab, shape.n_heads * shape.head_dim
+    ones = torch.ones(d, device="cuda", dtype=dt)
+    W = {"tok_emb": normal(v, d), "lm_head": normal(v, d, lm_head_scale), "final_norm": ones,
+         "lookahead": normal(max(k, 1), d)[:k].contiguous()}
+    for name, (r, c) in {"wq": (hd, d), "wk": (hd, d), "wv": (hd, d), "wo": (d, hd), "w_gate": (f, d),
+                         "w_up": (f, d), "w_down": (d, f)}.items():
+        W[name] = [normal(r, c) for _ in range(shape.n_layers)]
+    W["attn_norm"] = [ones] * shape.n_layers
+    W["ffn_norm"] = [ones] * shape.n_layers
+    return W
+
+
+def cpu_baseline(w, k, budget_s=20.0):
+    """The CPU oracle as it stands, timed on this machine's host cores on a bounded sample of the
+    same workload: the same layer shapes with 2 and with 1 of the layers (the difference gives the
+    per-layer cost), short context; scaled to the full depth."""
+    sys.path.insert(0, os.path.join(ROOT, "oracle"))
+    import numpy as np
+    import pass_oracle as O
+    from paper_2311_13581_amd import synth
+
+    cores = len(os.sched_getaffinity(0))
+    threads = int(os.environ.get("OMP_NUM_THREADS", cores))
+    ctx = 16
+    per_iter = {}
+    for nl in (1, 2):
+        shp = synth.scaled(w, n_layers=nl).shape
+        W = synth.make_weights(shp, w.seed, max(k, 1), w.lm_head_scale)
+        seq = O.Model(shp, W, k).sequence(ctx + 8 * (k + 2) + 8)
+        seq.prefill(np.arange(ctx, dtype=np.int32) % shp.vocab)
+        seq.draft(w.temperature, 1)
+        seq.verify(w.temperature, 1)  # warm
+        t0 = time.perf_counter()
+        n = 0
+        while n < 2 or (time.perf_counter() - t0 < budget_s / 4 and n < 8):
+            seq.draft(w.temperature, 1)
+            seq.verify(w.temperature, 1)
+            n += 1
+        per_iter[nl] = (time.perf_counter() - t0) / n
+    layer = per_iter[2] - per_iter[1]
+    full = per_iter[1] - layer + w.shape.n_layers * layer
+    toks = 2.0 * w.batch / full if w.batch == 1 else None
+    return {"value": toks if toks else 2.0 / full, "unit": "tokens/s", "cores": min(cores, threads), "kind": "oracle",
+            "sample": f"oracle PaSS iterations (k={k}, batch 1, context {ctx}) on the workload's layer shapes with 1 and "
+                      f"2 layers; per-layer cost scaled to {w.shape.n_layers} layers; {full * 1e3:.0f} ms per "
+                      "iteration estimated, 2 tokens per iteration"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=64)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="7b_k4_greedy")
+    ap.add_argument("--k", type=int, default=None)
+    ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (not a valid bench line)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--path", type=int, default=0, help="1 = force the generic kernels")
+    ap.add_argument("--graph", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the decode path shards by sequence; no multi-GPU "
+              "figure exists); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2311_13581_amd import binding, synth
+
+    w = synth.WORKLOADS[args.workload]
+    if args.layers:
+        w = synth.scaled(w, n_layers=args.layers)
+    k = w.k if args.k is None else args.k
+    shape = w.shape
+    prompts = synth.make_prompts(w)
+    total_iters = args.steps + args.warmup + 8
+    max_len = max(len(p) for p in prompts) + (k + 2) * total_iters + k + 2
+    g = binding.Pass(binding.make_config(shape, k, w.batch, max_len, 64), {"path": args.path, "graph": args.graph})
+    W = device_weights(torch, shape, k, w.lm_head_scale, w.seed)
+    g.load_weights(W)
+    del W
+    torch.cuda.empty_cache()
+    for i, p in enumerate(prompts):
+        g.prefill(i, p, seq_id=i)
+    slots = list(range(w.batch))
+    seed = synth.sampling_seed(w)
+
+    g.run_iterations(slots, args.warmup, w.temperature, seed)
+    ctx0 = [g.seq_len(s)[0] for s in slots]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    st = g.run_iterations(slots, args.steps, w.temperature, seed)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ctx1 = [g.seq_len(s)[0] for s in slots]
+
+    M = (1 + k) * w.batch
+    ctx_mid = [(a + b) / 2 for a, b in zip(ctx0, ctx1)]
+    call_bytes = algorithmic_bytes_per_call(shape, k, ctx_mid)
+    n_calls = args.steps  # per kind
+    draft_ms = st["draft_ms"] / n_calls
+    verify_ms = st["verify_ms"] / n_calls
+    step_gbs = call_bytes / ((draft_ms + verify_ms) / 2 * 1e-3) / 1e9
+
+    # dominant kernel, timed live with HIP events on the library's stream
+    g.set_option("kernel_timing", 1)
+    g.run_iterations(slots, 4, w.temperature, seed)
+    kms, kn = g.kernel_time()
+    g.set_option("kernel_timing", 0)
+    k_avg_s = kms / max(kn, 1) * 1e-3
+    k_bytes = gate_up_kernel_bytes(shape, M)
+    achieved = k_bytes / k_avg_s / 1e9
+
+    out = {
+        "metric": "generated tokens/s + (1+k)-token step HBM GB/s vs peak, 7B-shaped bf16, k=4",
+        "value": st["tokens_out"] / dt,
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if shape.dtype == 1 else "f32",
+        "data": "synthetic",
+        "config": {"workload": w.name, "k": k, "batch": w.batch, "prompt_len": [len(p) for p in prompts],
+                   "n_layers": shape.n_layers, "d_model": shape.d_model, "vocab": shape.vocab,
+                   "temperature": w.temperature, "context_during_timing": [min(ctx0), max(ctx1)],
+                   "graph": args.graph, "path": "generic" if args.path else "auto"},
+        "draft_call_ms": draft_ms,
+        "verify_call_ms": verify_ms,
+        "acceptance_rate": st["drafts_accepted"] / max(1, st["drafts_proposed"]),
+        "tokens_per_iteration": st["tokens_out"] / max(1, st["iterations"]),
+        "step_hbm": {"algorithmic_bytes_per_call": call_bytes, "achieved_GBps": step_gbs,
+                     "frac_of_peak": step_gbs / HBM_PEAK_GBS},
+        "roofline": {"bound": "hbm", "kernel": "gate_up_gemm_silu", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "bytes_per_launch": k_bytes, "avg_launch_us": k_avg_s * 1e6, "launches_timed": kn},
+    }
+    g.close()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, k)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -138,6 +138,12 @@ int pass_verify(pass_ctx *ctx, const int32_t *slots, int n_slots, const pass_sam
 int pass_generate(pass_ctx *ctx, const int32_t *slots, int n_slots, int max_new,
                   const pass_sampling *sp, int32_t *out_tokens, pass_stats *out_stats);
 
+/* The body of Algorithm 1's loop exactly n_iters times for a batch of slots (no length target):
+ * the serving-loop primitive.  Tokens accumulate in the per-slot token buffer; out_stats (may be
+ * NULL) counts them.  Errors: PASS_ECAPACITY when a slot cannot take another iteration. */
+int pass_run_iterations(pass_ctx *ctx, const int32_t *slots, int n_slots, int n_iters,
+                        const pass_sampling *sp, pass_stats *out_stats);
+
 /* Parity hook: fp32 logits [(1+k) * vocab] of the slot's last drafting (which = 0) or
  * validation (which = 1) call, copied to host memory. */
 int pass_get_logits(pass_ctx *ctx, int slot, int which, float *out);
@@ -145,8 +151,10 @@ int pass_get_logits(pass_ctx *ctx, int slot, int which, float *out);
 /* kv_len and number of generated tokens of a slot (either pointer may be NULL). */
 int pass_seq_len(pass_ctx *ctx, int slot, int32_t *kv_len, int32_t *n_generated);
 
-/* Options: "graph" (1 = replay the step as a HIP graph, default 0 until captured paths are
- * enabled), "path" (0 = auto, 1 = force the generic kernels).  Unknown names: PASS_EINVAL. */
+/* Options: "graph" (1 = replay the step as a HIP graph), "path" (0 = auto, 1 = force the generic
+ * kernels; before pass_load_weights), "kernel_timing" (1 = bracket every launch of the dominant
+ * kernel, the gate/up GEMM, with HIP events on the context's stream and synchronise after each
+ * model call; setting it resets the counters).  Unknown names: PASS_EINVAL. */
 int pass_set_option(pass_ctx *ctx, const char *name, int value);
 
 /* Timed replay of one drafting-shaped step on the given slots without changing any sequence
@@ -156,6 +164,10 @@ int pass_time_step(pass_ctx *ctx, const int32_t *slots, int n_slots, int warmup,
                    double *out_ms);
 
 /* Message of the last failure on ctx; ctx == NULL: of the last failed pass_create. */
+/* Sum of the event-measured durations (ms) and the number of launches of the dominant kernel
+ * since "kernel_timing" was last set. */
+int pass_kernel_time(pass_ctx *ctx, double *total_ms, int64_t *launches);
+
 const char *pass_last_error(pass_ctx *ctx);
 void pass_destroy(pass_ctx *ctx);
 

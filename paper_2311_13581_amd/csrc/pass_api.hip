@@ -62,6 +62,11 @@ struct pass_ctx {
   int32_t *report_host = nullptr;       // pinned
   int32_t *block_table_host = nullptr;  // pinned mirror of P.block_table
   hipEvent_t ev[3];
+  // optional timing of the dominant kernel (the gate/up GEMM): one event pair per layer
+  int opt_kernel_timing = 0;
+  std::vector<hipEvent_t> kev;
+  double kernel_ms = 0;
+  int64_t kernel_launches = 0;
   std::string err;
 };
 
@@ -238,6 +243,11 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
   const int dt = c->cfg.dtype, M = B * R;
   hipStream_t s = c->stream;
   const int S = choose_splits(c, B, R, max_keys);
+  const bool timing = c->opt_kernel_timing && mode != MODE_PREFILL;
+  if (timing && c->kev.empty()) {
+    c->kev.resize(2 * P.L);
+    for (auto &e : c->kev) HIP_TRY(c, hipEventCreate(&e));
+  }
   launch_assemble(P, dt, c->tok_emb, c->lookahead, mode, B, R, s);
   for (int l = 0; l < P.L; ++l) {
     const LayerW &w = c->layers[l];
@@ -247,7 +257,9 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
     launch_attention(P, dt, l, B, R, S, 0, s);
     launch_gemm_generic(dt, P.attn, w.wo, P.h, M, P.d, P.D, P.d, nullptr, 1, s);
     launch_rmsnorm(P, dt, P.h, w.ffn_norm, P.xn, M, s);
+    if (timing) HIP_TRY(c, hipEventRecord(c->kev[2 * l], s));
     launch_gemm_generic(dt, P.xn, w.wgu, P.gu, M, 2 * P.F, P.d, 2 * P.F, nullptr, 0, s);
+    if (timing) HIP_TRY(c, hipEventRecord(c->kev[2 * l + 1], s));
     launch_silu_mul(P, M, s);
     launch_gemm_generic(dt, P.act, w.wdown, P.h, M, P.d, P.F, P.d, nullptr, 1, s);
   }
@@ -256,6 +268,15 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
     launch_gemm_generic(dt, P.xn, c->lm_head, logits_base, M, P.V, P.d, P.V, P.row_out, 0, s);
   }
   HIP_TRY(c, hipGetLastError());
+  if (timing) {
+    HIP_TRY(c, hipStreamSynchronize(s));
+    for (int l = 0; l < P.L; ++l) {
+      float ms = 0;
+      HIP_TRY(c, hipEventElapsedTime(&ms, c->kev[2 * l], c->kev[2 * l + 1]));
+      c->kernel_ms += ms;
+      c->kernel_launches += 1;
+    }
+  }
   return PASS_OK;
 }
 
@@ -587,6 +608,56 @@ int pass_generate(pass_ctx *c, const int32_t *slots, int n_slots, int max_new, c
   return rc;
 }
 
+int pass_run_iterations(pass_ctx *c, const int32_t *slots, int n_slots, int n_iters, const pass_sampling *sp,
+                        pass_stats *out_stats) {
+  if (!c) return PASS_EINVAL;
+  int rc;
+  if ((rc = check_slots(c, slots, n_slots, 1))) return rc;
+  if ((rc = check_sampling(c, sp))) return rc;
+  if (n_iters < 0) return fail(c, PASS_EINVAL, "n_iters negative");
+  const int k = c->cfg.k;
+  pass_stats st;
+  memset(&st, 0, sizeof st);
+  if ((rc = set_step_slots(c, slots, n_slots))) return rc;
+  for (int it = 0; it < n_iters; ++it) {
+    for (int b = 0; b < n_slots; ++b) {
+      Slot &s = c->slots[slots[b]];
+      if (s.kv_len + 2 + k > c->cfg.max_seq_len) return fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]);
+      if ((rc = ensure_pages(c, slots[b], s.kv_len + 2 + k))) return rc;
+    }
+    HIP_TRY(c, hipEventRecord(c->ev[0], c->stream));
+    if ((rc = issue_draft(c, slots, n_slots, sp, 1))) return rc;
+    HIP_TRY(c, hipEventRecord(c->ev[1], c->stream));
+    if ((rc = issue_verify(c, slots, n_slots, sp, 1))) return rc;
+    HIP_TRY(c, hipEventRecord(c->ev[2], c->stream));
+    if ((rc = fetch_report(c, n_slots))) return rc;
+    float ms_d = 0, ms_v = 0;
+    HIP_TRY(c, hipEventElapsedTime(&ms_d, c->ev[0], c->ev[1]));
+    HIP_TRY(c, hipEventElapsedTime(&ms_v, c->ev[1], c->ev[2]));
+    st.draft_ms += ms_d;
+    st.verify_ms += ms_v;
+    for (int b = 0; b < n_slots; ++b) {
+      const int32_t *r = c->report_host + b * kReportStride;
+      Slot &s = c->slots[slots[b]];
+      st.iterations += 1;
+      st.drafts_proposed += k;
+      st.drafts_accepted += r[2];
+      st.tokens_out += r[1] - s.n_gen;
+      s.kv_len = r[0];
+      s.n_gen = r[1];
+    }
+  }
+  if (out_stats) *out_stats = st;
+  return PASS_OK;
+}
+
+int pass_kernel_time(pass_ctx *c, double *total_ms, int64_t *launches) {
+  if (!c || !total_ms || !launches) return PASS_EINVAL;
+  *total_ms = c->kernel_ms;
+  *launches = c->kernel_launches;
+  return PASS_OK;
+}
+
 int pass_get_logits(pass_ctx *c, int slot, int which, float *out) {
   if (!c) return PASS_EINVAL;
   if (slot < 0 || slot >= c->cfg.max_slots || !out || (which != 0 && which != 1)) return fail(c, PASS_EINVAL, "bad argument");
@@ -609,6 +680,12 @@ int pass_seq_len(pass_ctx *c, int slot, int32_t *kv_len, int32_t *n_generated) {
 int pass_set_option(pass_ctx *c, const char *name, int value) {
   if (!c || !name) return PASS_EINVAL;
   if (!strcmp(name, "graph")) { c->opt_graph = value; return PASS_OK; }
+  if (!strcmp(name, "kernel_timing")) {
+    c->opt_kernel_timing = value;
+    c->kernel_ms = 0;
+    c->kernel_launches = 0;
+    return PASS_OK;
+  }
   if (!strcmp(name, "path")) {
     if (c->weights_loaded) return fail(c, PASS_ESTATE, "\"path\" must be set before pass_load_weights");
     c->opt_path = value;
@@ -647,6 +724,7 @@ void pass_destroy(pass_ctx *c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->stream);
   for (auto &ev : c->ev) (void)hipEventDestroy(ev);
+  for (auto &ev : c->kev) (void)hipEventDestroy(ev);
   if (c->report_host) (void)hipHostFree(c->report_host);
   if (c->block_table_host) (void)hipHostFree(c->block_table_host);
   delete c;
