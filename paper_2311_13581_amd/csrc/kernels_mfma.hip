@@ -1,0 +1,323 @@
+// Matrix-core path of the (1+k)-row decode step for bf16 models on gfx950.
+//
+// The step is bound by streaming the weights once (Section 2.2 of the paper: a few extra rows
+// cost about as much as one row because decoding is memory-bound).  Every weight matrix is
+// repacked at load time into tiles of 16 output features x 32 input features, stored in the lane
+// order of v_mfma_f32_16x16x32_bf16's A operand, so that one wavefront fetches a tile as 64
+// adjacent 16-byte loads (1 KB, fully coalesced) and a strip of 16 output features is one
+// contiguous run of K/32 KB.  The M <= 64 activation rows are the B operand (rows padded to 16
+// per MFMA; with M = 5 the matrix core still runs far below its rate, the kernel stays bound by
+// HBM).  A workgroup of 16 wavefronts owns one strip (two for gate/up) and splits K among its
+// wavefronts; partial tiles are reduced through LDS in a fixed order (deterministic), and the
+// epilogue is fused:
+//   QKV     : RMSNorm scale, rotary embedding, q to the workspace, K/V rows into the paged cache
+//   RESID   : residual add, bf16 copy of h * gain of the next norm, partial sums of h^2
+//   GATEUP  : RMSNorm scale, silu(gate) * up in bf16
+//   LOGITS  : RMSNorm scale, fp32 logits into the slot's logits rows
+// RMSNorm is folded: the producer stores bf16(h * gain) and per-strip partial sums of h^2; the
+// consumer multiplies its accumulators by rsqrt(mean(h^2) + eps), which commutes with the GEMM.
+#include "pass_internal.h"
+
+namespace pass {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kGemmWaves = 16;
+constexpr int kGemmThreads = kGemmWaves * 64;
+
+// ---------------------------------------------------------------------------------------------
+// Weight repacking: plain [N][K] bf16 -> tiles [strip][K/32][64 lanes][8], lane l of a tile holds
+// row (l % 16), columns (l / 16) * 8 .. + 8 of the tile.  Destination strip = off + stride * s.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void pack_tiles_kernel(const uint4 *src, uint4 *dst, int N, int K,
+                                                         int strip_off, int strip_stride) {
+  const int KT = K / 32;
+  size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;  // one 16-byte chunk each
+  size_t total = (size_t)(N / 16) * KT * 64;
+  if (idx >= total) return;
+  int lane = (int)(idx & 63);
+  size_t tile = idx >> 6;
+  int kt = (int)(tile % KT);
+  int s = (int)(tile / KT);
+  int row = s * 16 + (lane & 15);
+  int col = kt * 32 + (lane >> 4) * 8;
+  size_t dstrip = (size_t)strip_off + (size_t)strip_stride * s;
+  dst[(dstrip * KT + kt) * 64 + lane] = src[((size_t)row * K + col) / 8];
+}
+
+void launch_pack_tiles(const uint16_t *src, uint16_t *dst, int N, int K, int strip_off, int strip_stride,
+                       hipStream_t s) {
+  size_t total = (size_t)(N / 16) * (K / 32) * 64;
+  pack_tiles_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint4 *)src, (uint4 *)dst, N, K,
+                                                                      strip_off, strip_stride);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Row assembly for the matrix-core path: h (fp32), xg = bf16(h * gain of the first norm), partial
+// sums of h^2 (partial 0 carries the whole row, the others are zero), rotary table, row tables.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint16_t *tok_emb,
+                                                            const uint16_t *lookahead, const uint16_t *gain0,
+                                                            int mode, int R) {
+  __shared__ float red[4];
+  int m = blockIdx.x, b = m / R, r = m % R;
+  int slot = p.step_slots[b];
+  int pos = p.kv_len[slot] + r;
+  const uint16_t *src;
+  if (mode == MODE_PREFILL) {
+    src = tok_emb + (size_t)p.prefill_ids[r] * p.d;
+  } else if (r == 0) {
+    src = tok_emb + (size_t)p.pending[slot] * p.d;
+  } else if (mode == MODE_DRAFT) {
+    src = lookahead + (size_t)(r - 1) * p.d;
+  } else {
+    src = tok_emb + (size_t)p.drafts[slot * kMaxK + (r - 1)] * p.d;
+  }
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < p.d; i += 256) {
+    float v = bf16_to_f32(src[i]);
+    p.h[(size_t)m * p.d + i] = v;
+    p.xg[(size_t)m * p.d + i] = f32_to_bf16(v * bf16_to_f32(gain0[i]));
+    ss += v * v;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const int NP = p.d / 16;
+  for (int i = threadIdx.x; i < NP; i += 256)
+    p.ssq[(size_t)i * kMaxRows + m] = (i == 0) ? (red[0] + red[1] + red[2] + red[3]) : 0.f;
+  int half = p.hd / 2;
+  for (int i = threadIdx.x; i < half; i += 256) {
+    double theta = pow((double)p.rope_base, -2.0 * (double)i / (double)p.hd);
+    double sn, cs;
+    sincos((double)pos * theta, &sn, &cs);
+    p.rope_cos[(size_t)m * half + i] = (float)cs;
+    p.rope_sin[(size_t)m * half + i] = (float)sn;
+  }
+  if (threadIdx.x == 0) {
+    p.row_pos[m] = pos;
+    p.row_slot[m] = slot;
+    p.row_out[m] = slot * (1 + p.k) + r;
+  }
+}
+
+void launch_assemble_mfma(const Params &p, const void *tok_emb, const void *lookahead, const void *gain0, int mode,
+                          int B, int R, hipStream_t s) {
+  assemble_mfma_kernel<<<B * R, 256, 0, s>>>(p, (const uint16_t *)tok_emb, (const uint16_t *)lookahead,
+                                             (const uint16_t *)gain0, mode, R);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The streaming GEMM
+// ---------------------------------------------------------------------------------------------
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_GATEUP = 2, EPI_LOGITS = 3 };
+
+struct GemmArgs {
+  const u32x4 *W;       // packed tiles
+  const uint16_t *X;    // [M][K] bf16
+  int M, K;
+  int layer;
+  const uint16_t *gain_next;  // RESID: gain of the norm that follows
+  float *logits;              // LOGITS: base of the [slot][1+k][V] logits
+};
+
+template <int MT, int EPI>
+__global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(Params p, GemmArgs a) {
+  constexpr int NS = (EPI == EPI_GATEUP) ? 2 : 1;
+  constexpr bool NORM = (EPI != EPI_RESID);
+  __shared__ floatx4 red[kGemmWaves][NS][MT][64];
+  __shared__ float red_ss[kGemmWaves][MT][16];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ml = lane & 15, g = lane >> 4;
+  const int KT = a.K >> 5;
+  const int strip0 = blockIdx.x * NS;
+
+  floatx4 acc[NS][MT];
+#pragma unroll
+  for (int s = 0; s < NS; ++s)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) acc[s][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  const u32x4 *wp = a.W + (size_t)strip0 * KT * 64 + lane;
+  const uint16_t *xp[MT];
+  bool xok[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    int m = mt * 16 + ml;
+    xok[mt] = m < a.M;
+    xp[mt] = a.X + (size_t)(xok[mt] ? m : 0) * a.K + g * 8;
+  }
+
+  constexpr int U = (NS * MT >= 6) ? 2 : 4;  // k-tiles in flight per wavefront and loop trip
+  for (int kt0 = wave; kt0 < KT; kt0 += kGemmWaves * U) {
+    u32x4 av[U][NS], bv[U][MT];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int kt = kt0 + u * kGemmWaves;
+      bool in = kt < KT;
+#pragma unroll
+      for (int s = 0; s < NS; ++s)
+        av[u][s] = in ? __builtin_nontemporal_load(wp + ((size_t)s * KT + kt) * 64) : u32x4{0, 0, 0, 0};
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        bv[u][mt] = (in && xok[mt]) ? *(const u32x4 *)(xp[mt] + kt * 32) : u32x4{0, 0, 0, 0};
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+          acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av[u][s]),
+                                                               __builtin_bit_cast(bf16x8, bv[u][mt]), acc[s][mt], 0, 0, 0);
+  }
+
+  // partial sums of h^2 (written by the producer of X) -> this wavefront's share
+  if (NORM) {
+    const int NP = p.d / 16;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      float ss = 0.f;
+      for (int i = wave * 4 + g; i < NP; i += kGemmWaves * 4) ss += p.ssq[(size_t)i * kMaxRows + mt * 16 + ml];
+      ss += __shfl_xor(ss, 16);
+      ss += __shfl_xor(ss, 32);
+      if (g == 0) red_ss[wave][mt][ml] = ss;
+    }
+  }
+#pragma unroll
+  for (int s = 0; s < NS; ++s)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) red[wave][s][mt][lane] = acc[s][mt];
+  __syncthreads();
+  if (wave != 0) return;
+
+  // wavefront 0: fixed-order reduction over the 16 wavefronts, then the fused epilogue.
+  // Lane (ml, g) holds Y[m = mt*16 + ml][n0 + 4g .. 4g+3].
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    floatx4 y[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      y[s] = red[0][s][mt][lane];
+#pragma unroll
+      for (int w = 1; w < kGemmWaves; ++w) y[s] += red[w][s][mt][lane];
+    }
+    const int m = mt * 16 + ml;
+    float inv = 1.f;
+    if (NORM) {
+      float ss = 0.f;
+#pragma unroll
+      for (int w = 0; w < kGemmWaves; ++w) ss += red_ss[w][mt][ml];
+      inv = 1.0f / sqrtf(ss / (float)p.d + p.eps);
+    }
+    const bool live = m < a.M;
+
+    if constexpr (EPI == EPI_LOGITS) {
+      if (live) {
+        float *o = a.logits + (size_t)p.row_out[m] * p.V + strip0 * 16 + 4 * g;
+        *(floatx4 *)o = y[0] * inv;
+      }
+    } else if constexpr (EPI == EPI_GATEUP) {
+      if (live) {
+        // strips 2b (gate) and 2b+1 (up) of the interleaved matrix both belong to features 16b..16b+15
+        int f0 = blockIdx.x * 16 + 4 * g;
+        uint16_t o[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float gt = y[0][r] * inv, up = y[1][r] * inv;
+          o[r] = f32_to_bf16(gt / (1.0f + __expf(-gt)) * up);
+        }
+        uint2 pk;
+        pk.x = (uint32_t)o[0] | ((uint32_t)o[1] << 16);
+        pk.y = (uint32_t)o[2] | ((uint32_t)o[3] << 16);
+        *(uint2 *)(p.act_bf16 + (size_t)m * p.F + f0) = pk;
+      }
+    } else if constexpr (EPI == EPI_RESID) {
+      int n = strip0 * 16 + 4 * g;
+      float ss = 0.f;
+      if (live) {
+        float *hp = p.h + (size_t)m * p.d + n;
+        floatx4 hv = *(floatx4 *)hp + y[0];
+        *(floatx4 *)hp = hv;
+        uint16_t o[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          o[r] = f32_to_bf16(hv[r] * bf16_to_f32(a.gain_next[n + r]));
+          ss += hv[r] * hv[r];
+        }
+        uint2 pk;
+        pk.x = (uint32_t)o[0] | ((uint32_t)o[1] << 16);
+        pk.y = (uint32_t)o[2] | ((uint32_t)o[3] << 16);
+        *(uint2 *)(p.xg + (size_t)m * p.d + n) = pk;
+      }
+      ss += __shfl_xor(ss, 16);
+      ss += __shfl_xor(ss, 32);
+      if (g == 0) p.ssq[(size_t)strip0 * kMaxRows + m] = ss;  // rows >= M get 0
+    } else {  // EPI_QKV
+      if (live) {
+        int n = strip0 * 16 + 4 * g;      // column in [0, 3D)
+        int which = n / p.D;              // 0 q, 1 k, 2 v
+        int c = n - which * p.D;          // column inside the projection
+        int head = c / p.hd, dim = c - head * p.hd;
+        floatx4 v = y[0] * inv;
+        if (which < 2) {
+          int half = p.hd / 2;
+          const float *cs = p.rope_cos + (size_t)m * half + dim / 2;
+          const float *sn = p.rope_sin + (size_t)m * half + dim / 2;
+          float x0 = v[0], x1 = v[1], x2 = v[2], x3 = v[3];
+          v[0] = x0 * cs[0] - x1 * sn[0];
+          v[1] = x0 * sn[0] + x1 * cs[0];
+          v[2] = x2 * cs[1] - x3 * sn[1];
+          v[3] = x2 * sn[1] + x3 * cs[1];
+        }
+        if (which == 0) {
+          *(floatx4 *)(p.qkv + (size_t)m * 3 * p.D + c) = v;
+        } else {
+          uint16_t *pool = (uint16_t *)(which == 1 ? p.k_pool : p.v_pool);
+          size_t off = kv_offset(p, a.layer, p.row_slot[m], p.row_pos[m], head) + dim;
+          uint2 pk;
+          pk.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+          pk.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+          *(uint2 *)(pool + off) = pk;
+        }
+      }
+    }
+  }
+}
+
+template <int EPI>
+static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hipStream_t s) {
+  constexpr int NS = (EPI == EPI_GATEUP) ? 2 : 1;
+  int grid = n_strips / NS;
+  int mt = (a.M + 15) / 16;
+  switch (mt) {
+    case 1: gemm_mfma_kernel<1, EPI><<<grid, kGemmThreads, 0, s>>>(p, a); break;
+    case 2: gemm_mfma_kernel<2, EPI><<<grid, kGemmThreads, 0, s>>>(p, a); break;
+    case 3: gemm_mfma_kernel<3, EPI><<<grid, kGemmThreads, 0, s>>>(p, a); break;
+    default: gemm_mfma_kernel<4, EPI><<<grid, kGemmThreads, 0, s>>>(p, a); break;
+  }
+}
+
+void launch_gemm_qkv(const Params &p, const void *W, int layer, int M, hipStream_t s) {
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, layer, nullptr, nullptr};
+  launch_gemm_epi<EPI_QKV>(p, a, 3 * p.D / 16, s);
+}
+void launch_gemm_resid(const Params &p, const void *W, const uint16_t *X, int K, const void *gain_next, int M,
+                       hipStream_t s) {
+  GemmArgs a{(const u32x4 *)W, X, M, K, 0, (const uint16_t *)gain_next, nullptr};
+  launch_gemm_epi<EPI_RESID>(p, a, p.d / 16, s);
+}
+void launch_gemm_gateup(const Params &p, const void *W, int M, hipStream_t s) {
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, nullptr};
+  launch_gemm_epi<EPI_GATEUP>(p, a, 2 * p.F / 16, s);
+}
+void launch_gemm_logits(const Params &p, const void *W, float *logits, int M, hipStream_t s) {
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, logits};
+  launch_gemm_epi<EPI_LOGITS>(p, a, p.V / 16, s);
+}
+
+}  // namespace pass

@@ -145,6 +145,7 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   P.h = A.take<float>(M * d); P.xn = A.take<float>(M * d); P.qkv = A.take<float>(M * 3 * D);
   P.attn = A.take<float>(M * D); P.gu = A.take<float>(M * 2 * F); P.act = A.take<float>(M * F);
   P.attn_bf16 = A.take<uint16_t>(M * D); P.act_bf16 = A.take<uint16_t>(M * F);
+  P.xg = A.take<uint16_t>(M * d); P.ssq = A.take<float>((d / 16 + 1) * M);
   P.part_acc = A.take<float>(M * c.n_heads * kMaxSplits * c.head_dim);
   P.part_m = A.take<float>(M * c.n_heads * kMaxSplits); P.part_l = A.take<float>(M * c.n_heads * kMaxSplits);
   size_t pool_elems = (size_t)c.n_layers * np * c.n_heads * c.page_size * c.head_dim;
@@ -248,6 +249,20 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
     c->kev.resize(2 * P.L);
     for (auto &e : c->kev) HIP_TRY(c, hipEventCreate(&e));
   }
+  if (c->use_mfma) {
+    launch_assemble_mfma(P, c->tok_emb, c->lookahead, c->layers[0].attn_norm, mode, B, R, s);
+    for (int l = 0; l < P.L; ++l) {
+      const LayerW &w = c->layers[l];
+      launch_gemm_qkv(P, w.wqkv, l, M, s);
+      launch_attention(P, dt, l, B, R, S, 1, s);
+      launch_gemm_resid(P, w.wo, P.attn_bf16, P.D, w.ffn_norm, M, s);
+      if (timing) HIP_TRY(c, hipEventRecord(c->kev[2 * l], s));
+      launch_gemm_gateup(P, w.wgu, M, s);
+      if (timing) HIP_TRY(c, hipEventRecord(c->kev[2 * l + 1], s));
+      launch_gemm_resid(P, w.wdown, P.act_bf16, P.F, l + 1 < P.L ? c->layers[l + 1].attn_norm : c->final_norm, M, s);
+    }
+    if (logits_base) launch_gemm_logits(P, c->lm_head, logits_base, M, s);
+  } else {
   launch_assemble(P, dt, c->tok_emb, c->lookahead, mode, B, R, s);
   for (int l = 0; l < P.L; ++l) {
     const LayerW &w = c->layers[l];
@@ -266,6 +281,7 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
   if (logits_base) {
     launch_rmsnorm(P, dt, P.h, c->final_norm, P.xn, M, s);
     launch_gemm_generic(dt, P.xn, c->lm_head, logits_base, M, P.V, P.d, P.V, P.row_out, 0, s);
+  }
   }
   HIP_TRY(c, hipGetLastError());
   if (timing) {
@@ -410,7 +426,43 @@ int pass_load_weights(pass_ctx *c, const pass_weights *w, int on_device) {
     HIP_TRY(c, hipMemcpyAsync(dst, src, elems * e, kind, c->stream));
     return PASS_OK;
   };
-  int rc;
+  int rc = PASS_OK;
+  c->use_mfma = c->opt_path != 1 && c->cfg.dtype == PASS_BF16 && d % 32 == 0 && D % 32 == 0 && F % 32 == 0 &&
+                V % 16 == 0;
+  if (c->use_mfma) {
+    // matrices go through the tile packer; on_device = 0 stages each tensor in the arena first
+    auto pack = [&](void *dst, const void *src, size_t N, size_t K, int strip_off, int strip_stride) -> int {
+      if (!src) return fail(c, PASS_EINVAL, "null weight pointer");
+      const void *dev_src = src;
+      if (!on_device) {
+        HIP_TRY(c, hipMemcpyAsync(c->staging, src, N * K * e, hipMemcpyHostToDevice, c->stream));
+        dev_src = c->staging;
+      }
+      launch_pack_tiles((const uint16_t *)dev_src, (uint16_t *)dst, (int)N, (int)K, strip_off, strip_stride, c->stream);
+      HIP_TRY(c, hipGetLastError());
+      return PASS_OK;
+    };
+    if ((rc = cp(c->tok_emb, w->tok_emb, V * d))) return rc;
+    if ((rc = pack(c->lm_head, w->lm_head, V, d, 0, 1))) return rc;
+    if ((rc = cp(c->final_norm, w->final_norm, d))) return rc;
+    if (c->cfg.k > 0 && (rc = cp(c->lookahead, w->lookahead, (size_t)c->cfg.k * d))) return rc;
+    for (int l = 0; l < c->P.L; ++l) {
+      LayerW &lw = c->layers[l];
+      if ((rc = cp(lw.attn_norm, w->attn_norm[l], d))) return rc;
+      if ((rc = cp(lw.ffn_norm, w->ffn_norm[l], d))) return rc;
+      const int ds = (int)(D / 16);
+      if ((rc = pack(lw.wqkv, w->wq[l], D, d, 0, 1))) return rc;
+      if ((rc = pack(lw.wqkv, w->wk[l], D, d, ds, 1))) return rc;
+      if ((rc = pack(lw.wqkv, w->wv[l], D, d, 2 * ds, 1))) return rc;
+      if ((rc = pack(lw.wo, w->wo[l], d, D, 0, 1))) return rc;
+      if ((rc = pack(lw.wgu, w->w_gate[l], F, d, 0, 2))) return rc;  // gate strips at even positions
+      if ((rc = pack(lw.wgu, w->w_up[l], F, d, 1, 2))) return rc;    // up strips at odd positions
+      if ((rc = pack(lw.wdown, w->w_down[l], d, F, 0, 1))) return rc;
+    }
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    c->weights_loaded = true;
+    return PASS_OK;
+  }
   if ((rc = cp(c->tok_emb, w->tok_emb, V * d))) return rc;
   if ((rc = cp(c->lm_head, w->lm_head, V * d))) return rc;
   if ((rc = cp(c->final_norm, w->final_norm, d))) return rc;

@@ -63,6 +63,8 @@ struct Params {
   float *act;      // [M][F]
   uint16_t *attn_bf16;  // [M][D]   matrix-core path
   uint16_t *act_bf16;   // [M][F]
+  uint16_t *xg;         // [M][d]   bf16(h * gain of the next norm)
+  float *ssq;           // [d/16][kMaxRows] per-strip partial sums of h^2
   float *part_acc, *part_m, *part_l;  // attention partials [M][H][S][hd], [M][H][S]
   // K/V pools: [layer][page][head][page_size][hd] in the model's storage type
   void *k_pool, *v_pool;
@@ -99,6 +101,14 @@ void launch_poke(int32_t *const *ptrs, const int32_t *vals, int n, hipStream_t s
 void launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t s);
 
 // matrix-core path (bf16, 16x32 weight tiles)
-void launch_pack_tiles(const uint16_t *src, uint16_t *dst, int N, int K, int n_src_rows_offset, hipStream_t s);
+void launch_pack_tiles(const uint16_t *src, uint16_t *dst, int N, int K, int strip_off, int strip_stride,
+                       hipStream_t s);
+void launch_assemble_mfma(const Params &p, const void *tok_emb, const void *lookahead, const void *gain0, int mode,
+                          int B, int R, hipStream_t s);
+void launch_gemm_qkv(const Params &p, const void *W, int layer, int M, hipStream_t s);
+void launch_gemm_resid(const Params &p, const void *W, const uint16_t *X, int K, const void *gain_next, int M,
+                       hipStream_t s);
+void launch_gemm_gateup(const Params &p, const void *W, int M, hipStream_t s);
+void launch_gemm_logits(const Params &p, const void *W, float *logits, int M, hipStream_t s);
 
 }  // namespace pass

@@ -160,3 +160,64 @@ def test_error_paths():
     g.draft([0], 0.0, 1)
     g.verify([0], 0.0, 1)
     g.close()
+
+
+# ---------------------------------------------------------------------------------------------
+# matrix-core (bf16 MFMA) path: shapes whose dimensions are multiples of the 16x32 weight tile
+# ---------------------------------------------------------------------------------------------
+MFMA_SMALL = synth.Workload("mfma_small", synth.ModelShape(2, 256, 4, 64, 704, 512, dtype=synth.BF16),
+                            40, 2, 1, (21, 21), 32, 1.0, 8.0)
+MFMA_HD128 = synth.Workload("mfma_hd128", synth.ModelShape(3, 512, 4, 128, 1184, 1008, dtype=synth.BF16),
+                            41, 4, 1, (70, 70), 32, 1.0, 6.0)
+
+
+@pytest.mark.parametrize("w", [MFMA_SMALL, MFMA_HD128], ids=["hd64", "hd128"])
+@pytest.mark.parametrize("temp", [0.0, 1.0])
+@pytest.mark.parametrize("path", [0, 1], ids=["mfma", "generic"])
+def test_mfma_path_stepwise(w, temp, path):
+    """Packed-tile MFMA GEMMs with fused epilogues against the oracle; the generic kernels on the
+    same model as a cross-check of the tolerance."""
+    g, m, _ = _both(w, w.k, options={"path": path})
+    prompt = synth.make_prompts(w)[0]
+    st = parity.stepwise_parity(g, m, 0, 5, prompt, 16, temp, 4242, parity.LOGIT_TOL[synth.BF16])
+    print(st)
+    assert st.iterations == 16 and st.resyncs <= 8
+    g.close()
+
+
+def test_mfma_path_batches_span_several_row_tiles():
+    """M = 4 slots x (1+4) rows = 20 rows (two 16-row MFMA tiles, ragged), ragged prompts: every
+    slot's tokens equal its single-slot run bit for bit, and prefill chunks (32 rows) agree with
+    the oracle through the stepwise check of one of the slots."""
+    w = MFMA_HD128
+    W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
+    lens = [9, 75, 33, 50]
+    prompts = [np.random.default_rng(10 + i).integers(0, w.shape.vocab, n).astype(np.int32) for i, n in enumerate(lens)]
+    g = _gpu(w.shape, W, w.k, max_slots=4)
+    for i, p in enumerate(prompts):
+        g.prefill(i, p, seq_id=i)
+    toks, stats = g.generate([0, 1, 2, 3], 24, 0.9, 77)
+    for i, p in enumerate(prompts):
+        g.prefill(i, p, seq_id=i)
+        single, _ = g.generate([i], 24, 0.9, 77)
+        assert np.array_equal(single[0], toks[i]), f"slot {i} depends on its batch"
+    m = O.Model(w.shape, W, w.k)
+    st = parity.stepwise_parity(g, m, 2, 2, prompts[1], 6, 0.9, 77, parity.LOGIT_TOL[synth.BF16])
+    print(st, stats)
+    assert st.iterations == 6
+    g.close()
+
+
+def test_7b_layer_shapes_two_layers():
+    """The 7B workload's layer shapes (d 4096, 32 heads x 128, FFN 11008, vocab 32000) with two
+    layers, k = 4: logits and decisions against the oracle at the real tile counts."""
+    w = synth.scaled(synth.WORKLOADS["7b_k4_greedy"], n_layers=2)
+    W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
+    g = _gpu(w.shape, W, w.k, max_seq_len=128, page_size=64)
+    m = O.Model(w.shape, W, w.k)
+    prompt = synth.make_prompts(w)[0][:37]
+    for temp in (0.0, 0.8):
+        st = parity.stepwise_parity(g, m, 0, 1, prompt, 2, temp, 99, parity.LOGIT_TOL[synth.BF16], max_len=128)
+        print(temp, st)
+        assert st.iterations == 2
+    g.close()
