@@ -24,8 +24,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kGemmWaves = 16;
-constexpr int kGemmThreads = kGemmWaves * 64;
+constexpr int kGemmWaves = 16;  // default wavefronts per workgroup
 
 // ---------------------------------------------------------------------------------------------
 // Weight repacking: plain [N][K] bf16 -> tiles [strip][K/32][64 lanes][8], lane l of a tile holds
@@ -124,8 +123,9 @@ struct GemmArgs {
   float *logits;              // LOGITS: base of the [slot][1+k][V] logits
 };
 
-template <int MT, int EPI>
-__global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(Params p, GemmArgs a) {
+template <int MT, int EPI, int WAVES, int U>
+__global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArgs a) {
+  constexpr int kGemmWaves = WAVES;
   constexpr int NS = (EPI == EPI_GATEUP) ? 2 : 1;
   constexpr bool NORM = (EPI != EPI_RESID);
   __shared__ floatx4 red[kGemmWaves][NS][MT][64];
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(Params p, GemmA
     xp[mt] = a.X + (size_t)(xok[mt] ? m : 0) * a.K + g * 8;
   }
 
-  constexpr int U = (NS * MT >= 6) ? 2 : 4;  // k-tiles in flight per wavefront and loop trip
+  // U = k-tiles in flight per wavefront and loop trip
   for (int kt0 = wave; kt0 < KT; kt0 += kGemmWaves * U) {
     u32x4 av[U][NS], bv[U][MT];
 #pragma unroll
@@ -292,13 +292,14 @@ __global__ __launch_bounds__(kGemmThreads) void gemm_mfma_kernel(Params p, GemmA
 template <int EPI>
 static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hipStream_t s) {
   constexpr int NS = (EPI == EPI_GATEUP) ? 2 : 1;
+  constexpr int T = kGemmWaves * 64;
   int grid = n_strips / NS;
   int mt = (a.M + 15) / 16;
   switch (mt) {
-    case 1: gemm_mfma_kernel<1, EPI><<<grid, kGemmThreads, 0, s>>>(p, a); break;
-    case 2: gemm_mfma_kernel<2, EPI><<<grid, kGemmThreads, 0, s>>>(p, a); break;
-    case 3: gemm_mfma_kernel<3, EPI><<<grid, kGemmThreads, 0, s>>>(p, a); break;
-    default: gemm_mfma_kernel<4, EPI><<<grid, kGemmThreads, 0, s>>>(p, a); break;
+    case 1: gemm_mfma_kernel<1, EPI, kGemmWaves, 4><<<grid, T, 0, s>>>(p, a); break;
+    case 2: gemm_mfma_kernel<2, EPI, kGemmWaves, 4><<<grid, T, 0, s>>>(p, a); break;
+    case 3: gemm_mfma_kernel<3, EPI, kGemmWaves, (NS > 1 ? 2 : 4)><<<grid, T, 0, s>>>(p, a); break;
+    default: gemm_mfma_kernel<4, EPI, kGemmWaves, (NS > 1 ? 2 : 4)><<<grid, T, 0, s>>>(p, a); break;
   }
 }
 
