@@ -36,28 +36,6 @@ def gate_up_kernel_bytes(shape, M):
     return 2 * shape.d_ffn * shape.d_model * esz + M * shape.d_model * 2 + M * shape.d_ffn * 2
 
 
-def device_weights(torch, shape, k, lm_head_scale, seed):
-    """Random-init N(0, 0.02) model generated on the device (same recipe as the synthetic
-    generator, different random stream): keeps the 13 GB off the host."""
-    g = torch.Generator(device="cuda")
-    g.manual_seed(seed)
-    dt = torch.bfloat16 if shape.dtype == 1 else torch.float32
-
-    def normal(rows, cols, scale=1.0):
-        return (torch.randn(rows, cols, generator=g, device="cuda", dtype=torch.float32) * (0.02 * scale)).to(dt)
-
-    d, f, v, hd = shape.d_model, shape.d_ffn, shape.vocab, shape.n_heads * shape.head_dim
-    ones = torch.ones(d, device="cuda", dtype=dt)
-    W = {"tok_emb": normal(v, d), "lm_head": normal(v, d, lm_head_scale), "final_norm": ones,
-         "lookahead": normal(max(k, 1), d)[:k].contiguous()}
-    for name, (r, c) in {"wq": (hd, d), "wk": (hd, d), "wv": (hd, d), "wo": (d, hd), "w_gate": (f, d),
-                         "w_up": (f, d), "w_down": (d, f)}.items():
-        W[name] = [normal(r, c) for _ in range(shape.n_layers)]
-    W["attn_norm"] = [ones] * shape.n_layers
-    W["ffn_norm"] = [ones] * shape.n_layers
-    return W
-
-
 def cpu_baseline(w, k, budget_s=20.0):
     """The CPU oracle as it stands, timed on this machine's host cores on a bounded sample of the
     same workload: the same layer shapes with 2 and with 1 of the layers (the difference gives the
@@ -113,7 +91,7 @@ def main():
 
     import numpy as np
     import torch
-    from paper_2311_13581_amd import binding, synth
+    from paper_2311_13581_amd import binding, devgen, synth
 
     w = synth.WORKLOADS[args.workload]
     if args.layers:
@@ -124,7 +102,7 @@ def main():
     total_iters = args.steps + args.warmup + 8
     max_len = max(len(p) for p in prompts) + (k + 2) * total_iters + k + 2
     g = binding.Pass(binding.make_config(shape, k, w.batch, max_len, 64), {"path": args.path, "graph": args.graph})
-    W = device_weights(torch, shape, k, w.lm_head_scale, w.seed)
+    W = devgen.device_weights(shape, k, w.lm_head_scale, w.seed)
     g.load_weights(W)
     del W
     torch.cuda.empty_cache()

@@ -17,10 +17,14 @@
  *   - The verify half is the same rule as Algorithm 2 (speculative sampling, appendix).
  *
  * Arithmetic: double precision everywhere, except where a storage format fixes the value:
- * weights are read in their storage type (fp32 or bfloat16), logits are emitted as fp32, and,
- * for bfloat16 models with act_bf16 = 1, the tensors that a bfloat16 model stores between
- * matrix products (normalised activations, q/k/v, attention output, gated FFN activation) are
- * rounded to bfloat16 (round-to-nearest-even).  The residual stream stays in double.
+ * weights are read in their storage type (fp32 or bfloat16), the K/V cache of a bfloat16 model
+ * holds bfloat16 values (round-to-nearest-even on write), logits are emitted as fp32.
+ * "We load models in bfloat16" (Training details) is read as a statement about storage: nothing
+ * between two matrix products is stored, so nothing else is rounded.  With act_bf16 = 1 the
+ * oracle additionally rounds the tensors an all-bfloat16 execution would round (normalised
+ * activations, q, attention output, gated FFN activation); that variant exists to measure how
+ * far such an execution sits from this one, it is not the reference.  The residual stream stays
+ * in double either way.
  *
  * Every row of a call is computed by the same sequence of operations whatever other rows share
  * the call, so a (1+k)-row call equals k+1 single-row calls bit for bit.
@@ -60,7 +64,7 @@ typedef struct {
   float rms_eps, rope_base;
   int32_t dtype;    /* ORC_F32 / ORC_BF16: storage type of every model tensor */
   int32_t k;        /* number of look-ahead embeddings, L in Algorithm 1 */
-  int32_t act_bf16; /* round stored activations to bfloat16 (see header) */
+  int32_t act_bf16; /* also round activations between matrix products to bfloat16 (see header) */
 } orc_config;
 
 typedef struct {
@@ -422,7 +426,8 @@ int orc_forward(orc_seq *s, int R, const int32_t *ids, const int32_t *la, int po
       rope(m, q + (size_t)r * D, pos0 + r);
       rope(m, kk + (size_t)r * D, pos0 + r);
     }
-    if (c->act_bf16) { round_vec(q, Rz * D); round_vec(kk, Rz * D); round_vec(vv, Rz * D); }
+    if (c->dtype == ORC_BF16) { round_vec(kk, Rz * D); round_vec(vv, Rz * D); } /* cache storage format */
+    if (c->act_bf16) round_vec(q, Rz * D);
     double *kc = s->kc + (size_t)l * s->max_len * D, *vc = s->vc + (size_t)l * s->max_len * D;
     for (int r = 0; r < R; ++r) {
       memcpy(kc + (size_t)(pos0 + r) * D, kk + (size_t)r * D, sizeof(double) * D);

@@ -167,7 +167,7 @@ class Model:
         self.shape = shape
         self.k = k
         if act_bf16 is None:
-            act_bf16 = shape.dtype == BF16
+            act_bf16 = False
         self.cfg = Config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn,
                           shape.vocab, shape.rms_eps, shape.rope_base, shape.dtype, k, int(act_bf16))
         self._keep = weights  # keep the numpy buffers alive

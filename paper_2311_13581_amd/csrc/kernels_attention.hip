@@ -38,8 +38,15 @@ __device__ __forceinline__ void load_chunk(const bf16_t *p, float (&o)[DPL]) {
   }
 }
 
+// How a row group's keys are cut into splits.  A function of the group's own key count only, so
+// that a sequence's arithmetic (and therefore its tokens) cannot depend on what else is batched.
+__device__ __forceinline__ void split_plan(int n_keys, int &n_splits, int &chunk) {
+  n_splits = min(kMaxSplits, (n_keys + 63) / 64);
+  chunk = ((n_keys + n_splits - 1) / n_splits + 15) & ~15;
+}
+
 template <typename T, int HD>
-__global__ __launch_bounds__(256) void attn_split_kernel(Params p, int layer, int R, int n_splits) {
+__global__ __launch_bounds__(256) void attn_split_kernel(Params p, int layer, int R) {
   constexpr int DPL = HD / 16;
   constexpr int RQ = kAttnRowsPerGroup;
   __shared__ float s_m[4][RQ], s_l[4][RQ];
@@ -53,7 +60,9 @@ __global__ __launch_bounds__(256) void attn_split_kernel(Params p, int layer, in
   const int slot = p.step_slots[b];
   const int pos0 = p.kv_len[slot] + r0;  // position of the group's first row
   const int n_keys = pos0 + nr;
-  int chunk = ((n_keys + n_splits - 1) / n_splits + 15) & ~15;
+  int n_splits, chunk;
+  split_plan(n_keys, n_splits, chunk);
+  if (split >= n_splits) return;
   const int k_lo = split * chunk;
   const int k_hi = min(n_keys, k_lo + chunk);
 
@@ -152,17 +161,23 @@ __global__ __launch_bounds__(256) void attn_split_kernel(Params p, int layer, in
       l_n += s_l[w][r] * f;
       v += s_acc[w][r][dim] * f;
     }
-    size_t pi = ((size_t)(b * R + r0 + r) * p.H + head) * n_splits + split;
+    size_t pi = ((size_t)(b * R + r0 + r) * p.H + head) * kMaxSplits + split;
     p.part_acc[pi * HD + dim] = v;
     if (dim == 0) { p.part_m[pi] = m_n; p.part_l[pi] = l_n; }
   }
 }
 
 // Merge the split partials of one (row, head): out = sum_s acc_s e^{m_s - m} / sum_s l_s e^{m_s - m}
-template <int HD, bool OUT_BF16>
-__global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int n_splits) {
+template <int HD, int OUT>
+__global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R) {
   int m = blockIdx.x, head = blockIdx.y, dim = threadIdx.x;
-  size_t pi = ((size_t)m * p.H + head) * n_splits;
+  // the row's group and its split plan, recomputed exactly as the split kernel did
+  constexpr int RQ = kAttnRowsPerGroup;
+  int b = m / R, r = m % R, r0 = (r / RQ) * RQ;
+  int n_keys = p.kv_len[p.step_slots[b]] + r0 + min(RQ, R - r0);
+  int n_splits, chunk;
+  split_plan(n_keys, n_splits, chunk);
+  size_t pi = ((size_t)m * p.H + head) * kMaxSplits;
   float m_n = -INFINITY;
   for (int s = 0; s < n_splits; ++s) m_n = fmaxf(m_n, p.part_m[pi + s]);
   float l_n = 0.f, v = 0.f;
@@ -174,10 +189,13 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int n_splits
   }
   float o = v / l_n;
   size_t oi = (size_t)m * p.D + head * HD + dim;
-  if (OUT_BF16)
-    p.attn_bf16[oi] = f32_to_bf16(o);
-  else
+  if (OUT == 1) {
+    uint16_t hi = f32_to_bf16(o);
+    p.attn_hi[oi] = hi;
+    p.attn_lo[oi] = f32_to_bf16(o - bf16_to_f32(hi));
+  } else {
     p.attn[oi] = o;
+  }
 }
 
 void launch_attention(const Params &p, int dtype, int layer, int B, int R, int n_splits, int out_bf16,
@@ -186,22 +204,22 @@ void launch_attention(const Params &p, int dtype, int layer, int B, int R, int n
   dim3 grid(n_splits, p.H, groups);
   if (p.hd == 128) {
     if (dtype == PASS_F32)
-      attn_split_kernel<float, 128><<<grid, 256, 0, s>>>(p, layer, R, n_splits);
+      attn_split_kernel<float, 128><<<grid, 256, 0, s>>>(p, layer, R);
     else
-      attn_split_kernel<bf16_t, 128><<<grid, 256, 0, s>>>(p, layer, R, n_splits);
-    if (out_bf16)
-      attn_combine_kernel<128, true><<<dim3(B * R, p.H), 128, 0, s>>>(p, n_splits);
+      attn_split_kernel<bf16_t, 128><<<grid, 256, 0, s>>>(p, layer, R);
+    if (out_bf16 == 1)
+      attn_combine_kernel<128, 1><<<dim3(B * R, p.H), 128, 0, s>>>(p, R);
     else
-      attn_combine_kernel<128, false><<<dim3(B * R, p.H), 128, 0, s>>>(p, n_splits);
+      attn_combine_kernel<128, 0><<<dim3(B * R, p.H), 128, 0, s>>>(p, R);
   } else {
     if (dtype == PASS_F32)
-      attn_split_kernel<float, 64><<<grid, 256, 0, s>>>(p, layer, R, n_splits);
+      attn_split_kernel<float, 64><<<grid, 256, 0, s>>>(p, layer, R);
     else
-      attn_split_kernel<bf16_t, 64><<<grid, 256, 0, s>>>(p, layer, R, n_splits);
-    if (out_bf16)
-      attn_combine_kernel<64, true><<<dim3(B * R, p.H), 64, 0, s>>>(p, n_splits);
+      attn_split_kernel<bf16_t, 64><<<grid, 256, 0, s>>>(p, layer, R);
+    if (out_bf16 == 1)
+      attn_combine_kernel<64, 1><<<dim3(B * R, p.H), 64, 0, s>>>(p, R);
     else
-      attn_combine_kernel<64, false><<<dim3(B * R, p.H), 64, 0, s>>>(p, n_splits);
+      attn_combine_kernel<64, 0><<<dim3(B * R, p.H), 64, 0, s>>>(p, R);
   }
 }
 

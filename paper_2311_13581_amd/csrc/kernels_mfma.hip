@@ -6,15 +6,24 @@
 // order of v_mfma_f32_16x16x32_bf16's A operand, so that one wavefront fetches a tile as 64
 // adjacent 16-byte loads (1 KB, fully coalesced) and a strip of 16 output features is one
 // contiguous run of K/32 KB.  The M <= 64 activation rows are the B operand (rows padded to 16
-// per MFMA; with M = 5 the matrix core still runs far below its rate, the kernel stays bound by
-// HBM).  A workgroup of 16 wavefronts owns one strip (two for gate/up) and splits K among its
-// wavefronts; partial tiles are reduced through LDS in a fixed order (deterministic), and the
-// epilogue is fused:
-//   QKV     : RMSNorm scale, rotary embedding, q to the workspace, K/V rows into the paged cache
-//   RESID   : residual add, bf16 copy of h * gain of the next norm, partial sums of h^2
-//   GATEUP  : RMSNorm scale, silu(gate) * up in bf16
+// per MFMA).  A workgroup of 16 wavefronts owns one strip (two for gate/up) and splits K among
+// its wavefronts; the next trip's weight tiles are requested before the current trip computes;
+// partial tiles are reduced through LDS in a fixed order (deterministic).
+//
+// Activations keep fp32-like precision although the matrix core takes bf16: every activation x
+// is carried as a pair (hi, lo) of bf16 values, hi = bf16(x), lo = bf16(x - hi), and each weight
+// tile is multiplied with both (two MFMAs).  At M = 5 the matrix core runs at a few percent of
+// its rate, so the second MFMA is free, and nothing but the weights and the K/V cache is ever
+// rounded to 8 bits of mantissa ("models are loaded in bfloat16" is a statement about storage).
+//
+// Fused epilogues:
+//   QKV     : RMSNorm scale, rotary embedding, q (fp32) to the workspace, K/V rows (bf16) into
+//             the paged cache
+//   RESID   : residual add into h (fp32), (hi, lo) of h * gain of the next norm, per-strip
+//             partial sums of h^2
+//   GATEUP  : RMSNorm scale, silu(gate) * up as (hi, lo)
 //   LOGITS  : RMSNorm scale, fp32 logits into the slot's logits rows
-// RMSNorm is folded: the producer stores bf16(h * gain) and per-strip partial sums of h^2; the
+// RMSNorm has no kernel: the producer stores (hi, lo) of h * gain and partial sums of h^2; the
 // consumer multiplies its accumulators by rsqrt(mean(h^2) + eps), which commutes with the GEMM.
 #include "pass_internal.h"
 
@@ -54,8 +63,29 @@ void launch_pack_tiles(const uint16_t *src, uint16_t *dst, int N, int K, int str
 }
 
 // ---------------------------------------------------------------------------------------------
-// Row assembly for the matrix-core path: h (fp32), xg = bf16(h * gain of the first norm), partial
-// sums of h^2 (partial 0 carries the whole row, the others are zero), rotary table, row tables.
+// (hi, lo) split of an fp32 value into two bf16: x = hi + lo up to 2^-17 relative
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo) {
+  hi = f32_to_bf16(x);
+  lo = f32_to_bf16(x - bf16_to_f32(hi));
+}
+__device__ __forceinline__ void store_split4(uint16_t *hi_p, uint16_t *lo_p, const float (&v)[4]) {
+  uint16_t h[4], l[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) split_bf16(v[r], h[r], l[r]);
+  uint2 ph, pl;
+  ph.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+  ph.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+  pl.x = (uint32_t)l[0] | ((uint32_t)l[1] << 16);
+  pl.y = (uint32_t)l[2] | ((uint32_t)l[3] << 16);
+  *(uint2 *)hi_p = ph;
+  *(uint2 *)lo_p = pl;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Row assembly for the matrix-core path: h (fp32), (hi, lo) of h * gain of the first norm,
+// partial sums of h^2 (partial 0 carries the whole row, the others are zero), rotary table,
+// row tables.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint16_t *tok_emb,
                                                             const uint16_t *lookahead, const uint16_t *gain0,
@@ -78,7 +108,10 @@ __global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint
   for (int i = threadIdx.x; i < p.d; i += 256) {
     float v = bf16_to_f32(src[i]);
     p.h[(size_t)m * p.d + i] = v;
-    p.xg[(size_t)m * p.d + i] = f32_to_bf16(v * bf16_to_f32(gain0[i]));
+    uint16_t hi, lo;
+    split_bf16(v * bf16_to_f32(gain0[i]), hi, lo);
+    p.xg_hi[(size_t)m * p.d + i] = hi;
+    p.xg_lo[(size_t)m * p.d + i] = lo;
     ss += v * v;
   }
 #pragma unroll
@@ -115,12 +148,12 @@ void launch_assemble_mfma(const Params &p, const void *tok_emb, const void *look
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_GATEUP = 2, EPI_LOGITS = 3 };
 
 struct GemmArgs {
-  const u32x4 *W;       // packed tiles
-  const uint16_t *X;    // [M][K] bf16
+  const u32x4 *W;                // packed tiles
+  const uint16_t *Xhi, *Xlo;     // [M][K] bf16 pair: the activation rows
   int M, K;
   int layer;
-  const uint16_t *gain_next;  // RESID: gain of the norm that follows
-  float *logits;              // LOGITS: base of the [slot][1+k][V] logits
+  const uint16_t *gain_next;     // RESID: gain of the norm that follows
+  float *logits;                 // LOGITS: base of the [slot][1+k][V] logits
 };
 
 template <int MT, int EPI, int WAVES, int U>
@@ -142,42 +175,62 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[s][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
+  // weight tiles of one loop trip: k-tiles kt0 + u * WAVES, u < U (interleaved over the wavefronts,
+  // so the workgroup walks its strip front to back)
   const u32x4 *wp = a.W + (size_t)strip0 * KT * 64 + lane;
-  const uint16_t *xp[MT];
+  u32x4 a_cur[U][NS], a_nxt[U][NS];
+  auto load_a = [&](u32x4 (&dst)[U][NS], int kt0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int kt = kt0 + u * kGemmWaves;
+#pragma unroll
+      for (int s = 0; s < NS; ++s)
+        dst[u][s] = (kt < KT) ? __builtin_nontemporal_load(wp + ((size_t)s * KT + kt) * 64) : u32x4{0, 0, 0, 0};
+    }
+  };
+  load_a(a_cur, wave);
+
   bool xok[MT];
+  size_t xoff[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     int m = mt * 16 + ml;
     xok[mt] = m < a.M;
-    xp[mt] = a.X + (size_t)(xok[mt] ? m : 0) * a.K + g * 8;
+    xoff[mt] = (size_t)(xok[mt] ? m : 0) * a.K + g * 8;
   }
 
-  // U = k-tiles in flight per wavefront and loop trip
   for (int kt0 = wave; kt0 < KT; kt0 += kGemmWaves * U) {
-    u32x4 av[U][NS], bv[U][MT];
+    load_a(a_nxt, kt0 + kGemmWaves * U);  // next trip's weights are requested before this trip computes
+    u32x4 bh[U][MT], bl[U][MT];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      int kt = kt0 + u * kGemmWaves;
-      bool in = kt < KT;
+      const int kt = kt0 + u * kGemmWaves;
 #pragma unroll
-      for (int s = 0; s < NS; ++s)
-        av[u][s] = in ? __builtin_nontemporal_load(wp + ((size_t)s * KT + kt) * 64) : u32x4{0, 0, 0, 0};
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        bv[u][mt] = (in && xok[mt]) ? *(const u32x4 *)(xp[mt] + kt * 32) : u32x4{0, 0, 0, 0};
+      for (int mt = 0; mt < MT; ++mt) {
+        const bool in = kt < KT && xok[mt];
+        bh[u][mt] = in ? *(const u32x4 *)(a.Xhi + xoff[mt] + kt * 32) : u32x4{0, 0, 0, 0};
+        bl[u][mt] = in ? *(const u32x4 *)(a.Xlo + xoff[mt] + kt * 32) : u32x4{0, 0, 0, 0};
+      }
     }
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int s = 0; s < NS; ++s)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-          acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av[u][s]),
-                                                               __builtin_bit_cast(bf16x8, bv[u][mt]), acc[s][mt], 0, 0, 0);
+        for (int mt = 0; mt < MT; ++mt) {
+          acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur[u][s]),
+                                                               __builtin_bit_cast(bf16x8, bl[u][mt]), acc[s][mt], 0, 0, 0);
+          acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur[u][s]),
+                                                               __builtin_bit_cast(bf16x8, bh[u][mt]), acc[s][mt], 0, 0, 0);
+        }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int s = 0; s < NS; ++s) a_cur[u][s] = a_nxt[u][s];
   }
 
   // partial sums of h^2 (written by the producer of X) -> this wavefront's share
-  if (NORM) {
+  if constexpr (NORM) {
     const int NP = p.d / 16;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -195,7 +248,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
   __syncthreads();
   if (wave != 0) return;
 
-  // wavefront 0: fixed-order reduction over the 16 wavefronts, then the fused epilogue.
+  // wavefront 0: fixed-order reduction over the wavefronts, then the fused epilogue.
   // Lane (ml, g) holds Y[m = mt*16 + ml][n0 + 4g .. 4g+3].
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -208,7 +261,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
     }
     const int m = mt * 16 + ml;
     float inv = 1.f;
-    if (NORM) {
+    if constexpr (NORM) {
       float ss = 0.f;
 #pragma unroll
       for (int w = 0; w < kGemmWaves; ++w) ss += red_ss[w][mt][ml];
@@ -225,16 +278,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
       if (live) {
         // strips 2b (gate) and 2b+1 (up) of the interleaved matrix both belong to features 16b..16b+15
         int f0 = blockIdx.x * 16 + 4 * g;
-        uint16_t o[4];
+        float t[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           float gt = y[0][r] * inv, up = y[1][r] * inv;
-          o[r] = f32_to_bf16(gt / (1.0f + __expf(-gt)) * up);
+          t[r] = gt / (1.0f + __expf(-gt)) * up;
         }
-        uint2 pk;
-        pk.x = (uint32_t)o[0] | ((uint32_t)o[1] << 16);
-        pk.y = (uint32_t)o[2] | ((uint32_t)o[3] << 16);
-        *(uint2 *)(p.act_bf16 + (size_t)m * p.F + f0) = pk;
+        store_split4(p.act_hi + (size_t)m * p.F + f0, p.act_lo + (size_t)m * p.F + f0, t);
       }
     } else if constexpr (EPI == EPI_RESID) {
       int n = strip0 * 16 + 4 * g;
@@ -243,16 +293,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
         float *hp = p.h + (size_t)m * p.d + n;
         floatx4 hv = *(floatx4 *)hp + y[0];
         *(floatx4 *)hp = hv;
-        uint16_t o[4];
+        float t[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          o[r] = f32_to_bf16(hv[r] * bf16_to_f32(a.gain_next[n + r]));
+          t[r] = hv[r] * bf16_to_f32(a.gain_next[n + r]);
           ss += hv[r] * hv[r];
         }
-        uint2 pk;
-        pk.x = (uint32_t)o[0] | ((uint32_t)o[1] << 16);
-        pk.y = (uint32_t)o[2] | ((uint32_t)o[3] << 16);
-        *(uint2 *)(p.xg + (size_t)m * p.d + n) = pk;
+        store_split4(p.xg_hi + (size_t)m * p.d + n, p.xg_lo + (size_t)m * p.d + n, t);
       }
       ss += __shfl_xor(ss, 16);
       ss += __shfl_xor(ss, 32);
@@ -277,6 +324,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
         if (which == 0) {
           *(floatx4 *)(p.qkv + (size_t)m * 3 * p.D + c) = v;
         } else {
+          // the cache is bf16 storage: the one place besides the weights where values are rounded
           uint16_t *pool = (uint16_t *)(which == 1 ? p.k_pool : p.v_pool);
           size_t off = kv_offset(p, a.layer, p.row_slot[m], p.row_pos[m], head) + dim;
           uint2 pk;
@@ -296,28 +344,28 @@ static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hi
   int grid = n_strips / NS;
   int mt = (a.M + 15) / 16;
   switch (mt) {
-    case 1: gemm_mfma_kernel<1, EPI, kGemmWaves, 4><<<grid, T, 0, s>>>(p, a); break;
-    case 2: gemm_mfma_kernel<2, EPI, kGemmWaves, 4><<<grid, T, 0, s>>>(p, a); break;
-    case 3: gemm_mfma_kernel<3, EPI, kGemmWaves, (NS > 1 ? 2 : 4)><<<grid, T, 0, s>>>(p, a); break;
-    default: gemm_mfma_kernel<4, EPI, kGemmWaves, (NS > 1 ? 2 : 4)><<<grid, T, 0, s>>>(p, a); break;
+    case 1: gemm_mfma_kernel<1, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
+    case 2: gemm_mfma_kernel<2, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
+    case 3: gemm_mfma_kernel<3, EPI, kGemmWaves, 1><<<grid, T, 0, s>>>(p, a); break;
+    default: gemm_mfma_kernel<4, EPI, kGemmWaves, 1><<<grid, T, 0, s>>>(p, a); break;
   }
 }
 
 void launch_gemm_qkv(const Params &p, const void *W, int layer, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, layer, nullptr, nullptr};
+  GemmArgs a{(const u32x4 *)W, p.xg_hi, p.xg_lo, M, p.d, layer, nullptr, nullptr};
   launch_gemm_epi<EPI_QKV>(p, a, 3 * p.D / 16, s);
 }
-void launch_gemm_resid(const Params &p, const void *W, const uint16_t *X, int K, const void *gain_next, int M,
-                       hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, X, M, K, 0, (const uint16_t *)gain_next, nullptr};
+void launch_gemm_resid(const Params &p, const void *W, const uint16_t *Xhi, const uint16_t *Xlo, int K,
+                       const void *gain_next, int M, hipStream_t s) {
+  GemmArgs a{(const u32x4 *)W, Xhi, Xlo, M, K, 0, (const uint16_t *)gain_next, nullptr};
   launch_gemm_epi<EPI_RESID>(p, a, p.d / 16, s);
 }
 void launch_gemm_gateup(const Params &p, const void *W, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, nullptr};
+  GemmArgs a{(const u32x4 *)W, p.xg_hi, p.xg_lo, M, p.d, 0, nullptr, nullptr};
   launch_gemm_epi<EPI_GATEUP>(p, a, 2 * p.F / 16, s);
 }
 void launch_gemm_logits(const Params &p, const void *W, float *logits, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, logits};
+  GemmArgs a{(const u32x4 *)W, p.xg_hi, p.xg_lo, M, p.d, 0, nullptr, logits};
   launch_gemm_epi<EPI_LOGITS>(p, a, p.V / 16, s);
 }
 

@@ -144,8 +144,10 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   P.rope_cos = A.take<float>(M * c.head_dim / 2); P.rope_sin = A.take<float>(M * c.head_dim / 2);
   P.h = A.take<float>(M * d); P.xn = A.take<float>(M * d); P.qkv = A.take<float>(M * 3 * D);
   P.attn = A.take<float>(M * D); P.gu = A.take<float>(M * 2 * F); P.act = A.take<float>(M * F);
-  P.attn_bf16 = A.take<uint16_t>(M * D); P.act_bf16 = A.take<uint16_t>(M * F);
-  P.xg = A.take<uint16_t>(M * d); P.ssq = A.take<float>((d / 16 + 1) * M);
+  P.attn_hi = A.take<uint16_t>(M * D); P.attn_lo = A.take<uint16_t>(M * D);
+  P.act_hi = A.take<uint16_t>(M * F); P.act_lo = A.take<uint16_t>(M * F);
+  P.xg_hi = A.take<uint16_t>(M * d); P.xg_lo = A.take<uint16_t>(M * d);
+  P.ssq = A.take<float>((d / 16 + 1) * M);
   P.part_acc = A.take<float>(M * c.n_heads * kMaxSplits * c.head_dim);
   P.part_m = A.take<float>(M * c.n_heads * kMaxSplits); P.part_l = A.take<float>(M * c.n_heads * kMaxSplits);
   size_t pool_elems = (size_t)c.n_layers * np * c.n_heads * c.page_size * c.head_dim;
@@ -230,11 +232,10 @@ int set_step_slots(pass_ctx *c, const int32_t *slots, int B) {
 }
 
 int choose_splits(const pass_ctx *c, int B, int R, int max_keys) {
-  int groups = B * ((R + kAttnRowsPerGroup - 1) / kAttnRowsPerGroup);
-  int by_fill = (1024 + groups * c->P.H - 1) / (groups * c->P.H);
-  int by_len = (max_keys + 63) / 64;
-  int s = std::min(by_fill, by_len);
-  return std::max(1, std::min(kMaxSplits, s));
+  // grid width only: each row group cuts its own keys by a rule of its own length (split_plan in
+  // the attention kernel); workgroups beyond a group's split count exit at once
+  (void)c; (void)B; (void)R;
+  return std::max(1, std::min(kMaxSplits, (max_keys + 63) / 64));
 }
 
 // One model call on B*R rows.  logits_base == nullptr: no LM head (prefill).
@@ -255,11 +256,12 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
       const LayerW &w = c->layers[l];
       launch_gemm_qkv(P, w.wqkv, l, M, s);
       launch_attention(P, dt, l, B, R, S, 1, s);
-      launch_gemm_resid(P, w.wo, P.attn_bf16, P.D, w.ffn_norm, M, s);
+      launch_gemm_resid(P, w.wo, P.attn_hi, P.attn_lo, P.D, w.ffn_norm, M, s);
       if (timing) HIP_TRY(c, hipEventRecord(c->kev[2 * l], s));
       launch_gemm_gateup(P, w.wgu, M, s);
       if (timing) HIP_TRY(c, hipEventRecord(c->kev[2 * l + 1], s));
-      launch_gemm_resid(P, w.wdown, P.act_bf16, P.F, l + 1 < P.L ? c->layers[l + 1].attn_norm : c->final_norm, M, s);
+      launch_gemm_resid(P, w.wdown, P.act_hi, P.act_lo, P.F,
+                        l + 1 < P.L ? c->layers[l + 1].attn_norm : c->final_norm, M, s);
     }
     if (logits_base) launch_gemm_logits(P, c->lm_head, logits_base, M, s);
   } else {
@@ -275,7 +277,7 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
     if (timing) HIP_TRY(c, hipEventRecord(c->kev[2 * l], s));
     launch_gemm_generic(dt, P.xn, w.wgu, P.gu, M, 2 * P.F, P.d, 2 * P.F, nullptr, 0, s);
     if (timing) HIP_TRY(c, hipEventRecord(c->kev[2 * l + 1], s));
-    launch_silu_mul(P, M, s);
+    launch_silu_mul(P, 0, M, s);
     launch_gemm_generic(dt, P.act, w.wdown, P.h, M, P.d, P.F, P.d, nullptr, 1, s);
   }
   if (logits_base) {

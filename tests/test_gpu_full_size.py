@@ -1,0 +1,141 @@
+"""Full-size GPU tests: the baseline configurations at their real shapes, in the launch
+configuration the benchmark times.  The oracle cannot run these end to end in reasonable time, so
+they combine (a) oracle comparisons on sampled sub-problems it can finish (full depth with a short
+context; one layer with a long context) and (b) properties that hold at any size (greedy PaSS ==
+greedy auto-regressive, batch independence, determinism, bookkeeping)."""
+import time
+
+import numpy as np
+import pytest
+
+import parity
+import pass_oracle as O
+from paper_2311_13581_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu_dev(w, k, max_slots, max_seq_len, page_size=64):
+    """Pass instance with the workload's model generated on the device."""
+    import torch
+    from paper_2311_13581_amd import binding, devgen
+    g = binding.Pass(binding.make_config(w.shape, k, max_slots, max_seq_len, page_size))
+    W = devgen.device_weights(w.shape, k, w.lm_head_scale, w.seed)
+    g.load_weights(W)
+    del W
+    torch.cuda.empty_cache()
+    return g
+
+
+def test_7b_full_depth_short_context_vs_oracle():
+    """Configuration 2's model at full depth (32 layers, 13.2 GB of bf16 weights shared byte for byte
+    with the oracle), 9-token prompt, k = 4: logits of both calls and all decisions."""
+    from paper_2311_13581_amd import binding
+    w = synth.WORKLOADS["7b_k4_greedy"]
+    t0 = time.time()
+    W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
+    print("weights generated in %.0f s" % (time.time() - t0), flush=True)
+    g = binding.Pass(binding.make_config(w.shape, w.k, 1, 64, 64))
+    g.load_weights(W)
+    m = O.Model(w.shape, W, w.k)
+    prompt = synth.make_prompts(w)[0][:9]
+    t0 = time.time()
+    st = parity.stepwise_parity(g, m, 0, 0, prompt, 1, 0.0, synth.sampling_seed(w), parity.LOGIT_TOL[synth.BF16],
+                                max_len=64)
+    print(st, "oracle+gpu %.0f s" % (time.time() - t0), flush=True)
+    assert st.iterations == 1
+    g.close()
+
+
+def test_long_context_single_layer_vs_oracle():
+    """One 7B-shaped layer, 1100-token prompt (18 pages, several attention splits, 35 prefill
+    chunks), k = 4, temperature 0.8: the attention path at long context against the oracle."""
+    w = synth.scaled(synth.WORKLOADS["7b_ksweep_t0.8"], n_layers=1, vocab=2048)
+    W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
+    from paper_2311_13581_amd import binding
+    g = binding.Pass(binding.make_config(w.shape, w.k, 1, 1280, 64))
+    g.load_weights(W)
+    m = O.Model(w.shape, W, w.k)
+    prompt = synth.make_prompts(w)[0][:1100]
+    st = parity.stepwise_parity(g, m, 0, 4, prompt, 2, 0.8, 31337, parity.LOGIT_TOL[synth.BF16], max_len=1280)
+    print(st, flush=True)
+    assert st.iterations == 2 and st.resyncs <= 1
+    g.close()
+
+
+def test_config2_greedy_pass_equals_autoregressive_at_full_size():
+    """Configuration 2 as benchmarked (7B, prompt 512, 256 new tokens, greedy): PaSS with k = 4 and
+    plain decoding (k = 0) produce the same 256 tokens; bookkeeping invariants hold."""
+    w = synth.WORKLOADS["7b_k4_greedy"]
+    prompt = synth.make_prompts(w)[0]
+    outs = {}
+    for k in (4, 0):
+        g = _gpu_dev(w, k, 1, 512 + 256 + 16)
+        g.prefill(0, prompt)
+        toks, st = g.generate([0], w.max_new, 0.0, 0)
+        kv, ng = g.seq_len(0)
+        assert kv == len(prompt) - 1 + ng and w.max_new <= ng <= w.max_new + k + 1
+        assert st["iterations"] * 2 <= w.max_new + k + 1
+        print(k, st, flush=True)
+        outs[k] = toks[0]
+        g.close()
+    assert np.array_equal(outs[4], outs[0])
+    assert outs[4].min() >= 0 and outs[4].max() < w.shape.vocab
+
+
+def test_config3_lookahead_sweep_is_deterministic_and_flat():
+    """Configuration 3 (7B, prompt 2048, temperature 0.8, k in {0,1,2,3,4,6}): each k runs twice
+    with identical tokens (bitwise determinism); the call latency is reported per k."""
+    w = synth.WORKLOADS["7b_ksweep_t0.8"]
+    prompt = synth.make_prompts(w)[0]
+    seed = synth.sampling_seed(w)
+    lat = {}
+    for k in w.k_sweep:
+        g = _gpu_dev(w, k, 1, 2048 + 256 + 16)
+        runs = []
+        for _ in range(2):
+            g.prefill(0, prompt, seq_id=9)
+            toks, st = g.generate([0], 64 if _ else w.max_new, 0.8, seed)
+            runs.append(toks[0])
+        assert np.array_equal(runs[0][:64], runs[1])
+        lat[k] = (st["draft_ms"] + st["verify_ms"]) / (2 * st["iterations"])
+        g.close()
+    print("call latency by k (ms):", {k: round(v, 3) for k, v in lat.items()}, flush=True)
+    assert lat[4] < 1.5 * lat[0]
+
+
+def test_config4_ragged_batch_matches_single_slot_runs():
+    """Configuration 4 (7B, 8 ragged prompts 128..2048, k = 4, temperature 1.0, 128 tokens each):
+    every slot's tokens equal its single-slot run bit for bit (M = 40 rows vs 5)."""
+    w = synth.WORKLOADS["7b_b8_ragged_t1"]
+    prompts = synth.make_prompts(w)
+    assert len(prompts) == 8 and min(map(len, prompts)) >= 128 and max(map(len, prompts)) <= 2048
+    seed = synth.sampling_seed(w)
+    g = _gpu_dev(w, w.k, 8, 2048 + 128 + 16)
+    for i, p in enumerate(prompts):
+        g.prefill(i, p, seq_id=i)
+    toks, st = g.generate(list(range(8)), w.max_new, 1.0, seed)
+    print(st, flush=True)
+    for i in (0, 3, 7):
+        g.prefill(i, prompts[i], seq_id=i)
+        single, _ = g.generate([i], w.max_new, 1.0, seed)
+        assert np.array_equal(single[0], toks[i]), f"slot {i} depends on its batch"
+    g.close()
+
+
+def test_config5_13b_long_prompt_runs_and_is_deterministic():
+    """Configuration 5 (13B, prompt 4096, k = 4, temperature 0.8, 256 tokens)."""
+    w = synth.WORKLOADS["13b_k4_t0.8"]
+    prompt = synth.make_prompts(w)[0]
+    seed = synth.sampling_seed(w)
+    g = _gpu_dev(w, w.k, 1, 4096 + 256 + 16)
+    runs = []
+    for n in (w.max_new, 48):
+        g.prefill(0, prompt, seq_id=2)
+        toks, st = g.generate([0], n, 0.8, seed)
+        runs.append(toks[0])
+    print(st, flush=True)
+    assert np.array_equal(runs[0][:48], runs[1])
+    kv, ng = g.seq_len(0)
+    assert kv == len(prompt) - 1 + ng
+    g.close()

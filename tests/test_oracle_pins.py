@@ -270,9 +270,11 @@ def test_block_forward_equals_sequential_rows_bitwise():
                 assert np.array_equal(a.read_kv(1, layer, pos), b.read_kv(1, layer, pos))
 
 
-def test_bf16_activation_schedule_rounds_cache():
+@pytest.mark.parametrize("act", [False, True])
+def test_bf16_model_caches_bf16_values(act):
+    """The K/V cache of a bf16 model holds bf16 values whether or not activations are rounded."""
     shape = synth.ModelShape(1, 64, 4, 16, 96, 40, dtype=synth.BF16)
-    m, _ = _model(shape, 3, 1, 1.0, act_bf16=True)
+    m, _ = _model(shape, 3, 1, 1.0, act_bf16=act)
     s = m.sequence(8)
     s.forward(np.array([3, 4], np.int32), np.zeros(2, np.int32), 0, want_logits=False)
     kv = s.read_kv(0, 0, 1)
