@@ -190,9 +190,11 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R) {
   float o = v / l_n;
   size_t oi = (size_t)m * p.D + head * HD + dim;
   if (OUT == 1) {
+    // (hi, lo) pair in the matrix-core activation layout: [m / 8][16 pseudo-rows][D]
     uint16_t hi = f32_to_bf16(o);
-    p.attn_hi[oi] = hi;
-    p.attn_lo[oi] = f32_to_bf16(o - bf16_to_f32(hi));
+    size_t xi = (size_t)((m >> 3) * 16 + (m & 7)) * p.D + head * HD + dim;
+    p.attn_x[xi] = hi;
+    p.attn_x[xi + (size_t)8 * p.D] = f32_to_bf16(o - bf16_to_f32(hi));
   } else {
     p.attn[oi] = o;
   }

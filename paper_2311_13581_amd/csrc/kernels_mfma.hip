@@ -11,10 +11,13 @@
 // partial tiles are reduced through LDS in a fixed order (deterministic).
 //
 // Activations keep fp32-like precision although the matrix core takes bf16: every activation x
-// is carried as a pair (hi, lo) of bf16 values, hi = bf16(x), lo = bf16(x - hi), and each weight
-// tile is multiplied with both (two MFMAs).  At M = 5 the matrix core runs at a few percent of
-// its rate, so the second MFMA is free, and nothing but the weights and the K/V cache is ever
-// rounded to 8 bits of mantissa ("models are loaded in bfloat16" is a statement about storage).
+// is carried as a pair (hi, lo) of bf16 values, hi = bf16(x), lo = bf16(x - hi).  Eight rows fill
+// one 16-column MFMA: columns 0..7 take the hi halves, columns 8..15 the lo halves of the same
+// rows, and the epilogue adds column j+8 to column j.  So a (1+k)-row call with k <= 7 costs one
+// MFMA and one activation load per weight tile, and nothing but the weights and the K/V cache is
+// ever rounded to 8 bits of mantissa ("models are loaded in bfloat16" is a statement about
+// storage).  Activation buffers are laid out for that: [group of 8 rows][16 pseudo-rows][K],
+// pseudo-row r < 8 = hi of row r, 8 + r = lo of row r.
 //
 // Fused epilogues:
 //   QKV     : RMSNorm scale, rotary embedding, q (fp32) to the workspace, K/V rows (bf16) into
@@ -63,23 +66,26 @@ void launch_pack_tiles(const uint16_t *src, uint16_t *dst, int N, int K, int str
 }
 
 // ---------------------------------------------------------------------------------------------
-// (hi, lo) split of an fp32 value into two bf16: x = hi + lo up to 2^-17 relative
+// Activation rows as (hi, lo) bf16 pairs in MFMA column order: x = hi + lo up to 2^-17 relative
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void split_bf16(float x, uint16_t &hi, uint16_t &lo) {
-  hi = f32_to_bf16(x);
-  lo = f32_to_bf16(x - bf16_to_f32(hi));
-}
-__device__ __forceinline__ void store_split4(uint16_t *hi_p, uint16_t *lo_p, const float (&v)[4]) {
+__device__ __forceinline__ size_t xs_hi_index(int m, int K) { return (size_t)((m >> 3) * 16 + (m & 7)) * K; }
+
+// four consecutive features of row m
+__device__ __forceinline__ void store_split4(uint16_t *xs, int m, int K, int k, const float (&v)[4]) {
   uint16_t h[4], l[4];
 #pragma unroll
-  for (int r = 0; r < 4; ++r) split_bf16(v[r], h[r], l[r]);
+  for (int r = 0; r < 4; ++r) {
+    h[r] = f32_to_bf16(v[r]);
+    l[r] = f32_to_bf16(v[r] - bf16_to_f32(h[r]));
+  }
   uint2 ph, pl;
   ph.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
   ph.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
   pl.x = (uint32_t)l[0] | ((uint32_t)l[1] << 16);
   pl.y = (uint32_t)l[2] | ((uint32_t)l[3] << 16);
-  *(uint2 *)hi_p = ph;
-  *(uint2 *)lo_p = pl;
+  uint16_t *hp = xs + xs_hi_index(m, K) + k;
+  *(uint2 *)hp = ph;
+  *(uint2 *)(hp + (size_t)8 * K) = pl;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -105,13 +111,14 @@ __global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint
     src = tok_emb + (size_t)p.drafts[slot * kMaxK + (r - 1)] * p.d;
   }
   float ss = 0.f;
+  uint16_t *xh = p.xg + xs_hi_index(m, p.d), *xl = xh + (size_t)8 * p.d;
   for (int i = threadIdx.x; i < p.d; i += 256) {
     float v = bf16_to_f32(src[i]);
     p.h[(size_t)m * p.d + i] = v;
-    uint16_t hi, lo;
-    split_bf16(v * bf16_to_f32(gain0[i]), hi, lo);
-    p.xg_hi[(size_t)m * p.d + i] = hi;
-    p.xg_lo[(size_t)m * p.d + i] = lo;
+    float x = v * bf16_to_f32(gain0[i]);
+    uint16_t hi = f32_to_bf16(x);
+    xh[i] = hi;
+    xl[i] = f32_to_bf16(x - bf16_to_f32(hi));
     ss += v * v;
   }
 #pragma unroll
@@ -148,24 +155,25 @@ void launch_assemble_mfma(const Params &p, const void *tok_emb, const void *look
 enum { EPI_QKV = 0, EPI_RESID = 1, EPI_GATEUP = 2, EPI_LOGITS = 3 };
 
 struct GemmArgs {
-  const u32x4 *W;                // packed tiles
-  const uint16_t *Xhi, *Xlo;     // [M][K] bf16 pair: the activation rows
+  const u32x4 *W;             // packed weight tiles
+  const uint16_t *X;          // activation rows, (hi, lo) pseudo-row layout [ceil(M/8)][16][K]
   int M, K;
   int layer;
-  const uint16_t *gain_next;     // RESID: gain of the norm that follows
-  float *logits;                 // LOGITS: base of the [slot][1+k][V] logits
+  const uint16_t *gain_next;  // RESID: gain of the norm that follows
+  float *logits;              // LOGITS: base of the [slot][1+k][V] logits
 };
 
+// MT = number of 8-row groups (one MFMA column block each)
 template <int MT, int EPI, int WAVES, int U>
 __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArgs a) {
   constexpr int kGemmWaves = WAVES;
   constexpr int NS = (EPI == EPI_GATEUP) ? 2 : 1;
   constexpr bool NORM = (EPI != EPI_RESID);
-  __shared__ floatx4 red[kGemmWaves][NS][MT][64];
-  __shared__ float red_ss[kGemmWaves][MT][16];
+  __shared__ floatx4 red[kGemmWaves][NS][64];  // one 8-row group at a time
+  __shared__ float red_ss[kGemmWaves][MT][8];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int ml = lane & 15, g = lane >> 4;
+  const int ml = lane & 15, g = lane >> 4;  // ml: MFMA column = pseudo-row; g: k-group of 8
   const int KT = a.K >> 5;
   const int strip0 = blockIdx.x * NS;
 
@@ -175,99 +183,124 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) acc[s][mt] = floatx4{0.f, 0.f, 0.f, 0.f};
 
-  // weight tiles of one loop trip: k-tiles kt0 + u * WAVES, u < U (interleaved over the wavefronts,
-  // so the workgroup walks its strip front to back)
-  const u32x4 *wp = a.W + (size_t)strip0 * KT * 64 + lane;
-  u32x4 a_cur[U][NS], a_nxt[U][NS];
-  auto load_a = [&](u32x4 (&dst)[U][NS], int kt0) {
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      int kt = kt0 + u * kGemmWaves;
-#pragma unroll
-      for (int s = 0; s < NS; ++s)
-        dst[u][s] = (kt < KT) ? __builtin_nontemporal_load(wp + ((size_t)s * KT + kt) * 64) : u32x4{0, 0, 0, 0};
-    }
-  };
-  load_a(a_cur, wave);
-
-  bool xok[MT];
-  size_t xoff[MT];
+  // Activation loads go through a buffer descriptor: a lane whose pseudo-row belongs to a row
+  // >= M gets an out-of-range offset and the hardware returns zeros without touching memory.
+  // All loads are unconditional instructions, so outstanding requests are counted exactly and a
+  // trip can wait for its activations while the next trip's weight tiles stay in flight.
+  const int n_groups = (a.M + 7) >> 3;
+  const __amdgpu_buffer_rsrc_t xr =
+      __builtin_amdgcn_make_buffer_rsrc((void *)a.X, 0, n_groups * 16 * a.K * 2, 0x00020000);
+  int xoff[MT];  // byte offset of this lane's 16 bytes in k-tile 0
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    int m = mt * 16 + ml;
-    xok[mt] = m < a.M;
-    xoff[mt] = (size_t)(xok[mt] ? m : 0) * a.K + g * 8;
+    int m = mt * 8 + (ml & 7);
+    xoff[mt] = (m < a.M) ? ((mt * 16 + ml) * a.K + g * 8) * 2 : 0x40000000;
   }
+  const u32x4 *wp = a.W + (size_t)strip0 * KT * 64 + lane;
 
-  for (int kt0 = wave; kt0 < KT; kt0 += kGemmWaves * U) {
-    load_a(a_nxt, kt0 + kGemmWaves * U);  // next trip's weights are requested before this trip computes
-    u32x4 bh[U][MT], bl[U][MT];
+  auto load_a = [&](u32x4 (&dst)[U][NS], int kt0) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const int kt = kt0 + u * kGemmWaves;
+    for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        const bool in = kt < KT && xok[mt];
-        bh[u][mt] = in ? *(const u32x4 *)(a.Xhi + xoff[mt] + kt * 32) : u32x4{0, 0, 0, 0};
-        bl[u][mt] = in ? *(const u32x4 *)(a.Xlo + xoff[mt] + kt * 32) : u32x4{0, 0, 0, 0};
-      }
-    }
+      for (int s = 0; s < NS; ++s)
+        dst[u][s] = __builtin_nontemporal_load(wp + ((size_t)s * KT + kt0 + u * kGemmWaves) * 64);
+  };
+  auto load_b = [&](u32x4 (&dst)[U][MT], int kt0) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        dst[u][mt] = __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[mt] + (kt0 + u * kGemmWaves) * 64, 0, 0);
+  };
+  auto mma = [&](const u32x4 (&av)[U][NS], const u32x4 (&bv)[U][MT]) {
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int s = 0; s < NS; ++s)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur[u][s]),
-                                                               __builtin_bit_cast(bf16x8, bl[u][mt]), acc[s][mt], 0, 0, 0);
-          acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a_cur[u][s]),
-                                                               __builtin_bit_cast(bf16x8, bh[u][mt]), acc[s][mt], 0, 0, 0);
-        }
+        for (int mt = 0; mt < MT; ++mt)
+          acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av[u][s]),
+                                                               __builtin_bit_cast(bf16x8, bv[u][mt]), acc[s][mt], 0, 0, 0);
+  };
+
+  // full trips: k-tiles kt0 + u * WAVES, u < U, with kt0 = wave + trip * WAVES * U (interleaved
+  // over the wavefronts, so the workgroup walks its strip front to back)
+  const int trip_tiles = kGemmWaves * U;
+  const int n_trips = KT / trip_tiles;
+  if (n_trips > 0) {
+    u32x4 a_cur[U][NS], a_nxt[U][NS], bv[U][MT];
+    load_a(a_cur, wave);
+    for (int t = 0; t < n_trips - 1; ++t) {
+      const int kt0 = wave + t * trip_tiles;
+      load_b(bv, kt0);
+      load_a(a_nxt, kt0 + trip_tiles);  // requested after the activations: stays in flight through the MFMAs
+      mma(a_cur, bv);
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+      for (int u = 0; u < U; ++u)
 #pragma unroll
-      for (int s = 0; s < NS; ++s) a_cur[u][s] = a_nxt[u][s];
+        for (int s = 0; s < NS; ++s) a_cur[u][s] = a_nxt[u][s];
+    }
+    load_b(bv, wave + (n_trips - 1) * trip_tiles);
+    mma(a_cur, bv);
+  }
+  // tail: the k-tiles that do not fill a trip, one per wavefront and step (wavefront-uniform bound)
+  for (int kt = n_trips * trip_tiles + wave; kt < KT; kt += kGemmWaves) {
+    u32x4 bv[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) bv[mt] = __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[mt] + kt * 64, 0, 0);
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      u32x4 av = __builtin_nontemporal_load(wp + ((size_t)s * KT + kt) * 64);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av),
+                                                             __builtin_bit_cast(bf16x8, bv[mt]), acc[s][mt], 0, 0, 0);
+    }
   }
 
-  // partial sums of h^2 (written by the producer of X) -> this wavefront's share
+  // partial sums of h^2 (written by the producer of X) -> this wavefront's share.
+  // Lane (ml & 7) covers row mt*8 + (ml & 7); the two halves of the columns take alternate partials.
   if constexpr (NORM) {
     const int NP = p.d / 16;
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
       float ss = 0.f;
-      for (int i = wave * 4 + g; i < NP; i += kGemmWaves * 4) ss += p.ssq[(size_t)i * kMaxRows + mt * 16 + ml];
+      for (int i = wave * 8 + g * 2 + (ml >> 3); i < NP; i += kGemmWaves * 8)
+        ss += p.ssq[(size_t)i * kMaxRows + mt * 8 + (ml & 7)];
+      ss += __shfl_xor(ss, 8);
       ss += __shfl_xor(ss, 16);
       ss += __shfl_xor(ss, 32);
-      if (g == 0) red_ss[wave][mt][ml] = ss;
+      if (lane < 8) red_ss[wave][mt][lane] = ss;
     }
   }
-#pragma unroll
-  for (int s = 0; s < NS; ++s)
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) red[wave][s][mt][lane] = acc[s][mt];
-  __syncthreads();
-  if (wave != 0) return;
-
-  // wavefront 0: fixed-order reduction over the wavefronts, then the fused epilogue.
-  // Lane (ml, g) holds Y[m = mt*16 + ml][n0 + 4g .. 4g+3].
+  // Per 8-row group: every wavefront posts its partial tile, wavefront 0 reduces them in a fixed
+  // order, adds the lo columns to the hi columns and runs the fused epilogue.
+  // Lanes with ml < 8 hold Y[m = mt*8 + ml][n0 + 4g .. 4g+3].
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
+    if (mt > 0) __syncthreads();  // the previous group has been read
+#pragma unroll
+    for (int s = 0; s < NS; ++s) red[wave][s][lane] = acc[s][mt];
+    __syncthreads();
+    if (wave != 0) continue;
     floatx4 y[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      y[s] = red[0][s][mt][lane];
+      y[s] = red[0][s][lane];
 #pragma unroll
-      for (int w = 1; w < kGemmWaves; ++w) y[s] += red[w][s][mt][lane];
+      for (int w = 1; w < kGemmWaves; ++w) y[s] += red[w][s][lane];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) y[s][r] += __shfl_xor(y[s][r], 8);
     }
-    const int m = mt * 16 + ml;
+    const int m = mt * 8 + (ml & 7);
     float inv = 1.f;
     if constexpr (NORM) {
       float ss = 0.f;
 #pragma unroll
-      for (int w = 0; w < kGemmWaves; ++w) ss += red_ss[w][mt][ml];
+      for (int w = 0; w < kGemmWaves; ++w) ss += red_ss[w][mt][ml & 7];
       inv = 1.0f / sqrtf(ss / (float)p.d + p.eps);
     }
-    const bool live = m < a.M;
+    const bool live = m < a.M && ml < 8;
 
     if constexpr (EPI == EPI_LOGITS) {
       if (live) {
@@ -284,7 +317,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
           float gt = y[0][r] * inv, up = y[1][r] * inv;
           t[r] = gt / (1.0f + __expf(-gt)) * up;
         }
-        store_split4(p.act_hi + (size_t)m * p.F + f0, p.act_lo + (size_t)m * p.F + f0, t);
+        store_split4(p.act_x, m, p.F, f0, t);
       }
     } else if constexpr (EPI == EPI_RESID) {
       int n = strip0 * 16 + 4 * g;
@@ -299,11 +332,11 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
           t[r] = hv[r] * bf16_to_f32(a.gain_next[n + r]);
           ss += hv[r] * hv[r];
         }
-        store_split4(p.xg_hi + (size_t)m * p.d + n, p.xg_lo + (size_t)m * p.d + n, t);
+        store_split4(p.xg, m, p.d, n, t);
       }
       ss += __shfl_xor(ss, 16);
       ss += __shfl_xor(ss, 32);
-      if (g == 0) p.ssq[(size_t)strip0 * kMaxRows + m] = ss;  // rows >= M get 0
+      if (lane < 8) p.ssq[(size_t)strip0 * kMaxRows + m] = ss;  // rows >= M get 0
     } else {  // EPI_QKV
       if (live) {
         int n = strip0 * 16 + 4 * g;      // column in [0, 3D)
@@ -342,30 +375,34 @@ static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hi
   constexpr int NS = (EPI == EPI_GATEUP) ? 2 : 1;
   constexpr int T = kGemmWaves * 64;
   int grid = n_strips / NS;
-  int mt = (a.M + 15) / 16;
+  int mt = (a.M + 7) / 8;
   switch (mt) {
     case 1: gemm_mfma_kernel<1, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
     case 2: gemm_mfma_kernel<2, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
-    case 3: gemm_mfma_kernel<3, EPI, kGemmWaves, 1><<<grid, T, 0, s>>>(p, a); break;
-    default: gemm_mfma_kernel<4, EPI, kGemmWaves, 1><<<grid, T, 0, s>>>(p, a); break;
+    case 3: gemm_mfma_kernel<3, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
+    case 4: gemm_mfma_kernel<4, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
+    case 5: gemm_mfma_kernel<5, EPI, kGemmWaves, 1><<<grid, T, 0, s>>>(p, a); break;
+    case 6: gemm_mfma_kernel<6, EPI, kGemmWaves, 1><<<grid, T, 0, s>>>(p, a); break;
+    case 7: gemm_mfma_kernel<7, EPI, kGemmWaves, 1><<<grid, T, 0, s>>>(p, a); break;
+    default: gemm_mfma_kernel<8, EPI, kGemmWaves, 1><<<grid, T, 0, s>>>(p, a); break;
   }
 }
 
 void launch_gemm_qkv(const Params &p, const void *W, int layer, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, p.xg_hi, p.xg_lo, M, p.d, layer, nullptr, nullptr};
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, layer, nullptr, nullptr};
   launch_gemm_epi<EPI_QKV>(p, a, 3 * p.D / 16, s);
 }
-void launch_gemm_resid(const Params &p, const void *W, const uint16_t *Xhi, const uint16_t *Xlo, int K,
-                       const void *gain_next, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, Xhi, Xlo, M, K, 0, (const uint16_t *)gain_next, nullptr};
+void launch_gemm_resid(const Params &p, const void *W, const uint16_t *X, int K, const void *gain_next, int M,
+                       hipStream_t s) {
+  GemmArgs a{(const u32x4 *)W, X, M, K, 0, (const uint16_t *)gain_next, nullptr};
   launch_gemm_epi<EPI_RESID>(p, a, p.d / 16, s);
 }
 void launch_gemm_gateup(const Params &p, const void *W, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, p.xg_hi, p.xg_lo, M, p.d, 0, nullptr, nullptr};
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, nullptr};
   launch_gemm_epi<EPI_GATEUP>(p, a, 2 * p.F / 16, s);
 }
 void launch_gemm_logits(const Params &p, const void *W, float *logits, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, p.xg_hi, p.xg_lo, M, p.d, 0, nullptr, logits};
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, logits};
   launch_gemm_epi<EPI_LOGITS>(p, a, p.V / 16, s);
 }
 

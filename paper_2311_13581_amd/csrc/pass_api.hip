@@ -144,9 +144,7 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   P.rope_cos = A.take<float>(M * c.head_dim / 2); P.rope_sin = A.take<float>(M * c.head_dim / 2);
   P.h = A.take<float>(M * d); P.xn = A.take<float>(M * d); P.qkv = A.take<float>(M * 3 * D);
   P.attn = A.take<float>(M * D); P.gu = A.take<float>(M * 2 * F); P.act = A.take<float>(M * F);
-  P.attn_hi = A.take<uint16_t>(M * D); P.attn_lo = A.take<uint16_t>(M * D);
-  P.act_hi = A.take<uint16_t>(M * F); P.act_lo = A.take<uint16_t>(M * F);
-  P.xg_hi = A.take<uint16_t>(M * d); P.xg_lo = A.take<uint16_t>(M * d);
+  P.attn_x = A.take<uint16_t>(2 * M * D); P.act_x = A.take<uint16_t>(2 * M * F); P.xg = A.take<uint16_t>(2 * M * d);
   P.ssq = A.take<float>((d / 16 + 1) * M);
   P.part_acc = A.take<float>(M * c.n_heads * kMaxSplits * c.head_dim);
   P.part_m = A.take<float>(M * c.n_heads * kMaxSplits); P.part_l = A.take<float>(M * c.n_heads * kMaxSplits);
@@ -256,11 +254,11 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
       const LayerW &w = c->layers[l];
       launch_gemm_qkv(P, w.wqkv, l, M, s);
       launch_attention(P, dt, l, B, R, S, 1, s);
-      launch_gemm_resid(P, w.wo, P.attn_hi, P.attn_lo, P.D, w.ffn_norm, M, s);
+      launch_gemm_resid(P, w.wo, P.attn_x, P.D, w.ffn_norm, M, s);
       if (timing) HIP_TRY(c, hipEventRecord(c->kev[2 * l], s));
       launch_gemm_gateup(P, w.wgu, M, s);
       if (timing) HIP_TRY(c, hipEventRecord(c->kev[2 * l + 1], s));
-      launch_gemm_resid(P, w.wdown, P.act_hi, P.act_lo, P.F,
+      launch_gemm_resid(P, w.wdown, P.act_x, P.F,
                         l + 1 < P.L ? c->layers[l + 1].attn_norm : c->final_norm, M, s);
     }
     if (logits_base) launch_gemm_logits(P, c->lm_head, logits_base, M, s);

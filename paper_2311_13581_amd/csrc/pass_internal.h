@@ -61,10 +61,11 @@ struct Params {
   float *attn;     // [M][D]
   float *gu;       // [M][2F]  gate | up
   float *act;      // [M][F]
-  // matrix-core path: activations as (hi, lo) bf16 pairs, x = hi + lo
-  uint16_t *attn_hi, *attn_lo;  // [M][D]  attention output
-  uint16_t *act_hi, *act_lo;    // [M][F]  silu(gate) * up
-  uint16_t *xg_hi, *xg_lo;      // [M][d]  h * gain of the next norm
+  // matrix-core path: activations as (hi, lo) bf16 pairs, x = hi + lo, laid out
+  // [group of 8 rows][16 pseudo-rows: hi of rows 0..7, lo of rows 0..7][K]
+  uint16_t *attn_x;  // K = D  attention output
+  uint16_t *act_x;   // K = F  silu(gate) * up
+  uint16_t *xg;      // K = d  h * gain of the next norm
   float *ssq;           // [d/16][kMaxRows] per-strip partial sums of h^2
   float *part_acc, *part_m, *part_l;  // attention partials [M][H][S][hd], [M][H][S]
   // K/V pools: [layer][page][head][page_size][hd] in the model's storage type
@@ -92,7 +93,7 @@ void launch_gemm_generic(int dtype, const float *X, const void *W, float *out, i
                          const int32_t *rowmap, int accumulate, hipStream_t s);
 void launch_rope_kv(const Params &p, int dtype, int layer, int M, hipStream_t s);
 void launch_silu_mul(const Params &p, int round_bf16, int M, hipStream_t s);
-// attention (both paths).  out_split: 0 = fp32 into p.attn, 1 = (hi, lo) bf16 pair into p.attn_hi / p.attn_lo
+// attention (both paths).  out_split: 0 = fp32 into p.attn, 1 = (hi, lo) bf16 pairs into p.attn_x
 void launch_attention(const Params &p, int dtype, int layer, int B, int R, int n_splits, int out_bf16,
                       hipStream_t s);
 // sampling epilogues (both paths)
@@ -107,8 +108,8 @@ void launch_pack_tiles(const uint16_t *src, uint16_t *dst, int N, int K, int str
 void launch_assemble_mfma(const Params &p, const void *tok_emb, const void *lookahead, const void *gain0, int mode,
                           int B, int R, hipStream_t s);
 void launch_gemm_qkv(const Params &p, const void *W, int layer, int M, hipStream_t s);
-void launch_gemm_resid(const Params &p, const void *W, const uint16_t *Xhi, const uint16_t *Xlo, int K,
-                       const void *gain_next, int M, hipStream_t s);
+void launch_gemm_resid(const Params &p, const void *W, const uint16_t *X, int K, const void *gain_next, int M,
+                       hipStream_t s);
 void launch_gemm_gateup(const Params &p, const void *W, int M, hipStream_t s);
 void launch_gemm_logits(const Params &p, const void *W, float *logits, int M, hipStream_t s);
 
