@@ -7,36 +7,14 @@
 //
 // Grid: (split, head, group).  A group is up to 8 consecutive rows of one slot.  Within the
 // workgroup (4 wavefronts) 16 lanes share one key: each lane holds hd/16 dimensions, so a key or
-// value row is fetched as 16 adjacent 16-byte loads; a wavefront covers 4 keys per iteration and
-// the workgroup 16.  Partial (max, sum, accumulator) triples go to a workspace and a second
-// kernel merges the splits.
+// value row is fetched as 16 adjacent 16-byte loads.  An iteration covers 64 keys: every 16-lane
+// group requests the K and V chunks of 4 keys before it computes on any of them.  The 16-lane dot
+// product is reduced with DPP row operations (no LDS traffic).  The 16 lane groups merge their
+// (max, sum, accumulator) triples through LDS; the workgroup writes its split's triple to a
+// workspace and a second, tiny kernel merges the splits.
 #include "pass_internal.h"
 
 namespace pass {
-
-template <int DPL>
-__device__ __forceinline__ void load_chunk(const float *p, float (&o)[DPL]) {
-  static_assert(DPL == 4 || DPL == 8, "head_dim 64 or 128");
-#pragma unroll
-  for (int i = 0; i < DPL; i += 4) {
-    float4 a = *(const float4 *)(p + i);
-    o[i] = a.x; o[i + 1] = a.y; o[i + 2] = a.z; o[i + 3] = a.w;
-  }
-}
-template <int DPL>
-__device__ __forceinline__ void load_chunk(const bf16_t *p, float (&o)[DPL]) {
-  if constexpr (DPL == 8) {
-    uint4 v = *(const uint4 *)p;
-    o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
-    o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
-    o[4] = __uint_as_float(v.z << 16); o[5] = __uint_as_float(v.z & 0xffff0000u);
-    o[6] = __uint_as_float(v.w << 16); o[7] = __uint_as_float(v.w & 0xffff0000u);
-  } else {
-    uint2 v = *(const uint2 *)p;
-    o[0] = __uint_as_float(v.x << 16); o[1] = __uint_as_float(v.x & 0xffff0000u);
-    o[2] = __uint_as_float(v.y << 16); o[3] = __uint_as_float(v.y & 0xffff0000u);
-  }
-}
 
 // How a row group's keys are cut into splits.  A function of the group's own key count only, so
 // that a sequence's arithmetic (and therefore its tokens) cannot depend on what else is batched.
@@ -45,12 +23,56 @@ __device__ __forceinline__ void split_plan(int n_keys, int &n_splits, int &chunk
   chunk = ((n_keys + n_splits - 1) / n_splits + 15) & ~15;
 }
 
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+// sum over the 16 lanes of a DPP row; every lane of the row ends with the total
+__device__ __forceinline__ float row_sum16(float v) {
+  v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);  // row_half_mirror
+  v += dpp_move<0x140>(v);  // row_mirror
+  return v;
+}
+
+template <int DPL>
+__device__ __forceinline__ void unpack_chunk(const float4 (&raw)[DPL / 4], float (&o)[DPL], const float *) {
+#pragma unroll
+  for (int i = 0; i < DPL / 4; ++i) { o[4 * i] = raw[i].x; o[4 * i + 1] = raw[i].y; o[4 * i + 2] = raw[i].z; o[4 * i + 3] = raw[i].w; }
+}
+template <int DPL>
+__device__ __forceinline__ void unpack_chunk(const uint32_t (&raw)[DPL / 2], float (&o)[DPL], const bf16_t *) {
+#pragma unroll
+  for (int i = 0; i < DPL / 2; ++i) { o[2 * i] = __uint_as_float(raw[i] << 16); o[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u); }
+}
+template <int DPL>
+__device__ __forceinline__ void load_raw(const float *p, float4 (&raw)[DPL / 4]) {
+#pragma unroll
+  for (int i = 0; i < DPL / 4; ++i) raw[i] = *(const float4 *)(p + 4 * i);
+}
+template <int DPL>
+__device__ __forceinline__ void load_raw(const bf16_t *p, uint32_t (&raw)[DPL / 2]) {
+  if constexpr (DPL == 8) {
+    uint4 v = *(const uint4 *)p;
+    raw[0] = v.x; raw[1] = v.y; raw[2] = v.z; raw[3] = v.w;
+  } else {
+    uint2 v = *(const uint2 *)p;
+    raw[0] = v.x; raw[1] = v.y;
+  }
+}
+template <typename T, int DPL> struct RawChunk;
+template <int DPL> struct RawChunk<float, DPL> { float4 v[DPL / 4]; };
+template <int DPL> struct RawChunk<bf16_t, DPL> { uint32_t v[DPL / 2]; };
+
 template <typename T, int HD>
 __global__ __launch_bounds__(256) void attn_split_kernel(Params p, int layer, int R) {
   constexpr int DPL = HD / 16;
   constexpr int RQ = kAttnRowsPerGroup;
-  __shared__ float s_m[4][RQ], s_l[4][RQ];
-  __shared__ float s_acc[4][RQ][HD];
+  constexpr int KU = 4;    // keys per 16-lane group and iteration
+  constexpr int NG = 16;   // 16-lane groups per workgroup
+  __shared__ float s_m[NG][RQ], s_l[NG][RQ];
+  __shared__ float s_acc[NG][RQ][HD];
 
   const int split = blockIdx.x, head = blockIdx.y, g = blockIdx.z;
   const int groups_per_slot = (R + RQ - 1) / RQ;
@@ -68,6 +90,7 @@ __global__ __launch_bounds__(256) void attn_split_kernel(Params p, int layer, in
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int sub = lane >> 4, dl = lane & 15;
+  const int grp = wave * 4 + sub;
   const T *kpool = (const T *)p.k_pool, *vpool = (const T *)p.v_pool;
   const float scale = rsqrtf((float)HD);
 
@@ -88,86 +111,75 @@ __global__ __launch_bounds__(256) void attn_split_kernel(Params p, int layer, in
     }
   }
 
-  for (int base = k_lo; base < k_hi; base += 16) {
-    const int key = base + wave * 4 + sub;
-    const bool valid = key < k_hi;
-    float kf[DPL], vf[DPL];
-    size_t off = 0;
-    if (valid) {
-      off = kv_offset(p, layer, slot, key, head) + dl * DPL;
-      load_chunk<DPL>(kpool + off, kf);
-      load_chunk<DPL>(vpool + off, vf);
-    } else {
+  for (int base = k_lo; base < k_hi; base += NG * KU) {
+    // request everything this iteration needs; keys past the range re-read the range's first key
+    RawChunk<T, DPL> kraw[KU], vraw[KU];
+    int key[KU];
 #pragma unroll
-      for (int i = 0; i < DPL; ++i) { kf[i] = 0.f; vf[i] = 0.f; }
+    for (int j = 0; j < KU; ++j) {
+      key[j] = base + j * NG + grp;
+      const int kk = key[j] < k_hi ? key[j] : k_lo;
+      const size_t off = kv_offset(p, layer, slot, kk, head) + dl * DPL;
+      load_raw<DPL>(kpool + off, kraw[j].v);
+      load_raw<DPL>(vpool + off, vraw[j].v);
     }
 #pragma unroll
-    for (int r = 0; r < RQ; ++r) {
-      float s = 0.f;
+    for (int j = 0; j < KU; ++j) {
+      const bool valid = key[j] < k_hi;
+      float kf[DPL], vf[DPL];
+      unpack_chunk<DPL>(kraw[j].v, kf, (const T *)nullptr);
+      unpack_chunk<DPL>(vraw[j].v, vf, (const T *)nullptr);
 #pragma unroll
-      for (int i = 0; i < DPL; ++i) s = fmaf(q[r][i], kf[i], s);
-      s += __shfl_xor(s, 1);
-      s += __shfl_xor(s, 2);
-      s += __shfl_xor(s, 4);
-      s += __shfl_xor(s, 8);
-      const bool ok = valid && (r < nr) && (key <= pos0 + r);
-      if (ok) {
-        float m_new = fmaxf(mx[r], s);
-        float alpha = (mx[r] == -INFINITY) ? 0.f : __expf(mx[r] - m_new);
-        float pw = __expf(s - m_new);
-        ls[r] = ls[r] * alpha + pw;
+      for (int r = 0; r < RQ; ++r) {
+        float s = 0.f;
 #pragma unroll
-        for (int i = 0; i < DPL; ++i) acc[r][i] = acc[r][i] * alpha + pw * vf[i];
-        mx[r] = m_new;
+        for (int i = 0; i < DPL; ++i) s = fmaf(q[r][i], kf[i], s);
+        s = row_sum16(s);
+        const bool ok = valid && (r < nr) && (key[j] <= pos0 + r);
+        if (ok) {
+          float m_new = fmaxf(mx[r], s);
+          float alpha = (mx[r] == -INFINITY) ? 0.f : __expf(mx[r] - m_new);
+          float pw = __expf(s - m_new);
+          ls[r] = ls[r] * alpha + pw;
+#pragma unroll
+          for (int i = 0; i < DPL; ++i) acc[r][i] = acc[r][i] * alpha + pw * vf[i];
+          mx[r] = m_new;
+        }
       }
     }
   }
 
-  // merge the 4 key sub-groups of the wavefront (lanes differing in bits 4 and 5)
+  // merge the 16 lane groups through LDS
 #pragma unroll
-  for (int o = 16; o <= 32; o <<= 1) {
+  for (int r = 0; r < RQ; ++r) {
+    if (dl == 0) { s_m[grp][r] = mx[r]; s_l[grp][r] = ls[r]; }
 #pragma unroll
-    for (int r = 0; r < RQ; ++r) {
-      float m_o = __shfl_xor(mx[r], o), l_o = __shfl_xor(ls[r], o);
-      float m_n = fmaxf(mx[r], m_o);
-      float fa = (mx[r] == -INFINITY) ? 0.f : __expf(mx[r] - m_n);
-      float fb = (m_o == -INFINITY) ? 0.f : __expf(m_o - m_n);
-      ls[r] = ls[r] * fa + l_o * fb;
-#pragma unroll
-      for (int i = 0; i < DPL; ++i) {
-        float a_o = __shfl_xor(acc[r][i], o);
-        acc[r][i] = acc[r][i] * fa + a_o * fb;
-      }
-      mx[r] = m_n;
-    }
-  }
-  if (sub == 0) {
-#pragma unroll
-    for (int r = 0; r < RQ; ++r) {
-      if (dl == 0) { s_m[wave][r] = mx[r]; s_l[wave][r] = ls[r]; }
-#pragma unroll
-      for (int i = 0; i < DPL; ++i) s_acc[wave][r][dl * DPL + i] = acc[r][i];
-    }
+    for (int i = 0; i < DPL; ++i) s_acc[grp][r][dl * DPL + i] = acc[r][i];
   }
   __syncthreads();
-  // merge the 4 wavefronts and write the partial of this split
+  const size_t pbase = ((size_t)(b * R + r0) * p.H + head) * kMaxSplits;  // row r: + r * H * kMaxSplits
   for (int e = threadIdx.x; e < nr * HD; e += 256) {
     int r = e / HD, dim = e % HD;
-    float m_n = fmaxf(fmaxf(s_m[0][r], s_m[1][r]), fmaxf(s_m[2][r], s_m[3][r]));
+    float m_n = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < NG; ++w) m_n = fmaxf(m_n, s_m[w][r]);
     float l_n = 0.f, v = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NG; ++w) {
       float f = (s_m[w][r] == -INFINITY) ? 0.f : __expf(s_m[w][r] - m_n);
       l_n += s_l[w][r] * f;
       v += s_acc[w][r][dim] * f;
     }
-    size_t pi = ((size_t)(b * R + r0 + r) * p.H + head) * kMaxSplits + split;
+    size_t pi = pbase + (size_t)r * p.H * kMaxSplits + split;
     p.part_acc[pi * HD + dim] = v;
     if (dim == 0) { p.part_m[pi] = m_n; p.part_l[pi] = l_n; }
   }
 }
 
-// Merge the split partials of one (row, head): out = sum_s acc_s e^{m_s - m} / sum_s l_s e^{m_s - m}
+// Merge the split partials of one (row, head): out = sum_s acc_s e^{m_s - m} / sum_s l_s e^{m_s - m}.
+// A kernel of its own: handing partials between workgroups inside one kernel needs device-scope
+// fences, which on this multi-die part write back and invalidate the per-die L2s and cost far more
+// than a launch.
 template <int HD, int OUT>
 __global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R) {
   int m = blockIdx.x, head = blockIdx.y, dim = threadIdx.x;
@@ -188,7 +200,6 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R) {
     v += p.part_acc[(pi + s) * HD + dim] * f;
   }
   float o = v / l_n;
-  size_t oi = (size_t)m * p.D + head * HD + dim;
   if (OUT == 1) {
     // (hi, lo) pair in the matrix-core activation layout: [m / 8][16 pseudo-rows][D]
     uint16_t hi = f32_to_bf16(o);
@@ -196,32 +207,32 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R) {
     p.attn_x[xi] = hi;
     p.attn_x[xi + (size_t)8 * p.D] = f32_to_bf16(o - bf16_to_f32(hi));
   } else {
-    p.attn[oi] = o;
+    p.attn[(size_t)m * p.D + head * HD + dim] = o;
   }
 }
 
-void launch_attention(const Params &p, int dtype, int layer, int B, int R, int n_splits, int out_bf16,
+void launch_attention(const Params &p, int dtype, int layer, int B, int R, int n_splits, int out_split,
                       hipStream_t s) {
   int groups = B * ((R + kAttnRowsPerGroup - 1) / kAttnRowsPerGroup);
-  dim3 grid(n_splits, p.H, groups);
+  dim3 grid(n_splits, p.H, groups), cgrid(B * R, p.H);
   if (p.hd == 128) {
     if (dtype == PASS_F32)
       attn_split_kernel<float, 128><<<grid, 256, 0, s>>>(p, layer, R);
     else
       attn_split_kernel<bf16_t, 128><<<grid, 256, 0, s>>>(p, layer, R);
-    if (out_bf16 == 1)
-      attn_combine_kernel<128, 1><<<dim3(B * R, p.H), 128, 0, s>>>(p, R);
+    if (out_split)
+      attn_combine_kernel<128, 1><<<cgrid, 128, 0, s>>>(p, R);
     else
-      attn_combine_kernel<128, 0><<<dim3(B * R, p.H), 128, 0, s>>>(p, R);
+      attn_combine_kernel<128, 0><<<cgrid, 128, 0, s>>>(p, R);
   } else {
     if (dtype == PASS_F32)
       attn_split_kernel<float, 64><<<grid, 256, 0, s>>>(p, layer, R);
     else
       attn_split_kernel<bf16_t, 64><<<grid, 256, 0, s>>>(p, layer, R);
-    if (out_bf16 == 1)
-      attn_combine_kernel<64, 1><<<dim3(B * R, p.H), 64, 0, s>>>(p, R);
+    if (out_split)
+      attn_combine_kernel<64, 1><<<cgrid, 64, 0, s>>>(p, R);
     else
-      attn_combine_kernel<64, 0><<<dim3(B * R, p.H), 64, 0, s>>>(p, R);
+      attn_combine_kernel<64, 0><<<cgrid, 64, 0, s>>>(p, R);
   }
 }
 

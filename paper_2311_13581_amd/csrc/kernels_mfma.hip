@@ -228,20 +228,25 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
   const int trip_tiles = kGemmWaves * U;
   const int n_trips = KT / trip_tiles;
   if (n_trips > 0) {
-    u32x4 a_cur[U][NS], a_nxt[U][NS], bv[U][MT];
+    // Both operands of trip t+1 are requested during trip t, activations first, so a trip only
+    // ever waits for requests that have had a whole trip to complete.
+    u32x4 a_cur[U][NS], a_nxt[U][NS], b_cur[U][MT], b_nxt[U][MT];
+    load_b(b_cur, wave);
     load_a(a_cur, wave);
     for (int t = 0; t < n_trips - 1; ++t) {
-      const int kt0 = wave + t * trip_tiles;
-      load_b(bv, kt0);
-      load_a(a_nxt, kt0 + trip_tiles);  // requested after the activations: stays in flight through the MFMAs
-      mma(a_cur, bv);
+      const int kt1 = wave + (t + 1) * trip_tiles;
+      load_b(b_nxt, kt1);
+      load_a(a_nxt, kt1);
+      mma(a_cur, b_cur);
 #pragma unroll
-      for (int u = 0; u < U; ++u)
+      for (int u = 0; u < U; ++u) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) a_cur[u][s] = a_nxt[u][s];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) b_cur[u][mt] = b_nxt[u][mt];
+      }
     }
-    load_b(bv, wave + (n_trips - 1) * trip_tiles);
-    mma(a_cur, bv);
+    mma(a_cur, b_cur);
   }
   // tail: the k-tiles that do not fill a trip, one per wavefront and step (wavefront-uniform bound)
   for (int kt = n_trips * trip_tiles + wave; kt < KT; kt += kGemmWaves) {
