@@ -119,7 +119,10 @@ class Pass:
             raise PassError(-1, "configuration not supported")
         self.arena = torch.empty(nbytes + 256, dtype=torch.uint8, device="cuda")
         base = (self.arena.data_ptr() + 255) & ~255
-        self.stream = torch.cuda.current_stream()
+        # a stream of the library's own (default priority): the null stream cannot be captured into
+        # HIP graphs.  Everything torch produced for us is complete before the library touches it.
+        self.stream = torch.cuda.Stream()
+        torch.cuda.synchronize()
         h = C.c_void_p()
         rc = self.lib.pass_create(C.byref(cfg), C.c_void_p(self.stream.cuda_stream), C.c_void_p(base), nbytes,
                                   C.byref(h))
@@ -163,6 +166,8 @@ class Pass:
             assert a.flags["C_CONTIGUOUS"] or a.size == 0
             return a.ctypes.data
 
+        if on_device:
+            torch.cuda.synchronize()  # tensors were produced on torch's streams
         w = PassWeights()
         keep = []
         for name in ("tok_emb", "lm_head", "final_norm"):

@@ -6,7 +6,9 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <map>
 #include <string>
+#include <tuple>
 #include <vector>
 
 #include "pass_internal.h"
@@ -63,6 +65,10 @@ struct pass_ctx {
   int32_t *block_table_host = nullptr;  // pinned mirror of P.block_table
   hipEvent_t ev[3];
   // optional timing of the dominant kernel (the gate/up GEMM): one event pair per layer
+  // captured (model call + epilogue) graphs, keyed by everything that is baked into the launches:
+  // mode, batch, attention grid width, sampling arguments
+  typedef std::tuple<int, int, int, uint32_t, uint32_t, uint32_t, int> GraphKey;
+  std::map<GraphKey, hipGraphExec_t> graphs;
   int opt_kernel_timing = 0;
   std::vector<hipEvent_t> kev;
   double kernel_ms = 0;
@@ -341,22 +347,59 @@ int max_keys_of(pass_ctx *c, const int32_t *slots, int B, int extra) {
 }
 
 // the two halves of an iteration, without host synchronisation
-int issue_draft(pass_ctx *c, const int32_t *slots, int B, const pass_sampling *sp, int commit) {
+int issue_call_eager(pass_ctx *c, int mode, const int32_t *slots, int B, const pass_sampling *sp, int commit) {
   const int R = 1 + c->cfg.k;
-  int rc = run_step(c, MODE_DRAFT, B, R, c->P.draft_logits, max_keys_of(c, slots, B, R), nullptr);
+  const bool draft = mode == MODE_DRAFT;
+  int rc = run_step(c, mode, B, R, draft ? c->P.draft_logits : c->P.verify_logits,
+                    max_keys_of(c, slots, B, draft ? R : R + 1), nullptr);
   if (rc) return rc;
-  launch_draft_epilogue(c->P, sample_args(sp, commit), B, R, c->stream);
+  if (draft)
+    launch_draft_epilogue(c->P, sample_args(sp, commit), B, R, c->stream);
+  else
+    launch_verify_epilogue(c->P, sample_args(sp, commit), B, R, c->stream);
   HIP_TRY(c, hipGetLastError());
   return PASS_OK;
 }
 
-int issue_verify(pass_ctx *c, const int32_t *slots, int B, const pass_sampling *sp, int commit) {
+// One model call plus its sampling epilogue.  With the "graph" option the launches are captured
+// once per (mode, batch, attention grid width, sampling arguments) and replayed: every kernel
+// reads positions, slots and tokens from device memory, so a replay needs no new arguments.
+int issue_call(pass_ctx *c, int mode, const int32_t *slots, int B, const pass_sampling *sp, int commit) {
+  // the null stream cannot be captured: graphs need a stream of their own
+  if (!c->opt_graph || c->opt_kernel_timing || c->stream == nullptr) return issue_call_eager(c, mode, slots, B, sp, commit);
   const int R = 1 + c->cfg.k;
-  int rc = run_step(c, MODE_VERIFY, B, R, c->P.verify_logits, max_keys_of(c, slots, B, R + 1), nullptr);
-  if (rc) return rc;
-  launch_verify_epilogue(c->P, sample_args(sp, commit), B, R, c->stream);
-  HIP_TRY(c, hipGetLastError());
+  const int S = choose_splits(c, B, R, max_keys_of(c, slots, B, mode == MODE_DRAFT ? R : R + 1));
+  uint32_t tbits;
+  memcpy(&tbits, &sp->temperature, 4);
+  pass_ctx::GraphKey key(mode, B, S, tbits, (uint32_t)sp->seed, (uint32_t)(sp->seed >> 32), commit);
+  auto it = c->graphs.find(key);
+  if (it == c->graphs.end()) {
+    if (c->graphs.size() >= 64) {  // bound the cache: drop everything, recapture on demand
+      for (auto &g : c->graphs) (void)hipGraphExecDestroy(g.second);
+      c->graphs.clear();
+    }
+    hipGraph_t graph = nullptr;
+    HIP_TRY(c, hipStreamBeginCapture(c->stream, hipStreamCaptureModeThreadLocal));
+    int rc = issue_call_eager(c, mode, slots, B, sp, commit);
+    hipError_t e = hipStreamEndCapture(c->stream, &graph);
+    if (rc) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+    if (e != hipSuccess) return fail(c, PASS_EDEVICE, "hipStreamEndCapture: %s", hipGetErrorString(e));
+    hipGraphExec_t exec = nullptr;
+    e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (e != hipSuccess) return fail(c, PASS_EDEVICE, "hipGraphInstantiate: %s", hipGetErrorString(e));
+    it = c->graphs.emplace(key, exec).first;
+  }
+  HIP_TRY(c, hipGraphLaunch(it->second, c->stream));
   return PASS_OK;
+}
+
+int issue_draft(pass_ctx *c, const int32_t *slots, int B, const pass_sampling *sp, int commit) {
+  return issue_call(c, MODE_DRAFT, slots, B, sp, commit);
+}
+
+int issue_verify(pass_ctx *c, const int32_t *slots, int B, const pass_sampling *sp, int commit) {
+  return issue_call(c, MODE_VERIFY, slots, B, sp, commit);
 }
 
 }  // namespace
@@ -777,6 +820,7 @@ void pass_destroy(pass_ctx *c) {
   (void)hipStreamSynchronize(c->stream);
   for (auto &ev : c->ev) (void)hipEventDestroy(ev);
   for (auto &ev : c->kev) (void)hipEventDestroy(ev);
+  for (auto &g : c->graphs) (void)hipGraphExecDestroy(g.second);
   if (c->report_host) (void)hipHostFree(c->report_host);
   if (c->block_table_host) (void)hipHostFree(c->block_table_host);
   delete c;

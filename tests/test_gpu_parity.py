@@ -221,3 +221,29 @@ def test_7b_layer_shapes_two_layers():
         print(temp, st)
         assert st.iterations == 2
     g.close()
+
+
+def test_graph_replay_equals_eager_launches():
+    """The captured (model call + epilogue) graph is replayed many times with eager work (prefill,
+    report copies, synchronisations) in between; every replay must give what eager launches give:
+    stepwise against the oracle with graphs on, and token-identical generations graph on / off."""
+    w = MFMA_HD128
+    W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
+    m = O.Model(w.shape, W, w.k)
+    prompt = synth.make_prompts(w)[0]
+    outs = {}
+    for graph in (1, 0):
+        g = _gpu(w.shape, W, w.k, max_slots=2, options={"graph": graph})
+        st = parity.stepwise_parity(g, m, 0, 9, prompt, 8, 1.0, 4242, parity.LOGIT_TOL[synth.BF16])
+        assert st.iterations == 8 and st.resyncs == 0
+        toks = []
+        for rep in range(3):  # same sequence three times: replays after replays
+            g.prefill(1, prompt[:33], seq_id=rep)
+            toks.append(g.generate([1], 40, 0.7, 5)[0][0])
+        g.prefill(0, prompt, seq_id=3)
+        g.prefill(1, prompt[:50], seq_id=4)
+        toks.append(g.generate([0, 1], 30, 1.0, 6)[0])
+        outs[graph] = toks
+        g.close()
+    for a, b in zip(outs[1], outs[0]):
+        assert np.array_equal(a, b)
