@@ -31,9 +31,23 @@ def algorithmic_bytes_per_call(shape, k, ctx_lens):
 
 def gate_up_kernel_bytes(shape, M):
     """Algorithmic bytes of one launch of the dominant kernel (gate/up GEMM + SiLU*mul): both
-    weight matrices once, the M input rows (bf16), the M activation rows written (bf16)."""
+    weight matrices once, the M input rows and the M activation rows written (each a pair of bf16
+    halves, 4 bytes per element)."""
     esz = 2 if shape.dtype == 1 else 4
-    return 2 * shape.d_ffn * shape.d_model * esz + M * shape.d_model * 2 + M * shape.d_ffn * 2
+    return 2 * shape.d_ffn * shape.d_model * esz + M * shape.d_model * 4 + M * shape.d_ffn * 4
+
+
+def measured_traffic(workload_name):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); None if there is no
+    summary for this workload."""
+    path = os.path.join(ROOT, "profiles", "7b_k4_gate_up_gemm_hbm_traffic.txt")
+    if workload_name != "7b_k4_greedy" or not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return int(line.split(":")[1])
+    return None
 
 
 def cpu_baseline(w, k, budget_s=20.0):
@@ -83,6 +97,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path", type=int, default=0, help="1 = force the generic kernels")
     ap.add_argument("--graph", type=int, default=1)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (a kernel of known traffic, for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the decode path shards by sequence; no multi-GPU "
@@ -161,10 +178,17 @@ def main():
         "step_hbm": {"algorithmic_bytes_per_call": call_bytes, "achieved_GBps": step_gbs,
                      "frac_of_peak": step_gbs / HBM_PEAK_GBS},
         "roofline": {"bound": "hbm", "kernel": "gate_up_gemm_silu", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": measured_traffic(w.name) if not args.layers and k == w.k else None,
                      "bytes_per_launch": k_bytes, "avg_launch_us": k_avg_s * 1e6, "launches_timed": kn},
     }
     g.close()
+    if args.calibrate_copy:
+        src = torch.ones(128 * 2 ** 20, dtype=torch.bfloat16, device="cuda")  # 256 MiB read, 256 MiB written
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src * 1)  # elementwise kernel: reads 256 MiB, writes 256 MiB (then a copy of the same size)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, k)
     print(json.dumps(out))
