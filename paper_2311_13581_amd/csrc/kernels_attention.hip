@@ -176,19 +176,198 @@ __global__ __launch_bounds__(256) void attn_split_kernel(Params p, int layer, in
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Matrix-core variant for bf16 caches with head_dim 128 and V stored transposed
+// ([page][head][dim][page_size], page_size a multiple of 32).
+//
+// A wavefront owns 32 consecutive keys per step.  Scores: S^T[key][col] = K[key][:] . Q[col][:]
+// with the K rows as the MFMA A operand (two 16-key tiles x four 32-dim blocks) and the queries as
+// B operand; columns 0..7 carry the hi halves of the (scaled) query rows, columns 8..15 the lo
+// halves (q = hi + lo, both bf16), so the sum of the two column halves is the fp32-accurate score.
+// The key order inside the two tiles is chosen so that a lane ends up with the scores of 8
+// consecutive keys -- exactly the 8 key slots it feeds, as probabilities (again hi / lo halves by
+// column), into the second MFMA O^T[dim][col] += V^T[dim][key] P[key][col], whose A operand is
+// eight consecutive keys of one dimension: one 16-byte load from the transposed V page.
+// Online softmax keeps one running maximum per query row, shared by the lanes of a wavefront.
+// ---------------------------------------------------------------------------------------------
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void split_plan_mfma(int n_keys, int &n_splits, int &chunk) {
+  int steps = (n_keys + 127) / 128;                    // 128 keys = one step of a 4-wavefront workgroup
+  int per = (steps + kMaxSplits - 1) / kMaxSplits;     // steps per split
+  chunk = per * 128;
+  n_splits = (n_keys + chunk - 1) / chunk;
+}
+
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
+  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+__global__ __launch_bounds__(256) void attn_split_mfma_kernel(Params p, int layer, int R) {
+  constexpr int HD = 128, RQ = kAttnRowsPerGroup;
+  __shared__ float s_m[4][RQ], s_l[4][RQ];
+  __shared__ float s_acc[4][RQ][HD];
+
+  const int split = blockIdx.x, head = blockIdx.y, grp_id = blockIdx.z;
+  const int groups_per_slot = (R + RQ - 1) / RQ;
+  const int b = grp_id / groups_per_slot;
+  const int r0 = (grp_id % groups_per_slot) * RQ;
+  const int nr = min(RQ, R - r0);
+  const int m0 = b * R + r0;
+  const int slot = p.row_slot[m0];
+  const int pos0 = p.row_pos[m0];
+  const int n_keys = pos0 + nr;
+  int n_splits, chunk;
+  split_plan_mfma(n_keys, n_splits, chunk);
+  if (split >= n_splits) return;
+  const int k_lo = split * chunk;
+  const int k_hi = min(n_keys, k_lo + chunk);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int ml = lane & 15, g = lane >> 4;
+  const int row = ml & 7;  // query row of this lane's column (both column halves)
+  const uint16_t *kpool = (const uint16_t *)p.k_pool, *vpool = (const uint16_t *)p.v_pool;
+
+  // query fragment: column ml = hi (ml < 8) or lo (ml >= 8) half of row (ml & 7), scaled by 1/sqrt(hd)
+  u32x4_t qf[4];
+  {
+    const float scale = rsqrtf((float)HD);
+    const bool live = row < nr;
+    const float *qp = p.qkv + (size_t)(m0 + (live ? row : 0)) * 3 * p.D + head * HD + g * 8;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float v[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float x = live ? qp[j * 32 + e] * scale : 0.f;
+        float hi = bf16_to_f32(f32_to_bf16(x));
+        v[e] = (ml < 8) ? hi : x - hi;
+      }
+      qf[j] = u32x4_t{pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3]), pack2_bf16(v[4], v[5]), pack2_bf16(v[6], v[7])};
+    }
+  }
+
+  f32x4_t o[8];
+#pragma unroll
+  for (int db = 0; db < 8; ++db) o[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+  float m_run = -INFINITY, l_run = 0.f;
+
+  for (int base = k_lo + wave * 32; base < k_hi; base += 128) {
+    // one page holds the 32 keys (page_size is a multiple of 32); the lookup is wavefront-uniform
+    const int page = p.block_table[(size_t)slot * p.pages_per_seq + (base >> p.page_shift)];
+    const int poff = base & (p.page_size - 1);
+    const size_t hbase = ((size_t)layer * p.n_pages + page) * p.H + head;
+    const uint16_t *kp = kpool + (hbase * p.page_size + poff) * HD;   // K[key][dim]
+    const uint16_t *vp = vpool + hbase * HD * p.page_size + poff;     // Vt[dim][key]
+    u32x4_t kt[2][4], vt[8];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int key = (ml >> 2) * 8 + t * 4 + (ml & 3);  // key slot ml of tile t
+#pragma unroll
+      for (int j = 0; j < 4; ++j) kt[t][j] = *(const u32x4_t *)(kp + (size_t)key * HD + j * 32 + g * 8);
+    }
+#pragma unroll
+    for (int db = 0; db < 8; ++db) vt[db] = *(const u32x4_t *)(vp + (size_t)(db * 16 + ml) * p.page_size + g * 8);
+
+    f32x4_t sc[2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      sc[t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kt[t][j]),
+                                                        __builtin_bit_cast(bf16x8_t, qf[j]), sc[t], 0, 0, 0);
+    }
+    // lane (column ml, g) now holds the scores of keys base + 8g + 4t + r; add the lo-half column
+    float s[8];
+    float m_blk = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        float v = sc[t][r];
+        v += dpp_move<0x128>(v);  // row_ror 8: column ml <-> ml + 8
+        const int key = base + 8 * g + 4 * t + r;
+        const bool ok = (row < nr) && (key < k_hi) && (key <= pos0 + row);
+        v = ok ? v : -INFINITY;
+        s[4 * t + r] = v;
+        m_blk = fmaxf(m_blk, v);
+      }
+    m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 16));
+    m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32));
+    const float m_new = fmaxf(m_run, m_blk);
+    const float alpha = (m_run == -INFINITY) ? 0.f : __expf(m_run - m_new);
+    float pv[8], psum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      float pe = (s[i] == -INFINITY) ? 0.f : __expf(s[i] - m_new);
+      psum += pe;
+      float hi = bf16_to_f32(f32_to_bf16(pe));
+      pv[i] = (ml < 8) ? hi : pe - hi;
+    }
+    l_run = l_run * alpha + psum;
+    m_run = m_new;
+    const u32x4_t pf = {pack2_bf16(pv[0], pv[1]), pack2_bf16(pv[2], pv[3]), pack2_bf16(pv[4], pv[5]),
+                        pack2_bf16(pv[6], pv[7])};
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      o[db] *= alpha;
+      o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vt[db]),
+                                                      __builtin_bit_cast(bf16x8_t, pf), o[db], 0, 0, 0);
+    }
+  }
+
+  // a row's sum of probabilities is spread over the four g groups
+  l_run += __shfl_xor(l_run, 16);
+  l_run += __shfl_xor(l_run, 32);
+  // hi + lo column halves; lane (ml < 8, g) then holds dims db*16 + 4g + r of row ml
+#pragma unroll
+  for (int db = 0; db < 8; ++db)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) o[db][r] += dpp_move<0x128>(o[db][r]);
+  if (ml < 8) {
+    if (g == 0) { s_m[wave][ml] = m_run; s_l[wave][ml] = l_run; }
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) s_acc[wave][ml][db * 16 + 4 * g + r] = o[db][r];
+  }
+  __syncthreads();
+  const size_t pbase = ((size_t)m0 * p.H + head) * kMaxSplits;
+  for (int e = threadIdx.x; e < nr * HD; e += 256) {
+    int r = e / HD, dim = e % HD;
+    float m_n = fmaxf(fmaxf(s_m[0][r], s_m[1][r]), fmaxf(s_m[2][r], s_m[3][r]));
+    float l_n = 0.f, v = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      float f = (s_m[w][r] == -INFINITY) ? 0.f : __expf(s_m[w][r] - m_n);
+      l_n += s_l[w][r] * f;
+      v += s_acc[w][r][dim] * f;
+    }
+    size_t pi = pbase + (size_t)r * p.H * kMaxSplits + split;
+    p.part_acc[pi * HD + dim] = v;
+    if (dim == 0) { p.part_m[pi] = m_n; p.part_l[pi] = l_n; }
+  }
+}
+
 // Merge the split partials of one (row, head): out = sum_s acc_s e^{m_s - m} / sum_s l_s e^{m_s - m}.
 // A kernel of its own: handing partials between workgroups inside one kernel needs device-scope
 // fences, which on this multi-die part write back and invalidate the per-die L2s and cost far more
 // than a launch.
 template <int HD, int OUT>
-__global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R) {
+__global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R, int mfma_plan) {
   int m = blockIdx.x, head = blockIdx.y, dim = threadIdx.x;
   // the row's group and its split plan, recomputed exactly as the split kernel did
   constexpr int RQ = kAttnRowsPerGroup;
   int b = m / R, r = m % R, r0 = (r / RQ) * RQ;
   int n_keys = p.kv_len[p.step_slots[b]] + r0 + min(RQ, R - r0);
   int n_splits, chunk;
-  split_plan(n_keys, n_splits, chunk);
+  if (mfma_plan)
+    split_plan_mfma(n_keys, n_splits, chunk);
+  else
+    split_plan(n_keys, n_splits, chunk);
   size_t pi = ((size_t)m * p.H + head) * kMaxSplits;
   float m_n = -INFINITY;
   for (int s = 0; s < n_splits; ++s) m_n = fmaxf(m_n, p.part_m[pi + s]);
@@ -215,24 +394,32 @@ void launch_attention(const Params &p, int dtype, int layer, int B, int R, int n
                       hipStream_t s) {
   int groups = B * ((R + kAttnRowsPerGroup - 1) / kAttnRowsPerGroup);
   dim3 grid(n_splits, p.H, groups), cgrid(B * R, p.H);
+  if (p.v_transposed) {  // bf16, head_dim 128, page_size % 32 == 0: matrix-core kernel
+    attn_split_mfma_kernel<<<grid, 256, 0, s>>>(p, layer, R);
+    if (out_split)
+      attn_combine_kernel<128, 1><<<cgrid, 128, 0, s>>>(p, R, 1);
+    else
+      attn_combine_kernel<128, 0><<<cgrid, 128, 0, s>>>(p, R, 1);
+    return;
+  }
   if (p.hd == 128) {
     if (dtype == PASS_F32)
       attn_split_kernel<float, 128><<<grid, 256, 0, s>>>(p, layer, R);
     else
       attn_split_kernel<bf16_t, 128><<<grid, 256, 0, s>>>(p, layer, R);
     if (out_split)
-      attn_combine_kernel<128, 1><<<cgrid, 128, 0, s>>>(p, R);
+      attn_combine_kernel<128, 1><<<cgrid, 128, 0, s>>>(p, R, 0);
     else
-      attn_combine_kernel<128, 0><<<cgrid, 128, 0, s>>>(p, R);
+      attn_combine_kernel<128, 0><<<cgrid, 128, 0, s>>>(p, R, 0);
   } else {
     if (dtype == PASS_F32)
       attn_split_kernel<float, 64><<<grid, 256, 0, s>>>(p, layer, R);
     else
       attn_split_kernel<bf16_t, 64><<<grid, 256, 0, s>>>(p, layer, R);
     if (out_split)
-      attn_combine_kernel<64, 1><<<cgrid, 64, 0, s>>>(p, R);
+      attn_combine_kernel<64, 1><<<cgrid, 64, 0, s>>>(p, R, 0);
     else
-      attn_combine_kernel<64, 0><<<cgrid, 64, 0, s>>>(p, R);
+      attn_combine_kernel<64, 0><<<cgrid, 64, 0, s>>>(p, R, 0);
   }
 }
 

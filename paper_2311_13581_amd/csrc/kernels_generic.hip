@@ -225,7 +225,11 @@ __global__ void fill_i32_kernel(int32_t *p, int32_t v, size_t n) {
 }
 void launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t s) {
   if (n == 0) return;
-  fill_i32_kernel<<<(unsigned)((n + 255) / 256), 256, 0, s>>>(p, v, n);
+  // chunks of 2^30 elements keep the grid size inside 32 bits
+  for (size_t done = 0; done < n; done += (size_t)1 << 30) {
+    size_t m = n - done < ((size_t)1 << 30) ? n - done : (size_t)1 << 30;
+    fill_i32_kernel<<<(unsigned)((m + 255) / 256), 256, 0, s>>>(p + done, v, m);
+  }
 }
 
 }  // namespace pass

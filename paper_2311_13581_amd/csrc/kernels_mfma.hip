@@ -364,11 +364,21 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
         } else {
           // the cache is bf16 storage: the one place besides the weights where values are rounded
           uint16_t *pool = (uint16_t *)(which == 1 ? p.k_pool : p.v_pool);
-          size_t off = kv_offset(p, a.layer, p.row_slot[m], p.row_pos[m], head) + dim;
-          uint2 pk;
-          pk.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-          pk.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
-          *(uint2 *)(pool + off) = pk;
+          if (which == 2 && p.v_transposed) {
+            // V page for the matrix-core attention: [head][dim][page_size]
+            int pos = p.row_pos[m];
+            int page = p.block_table[(size_t)p.row_slot[m] * p.pages_per_seq + (pos >> p.page_shift)];
+            size_t base = ((((size_t)a.layer * p.n_pages + page) * p.H + head) * p.hd + dim) * p.page_size +
+                          (pos & (p.page_size - 1));
+#pragma unroll
+            for (int r = 0; r < 4; ++r) pool[base + (size_t)r * p.page_size] = f32_to_bf16(v[r]);
+          } else {
+            size_t off = kv_offset(p, a.layer, p.row_slot[m], p.row_pos[m], head) + dim;
+            uint2 pk;
+            pk.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+            pk.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+            *(uint2 *)(pool + off) = pk;
+          }
         }
       }
     }

@@ -55,7 +55,7 @@ struct pass_ctx {
   std::vector<LayerW> layers;
   bool weights_loaded = false;
   bool use_mfma = false;  // matrix-core path active (set by pass_load_weights)
-  int opt_graph = 0, opt_path = 0;
+  int opt_graph = 0, opt_path = 0, opt_attn = 0;
   // device scratch
   int32_t *prompt_buf, *report_dev;
   // host
@@ -238,7 +238,8 @@ int set_step_slots(pass_ctx *c, const int32_t *slots, int B) {
 int choose_splits(const pass_ctx *c, int B, int R, int max_keys) {
   // grid width only: each row group cuts its own keys by a rule of its own length (split_plan in
   // the attention kernel); workgroups beyond a group's split count exit at once
-  (void)c; (void)B; (void)R;
+  (void)B; (void)R;
+  if (c->P.v_transposed) return std::max(1, std::min(kMaxSplits, (max_keys + 127) / 128));
   return std::max(1, std::min(kMaxSplits, (max_keys + 63) / 64));
 }
 
@@ -447,6 +448,13 @@ int pass_create(const pass_config *cfg, void *hip_stream, void *device_arena, si
   launch_fill_i32(c->P.kv_len, 0, state_ints, c->stream);
   launch_fill_i32(c->P.block_table, 0, S * c->P.pages_per_seq, c->stream);
   launch_fill_i32(c->P.fallbacks, 0, 1, c->stream);
+  {
+    // K/V pools start as zeros: positions that are masked out of an attention tile are still
+    // multiplied (by probability 0) in the matrix-core kernel and must never hold NaN patterns
+    size_t pool_bytes = (size_t)cfg->n_layers * c->P.n_pages * cfg->n_heads * cfg->page_size * cfg->head_dim * c->esz;
+    launch_fill_i32((int32_t *)c->P.k_pool, 0, pool_bytes / 4, c->stream);
+    launch_fill_i32((int32_t *)c->P.v_pool, 0, pool_bytes / 4, c->stream);
+  }
   launch_fill_i32(c->P.gen_limit, INT_MAX, S, c->stream);
   launch_fill_i32(c->P.step_slots, 0, kMaxRows, c->stream);
   e = hipGetLastError();
@@ -472,6 +480,8 @@ int pass_load_weights(pass_ctx *c, const pass_weights *w, int on_device) {
   int rc = PASS_OK;
   c->use_mfma = c->opt_path != 1 && c->cfg.dtype == PASS_BF16 && d % 32 == 0 && D % 32 == 0 && F % 32 == 0 &&
                 V % 16 == 0;
+  // matrix-core attention: transposed V pages (nothing is cached yet, so the layout can still be chosen)
+  c->P.v_transposed = c->use_mfma && c->opt_attn != 1 && c->cfg.head_dim == 128 && c->cfg.page_size % 32 == 0;
   if (c->use_mfma) {
     // matrices go through the tile packer; on_device = 0 stages each tensor in the arena first
     auto pack = [&](void *dst, const void *src, size_t N, size_t K, int strip_off, int strip_stride) -> int {
@@ -779,6 +789,11 @@ int pass_set_option(pass_ctx *c, const char *name, int value) {
     c->opt_kernel_timing = value;
     c->kernel_ms = 0;
     c->kernel_launches = 0;
+    return PASS_OK;
+  }
+  if (!strcmp(name, "attention")) {
+    if (c->weights_loaded) return fail(c, PASS_ESTATE, "\"attention\" must be set before pass_load_weights");
+    c->opt_attn = value;
     return PASS_OK;
   }
   if (!strcmp(name, "path")) {

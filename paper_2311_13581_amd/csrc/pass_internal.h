@@ -38,6 +38,7 @@ struct Params {
   int L, d, H, hd, D, F, V, k;
   int max_slots, max_seq_len, page_size, page_shift, n_pages, pages_per_seq;
   int gen_cap;
+  int v_transposed;  // V pages hold [head][dim][page_size] (matrix-core attention) instead of [head][page_size][dim]
   float eps, rope_base;
   // per-slot state (device), indexed by slot
   int32_t *kv_len, *pending, *first, *drafts /*[slot][kMaxK]*/, *n_gen, *n_acc, *frozen, *gen_limit;

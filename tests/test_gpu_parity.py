@@ -247,3 +247,21 @@ def test_graph_replay_equals_eager_launches():
         g.close()
     for a, b in zip(outs[1], outs[0]):
         assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("temp", [0.0, 0.9])
+@pytest.mark.parametrize("plen", [5, 70, 200])
+def test_matrix_core_attention(temp, plen):
+    """bf16, head_dim 128, 64-position pages: the MFMA attention kernel over transposed V pages
+    (prompt lengths below one 32-key block, inside one step, and over several splits), against the
+    oracle, and against the lane-per-key kernel on the same model ("attention" option)."""
+    w = MFMA_HD128
+    W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
+    m = O.Model(w.shape, W, w.k)
+    prompt = np.random.default_rng(plen).integers(0, w.shape.vocab, plen).astype(np.int32)
+    for attn in (0, 1):
+        g = _gpu(w.shape, W, w.k, max_seq_len=384, page_size=64, options={"attention": attn})
+        st = parity.stepwise_parity(g, m, 0, 2, prompt, 6, temp, 777, parity.LOGIT_TOL[synth.BF16], max_len=384)
+        print(attn, st)
+        assert st.iterations == 6 and st.resyncs == 0 and st.max_rel_err < 1e-3
+        g.close()
