@@ -97,6 +97,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--path", type=int, default=0, help="1 = force the generic kernels")
     ap.add_argument("--graph", type=int, default=1)
+    ap.add_argument("--gemm-cfg", type=int, action="append", default=[],
+                    help="tuning: launch shape override(s), kind*10000 + wavefronts*100 + unroll")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (a kernel of known traffic, for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -119,6 +121,8 @@ def main():
     total_iters = args.steps + args.warmup + 8
     max_len = max(len(p) for p in prompts) + (k + 2) * total_iters + k + 2
     g = binding.Pass(binding.make_config(shape, k, w.batch, max_len, 64), {"path": args.path, "graph": args.graph})
+    for cfg in args.gemm_cfg:
+        g.set_option("gemm_cfg", cfg)
     W = devgen.device_weights(shape, k, w.lm_head_scale, w.seed)
     g.load_weights(W)
     del W

@@ -154,7 +154,9 @@ int pass_seq_len(pass_ctx *ctx, int slot, int32_t *kv_len, int32_t *n_generated)
 /* Options: "graph" (1 = replay each model call and its epilogue as a captured HIP graph; ignored
  * when the context runs on the null stream, which cannot be captured), "path" (0 = auto, 1 = force the generic
  * kernels; before pass_load_weights), "attention" (0 = auto, 1 = never use the matrix-core attention
- * kernel and its transposed V pages; before pass_load_weights), "kernel_timing" (1 = bracket every launch of the dominant
+ * kernel and its transposed V pages; before pass_load_weights), "gemm_cfg" (launch shape of the decode-sized matrix-core GEMMs, process-wide:
+ * kind * 10000 + wavefronts * 100 + unroll with kind 0 QKV, 1 Wo, 2 gate/up, 3 LM head, 4 down, wavefronts 4/8/16,
+ * unroll 1/2/4), "kernel_timing" (1 = bracket every launch of the dominant
  * kernel, the gate/up GEMM, with HIP events on the context's stream and synchronise after each
  * model call; setting it resets the counters).  Unknown names: PASS_EINVAL. */
 int pass_set_option(pass_ctx *ctx, const char *name, int value);

@@ -62,14 +62,15 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(LIB_PATH):
-        raise FileNotFoundError(f"{LIB_PATH} is not built: run `python -m paper_2311_13581_amd.build` "
+    path = os.environ.get("PASS_HIP_LIBRARY", LIB_PATH)  # development: compare two builds in one run
+    if not os.path.exists(path):
+        raise FileNotFoundError(f"{path} is not built: run `python -m paper_2311_13581_amd.build` "
                                 "(there is no fallback path)")
     # PyTorch ships its own HIP runtime under the same soname as the system one; whichever is
     # loaded first serves the whole process.  Import torch first so that the arena it allocates
     # and the kernels launched here share one runtime.
     import torch  # noqa: F401
-    L = C.CDLL(LIB_PATH)
+    L = C.CDLL(path)
     ip = C.POINTER(C.c_int32)
     L.pass_arena_bytes.restype = C.c_size_t
     L.pass_arena_bytes.argtypes = [C.POINTER(PassConfig)]

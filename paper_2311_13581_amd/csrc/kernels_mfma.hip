@@ -385,14 +385,48 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
   }
 }
 
+// Launch shape of the decode-sized GEMMs (one 8-row group): wavefronts per workgroup and k-tiles
+// per trip, per epilogue kind.  Defaults chosen by sweeping the benchmark on MI355X; the "gemm_cfg"
+// option of the library overrides them (value = kind * 10000 + wavefronts * 100 + unroll).
+static int g_cfg_waves[5] = {8, 16, 4, 16, 16};  // QKV, Wo, gate/up, LM head, down
+static int g_cfg_unroll[5] = {1, 1, 1, 2, 1};
+
+int set_gemm_config(int kind, int waves, int unroll) {
+  if (kind < 0 || kind > 4) return -1;
+  if (waves != 4 && waves != 8 && waves != 16) return -1;
+  if (unroll != 1 && unroll != 2 && unroll != 4) return -1;
+  g_cfg_waves[kind] = waves;
+  g_cfg_unroll[kind] = unroll;
+  return 0;
+}
+
+template <int EPI, int W, int U>
+static void launch_one(const Params &p, const GemmArgs &a, int grid, hipStream_t s) {
+  gemm_mfma_kernel<1, EPI, W, U><<<grid, W * 64, 0, s>>>(p, a);
+}
+
 template <int EPI>
-static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hipStream_t s) {
+static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hipStream_t s, int kind = EPI) {
   constexpr int NS = (EPI == EPI_GATEUP) ? 2 : 1;
   constexpr int T = kGemmWaves * 64;
   int grid = n_strips / NS;
   int mt = (a.M + 7) / 8;
+  if (mt == 1) {
+    const int w = g_cfg_waves[kind], u = g_cfg_unroll[kind];
+    switch (w * 10 + u) {
+      case 161: launch_one<EPI, 16, 1>(p, a, grid, s); break;
+      case 162: launch_one<EPI, 16, 2>(p, a, grid, s); break;
+      case 164: launch_one<EPI, 16, 4>(p, a, grid, s); break;
+      case 81: launch_one<EPI, 8, 1>(p, a, grid, s); break;
+      case 82: launch_one<EPI, 8, 2>(p, a, grid, s); break;
+      case 84: launch_one<EPI, 8, 4>(p, a, grid, s); break;
+      case 41: launch_one<EPI, 4, 1>(p, a, grid, s); break;
+      case 42: launch_one<EPI, 4, 2>(p, a, grid, s); break;
+      default: launch_one<EPI, 4, 4>(p, a, grid, s); break;
+    }
+    return;
+  }
   switch (mt) {
-    case 1: gemm_mfma_kernel<1, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
     case 2: gemm_mfma_kernel<2, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
     case 3: gemm_mfma_kernel<3, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
     case 4: gemm_mfma_kernel<4, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
@@ -410,7 +444,7 @@ void launch_gemm_qkv(const Params &p, const void *W, int layer, int M, hipStream
 void launch_gemm_resid(const Params &p, const void *W, const uint16_t *X, int K, const void *gain_next, int M,
                        hipStream_t s) {
   GemmArgs a{(const u32x4 *)W, X, M, K, 0, (const uint16_t *)gain_next, nullptr};
-  launch_gemm_epi<EPI_RESID>(p, a, p.d / 16, s);
+  launch_gemm_epi<EPI_RESID>(p, a, p.d / 16, s, K == p.F ? 4 : 1);  // the down projection has its own shape
 }
 void launch_gemm_gateup(const Params &p, const void *W, int M, hipStream_t s) {
   GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, nullptr};

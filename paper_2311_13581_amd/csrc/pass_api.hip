@@ -108,6 +108,7 @@ bool config_ok(const pass_config *c, std::string *why) {
   if (c->k < 0 || c->k > kMaxK) return bad("k out of range");
   if (c->max_slots < 1 || (1 + c->k) * c->max_slots > kMaxRows) return bad("(1+k)*max_slots exceeds PASS_MAX_ROWS");
   if (c->max_seq_len < 2 + c->k) return bad("max_seq_len too small");
+  if (c->max_seq_len > 65536) return bad("max_seq_len above 65536");
   if (c->page_size < 16 || (c->page_size & (c->page_size - 1))) return bad("page_size must be a power of two >= 16");
   if (c->n_pages < 0) return bad("n_pages negative");
   if (!(c->rms_eps > 0) || !(c->rope_base > 1)) return bad("rms_eps / rope_base");
@@ -785,6 +786,13 @@ int pass_seq_len(pass_ctx *c, int slot, int32_t *kv_len, int32_t *n_generated) {
 int pass_set_option(pass_ctx *c, const char *name, int value) {
   if (!c || !name) return PASS_EINVAL;
   if (!strcmp(name, "graph")) { c->opt_graph = value; return PASS_OK; }
+  if (!strcmp(name, "gemm_cfg")) {
+    if (set_gemm_config(value / 10000, (value / 100) % 100, value % 100))
+      return fail(c, PASS_EINVAL, "gemm_cfg: kind 0..4, wavefronts 4/8/16, unroll 1/2/4");
+    for (auto &g : c->graphs) (void)hipGraphExecDestroy(g.second);  // captured launches carry the old shape
+    c->graphs.clear();
+    return PASS_OK;
+  }
   if (!strcmp(name, "kernel_timing")) {
     c->opt_kernel_timing = value;
     c->kernel_ms = 0;

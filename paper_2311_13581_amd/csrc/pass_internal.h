@@ -112,6 +112,7 @@ void launch_gemm_qkv(const Params &p, const void *W, int layer, int M, hipStream
 void launch_gemm_resid(const Params &p, const void *W, const uint16_t *X, int K, const void *gain_next, int M,
                        hipStream_t s);
 void launch_gemm_gateup(const Params &p, const void *W, int M, hipStream_t s);
+int set_gemm_config(int kind, int waves, int unroll);  // kind: 0 QKV, 1 Wo, 2 gate/up, 3 LM head, 4 down
 void launch_gemm_logits(const Params &p, const void *W, float *logits, int M, hipStream_t s);
 
 }  // namespace pass
