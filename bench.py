@@ -99,6 +99,8 @@ def main():
     ap.add_argument("--graph", type=int, default=1)
     ap.add_argument("--gemm-cfg", type=int, action="append", default=[],
                     help="tuning: launch shape override(s), kind*10000 + wavefronts*100 + unroll")
+    ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
+                    help="tuning: a library option (pass_set_option) to set before the run")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (a kernel of known traffic, for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -123,6 +125,9 @@ def main():
     g = binding.Pass(binding.make_config(shape, k, w.batch, max_len, 64), {"path": args.path, "graph": args.graph})
     for cfg in args.gemm_cfg:
         g.set_option("gemm_cfg", cfg)
+    for opt in args.option:
+        name, val = opt.split("=")
+        g.set_option(name, int(val))
     W = devgen.device_weights(shape, k, w.lm_head_scale, w.seed)
     g.load_weights(W)
     del W

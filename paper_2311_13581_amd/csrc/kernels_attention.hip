@@ -201,10 +201,6 @@ __device__ __forceinline__ void split_plan_mfma(int n_keys, int &n_splits, int &
   n_splits = (n_keys + chunk - 1) / chunk;
 }
 
-__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
-}
-
 __global__ __launch_bounds__(256) void attn_split_mfma_kernel(Params p, int layer, int R) {
   constexpr int HD = 128, RQ = kAttnRowsPerGroup;
   __shared__ float s_m[4][RQ], s_l[4][RQ];
@@ -236,17 +232,22 @@ __global__ __launch_bounds__(256) void attn_split_mfma_kernel(Params p, int laye
     const float scale = rsqrtf((float)HD);
     const bool live = row < nr;
     const float *qp = p.qkv + (size_t)(m0 + (live ? row : 0)) * 3 * p.D + head * HD + g * 8;
+    // all eight 16-byte loads are issued before any is used (rows that do not exist read row 0
+    // and are zeroed afterwards: a load under a condition would be waited for on the spot)
+    f32x4_t raw[4][2];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      float v[8];
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float x = live ? qp[j * 32 + e] * scale : 0.f;
-        float hi = bf16_to_f32(f32_to_bf16(x));
-        v[e] = (ml < 8) ? hi : x - hi;
-      }
-      qf[j] = u32x4_t{pack2_bf16(v[0], v[1]), pack2_bf16(v[2], v[3]), pack2_bf16(v[4], v[5]), pack2_bf16(v[6], v[7])};
+      raw[j][0] = *(const f32x4_t *)(qp + j * 32);
+      raw[j][1] = *(const f32x4_t *)(qp + j * 32 + 4);
     }
+    const float sc_q = live ? scale : 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        qf[j][2 * h] = split2_bf16(raw[j][h][0] * sc_q, raw[j][h][1] * sc_q, ml < 8);
+        qf[j][2 * h + 1] = split2_bf16(raw[j][h][2] * sc_q, raw[j][h][3] * sc_q, ml < 8);
+      }
   }
 
   f32x4_t o[8];
@@ -302,15 +303,13 @@ __global__ __launch_bounds__(256) void attn_split_mfma_kernel(Params p, int laye
     float pv[8], psum = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      float pe = (s[i] == -INFINITY) ? 0.f : __expf(s[i] - m_new);
-      psum += pe;
-      float hi = bf16_to_f32(f32_to_bf16(pe));
-      pv[i] = (ml < 8) ? hi : pe - hi;
+      pv[i] = (s[i] == -INFINITY) ? 0.f : __expf(s[i] - m_new);
+      psum += pv[i];
     }
     l_run = l_run * alpha + psum;
     m_run = m_new;
-    const u32x4_t pf = {pack2_bf16(pv[0], pv[1]), pack2_bf16(pv[2], pv[3]), pack2_bf16(pv[4], pv[5]),
-                        pack2_bf16(pv[6], pv[7])};
+    const u32x4_t pf = {split2_bf16(pv[0], pv[1], ml < 8), split2_bf16(pv[2], pv[3], ml < 8),
+                        split2_bf16(pv[4], pv[5], ml < 8), split2_bf16(pv[6], pv[7], ml < 8)};
 #pragma unroll
     for (int db = 0; db < 8; ++db) {
       o[db] *= alpha;
@@ -369,22 +368,41 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R, int m
   else
     split_plan(n_keys, n_splits, chunk);
   size_t pi = ((size_t)m * p.H + head) * kMaxSplits;
-  float m_n = -INFINITY;
-  for (int s = 0; s < n_splits; ++s) m_n = fmaxf(m_n, p.part_m[pi + s]);
-  float l_n = 0.f, v = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    float ms = p.part_m[pi + s];
-    float f = (ms == -INFINITY) ? 0.f : __expf(ms - m_n);
-    l_n += p.part_l[pi + s] * f;
-    v += p.part_acc[(pi + s) * HD + dim] * f;
+  // eight splits at a time: their triples are requested together (indices clamped, surplus
+  // dropped) and merged into the running triple in split order
+  float m_n = -INFINITY, l_n = 0.f, v = 0.f;
+  for (int s0 = 0; s0 < n_splits; s0 += 8) {
+    float pm[8], pl[8], pa[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int s = min(s0 + u, n_splits - 1);
+      pm[u] = p.part_m[pi + s];
+      pl[u] = p.part_l[pi + s];
+      pa[u] = p.part_acc[(pi + s) * HD + dim];
+    }
+    float m_new = m_n;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (s0 + u < n_splits) m_new = fmaxf(m_new, pm[u]);
+    const float f0 = (m_n == -INFINITY) ? 0.f : __expf(m_n - m_new);
+    l_n *= f0;
+    v *= f0;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (s0 + u < n_splits) {
+        const float f = (pm[u] == -INFINITY) ? 0.f : __expf(pm[u] - m_new);
+        l_n += pl[u] * f;
+        v += pa[u] * f;
+      }
+    m_n = m_new;
   }
   float o = v / l_n;
   if (OUT == 1) {
-    // (hi, lo) pair in the matrix-core activation layout: [m / 8][16 pseudo-rows][D]
+    // (hi, lo) pair in the tiled activation layout of the matrix-core GEMMs
     uint16_t hi = f32_to_bf16(o);
-    size_t xi = (size_t)((m >> 3) * 16 + (m & 7)) * p.D + head * HD + dim;
+    size_t xi = xs_index(m, p.D, head * HD + dim);
     p.attn_x[xi] = hi;
-    p.attn_x[xi + (size_t)8 * p.D] = f32_to_bf16(o - bf16_to_f32(hi));
+    p.attn_x[xi + kXsLoOffset] = f32_to_bf16(o - bf16_to_f32(hi));
   } else {
     p.attn[(size_t)m * p.D + head * HD + dim] = o;
   }

@@ -99,6 +99,47 @@ __device__ MaxSum block_ms(MaxSum v, MaxSum *sh) {
   return r;
 }
 
+// Walk NR logits rows of V entries in groups of four consecutive entries ("quads", the unit one
+// Philox call covers): f(quad index, values[NR][4], number of valid entries).  A thread takes
+// quads threadIdx.x, + kEpiThreads, ... in ascending order.  When V is a multiple of 4 a quad is
+// one 16-byte load and the loads of four quads are issued before the first is used (indices
+// clamped, results of quads that do not exist dropped): a load under a condition would be
+// waited for on the spot, and a row is only V / (4 * kEpiThreads) quads deep per thread.
+template <int NR, typename F>
+__device__ __forceinline__ void scan_rows(const float *const (&rows)[NR], int V, F &&f) {
+  if ((V & 3) == 0) {
+    constexpr int U = 4;
+    const int V4 = V >> 2;
+    for (int q0 = threadIdx.x; q0 < V4; q0 += U * kEpiThreads) {
+      float4 v[U][NR];
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int r = 0; r < NR; ++r) v[u][r] = ((const float4 *)rows[r])[min(q0 + u * kEpiThreads, V4 - 1)];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int q = q0 + u * kEpiThreads;
+        if (q < V4) {
+          float x[NR][4];
+#pragma unroll
+          for (int r = 0; r < NR; ++r) { x[r][0] = v[u][r].x; x[r][1] = v[u][r].y; x[r][2] = v[u][r].z; x[r][3] = v[u][r].w; }
+          f(q, x, 4);
+        }
+      }
+    }
+  } else {
+    for (int q = threadIdx.x; q * 4 < V; q += kEpiThreads) {
+      const int n = min(4, V - q * 4);
+      float x[NR][4];
+#pragma unroll
+      for (int r = 0; r < NR; ++r)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[r][e] = rows[r][q * 4 + min(e, n - 1)];
+      f(q, x, n);
+    }
+  }
+}
+
 // Gumbel-max over softmax(logits * inv_t) (or plain argmax when greedy) fused with ln-sum-exp.
 __device__ void sample_row(const float *logits, int V, bool greedy, float inv_t, uint32_t k0, uint32_t k1,
                            uint32_t c1, uint32_t c2, uint32_t c3, Best &best, MaxSum &ms) {
@@ -106,14 +147,14 @@ __device__ void sample_row(const float *logits, int V, bool greedy, float inv_t,
   best.idx = -1;
   ms.m = -INFINITY;
   ms.s = 0.f;
-  for (int q4 = threadIdx.x; q4 * 4 < V; q4 += kEpiThreads) {
+  const float *const rows[1] = {logits};
+  scan_rows<1>(rows, V, [&](int q4, const float (&x)[1][4], int n) {
     uint32_t rnd[4] = {0, 0, 0, 0};
     if (!greedy) philox4x32_10((uint32_t)q4, c1, c2, c3, k0, k1, rnd);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      int j = q4 * 4 + e;
-      if (j < V) {
-        float l = logits[j];
+      if (e < n) {
+        float l = x[0][e];
         float a = l * inv_t;
         if (a > ms.m) {
           ms.s = (ms.m == -INFINITY) ? 1.f : ms.s * expf(ms.m - a) + 1.f;
@@ -123,11 +164,11 @@ __device__ void sample_row(const float *logits, int V, bool greedy, float inv_t,
         }
         Best c;
         c.s = greedy ? l : a + gumbel(u01(rnd[e]));
-        c.idx = j;
+        c.idx = q4 * 4 + e;
         best = better(best, c);
       }
     }
-  }
+  });
 }
 
 __global__ __launch_bounds__(kEpiThreads) void draft_epilogue_kernel(Params p, SampleArgs a, int R) {
@@ -234,23 +275,23 @@ __global__ __launch_bounds__(kEpiThreads) void verify_decide_kernel(Params p, Sa
     Best best;
     best.s = -INFINITY;
     best.idx = -1;
-    for (int q4 = threadIdx.x; q4 * 4 < V; q4 += kEpiThreads) {
+    const float *const rows[2] = {pr, dr};
+    scan_rows<2>(rows, V, [&](int q4, const float (&x)[2][4], int n) {
       uint32_t rnd[4];
       philox4x32_10((uint32_t)q4, it, c2, sid, a.seed_lo, a.seed_hi, rnd);
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
-        int j = q4 * 4 + e;
-        if (j < V) {
-          float w = expf(pr[j] * inv_t - z_p) - expf(dr[j] * inv_t - z_d);
+        if (e < n) {
+          float w = expf(x[0][e] * inv_t - z_p) - expf(x[1][e] * inv_t - z_d);
           if (w > 0.f) {
             Best c;
             c.s = logf(w) + gumbel(u01(rnd[e]));
-            c.idx = j;
+            c.idx = q4 * 4 + e;
             best = better(best, c);
           }
         }
       }
-    }
+    });
     best = block_best(best, sh_b);
     if (best.idx < 0) {
       // residual empty through rounding: draw from p_t with the same counters

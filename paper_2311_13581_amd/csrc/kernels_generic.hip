@@ -8,7 +8,8 @@ namespace pass {
 // Row assembly (Section 2.2.1: the look-ahead embeddings are appended after the sequence;
 // Algorithm 1: drafting call on (x_n, [LA]_1..[LA]_k), validation call on (x_{n+1}, drafts)).
 // Row m = b*R + r belongs to slot step_slots[b] at position kv_len[slot] + r.
-// Also fills the rotary table of the step (angles in double: pos * base^(-2i/hd)).
+// Also fills the rotary table of the step (angles in double: pos * base^(-2i/hd), the
+// frequencies from the table made at create).
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void assemble_kernel(Params p, const T *tok_emb, const T *lookahead, int mode,
@@ -30,9 +31,8 @@ __global__ __launch_bounds__(256) void assemble_kernel(Params p, const T *tok_em
   for (int i = threadIdx.x; i < p.d; i += blockDim.x) dst[i] = load_f(src, i);
   int half = p.hd / 2;
   for (int i = threadIdx.x; i < half; i += blockDim.x) {
-    double theta = pow((double)p.rope_base, -2.0 * (double)i / (double)p.hd);
     double sn, cs;
-    sincos((double)pos * theta, &sn, &cs);
+    sincos((double)pos * p.rope_theta[i], &sn, &cs);
     p.rope_cos[(size_t)m * half + i] = (float)cs;
     p.rope_sin[(size_t)m * half + i] = (float)sn;
   }

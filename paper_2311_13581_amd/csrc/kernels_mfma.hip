@@ -16,8 +16,10 @@
 // rows, and the epilogue adds column j+8 to column j.  So a (1+k)-row call with k <= 7 costs one
 // MFMA and one activation load per weight tile, and nothing but the weights and the K/V cache is
 // ever rounded to 8 bits of mantissa ("models are loaded in bfloat16" is a statement about
-// storage).  Activation buffers are laid out for that: [group of 8 rows][16 pseudo-rows][K],
-// pseudo-row r < 8 = hi of row r, 8 + r = lo of row r.
+// storage).  Activation buffers are laid out for that, in tiles like the weights:
+// [group of 8 rows][K/32][64 lanes][8], lane (k/8 % 4) * 16 + c holds 8 consecutive features of
+// pseudo-row c (c < 8: hi of row c, c >= 8: lo of row c - 8), so a wavefront fetches its B operand
+// of a k-tile as 1 KB of whole cache lines.
 //
 // Fused epilogues:
 //   QKV     : RMSNorm scale, rotary embedding, q (fp32) to the workspace, K/V rows (bf16) into
@@ -68,24 +70,17 @@ void launch_pack_tiles(const uint16_t *src, uint16_t *dst, int N, int K, int str
 // ---------------------------------------------------------------------------------------------
 // Activation rows as (hi, lo) bf16 pairs in MFMA column order: x = hi + lo up to 2^-17 relative
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ size_t xs_hi_index(int m, int K) { return (size_t)((m >> 3) * 16 + (m & 7)) * K; }
 
 // four consecutive features of row m
 __device__ __forceinline__ void store_split4(uint16_t *xs, int m, int K, int k, const float (&v)[4]) {
-  uint16_t h[4], l[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    h[r] = f32_to_bf16(v[r]);
-    l[r] = f32_to_bf16(v[r] - bf16_to_f32(h[r]));
-  }
   uint2 ph, pl;
-  ph.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-  ph.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
-  pl.x = (uint32_t)l[0] | ((uint32_t)l[1] << 16);
-  pl.y = (uint32_t)l[2] | ((uint32_t)l[3] << 16);
-  uint16_t *hp = xs + xs_hi_index(m, K) + k;
+  ph.x = pack2_bf16(v[0], v[1]);
+  ph.y = pack2_bf16(v[2], v[3]);
+  pl.x = pack2_bf16(v[0] - __uint_as_float(ph.x << 16), v[1] - __uint_as_float(ph.x & 0xffff0000u));
+  pl.y = pack2_bf16(v[2] - __uint_as_float(ph.y << 16), v[3] - __uint_as_float(ph.y & 0xffff0000u));
+  uint16_t *hp = xs + xs_index(m, K, k);
   *(uint2 *)hp = ph;
-  *(uint2 *)(hp + (size_t)8 * K) = pl;
+  *(uint2 *)(hp + kXsLoOffset) = pl;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -110,16 +105,33 @@ __global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint
   } else {
     src = tok_emb + (size_t)p.drafts[slot * kMaxK + (r - 1)] * p.d;
   }
+  // eight consecutive features per thread and trip: one 16-byte load of the embedding row and of
+  // the gain, two 16-byte stores of h, one 16-byte store each of the hi and the lo tile slots
   float ss = 0.f;
-  uint16_t *xh = p.xg + xs_hi_index(m, p.d), *xl = xh + (size_t)8 * p.d;
-  for (int i = threadIdx.x; i < p.d; i += 256) {
-    float v = bf16_to_f32(src[i]);
-    p.h[(size_t)m * p.d + i] = v;
-    float x = v * bf16_to_f32(gain0[i]);
-    uint16_t hi = f32_to_bf16(x);
-    xh[i] = hi;
-    xl[i] = f32_to_bf16(x - bf16_to_f32(hi));
-    ss += v * v;
+  for (int c0 = threadIdx.x * 8; c0 < p.d; c0 += 256 * 8) {
+    const uint4 sv = *(const uint4 *)(src + c0), gv = *(const uint4 *)(gain0 + c0);
+    const uint32_t sw[4] = {sv.x, sv.y, sv.z, sv.w}, gw[4] = {gv.x, gv.y, gv.z, gv.w};
+    float v[8], x[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[2 * e] = __uint_as_float(sw[e] << 16);
+      v[2 * e + 1] = __uint_as_float(sw[e] & 0xffff0000u);
+      x[2 * e] = v[2 * e] * __uint_as_float(gw[e] << 16);
+      x[2 * e + 1] = v[2 * e + 1] * __uint_as_float(gw[e] & 0xffff0000u);
+    }
+    float4 *hp = (float4 *)(p.h + (size_t)m * p.d + c0);
+    hp[0] = make_float4(v[0], v[1], v[2], v[3]);
+    hp[1] = make_float4(v[4], v[5], v[6], v[7]);
+    uint4 hi, lo;
+    hi.x = split2_bf16(x[0], x[1], true); lo.x = split2_bf16(x[0], x[1], false);
+    hi.y = split2_bf16(x[2], x[3], true); lo.y = split2_bf16(x[2], x[3], false);
+    hi.z = split2_bf16(x[4], x[5], true); lo.z = split2_bf16(x[4], x[5], false);
+    hi.w = split2_bf16(x[6], x[7], true); lo.w = split2_bf16(x[6], x[7], false);
+    uint16_t *xh = p.xg + xs_index(m, p.d, c0);
+    *(uint4 *)xh = hi;
+    *(uint4 *)(xh + kXsLoOffset) = lo;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
   }
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
@@ -130,9 +142,8 @@ __global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint
     p.ssq[(size_t)i * kMaxRows + m] = (i == 0) ? (red[0] + red[1] + red[2] + red[3]) : 0.f;
   int half = p.hd / 2;
   for (int i = threadIdx.x; i < half; i += 256) {
-    double theta = pow((double)p.rope_base, -2.0 * (double)i / (double)p.hd);
     double sn, cs;
-    sincos((double)pos * theta, &sn, &cs);
+    sincos((double)pos * p.rope_theta[i], &sn, &cs);
     p.rope_cos[(size_t)m * half + i] = (float)cs;
     p.rope_sin[(size_t)m * half + i] = (float)sn;
   }
@@ -156,19 +167,24 @@ enum { EPI_QKV = 0, EPI_RESID = 1, EPI_GATEUP = 2, EPI_LOGITS = 3 };
 
 struct GemmArgs {
   const u32x4 *W;             // packed weight tiles
-  const uint16_t *X;          // activation rows, (hi, lo) pseudo-row layout [ceil(M/8)][16][K]
+  const uint16_t *X;          // activation rows as (hi, lo) tiles [ceil(M/8)][K/32][64 lanes][8]
   int M, K;
   int layer;
   const uint16_t *gain_next;  // RESID: gain of the norm that follows
   float *logits;              // LOGITS: base of the [slot][1+k][V] logits
 };
 
-// MT = number of 8-row groups (one MFMA column block each)
-template <int MT, int EPI, int WAVES, int U>
+// MT = number of 8-row groups (one MFMA column block each); NB = output blocks per workgroup (a
+// block is one strip of 16 features, or the gate strip and the up strip of 16 FFN features).
+// Every activation tile a wavefront loads is used for all NB blocks, so the activation traffic
+// out of L2 per weight byte falls as 1/NB: that traffic, not HBM, bounds the calls with many rows.
+template <int MT, int EPI, int WAVES, int U, int NB>
 __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArgs a) {
   constexpr int kGemmWaves = WAVES;
-  constexpr int NS = (EPI == EPI_GATEUP) ? 2 : 1;
+  constexpr int PER = (EPI == EPI_GATEUP) ? 2 : 1;  // strips per block
+  constexpr int NS = NB * PER;
   constexpr bool NORM = (EPI != EPI_RESID);
+  static_assert(WAVES * NS <= 32 && NB <= WAVES, "reduction buffer must fit the static LDS limit");
   __shared__ floatx4 red[kGemmWaves][NS][64];  // one 8-row group at a time
   __shared__ float red_ss[kGemmWaves][MT][8];
 
@@ -194,7 +210,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     int m = mt * 8 + (ml & 7);
-    xoff[mt] = (m < a.M) ? ((mt * 16 + ml) * a.K + g * 8) * 2 : 0x40000000;
+    xoff[mt] = (m < a.M) ? (mt * KT * 64 + lane) * 16 : 0x40000000;
   }
   const u32x4 *wp = a.W + (size_t)strip0 * KT * 64 + lane;
 
@@ -210,7 +226,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
-        dst[u][mt] = __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[mt] + (kt0 + u * kGemmWaves) * 64, 0, 0);
+        dst[u][mt] = __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[mt] + (kt0 + u * kGemmWaves) * 1024, 0, 0);
   };
   auto mma = [&](const u32x4 (&av)[U][NS], const u32x4 (&bv)[U][MT]) {
 #pragma unroll
@@ -252,7 +268,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
   for (int kt = n_trips * trip_tiles + wave; kt < KT; kt += kGemmWaves) {
     u32x4 bv[MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) bv[mt] = __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[mt] + kt * 64, 0, 0);
+    for (int mt = 0; mt < MT; ++mt) bv[mt] = __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[mt] + kt * 1024, 0, 0);
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
       u32x4 av = __builtin_nontemporal_load(wp + ((size_t)s * KT + kt) * 64);
@@ -278,8 +294,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
       if (lane < 8) red_ss[wave][mt][lane] = ss;
     }
   }
-  // Per 8-row group: every wavefront posts its partial tile, wavefront 0 reduces them in a fixed
-  // order, adds the lo columns to the hi columns and runs the fused epilogue.
+  // Per 8-row group: every wavefront posts its partial tiles, wavefront j < NB reduces those of
+  // block j in a fixed order, adds the lo columns to the hi columns and runs the fused epilogue.
   // Lanes with ml < 8 hold Y[m = mt*8 + ml][n0 + 4g .. 4g+3].
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -287,13 +303,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
 #pragma unroll
     for (int s = 0; s < NS; ++s) red[wave][s][lane] = acc[s][mt];
     __syncthreads();
-    if (wave != 0) continue;
-    floatx4 y[NS];
+    if (wave >= NB) continue;
+    const int blk = wave;
+    const int strip = strip0 + blk * PER;
+    floatx4 y[PER];
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-      y[s] = red[0][s][lane];
+    for (int s = 0; s < PER; ++s) {
+      y[s] = red[0][blk * PER + s][lane];
 #pragma unroll
-      for (int w = 1; w < kGemmWaves; ++w) y[s] += red[w][s][lane];
+      for (int w = 1; w < kGemmWaves; ++w) y[s] += red[w][blk * PER + s][lane];
 #pragma unroll
       for (int r = 0; r < 4; ++r) y[s][r] += __shfl_xor(y[s][r], 8);
     }
@@ -309,13 +327,13 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
 
     if constexpr (EPI == EPI_LOGITS) {
       if (live) {
-        float *o = a.logits + (size_t)p.row_out[m] * p.V + strip0 * 16 + 4 * g;
+        float *o = a.logits + (size_t)p.row_out[m] * p.V + strip * 16 + 4 * g;
         *(floatx4 *)o = y[0] * inv;
       }
     } else if constexpr (EPI == EPI_GATEUP) {
       if (live) {
         // strips 2b (gate) and 2b+1 (up) of the interleaved matrix both belong to features 16b..16b+15
-        int f0 = blockIdx.x * 16 + 4 * g;
+        int f0 = (blockIdx.x * NB + blk) * 16 + 4 * g;
         float t[4];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -325,7 +343,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
         store_split4(p.act_x, m, p.F, f0, t);
       }
     } else if constexpr (EPI == EPI_RESID) {
-      int n = strip0 * 16 + 4 * g;
+      int n = strip * 16 + 4 * g;
       float ss = 0.f;
       if (live) {
         float *hp = p.h + (size_t)m * p.d + n;
@@ -341,10 +359,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
       }
       ss += __shfl_xor(ss, 16);
       ss += __shfl_xor(ss, 32);
-      if (lane < 8) p.ssq[(size_t)strip0 * kMaxRows + m] = ss;  // rows >= M get 0
+      if (lane < 8) p.ssq[(size_t)strip * kMaxRows + m] = ss;  // rows >= M get 0
     } else {  // EPI_QKV
       if (live) {
-        int n = strip0 * 16 + 4 * g;      // column in [0, 3D)
+        int n = strip * 16 + 4 * g;       // column in [0, 3D)
         int which = n / p.D;              // 0 q, 1 k, 2 v
         int c = n - which * p.D;          // column inside the projection
         int head = c / p.hd, dim = c - head * p.hd;
@@ -375,8 +393,8 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
           } else {
             size_t off = kv_offset(p, a.layer, p.row_slot[m], p.row_pos[m], head) + dim;
             uint2 pk;
-            pk.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
-            pk.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+            pk.x = pack2_bf16(v[0], v[1]);
+            pk.y = pack2_bf16(v[2], v[3]);
             *(uint2 *)(pool + off) = pk;
           }
         }
@@ -390,6 +408,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
 // option of the library overrides them (value = kind * 10000 + wavefronts * 100 + unroll).
 static int g_cfg_waves[5] = {8, 16, 4, 16, 16};  // QKV, Wo, gate/up, LM head, down
 static int g_cfg_unroll[5] = {1, 1, 1, 2, 1};
+// Calls with more than 8 rows: wavefronts and output blocks per workgroup
+// (override: 1000000 + kind * 10000 + wavefronts * 100 + blocks).
+static int g_big_waves[5] = {8, 16, 8, 8, 16};
+static int g_big_blocks[5] = {4, 1, 1, 4, 1};
 
 int set_gemm_config(int kind, int waves, int unroll) {
   if (kind < 0 || kind > 4) return -1;
@@ -400,18 +422,48 @@ int set_gemm_config(int kind, int waves, int unroll) {
   return 0;
 }
 
+int set_gemm_config_big(int kind, int waves, int blocks) {
+  if (kind < 0 || kind > 4) return -1;
+  if (waves != 8 && waves != 16) return -1;
+  if (blocks != 1 && blocks != 2 && blocks != 4) return -1;
+  g_big_waves[kind] = waves;
+  g_big_blocks[kind] = blocks;
+  return 0;
+}
+
 template <int EPI, int W, int U>
 static void launch_one(const Params &p, const GemmArgs &a, int grid, hipStream_t s) {
-  gemm_mfma_kernel<1, EPI, W, U><<<grid, W * 64, 0, s>>>(p, a);
+  gemm_mfma_kernel<1, EPI, W, U, 1><<<grid, W * 64, 0, s>>>(p, a);
+}
+
+template <int EPI, int W, int NB>
+static void launch_big(const Params &p, const GemmArgs &a, int n_blocks, int mt, hipStream_t s) {
+  constexpr int PER = (EPI == EPI_GATEUP) ? 2 : 1;
+  if constexpr (W * NB * PER > 32) {
+    launch_big<EPI, 8, 1>(p, a, n_blocks, mt, s);
+  } else {
+    const int grid = n_blocks / NB;
+    constexpr int T = W * 64;
+    constexpr int U2 = (NB == 1 && W == 16) ? 2 : 1;  // two k-tiles per trip while registers allow
+    switch (mt) {
+      case 2: gemm_mfma_kernel<2, EPI, W, U2, NB><<<grid, T, 0, s>>>(p, a); break;
+      case 3: gemm_mfma_kernel<3, EPI, W, U2, NB><<<grid, T, 0, s>>>(p, a); break;
+      case 4: gemm_mfma_kernel<4, EPI, W, U2, NB><<<grid, T, 0, s>>>(p, a); break;
+      case 5: gemm_mfma_kernel<5, EPI, W, 1, NB><<<grid, T, 0, s>>>(p, a); break;
+      case 6: gemm_mfma_kernel<6, EPI, W, 1, NB><<<grid, T, 0, s>>>(p, a); break;
+      case 7: gemm_mfma_kernel<7, EPI, W, 1, NB><<<grid, T, 0, s>>>(p, a); break;
+      default: gemm_mfma_kernel<8, EPI, W, 1, NB><<<grid, T, 0, s>>>(p, a); break;
+    }
+  }
 }
 
 template <int EPI>
 static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hipStream_t s, int kind = EPI) {
-  constexpr int NS = (EPI == EPI_GATEUP) ? 2 : 1;
-  constexpr int T = kGemmWaves * 64;
-  int grid = n_strips / NS;
+  constexpr int PER = (EPI == EPI_GATEUP) ? 2 : 1;
+  const int n_blocks = n_strips / PER;
   int mt = (a.M + 7) / 8;
   if (mt == 1) {
+    const int grid = n_blocks;
     const int w = g_cfg_waves[kind], u = g_cfg_unroll[kind];
     switch (w * 10 + u) {
       case 161: launch_one<EPI, 16, 1>(p, a, grid, s); break;
@@ -426,14 +478,15 @@ static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hi
     }
     return;
   }
-  switch (mt) {
-    case 2: gemm_mfma_kernel<2, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
-    case 3: gemm_mfma_kernel<3, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
-    case 4: gemm_mfma_kernel<4, EPI, kGemmWaves, 2><<<grid, T, 0, s>>>(p, a); break;
-    case 5: gemm_mfma_kernel<5, EPI, kGemmWaves, 1><<<grid, T, 0, s>>>(p, a); break;
-    case 6: gemm_mfma_kernel<6, EPI, kGemmWaves, 1><<<grid, T, 0, s>>>(p, a); break;
-    case 7: gemm_mfma_kernel<7, EPI, kGemmWaves, 1><<<grid, T, 0, s>>>(p, a); break;
-    default: gemm_mfma_kernel<8, EPI, kGemmWaves, 1><<<grid, T, 0, s>>>(p, a); break;
+  int w = g_big_waves[kind], nb = g_big_blocks[kind];
+  while (nb > 1 && n_blocks % nb != 0) nb >>= 1;  // a workgroup's blocks must all exist
+  switch (w * 10 + nb) {
+    case 161: launch_big<EPI, 16, 1>(p, a, n_blocks, mt, s); break;
+    case 162: launch_big<EPI, 16, 2>(p, a, n_blocks, mt, s); break;
+    case 81: launch_big<EPI, 8, 1>(p, a, n_blocks, mt, s); break;
+    case 82: launch_big<EPI, 8, 2>(p, a, n_blocks, mt, s); break;
+    case 84: launch_big<EPI, 8, 4>(p, a, n_blocks, mt, s); break;
+    default: launch_big<EPI, 16, 1>(p, a, n_blocks, mt, s); break;
   }
 }
 

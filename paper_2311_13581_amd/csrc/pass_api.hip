@@ -150,6 +150,7 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   P.step_slots = A.take<int32_t>(M);
   P.row_pos = A.take<int32_t>(M); P.row_slot = A.take<int32_t>(M); P.row_out = A.take<int32_t>(M);
   P.rope_cos = A.take<float>(M * c.head_dim / 2); P.rope_sin = A.take<float>(M * c.head_dim / 2);
+  P.rope_theta = A.take<double>(c.head_dim / 2);
   P.h = A.take<float>(M * d); P.xn = A.take<float>(M * d); P.qkv = A.take<float>(M * 3 * D);
   P.attn = A.take<float>(M * D); P.gu = A.take<float>(M * 2 * F); P.act = A.take<float>(M * F);
   P.attn_x = A.take<uint16_t>(2 * M * D); P.act_x = A.take<uint16_t>(2 * M * F); P.xg = A.take<uint16_t>(2 * M * d);
@@ -459,6 +460,11 @@ int pass_create(const pass_config *cfg, void *hip_stream, void *device_arena, si
   }
   launch_fill_i32(c->P.gen_limit, INT_MAX, S, c->stream);
   launch_fill_i32(c->P.step_slots, 0, kMaxRows, c->stream);
+  // rotary frequencies theta_i = base^(-2i/hd), in double (the angle pos * theta_i is formed in double too)
+  std::vector<double> theta(cfg->head_dim / 2);
+  for (int i = 0; i < cfg->head_dim / 2; ++i) theta[i] = pow((double)cfg->rope_base, -2.0 * i / (double)cfg->head_dim);
+  e = hipMemcpyAsync(c->P.rope_theta, theta.data(), theta.size() * sizeof(double), hipMemcpyHostToDevice, c->stream);
+  if (e != hipSuccess) return die(e);
   e = hipGetLastError();
   if (e != hipSuccess) return die(e);
   e = hipStreamSynchronize(c->stream);
@@ -788,7 +794,11 @@ int pass_set_option(pass_ctx *c, const char *name, int value) {
   if (!c || !name) return PASS_EINVAL;
   if (!strcmp(name, "graph")) { c->opt_graph = value; return PASS_OK; }
   if (!strcmp(name, "gemm_cfg")) {
-    if (set_gemm_config(value / 10000, (value / 100) % 100, value % 100))
+    if (value >= 1000000) {
+      int v = value - 1000000;
+      if (set_gemm_config_big(v / 10000, (v / 100) % 100, v % 100))
+        return fail(c, PASS_EINVAL, "gemm_cfg (more than 8 rows): kind 0..4, wavefronts 8/16, blocks 1/2/4");
+    } else if (set_gemm_config(value / 10000, (value / 100) % 100, value % 100))
       return fail(c, PASS_EINVAL, "gemm_cfg: kind 0..4, wavefronts 4/8/16, unroll 1/2/4");
     for (auto &g : c->graphs) (void)hipGraphExecDestroy(g.second);  // captured launches carry the old shape
     c->graphs.clear();

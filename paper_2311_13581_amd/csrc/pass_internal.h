@@ -21,11 +21,19 @@ struct bf16_t {
 };
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
+// round to nearest even; gfx950 has the conversion in hardware (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return __builtin_bit_cast(uint16_t, (__bf16)f); }
+// two values into one register: `lo` in bits 0..15, `hi` in bits 16..31
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t));
+}
+// (hi, lo) split of two values, x = hi + lo with both halves bf16: the hi pair or the lo pair
+__device__ __forceinline__ uint32_t split2_bf16(float a, float b, bool take_hi) {
+  uint32_t ph = pack2_bf16(a, b);
+  uint32_t pl = pack2_bf16(a - __uint_as_float(ph << 16), b - __uint_as_float(ph & 0xffff0000u));
+  return take_hi ? ph : pl;
 }
 __device__ __forceinline__ float load_f(const float *p, size_t i) { return p[i]; }
 __device__ __forceinline__ float load_f(const bf16_t *p, size_t i) { return bf16_to_f32(p[i].bits); }
@@ -55,6 +63,7 @@ struct Params {
   int32_t *prefill_ids;  // [R]
   int32_t *row_pos, *row_slot, *row_out;  // [M]
   float *rope_cos, *rope_sin;             // [M][hd/2]
+  double *rope_theta;                     // [hd/2] base^(-2i/hd), filled at create
   // workspaces
   float *h;        // [M][d]   residual stream
   float *xn;       // [M][d]
@@ -95,7 +104,7 @@ void launch_gemm_generic(int dtype, const float *X, const void *W, float *out, i
 void launch_rope_kv(const Params &p, int dtype, int layer, int M, hipStream_t s);
 void launch_silu_mul(const Params &p, int round_bf16, int M, hipStream_t s);
 // attention (both paths).  out_split: 0 = fp32 into p.attn, 1 = (hi, lo) bf16 pairs into p.attn_x
-void launch_attention(const Params &p, int dtype, int layer, int B, int R, int n_splits, int out_bf16,
+void launch_attention(const Params &p, int dtype, int layer, int B, int R, int n_splits, int out_split,
                       hipStream_t s);
 // sampling epilogues (both paths)
 void launch_draft_epilogue(const Params &p, const SampleArgs &a, int B, int R, hipStream_t s);
@@ -112,6 +121,15 @@ void launch_gemm_qkv(const Params &p, const void *W, int layer, int M, hipStream
 void launch_gemm_resid(const Params &p, const void *W, const uint16_t *X, int K, const void *gain_next, int M,
                        hipStream_t s);
 void launch_gemm_gateup(const Params &p, const void *W, int M, hipStream_t s);
+// (hi, lo) activation buffers of the matrix-core path, K features per row, tiled like the MFMA B
+// operand: [m / 8][K / 32][64 lanes][8 features]; lane = (k / 8 % 4) * 16 + m % 8 for the hi half,
+// 8 lanes further for the lo half.  Element index of the hi half of feature k of row m:
+__device__ __forceinline__ size_t xs_index(int m, int K, int k) {
+  return ((((size_t)(m >> 3) * (K >> 5) + (k >> 5)) * 64 + ((k >> 3) & 3) * 16 + (m & 7)) << 3) + (k & 7);
+}
+constexpr int kXsLoOffset = 64;  // elements from a hi half to its lo half
+
+int set_gemm_config_big(int kind, int waves, int blocks);  // calls with more than 8 rows
 int set_gemm_config(int kind, int waves, int unroll);  // kind: 0 QKV, 1 Wo, 2 gate/up, 3 LM head, 4 down
 void launch_gemm_logits(const Params &p, const void *W, float *logits, int M, hipStream_t s);
 

@@ -265,3 +265,4 @@ def test_matrix_core_attention(temp, plen):
         print(attn, st)
         assert st.iterations == 6 and st.resyncs == 0 and st.max_rel_err < 1e-3
         g.close()
+
