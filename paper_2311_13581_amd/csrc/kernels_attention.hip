@@ -201,7 +201,7 @@ __device__ __forceinline__ void split_plan_mfma(int n_keys, int &n_splits, int &
   n_splits = (n_keys + chunk - 1) / chunk;
 }
 
-__global__ __launch_bounds__(256) void attn_split_mfma_kernel(Params p, int layer, int R) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void attn_split_mfma_kernel(Params p, int layer, int R) {
   constexpr int HD = 128, RQ = kAttnRowsPerGroup;
   __shared__ float s_m[4][RQ], s_l[4][RQ];
   __shared__ float s_acc[4][RQ][HD];
@@ -221,7 +221,8 @@ __global__ __launch_bounds__(256) void attn_split_mfma_kernel(Params p, int laye
   const int k_lo = split * chunk;
   const int k_hi = min(n_keys, k_lo + chunk);
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  // the wavefront index as a scalar: the page lookup below then is a scalar load
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int ml = lane & 15, g = lane >> 4;
   const int row = ml & 7;  // query row of this lane's column (both column halves)
   const uint16_t *kpool = (const uint16_t *)p.k_pool, *vpool = (const uint16_t *)p.v_pool;
@@ -271,6 +272,10 @@ __global__ __launch_bounds__(256) void attn_split_mfma_kernel(Params p, int laye
     }
 #pragma unroll
     for (int db = 0; db < 8; ++db) vt[db] = *(const u32x4_t *)(vp + (size_t)(db * 16 + ml) * p.page_size + g * 8);
+    // all sixteen requests leave before anything is computed: left alone, the instruction
+    // scheduler moves the V requests behind the score MFMAs to save registers, and the block
+    // pays two trips to memory in a row
+    __builtin_amdgcn_sched_barrier(0);
 
     f32x4_t sc[2];
 #pragma unroll
@@ -361,7 +366,7 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R, int m
   // the row's group and its split plan, recomputed exactly as the split kernel did
   constexpr int RQ = kAttnRowsPerGroup;
   int b = m / R, r = m % R, r0 = (r / RQ) * RQ;
-  int n_keys = p.kv_len[p.step_slots[b]] + r0 + min(RQ, R - r0);
+  int n_keys = p.row_pos[b * R + r0] + min(RQ, R - r0);  // as the split kernel: position of the group's first row
   int n_splits, chunk;
   if (mfma_plan)
     split_plan_mfma(n_keys, n_splits, chunk);

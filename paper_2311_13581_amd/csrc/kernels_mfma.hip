@@ -479,6 +479,7 @@ static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hi
     return;
   }
   int w = g_big_waves[kind], nb = g_big_blocks[kind];
+  if (mt == 8 && nb == 4) nb = 2;                 // 64 rows x 4 blocks does not fit the register file
   while (nb > 1 && n_blocks % nb != 0) nb >>= 1;  // a workgroup's blocks must all exist
   switch (w * 10 + nb) {
     case 161: launch_big<EPI, 16, 1>(p, a, n_blocks, mt, s); break;
