@@ -156,9 +156,11 @@ int pass_seq_len(pass_ctx *ctx, int slot, int32_t *kv_len, int32_t *n_generated)
  * kernels; before pass_load_weights), "attention" (0 = auto, 1 = never use the matrix-core attention
  * kernel and its transposed V pages; before pass_load_weights), "gemm_cfg" (launch shape of the decode-sized matrix-core GEMMs, process-wide:
  * kind * 10000 + wavefronts * 100 + unroll with kind 0 QKV, 1 Wo, 2 gate/up, 3 LM head, 4 down, wavefronts 4/8/16,
- * unroll 1/2/4), "kernel_timing" (1 = bracket every launch of the dominant
- * kernel, the gate/up GEMM, with HIP events on the context's stream and synchronise after each
- * model call; setting it resets the counters).  Unknown names: PASS_EINVAL. */
+ * unroll 1/2/4; for calls with more than 8 rows 1000000 + kind * 10000 + wavefronts * 100 + blocks with
+ * wavefronts 8/16 and blocks (strips of 16 output features per workgroup) 1/2/4), "kernel_timing" (1 = after every model call, launch the dominant kernel, the gate/up GEMM,
+ * once per layer with that layer's weights on the call's rows, back to back between two HIP events on
+ * the context's stream, and synchronise; the launches write workspaces only; setting the option resets
+ * the counters pass_kernel_time reports).  Unknown names: PASS_EINVAL. */
 int pass_set_option(pass_ctx *ctx, const char *name, int value);
 
 /* Timed replay of one drafting-shaped step on the given slots without changing any sequence

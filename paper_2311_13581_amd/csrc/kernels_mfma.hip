@@ -15,8 +15,8 @@
 // one 16-column MFMA: columns 0..7 take the hi halves, columns 8..15 the lo halves of the same
 // rows, and the epilogue adds column j+8 to column j.  So a (1+k)-row call with k <= 7 costs one
 // MFMA and one activation load per weight tile, and nothing but the weights and the K/V cache is
-// ever rounded to 8 bits of mantissa ("models are loaded in bfloat16" is a statement about
-// storage).  Activation buffers are laid out for that, in tiles like the weights:
+// ever rounded to 8 bits of mantissa (the paper's bfloat16 is read as the storage format of the
+// model, Training details).  Activation buffers are laid out for that, in tiles like the weights:
 // [group of 8 rows][K/32][64 lanes][8], lane (k/8 % 4) * 16 + c holds 8 consecutive features of
 // pseudo-row c (c < 8: hi of row c, c >= 8: lo of row c - 8), so a wavefront fetches its B operand
 // of a k-tile as 1 KB of whole cache lines.
