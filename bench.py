@@ -95,6 +95,7 @@ def main():
     ap.add_argument("--k", type=int, default=None)
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (not a valid bench line)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-k0", action="store_true", help="skip the k = 0 comparison run")
     ap.add_argument("--path", type=int, default=0, help="1 = force the generic kernels")
     ap.add_argument("--graph", type=int, default=1)
     ap.add_argument("--gemm-cfg", type=int, action="append", default=[],
@@ -130,10 +131,16 @@ def main():
         g.set_option(name, int(val))
     W = devgen.device_weights(shape, k, w.lm_head_scale, w.seed)
     g.load_weights(W)
+    g0 = None
+    if k > 0 and not args.no_k0:
+        g0 = binding.Pass(binding.make_config(shape, 0, w.batch, max_len, 64), {"path": args.path, "graph": args.graph})
+        g0.load_weights(W)
     del W
     torch.cuda.empty_cache()
     for i, p in enumerate(prompts):
         g.prefill(i, p, seq_id=i)
+        if g0 is not None:
+            g0.prefill(i, p, seq_id=i)
     slots = list(range(w.batch))
     seed = synth.sampling_seed(w)
 
@@ -163,6 +170,17 @@ def main():
     k_bytes = gate_up_kernel_bytes(shape, M)
     achieved = k_bytes / k_avg_s / 1e9
 
+    # the same model call with no look-ahead rows (k = 0): the paper's premise is that the (1+k)-row
+    # step costs about what the one-row step costs (Section 2.2)
+    k0 = None
+    if g0 is not None:
+        g0.run_iterations(slots, max(2, args.warmup // 2), w.temperature, seed)
+        n0 = max(8, args.steps // 2)
+        st0 = g0.run_iterations(slots, n0, w.temperature, seed)
+        k0_ms = (st0["draft_ms"] + st0["verify_ms"]) / (2 * n0)
+        k0 = {"k0_call_ms": k0_ms, "ratio": (draft_ms + verify_ms) / 2 / k0_ms, "calls_timed": 2 * n0}
+        g0.close()
+
     out = {
         "metric": "generated tokens/s + (1+k)-token step HBM GB/s vs peak, 7B-shaped bf16, k=4",
         "value": st["tokens_out"] / dt,
@@ -186,6 +204,7 @@ def main():
         "tokens_per_iteration": st["tokens_out"] / max(1, st["iterations"]),
         "step_hbm": {"algorithmic_bytes_per_call": call_bytes, "achieved_GBps": step_gbs,
                      "frac_of_peak": step_gbs / HBM_PEAK_GBS},
+        "k_vs_k0": k0,
         "roofline": {"bound": "hbm", "kernel": "gate_up_gemm_silu", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(w.name) if not args.layers and k == w.k else None,
