@@ -8,8 +8,8 @@
  *
  * What it implements, and from where:
  *   - A LLaMA-style decoder-only transformer forward with a per-sequence K/V cache
- *     (paper, Experiments: "re-implementation of the 7B LLaMa model"; Baselines: KV cache
- *     updated after every model call; Training details: models loaded in bfloat16).
+ *     (paper, Experiments: the authors' own 7B LLaMA re-implementation; Baselines: the KV
+ *     cache is updated after every model call; Training details: bfloat16 models).
  *   - Algorithm 1 (PaSS): draft call on (last token, [LA]_1..[LA]_L), validation call on
  *     (x_{n+1}, drafts), accept chain r < min(1, p/d), residual resampling from (p - d)_+,
  *     extra token when every draft is accepted.  Section 2.2 gives the two-phase structure,
@@ -19,7 +19,7 @@
  * Arithmetic: double precision everywhere, except where a storage format fixes the value:
  * weights are read in their storage type (fp32 or bfloat16), the K/V cache of a bfloat16 model
  * holds bfloat16 values (round-to-nearest-even on write), logits are emitted as fp32.
- * "We load models in bfloat16" (Training details) is read as a statement about storage: nothing
+ * The bfloat16 of the paper's Training details is read as a statement about storage: nothing
  * between two matrix products is stored, so nothing else is rounded.  With act_bf16 = 1 the
  * oracle additionally rounds the tensors an all-bfloat16 execution would round (normalised
  * activations, q, attention output, gated FFN activation); that variant exists to measure how
@@ -40,7 +40,11 @@
  *   - "sample" = Gumbel-max over the counter-based Philox4x32-10 generator, which is exact in
  *     distribution and independent of summation order; ties go to the lowest index;
  *   - r is drawn from the open interval (0,1); the test is ln r + ln d(x) < ln p(x);
- *   - temperature 0 means greedy: every sample is an argmax (the one-hot limit of the rule).
+ *   - temperature 0 means greedy: every sample is an argmax (the one-hot limit of the rule);
+ *   - top-k sampling (Experimental setup: k = 10, and k = 25 for pass@10): the draft and the
+ *     target distribution are each the softmax over the row's own k largest logits (ties at the
+ *     boundary go to the lower index), zero elsewhere; the accept test and the residual use
+ *     these filtered distributions.  top_k = 0 means no filter; greedy ignores it.
  *
  * parity status: the forward pass of large random models has no external reference value
  * (structure is pinned by closed forms, row independence and greedy equivalence; absolute
@@ -75,7 +79,7 @@ typedef struct {
 
 typedef struct {
   float temperature; /* 0 = greedy */
-  int32_t top_k;     /* 0 = off (only value supported) */
+  int32_t top_k;     /* 0 = off; K > 0: sample from the K largest logits of a row only */
   uint64_t seed;
 } orc_sampling;
 
@@ -171,28 +175,58 @@ typedef struct {
   uint32_t seq_id, iteration, row, purpose;
 } orc_ctr;
 
-/* ln sum_j exp(l_j * inv_temp) */
-static double log_sum_exp(const float *logits, int V, double inv_temp) {
+/*
+ * Top-k filter: keep[j] = 1 for the K largest logits of the row, found one maximum at a time
+ * (ties: lower index first); K <= 0 or K >= V keeps every entry.  Returns 1 iff the kept set
+ * cannot change when every score l_j * inv_temp moves by at most tau.
+ */
+static int topk_keep(const float *logits, int V, int K, double inv_temp, double tau,
+                     unsigned char *keep) {
+  if (K <= 0 || K >= V) { memset(keep, 1, (size_t)V); return 1; }
+  memset(keep, 0, (size_t)V);
+  double last = 0.0;
+  for (int n = 0; n < K; ++n) {
+    int best = -1;
+    for (int j = 0; j < V; ++j)
+      if (!keep[j] && (best < 0 || logits[j] > logits[best])) best = j;
+    keep[best] = 1;
+    last = (double)logits[best];
+  }
+  double next = -INFINITY;
+  for (int j = 0; j < V; ++j)
+    if (!keep[j] && (double)logits[j] > next) next = (double)logits[j];
+  return (tau == 0.0) ? 1 : ((last - next) * inv_temp > 2.0 * tau);
+}
+
+/* ln sum_{j kept} exp(l_j * inv_temp) */
+static double log_sum_exp(const float *logits, const unsigned char *keep, int V, double inv_temp) {
   double mx = -INFINITY;
   for (int j = 0; j < V; ++j) {
+    if (!keep[j]) continue;
     double a = (double)logits[j] * inv_temp;
     if (a > mx) mx = a;
   }
   double s = 0.0;
-  for (int j = 0; j < V; ++j) s += exp((double)logits[j] * inv_temp - mx);
+  for (int j = 0; j < V; ++j)
+    if (keep[j]) s += exp((double)logits[j] * inv_temp - mx);
   return mx + log(s);
 }
 
 /*
- * Draw from softmax(logits / temperature) by Gumbel-max: argmax_j (l_j/T + G_j).
- * temperature == 0: plain argmax.  Ties go to the lowest index.
- * *stable = 1 iff the winner cannot change when every score moves by at most tau.
+ * Draw from softmax(logits / temperature), restricted to the row's top_k logits when top_k > 0,
+ * by Gumbel-max: argmax_j (l_j/T + G_j).  temperature == 0: plain argmax.  Ties go to the lowest
+ * index.  *stable = 1 iff the winner (and the kept set) cannot change when every score moves by
+ * at most tau.
  */
-int orc_sample_softmax(const float *logits, int V, double temperature, const orc_ctr *c,
+int orc_sample_softmax(const float *logits, int V, double temperature, int top_k, const orc_ctr *c,
                        double tau, int *stable) {
+  unsigned char *keep = (unsigned char *)malloc((size_t)V);
+  int set_ok = topk_keep(logits, V, temperature == 0.0 ? 0 : top_k,
+                         temperature == 0.0 ? 1.0 : 1.0 / temperature, tau, keep);
   int best = 0;
   double sb = -INFINITY, s2 = -INFINITY;
   for (int j = 0; j < V; ++j) {
+    if (!keep[j]) continue;
     double s;
     if (temperature == 0.0) {
       s = (double)logits[j];
@@ -203,20 +237,22 @@ int orc_sample_softmax(const float *logits, int V, double temperature, const orc
     if (s > sb) { s2 = sb; sb = s; best = j; }
     else if (s > s2) { s2 = s; }
   }
-  if (stable) *stable = (tau == 0.0) ? 1 : (sb - s2 > 2.0 * tau);
+  free(keep);
+  if (stable) *stable = (tau == 0.0) ? 1 : (set_ok && sb - s2 > 2.0 * tau);
   return best;
 }
 
 /*
  * Accept test of Algorithm 1 for one drafted token x:  r < min(1, p(x)/d(x)), written as
- * ln r + ln d(x) < ln p(x) with p, d the post-temperature softmax of the verify / draft row.
+ * ln r + ln d(x) < ln p(x) with p, d the post-temperature (top-k filtered) softmax of the
+ * verify / draft row; p(x) = 0 (x outside the target's top k) rejects.
  * Greedy: accept iff x is the argmax of the verify row (one-hot limit).
  */
 int orc_accept(const float *p_logits, const float *d_logits, int V, int x, double temperature,
-               const orc_ctr *c, double tau, int *stable) {
+               int top_k, const orc_ctr *c, double tau, int *stable) {
   if (temperature == 0.0) {
     int st;
-    int am = orc_sample_softmax(p_logits, V, 0.0, c, tau, &st);
+    int am = orc_sample_softmax(p_logits, V, 0.0, 0, c, tau, &st);
     if (stable) {
       if (am == x) *stable = st;
       else {
@@ -227,30 +263,40 @@ int orc_accept(const float *p_logits, const float *d_logits, int V, int x, doubl
     return am == x;
   }
   double it = 1.0 / temperature;
-  double lp = (double)p_logits[x] * it - log_sum_exp(p_logits, V, it);
-  double ld = (double)d_logits[x] * it - log_sum_exp(d_logits, V, it);
+  unsigned char *kp = (unsigned char *)malloc((size_t)V), *kd = (unsigned char *)malloc((size_t)V);
+  int set_ok = topk_keep(p_logits, V, top_k, it, tau, kp) & topk_keep(d_logits, V, top_k, it, tau, kd);
+  int in_p = kp[x], in_d = kd[x];
+  double lp = in_p ? (double)p_logits[x] * it - log_sum_exp(p_logits, kp, V, it) : -INFINITY;
+  double ld = in_d ? (double)d_logits[x] * it - log_sum_exp(d_logits, kd, V, it) : -INFINITY;
+  free(kp);
+  free(kd);
   double r = orc_uniform(c->seed, c->seq_id, c->iteration, c->row, ORC_ACCEPT, 0);
   double lhs = log(r) + ld;
-  if (stable) *stable = (tau == 0.0) ? 1 : (fabs(lp - lhs) > 4.0 * tau);
+  if (stable) *stable = (tau == 0.0) ? 1 : (set_ok && (!in_p || fabs(lp - lhs) > 4.0 * tau));
   return lhs < lp;
 }
 
 /*
  * Draw from the normalised residual (p - d)_+ by Gumbel-max over ln max(0, p_j - d_j) + G_j
- * (the normaliser cancels in an argmax).  Greedy: argmax of the verify row.  If the residual
- * is empty (possible only through rounding), fall back to sampling from p; *fallback = 1.
- * *stable: winner unchanged when ln p_j and ln d_j each move by at most tau.
+ * (the normaliser cancels in an argmax), p and d top-k filtered as above.  Greedy: argmax of the
+ * verify row.  If the residual is empty (possible only through rounding), fall back to sampling
+ * from p; *fallback = 1.
+ * *stable: winner unchanged when ln p_j and ln d_j each move by at most tau (and the kept sets
+ * cannot change).
  */
 int orc_sample_residual(const float *p_logits, const float *d_logits, int V, double temperature,
-                        const orc_ctr *c, double tau, int *stable, int *fallback) {
+                        int top_k, const orc_ctr *c, double tau, int *stable, int *fallback) {
   if (fallback) *fallback = 0;
-  if (temperature == 0.0) return orc_sample_softmax(p_logits, V, 0.0, c, tau, stable);
+  if (temperature == 0.0) return orc_sample_softmax(p_logits, V, 0.0, 0, c, tau, stable);
   double it = 1.0 / temperature;
-  double zp = log_sum_exp(p_logits, V, it), zd = log_sum_exp(d_logits, V, it);
+  unsigned char *kp = (unsigned char *)malloc((size_t)V), *kd = (unsigned char *)malloc((size_t)V);
+  int set_ok = topk_keep(p_logits, V, top_k, it, tau, kp) & topk_keep(d_logits, V, top_k, it, tau, kd);
+  double zp = log_sum_exp(p_logits, kp, V, it), zd = log_sum_exp(d_logits, kd, V, it);
   int best = -1;
   double sb = -INFINITY;
   for (int j = 0; j < V; ++j) {
-    double p = exp((double)p_logits[j] * it - zp), d = exp((double)d_logits[j] * it - zd);
+    double p = kp[j] ? exp((double)p_logits[j] * it - zp) : 0.0;
+    double d = kd[j] ? exp((double)d_logits[j] * it - zd) : 0.0;
     double w = p - d;
     if (!(w > 0.0)) continue;
     double u = orc_uniform(c->seed, c->seq_id, c->iteration, c->row, c->purpose, (uint32_t)j);
@@ -258,21 +304,25 @@ int orc_sample_residual(const float *p_logits, const float *d_logits, int V, dou
     if (s > sb) { sb = s; best = j; }
   }
   if (best < 0) {
+    free(kp);
+    free(kd);
     if (fallback) *fallback = 1;
     if (stable) *stable = 0;
-    return orc_sample_softmax(p_logits, V, temperature, c, tau, NULL);
+    return orc_sample_softmax(p_logits, V, temperature, top_k, c, tau, NULL);
   }
   if (stable) {
-    if (tau == 0.0) { *stable = 1; return best; }
+    if (tau == 0.0) { *stable = 1; free(kp); free(kd); return best; }
     double up = exp(tau), dn = exp(-tau);
-    double pb = exp((double)p_logits[best] * it - zp), db = exp((double)d_logits[best] * it - zd);
+    double pb = kp[best] ? exp((double)p_logits[best] * it - zp) : 0.0;
+    double db = kd[best] ? exp((double)d_logits[best] * it - zd) : 0.0;
     double wlo = pb * dn - db * up;
-    int ok = wlo > 0.0;
+    int ok = set_ok && wlo > 0.0;
     double ub = orc_uniform(c->seed, c->seq_id, c->iteration, c->row, c->purpose, (uint32_t)best);
     double slo = ok ? log(wlo) + gumbel(ub) - tau : -INFINITY;
     for (int j = 0; ok && j < V; ++j) {
       if (j == best) continue;
-      double p = exp((double)p_logits[j] * it - zp), d = exp((double)d_logits[j] * it - zd);
+      double p = kp[j] ? exp((double)p_logits[j] * it - zp) : 0.0;
+      double d = kd[j] ? exp((double)d_logits[j] * it - zd) : 0.0;
       double whi = p * up - d * dn;
       if (!(whi > 0.0)) continue;
       double u = orc_uniform(c->seed, c->seq_id, c->iteration, c->row, c->purpose, (uint32_t)j);
@@ -280,6 +330,8 @@ int orc_sample_residual(const float *p_logits, const float *d_logits, int V, dou
     }
     *stable = ok;
   }
+  free(kp);
+  free(kd);
   return best;
 }
 
@@ -515,7 +567,7 @@ int orc_prefill(orc_seq *s, const int32_t *prompt, int n) {
  */
 int orc_draft(orc_seq *s, const orc_sampling *sp, double tau, int32_t *out_first,
               int32_t *out_drafts) {
-  if (!s || !sp || sp->top_k != 0 || sp->temperature < 0) return ORC_EINVAL;
+  if (!s || !sp || sp->top_k < 0 || sp->temperature < 0) return ORC_EINVAL;
   if (s->state != 1) return ORC_ESTATE;
   const orc_config *c = &s->m->c;
   int k = c->k, V = c->vocab;
@@ -527,8 +579,8 @@ int orc_draft(orc_seq *s, const orc_sampling *sp, double tau, int32_t *out_first
   if (rc) return rc;
   for (int t = 0; t <= k; ++t) {
     orc_ctr ctr = {sp->seed, s->seq_id, s->iteration, (uint32_t)t, ORC_DRAFT};
-    int tok = orc_sample_softmax(s->draft_logits + (size_t)t * V, V, sp->temperature, &ctr, tau,
-                                 &s->draft_stable[t]);
+    int tok = orc_sample_softmax(s->draft_logits + (size_t)t * V, V, sp->temperature, sp->top_k, &ctr,
+                                 tau, &s->draft_stable[t]);
     if (t == 0) s->first = tok; else s->drafts[t - 1] = tok;
   }
   s->kv_len += 1;
@@ -549,7 +601,7 @@ int orc_draft(orc_seq *s, const orc_sampling *sp, double tau, int32_t *out_first
  */
 int orc_verify(orc_seq *s, const orc_sampling *sp, double tau, int32_t *out_n_accepted,
                int32_t *out_tokens) {
-  if (!s || !sp || sp->top_k != 0 || sp->temperature < 0) return ORC_EINVAL;
+  if (!s || !sp || sp->top_k < 0 || sp->temperature < 0) return ORC_EINVAL;
   if (s->state != 2) return ORC_ESTATE;
   const orc_config *c = &s->m->c;
   int k = c->k, V = c->vocab;
@@ -565,20 +617,21 @@ int orc_verify(orc_seq *s, const orc_sampling *sp, double tau, int32_t *out_n_ac
     const float *p = s->verify_logits + (size_t)(t - 1) * V;
     const float *dl = s->draft_logits + (size_t)t * V;
     orc_ctr ctr = {sp->seed, s->seq_id, s->iteration, (uint32_t)t, ORC_ACCEPT};
-    if (orc_accept(p, dl, V, s->drafts[t - 1], sp->temperature, &ctr, tau, &s->accept_stable[t])) {
+    if (orc_accept(p, dl, V, s->drafts[t - 1], sp->temperature, sp->top_k, &ctr, tau,
+                   &s->accept_stable[t])) {
       if (out_tokens) out_tokens[a] = s->drafts[t - 1];
       a += 1;
     } else {
       int fb = 0;
       ctr.purpose = ORC_RESIDUAL;
-      y = orc_sample_residual(p, dl, V, sp->temperature, &ctr, tau, &s->final_stable, &fb);
+      y = orc_sample_residual(p, dl, V, sp->temperature, sp->top_k, &ctr, tau, &s->final_stable, &fb);
       s->fallback_count += fb;
       break;
     }
   }
   if (a == k) {
     orc_ctr ctr = {sp->seed, s->seq_id, s->iteration, (uint32_t)(k + 1), ORC_BONUS};
-    y = orc_sample_softmax(s->verify_logits + (size_t)k * V, V, sp->temperature, &ctr, tau,
+    y = orc_sample_softmax(s->verify_logits + (size_t)k * V, V, sp->temperature, sp->top_k, &ctr, tau,
                            &s->final_stable);
   }
   if (out_tokens) out_tokens[a] = y;
@@ -643,7 +696,7 @@ int orc_generate_ar(orc_seq *s, int max_new, const orc_sampling *sp, int32_t *ou
     if (rc) { free(lg); return rc; }
     orc_ctr ctr = {sp->seed, s->seq_id, (uint32_t)(i / 2), (uint32_t)(i & 1),
                    (i & 1) ? ORC_BONUS : ORC_DRAFT};
-    int tok = orc_sample_softmax(lg, V, sp->temperature, &ctr, 0.0, NULL);
+    int tok = orc_sample_softmax(lg, V, sp->temperature, sp->top_k, &ctr, 0.0, NULL);
     s->kv_len += 1;
     s->pending = tok;
     out_tokens[i] = tok;

@@ -64,9 +64,9 @@ def lib():
         L.orc_uniform.argtypes = [C.c_uint64] + [C.c_uint32] * 5
         fp = C.POINTER(C.c_float)
         ip = C.POINTER(C.c_int32)
-        L.orc_sample_softmax.argtypes = [fp, C.c_int, C.c_double, C.POINTER(Ctr), C.c_double, ip]
-        L.orc_accept.argtypes = [fp, fp, C.c_int, C.c_int, C.c_double, C.POINTER(Ctr), C.c_double, ip]
-        L.orc_sample_residual.argtypes = [fp, fp, C.c_int, C.c_double, C.POINTER(Ctr), C.c_double, ip, ip]
+        L.orc_sample_softmax.argtypes = [fp, C.c_int, C.c_double, C.c_int, C.POINTER(Ctr), C.c_double, ip]
+        L.orc_accept.argtypes = [fp, fp, C.c_int, C.c_int, C.c_double, C.c_int, C.POINTER(Ctr), C.c_double, ip]
+        L.orc_sample_residual.argtypes = [fp, fp, C.c_int, C.c_double, C.c_int, C.POINTER(Ctr), C.c_double, ip, ip]
         L.orc_model_create.restype = C.c_void_p
         L.orc_model_create.argtypes = [C.POINTER(Config), C.POINTER(Weights)]
         L.orc_model_free.argtypes = [C.c_void_p]
@@ -130,29 +130,29 @@ def _ctr(seed, seq_id, iteration, row, purpose):
     return Ctr(seed, seq_id, iteration, row, purpose)
 
 
-def sample_softmax(logits, temperature, seed=0, seq_id=0, iteration=0, row=0, purpose=DRAFT, tau=0.0):
+def sample_softmax(logits, temperature, seed=0, seq_id=0, iteration=0, row=0, purpose=DRAFT, tau=0.0, top_k=0):
     logits = np.ascontiguousarray(logits, dtype=np.float32)
     st = C.c_int32(0)
     c = _ctr(seed, seq_id, iteration, row, purpose)
-    tok = lib().orc_sample_softmax(_fp(logits), logits.size, temperature, C.byref(c), tau, C.byref(st))
+    tok = lib().orc_sample_softmax(_fp(logits), logits.size, temperature, top_k, C.byref(c), tau, C.byref(st))
     return tok, bool(st.value)
 
 
-def accept(p_logits, d_logits, x, temperature, seed=0, seq_id=0, iteration=0, row=1, tau=0.0):
+def accept(p_logits, d_logits, x, temperature, seed=0, seq_id=0, iteration=0, row=1, tau=0.0, top_k=0):
     p = np.ascontiguousarray(p_logits, dtype=np.float32)
     d = np.ascontiguousarray(d_logits, dtype=np.float32)
     st = C.c_int32(0)
     c = _ctr(seed, seq_id, iteration, row, ACCEPT)
-    a = lib().orc_accept(_fp(p), _fp(d), p.size, int(x), temperature, C.byref(c), tau, C.byref(st))
+    a = lib().orc_accept(_fp(p), _fp(d), p.size, int(x), temperature, top_k, C.byref(c), tau, C.byref(st))
     return bool(a), bool(st.value)
 
 
-def sample_residual(p_logits, d_logits, temperature, seed=0, seq_id=0, iteration=0, row=1, tau=0.0):
+def sample_residual(p_logits, d_logits, temperature, seed=0, seq_id=0, iteration=0, row=1, tau=0.0, top_k=0):
     p = np.ascontiguousarray(p_logits, dtype=np.float32)
     d = np.ascontiguousarray(d_logits, dtype=np.float32)
     st, fb = C.c_int32(0), C.c_int32(0)
     c = _ctr(seed, seq_id, iteration, row, RESIDUAL)
-    tok = lib().orc_sample_residual(_fp(p), _fp(d), p.size, temperature, C.byref(c), tau,
+    tok = lib().orc_sample_residual(_fp(p), _fp(d), p.size, temperature, top_k, C.byref(c), tau,
                                     C.byref(st), C.byref(fb))
     return tok, bool(st.value), bool(fb.value)
 
@@ -225,22 +225,22 @@ class Sequence:
         p = np.ascontiguousarray(prompt, dtype=np.int32)
         _check(lib().orc_prefill(self.handle, _ip(p), p.size), "prefill")
 
-    def draft(self, temperature, seed, tau=0.0):
-        sp = Sampling(temperature, 0, seed)
+    def draft(self, temperature, seed, tau=0.0, top_k=0):
+        sp = Sampling(temperature, top_k, seed)
         first = C.c_int32(0)
         drafts = np.zeros(max(1, self.k), dtype=np.int32)
         _check(lib().orc_draft(self.handle, C.byref(sp), tau, C.byref(first), _ip(drafts)), "draft")
         return int(first.value), drafts[:self.k].copy()
 
-    def verify(self, temperature, seed, tau=0.0):
-        sp = Sampling(temperature, 0, seed)
+    def verify(self, temperature, seed, tau=0.0, top_k=0):
+        sp = Sampling(temperature, top_k, seed)
         a = C.c_int32(0)
         toks = np.zeros(self.k + 1, dtype=np.int32)
         _check(lib().orc_verify(self.handle, C.byref(sp), tau, C.byref(a), _ip(toks)), "verify")
         return int(a.value), toks[:a.value + 1].copy()
 
-    def generate(self, max_new, temperature, seed, tau=0.0):
-        sp = Sampling(temperature, 0, seed)
+    def generate(self, max_new, temperature, seed, tau=0.0, top_k=0):
+        sp = Sampling(temperature, top_k, seed)
         out = np.zeros(max(1, max_new), dtype=np.int32)
         cap = max_new // 2 + 2
         acc = np.zeros(cap, dtype=np.int32)
@@ -251,8 +251,8 @@ class Sequence:
         n = iters.value
         return out[:max_new].copy(), acc[:n].copy(), stab[:n].astype(bool)
 
-    def generate_ar(self, max_new, temperature, seed):
-        sp = Sampling(temperature, 0, seed)
+    def generate_ar(self, max_new, temperature, seed, top_k=0):
+        sp = Sampling(temperature, top_k, seed)
         out = np.zeros(max(1, max_new), dtype=np.int32)
         _check(lib().orc_generate_ar(self.handle, max_new, C.byref(sp), _ip(out)), "generate_ar")
         return out[:max_new].copy()

@@ -480,3 +480,134 @@ def test_draft_and_verify_calls_feed_the_rows_algorithm_1_names():
     s.draft(1.0, 6)
     ref_d2 = torch_ref.forward_full(shape, W, np.array(hist), k).numpy()[-(k + 1):]
     assert np.allclose(s.logits(0), ref_d2, rtol=0, atol=1e-6 * np.abs(ref_d2).max())
+
+
+# ------------------------------------------------------------------------------------------
+# top-k sampling (Experimental setup: top-k sampling with k = 10, k = 25 for pass@10)
+# ------------------------------------------------------------------------------------------
+def _topk_probs(logits, temp, K):
+    """The filtered distribution from library routines: torch.topk picks the K largest logits,
+    softmax over them, zero elsewhere."""
+    t = torch.from_numpy(np.asarray(logits, dtype=np.float32)).double()
+    vals, idx = torch.topk(t, K)
+    p = torch.zeros_like(t)
+    p[idx] = torch.softmax(vals / temp, 0)
+    return p.numpy()
+
+
+@pytest.mark.parametrize("K,temp", [(3, 0.8), (10, 1.0), (25, 0.8)])
+def test_topk_sample_law_and_support(K, temp):
+    """Draws with a top-k filter follow the softmax over the K largest logits and never leave it."""
+    V = 40
+    logits = synth.random_logits(21, 1, V, 1.5)[0]
+    probs = _topk_probs(logits, temp, K)
+    N = 40000
+    counts = np.zeros(V)
+    for i in range(N):
+        tok, _ = O.sample_softmax(logits, temp, seed=5, seq_id=i, top_k=K)
+        counts[tok] += 1
+    assert np.all(counts[probs == 0] == 0)
+    assert _chi2_ok(counts, probs)
+
+
+def test_topk_degenerate_cases():
+    """K = 0 and K >= V are no filter (same draws as without); K = 1 is the argmax at any
+    temperature; greedy ignores K; ties at the boundary keep the lower index."""
+    V = 17
+    logits = synth.random_logits(22, 1, V, 1.0)[0]
+    for i in range(300):
+        ref = O.sample_softmax(logits, 0.9, seed=2, seq_id=i)[0]
+        assert O.sample_softmax(logits, 0.9, seed=2, seq_id=i, top_k=V)[0] == ref
+        assert O.sample_softmax(logits, 0.9, seed=2, seq_id=i, top_k=V + 5)[0] == ref
+        assert O.sample_softmax(logits, 1.7, seed=2, seq_id=i, top_k=1)[0] == int(np.argmax(logits))
+    assert O.sample_softmax(logits, 0.0, top_k=3)[0] == int(np.argmax(logits))
+    tie = np.array([1.0, 5.0, 3.0, 3.0, 3.0, 0.0], np.float32)  # K = 2 keeps {1, 2}; K = 3 keeps {1, 2, 3}
+    seen2, seen3 = set(), set()
+    for i in range(2000):
+        seen2.add(O.sample_softmax(tie, 5.0, seed=1, seq_id=i, top_k=2)[0])
+        seen3.add(O.sample_softmax(tie, 5.0, seed=1, seq_id=i, top_k=3)[0])
+    assert seen2 == {1, 2} and seen3 == {1, 2, 3}
+
+
+def test_topk_speculative_step_output_law_is_filtered_target():
+    """With both distributions top-k filtered the rejection scheme still emits exactly the
+    (filtered) target distribution; P(accept) = sum min(p', d'); a draft outside the target's
+    top k is always rejected; the residual never lands where p' <= d'."""
+    V, K, temp = 30, 6, 0.8
+    lg = synth.random_logits(23, 2, V, 1.3)
+    p = _topk_probs(lg[0], temp, K)
+    d = _topk_probs(lg[1], temp, K)
+    res = np.maximum(p - d, 0)
+    N = 40000
+    counts = np.zeros(V)
+    n_acc = 0
+    for i in range(N):
+        x, _ = O.sample_softmax(lg[1], temp, seed=9, seq_id=i, row=1, purpose=O.DRAFT, top_k=K)
+        a, _ = O.accept(lg[0], lg[1], x, temp, seed=9, seq_id=i, row=1, top_k=K)
+        if p[x] == 0:
+            assert not a
+        if a:
+            n_acc += 1
+            counts[x] += 1
+        else:
+            y, _, fb = O.sample_residual(lg[0], lg[1], temp, seed=9, seq_id=i, row=1, top_k=K)
+            assert not fb and res[y] > 0
+            counts[y] += 1
+    expect = np.minimum(p, d).sum()
+    assert abs(n_acc / N - expect) < 4.5 * np.sqrt(expect * (1 - expect) / N)
+    assert 0.02 * N < n_acc < 0.98 * N
+    assert _chi2_ok(counts, p)
+
+
+def test_topk_stability_flags():
+    """The kept set is reported unstable when the K-th and (K+1)-th scores are closer than the
+    margin, stable otherwise."""
+    l = np.array([4.0, 3.0, 2.0, 1.999, -5.0], np.float32)
+    assert not O.sample_softmax(l, 1.0, seed=1, tau=1e-2, top_k=3)[1]      # 2.0 vs 1.999 at the boundary
+    far = np.array([4.0, -30.0, -30.0, -31.0, -35.0], np.float32)
+    tok, stable = O.sample_softmax(far, 1.0, seed=1, tau=1e-2, top_k=3)   # winner clear, boundary gap 1.0
+    assert tok == 0 and stable
+
+
+def test_topk_pass_with_k0_is_filtered_autoregressive_sampling_inside_the_top_k():
+    """PaSS with no look-ahead rows and a top-k filter is auto-regressive top-k sampling with the
+    same counters, and every token lies among the K largest reference logits at its position
+    (logits from the library composition)."""
+    w = TINY
+    W = synth.make_weights(w.shape, 8, 1, 4.0)
+    m = O.Model(w.shape, W, 0)
+    prompt = synth.make_prompts(w)[0]
+    K = 5
+    a = m.sequence(128)
+    a.prefill(prompt)
+    toks, _, _ = a.generate(24, 0.9, 1234, top_k=K)
+    b = m.sequence(128)
+    b.prefill(prompt)
+    assert np.array_equal(toks, b.generate_ar(24, 0.9, 1234, top_k=K))
+    seq = list(prompt)
+    for t in toks[:12]:
+        lg = torch_ref.forward_full(w.shape, W, np.array(seq), 0)[-1].numpy()
+        assert t in np.argsort(-lg)[:K]
+        seq.append(int(t))
+
+
+def test_topk_pass_keeps_the_greedy_and_bookkeeping_invariants():
+    """Greedy PaSS is unchanged by a top-k argument; sampled PaSS with top-k keeps
+    tokens/iteration in [2, k+2] and kv_len = #tokens - 1."""
+    w = TINY
+    W = synth.make_weights(w.shape, 3, 2, 8.0)
+    m = O.Model(w.shape, W, 2)
+    prompt = synth.make_prompts(w)[0]
+    a, b = m.sequence(160), m.sequence(160)
+    a.prefill(prompt)
+    b.prefill(prompt)
+    assert np.array_equal(a.generate(30, 0.0, 7)[0], b.generate(30, 0.0, 7, top_k=4)[0])
+    c = m.sequence(160)
+    c.prefill(prompt)
+    n_tok = len(prompt)
+    for it in range(12):
+        c.draft(0.8, 99, top_k=10)
+        acc, out = c.verify(0.8, 99, top_k=10)
+        n_tok += 1 + len(out)
+        assert 0 <= acc <= 2 and len(out) == acc + 1
+        assert c.kv_len == n_tok - 1
