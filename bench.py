@@ -96,6 +96,8 @@ def main():
     ap.add_argument("--layers", type=int, default=None, help="debug: fewer layers (not a valid bench line)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-k0", action="store_true", help="skip the k = 0 comparison run")
+    ap.add_argument("--top-k", type=int, default=0, help="top-k sampling filter (the paper samples with 10 and 25)")
+    ap.add_argument("--temperature", type=float, default=None, help="override the workload's temperature")
     ap.add_argument("--path", type=int, default=0, help="1 = force the generic kernels")
     ap.add_argument("--graph", type=int, default=1)
     ap.add_argument("--gemm-cfg", type=int, action="append", default=[],
@@ -120,6 +122,8 @@ def main():
         w = synth.scaled(w, n_layers=args.layers)
     k = w.k if args.k is None else args.k
     shape = w.shape
+    temp = w.temperature if args.temperature is None else args.temperature
+    top_k = args.top_k
     prompts = synth.make_prompts(w)
     total_iters = args.steps + args.warmup + 8
     max_len = max(len(p) for p in prompts) + (k + 2) * total_iters + k + 2
@@ -144,11 +148,11 @@ def main():
     slots = list(range(w.batch))
     seed = synth.sampling_seed(w)
 
-    g.run_iterations(slots, args.warmup, w.temperature, seed)
+    g.run_iterations(slots, args.warmup, temp, seed, top_k)
     ctx0 = [g.seq_len(s)[0] for s in slots]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    st = g.run_iterations(slots, args.steps, w.temperature, seed)
+    st = g.run_iterations(slots, args.steps, temp, seed, top_k)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ctx1 = [g.seq_len(s)[0] for s in slots]
@@ -163,7 +167,7 @@ def main():
 
     # dominant kernel, timed live with HIP events on the library's stream
     g.set_option("kernel_timing", 1)
-    g.run_iterations(slots, 4, w.temperature, seed)
+    g.run_iterations(slots, 4, temp, seed, top_k)
     kms, kn = g.kernel_time()
     g.set_option("kernel_timing", 0)
     k_avg_s = kms / max(kn, 1) * 1e-3
@@ -174,9 +178,9 @@ def main():
     # step costs about what the one-row step costs (Section 2.2)
     k0 = None
     if g0 is not None:
-        g0.run_iterations(slots, max(2, args.warmup // 2), w.temperature, seed)
+        g0.run_iterations(slots, max(2, args.warmup // 2), temp, seed, top_k)
         n0 = max(8, args.steps // 2)
-        st0 = g0.run_iterations(slots, n0, w.temperature, seed)
+        st0 = g0.run_iterations(slots, n0, temp, seed, top_k)
         k0_ms = (st0["draft_ms"] + st0["verify_ms"]) / (2 * n0)
         k0 = {"k0_call_ms": k0_ms, "ratio": (draft_ms + verify_ms) / 2 / k0_ms, "calls_timed": 2 * n0}
         g0.close()
@@ -196,7 +200,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "k": k, "batch": w.batch, "prompt_len": [len(p) for p in prompts],
                    "n_layers": shape.n_layers, "d_model": shape.d_model, "vocab": shape.vocab,
-                   "temperature": w.temperature, "context_during_timing": [min(ctx0), max(ctx1)],
+                   "temperature": temp, "top_k": top_k, "context_during_timing": [min(ctx0), max(ctx1)],
                    "graph": args.graph, "path": "generic" if args.path else "auto"},
         "draft_call_ms": draft_ms,
         "verify_call_ms": verify_ms,

@@ -67,7 +67,10 @@ typedef struct {
 
 typedef struct {
   float temperature;   /* 0 = greedy (every sample is an argmax, lowest index on ties)         */
-  int32_t top_k;       /* must be 0 (reserved for the top-k filter)                            */
+  int32_t top_k;       /* 0 = no filter; K > 0 = top-k sampling (Experimental setup: k = 10, 25): the
+                          draft and the target distribution are each the softmax over the row's own
+                          K largest logits (boundary ties keep the lower indices), zero elsewhere;
+                          ignored when temperature is 0; K >= vocab filters nothing; negative: EINVAL */
   uint64_t seed;       /* Philox4x32-10 key; streams are separated by sequence id, iteration,
                           row and purpose, so results do not depend on batch composition      */
 } pass_sampling;

@@ -188,34 +188,34 @@ class Pass:
     def release(self, slot: int):
         self._check(self.lib.pass_release(self.h, slot))
 
-    def draft(self, slots, temperature: float, seed: int):
+    def draft(self, slots, temperature: float, seed: int, top_k: int = 0):
         s = np.ascontiguousarray(slots, dtype=np.int32)
-        sp = PassSampling(temperature, 0, seed)
+        sp = PassSampling(temperature, top_k, seed)
         first = np.zeros(s.size, dtype=np.int32)
         drafts = np.zeros(max(1, s.size * self.k), dtype=np.int32)
         self._check(self.lib.pass_draft(self.h, _ip(s), s.size, C.byref(sp), _ip(first), _ip(drafts)))
         return first, drafts[:s.size * self.k].reshape(s.size, self.k)
 
-    def verify(self, slots, temperature: float, seed: int):
+    def verify(self, slots, temperature: float, seed: int, top_k: int = 0):
         s = np.ascontiguousarray(slots, dtype=np.int32)
-        sp = PassSampling(temperature, 0, seed)
+        sp = PassSampling(temperature, top_k, seed)
         n_acc = np.zeros(s.size, dtype=np.int32)
         toks = np.zeros(s.size * (self.k + 1), dtype=np.int32)
         self._check(self.lib.pass_verify(self.h, _ip(s), s.size, C.byref(sp), _ip(n_acc), _ip(toks)))
         return n_acc, toks.reshape(s.size, self.k + 1)
 
-    def generate(self, slots, max_new: int, temperature: float, seed: int):
+    def generate(self, slots, max_new: int, temperature: float, seed: int, top_k: int = 0):
         s = np.ascontiguousarray(slots, dtype=np.int32)
-        sp = PassSampling(temperature, 0, seed)
+        sp = PassSampling(temperature, top_k, seed)
         out = np.zeros(max(1, s.size * max_new), dtype=np.int32)
         st = PassStats()
         self._check(self.lib.pass_generate(self.h, _ip(s), s.size, max_new, C.byref(sp), _ip(out), C.byref(st)))
         stats = {f: getattr(st, f) for f, _ in PassStats._fields_}
         return out[:s.size * max_new].reshape(s.size, max_new), stats
 
-    def run_iterations(self, slots, n_iters: int, temperature: float, seed: int) -> dict:
+    def run_iterations(self, slots, n_iters: int, temperature: float, seed: int, top_k: int = 0) -> dict:
         s = np.ascontiguousarray(slots, dtype=np.int32)
-        sp = PassSampling(temperature, 0, seed)
+        sp = PassSampling(temperature, top_k, seed)
         st = PassStats()
         self._check(self.lib.pass_run_iterations(self.h, _ip(s), s.size, n_iters, C.byref(sp), C.byref(st)))
         return {f: getattr(st, f) for f, _ in PassStats._fields_}

@@ -11,6 +11,14 @@
 // key = seed and counter = (j/4, iteration, row | purpose << 8, sequence id); an argmax is
 // independent of reduction order, so wavefront reductions give the same winner as a serial loop.
 // Ties go to the lowest index.  temperature == 0 is greedy (argmax of the logits).
+//
+// Top-k sampling (the paper's sampler, Experimental setup: k = 10, and 25 for pass@10): the draft
+// and the target distribution are each the softmax over the row's own K largest logits, zero
+// elsewhere; ties at the boundary keep the lower indices.  A row's filter is two numbers found by
+// a radix select over order-preserving integer keys: the key of the K-th largest logit and the
+// highest index that may still be kept among the logits equal to it.  Entries outside the filter
+// are skipped by every scan (ln-sum-exp, draws, residual) and have probability zero in the accept
+// test.  K = 0 is no filter (key 0, every index allowed).
 #include "pass_internal.h"
 
 namespace pass {
@@ -140,9 +148,125 @@ __device__ __forceinline__ void scan_rows(const float *const (&rows)[NR], int V,
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// top-k filter
+// ---------------------------------------------------------------------------------------------
+// order-preserving key of a logit: a > b  <=>  key(a) > key(b); -0 and +0 share a key
+__device__ __forceinline__ uint32_t order_key(float f) {
+  uint32_t u = __float_as_uint(f);
+  if (u == 0x80000000u) u = 0;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+struct RowFilter {
+  uint32_t key;  // key of the K-th largest logit (0: keep everything)
+  int tie_max;   // highest index kept among the logits whose key equals `key`
+};
+__device__ __forceinline__ bool kept(const RowFilter &f, float l, int j) {
+  uint32_t k = order_key(l);
+  return k > f.key || (k == f.key && j <= f.tie_max);
+}
+
+constexpr int kSelBins = 2048;  // 11 + 11 + 10 bits
+struct SelectShared {
+  int hist[kSelBins];
+  int wave_tot[kEpiWaves];
+  int bin, rank;
+};
+
+// Exclusive prefix sum over the threads of the workgroup, in thread order.
+__device__ int block_exclusive_scan(int v, int *wave_tot) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int t = __shfl_up(inc, o);
+    if (lane >= o) inc += t;
+  }
+  __syncthreads();
+  if (lane == 63) wave_tot[wave] = inc;
+  __syncthreads();
+  int off = 0;
+  for (int w = 0; w < wave; ++w) off += wave_tot[w];
+  return off + inc - v;
+}
+
+// The histogram holds counts per digit; find the digit that contains the rank-th largest element
+// (rank >= 1, counted from the top digit down) and the rank inside that digit.
+__device__ void find_digit(SelectShared &sh, int n_bins, int rank, int &digit, int &rank_in) {
+  const int bpt = n_bins / kEpiThreads;           // bins per thread (n_bins is a multiple of 512)
+  const int hi = n_bins - threadIdx.x * bpt - 1;  // thread 0 owns the top bins
+  int local = 0;
+  for (int i = 0; i < bpt; ++i) local += sh.hist[hi - i];
+  const int above = block_exclusive_scan(local, sh.wave_tot);
+  if (above < rank && rank <= above + local) {
+    int acc = above;
+    for (int i = 0; i < bpt; ++i) {
+      int c = sh.hist[hi - i];
+      if (rank <= acc + c) { sh.bin = hi - i; sh.rank = rank - acc; break; }
+      acc += c;
+    }
+  }
+  __syncthreads();
+  digit = sh.bin;
+  rank_in = sh.rank;
+  __syncthreads();
+}
+
+// Filter of one row for top-K sampling, by the whole workgroup: three counting passes over the
+// row (it sits in L2: the LM head has just written it).  K <= 0 or K >= V: no filter.
+__device__ RowFilter select_top_k(const float *row, int V, int K, SelectShared &sh) {
+  RowFilter f;
+  f.key = 0;
+  f.tie_max = V;
+  if (K <= 0 || K >= V) return f;
+  const float *const rows[1] = {row};
+  uint32_t prefix = 0, mask = 0;
+  int rank = K;
+  const int shifts[3] = {21, 10, 0}, bits[3] = {11, 11, 10};
+  for (int pass = 0; pass < 3; ++pass) {
+    const int n_bins = 1 << bits[pass];
+    for (int i = threadIdx.x; i < kSelBins; i += kEpiThreads) sh.hist[i] = 0;
+    __syncthreads();
+    const int shift = shifts[pass];
+    scan_rows<1>(rows, V, [&](int q4, const float (&x)[1][4], int n) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        if (e < n) {
+          uint32_t k = order_key(x[0][e]);
+          if ((k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & (n_bins - 1)], 1);
+        }
+      }
+    });
+    __syncthreads();
+    int digit, rank_in;
+    find_digit(sh, n_bins < kEpiThreads ? kEpiThreads : n_bins, rank, digit, rank_in);
+    prefix |= (uint32_t)digit << shift;
+    mask |= (uint32_t)(n_bins - 1) << shift;
+    if (pass == 2) {
+      // `rank_in` of the sh.hist[digit] logits equal to the threshold are kept: the lowest indices
+      const int n_equal = sh.hist[digit];
+      f.key = prefix;
+      if (rank_in < n_equal) {
+        // rare (exactly equal logits across the boundary): one thread walks the row in index order
+        if (threadIdx.x == 0) {
+          int seen = 0, j = 0;
+          for (; j < V; ++j)
+            if (order_key(row[j]) == prefix && ++seen == rank_in) break;
+          sh.bin = j;
+        }
+        __syncthreads();
+        f.tie_max = sh.bin;
+        __syncthreads();
+      }
+    }
+    rank = rank_in;
+  }
+  return f;
+}
+
 // Gumbel-max over softmax(logits * inv_t) (or plain argmax when greedy) fused with ln-sum-exp.
 __device__ void sample_row(const float *logits, int V, bool greedy, float inv_t, uint32_t k0, uint32_t k1,
-                           uint32_t c1, uint32_t c2, uint32_t c3, Best &best, MaxSum &ms) {
+                           uint32_t c1, uint32_t c2, uint32_t c3, const RowFilter &flt, Best &best, MaxSum &ms) {
   best.s = -INFINITY;
   best.idx = -1;
   ms.m = -INFINITY;
@@ -153,7 +277,7 @@ __device__ void sample_row(const float *logits, int V, bool greedy, float inv_t,
     if (!greedy) philox4x32_10((uint32_t)q4, c1, c2, c3, k0, k1, rnd);
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      if (e < n) {
+      if (e < n && kept(flt, x[0][e], q4 * 4 + e)) {
         float l = x[0][e];
         float a = l * inv_t;
         if (a > ms.m) {
@@ -174,15 +298,21 @@ __device__ void sample_row(const float *logits, int V, bool greedy, float inv_t,
 __global__ __launch_bounds__(kEpiThreads) void draft_epilogue_kernel(Params p, SampleArgs a, int R) {
   __shared__ Best sh_b[kEpiWaves];
   __shared__ MaxSum sh_m[kEpiWaves];
+  __shared__ SelectShared sh_sel;
   int m = blockIdx.x, b = m / R, r = m % R;
   int slot = p.step_slots[b];
   const float *logits = p.draft_logits + ((size_t)slot * (1 + p.k) + r) * p.V;
   bool greedy = a.temperature == 0.f;
   float inv_t = greedy ? 1.f : 1.f / a.temperature;
+  const RowFilter flt = select_top_k(logits, p.V, greedy ? 0 : a.top_k, sh_sel);
+  if (threadIdx.x == 0) {  // the validation call evaluates d_t through the same filter
+    p.flt_key_d[slot * (kMaxK + 1) + r] = flt.key;
+    p.flt_tie_d[slot * (kMaxK + 1) + r] = flt.tie_max;
+  }
   Best best;
   MaxSum ms;
   sample_row(logits, p.V, greedy, inv_t, a.seed_lo, a.seed_hi, p.iter[slot], (uint32_t)r | (PURPOSE_DRAFT << 8),
-             p.seq_id[slot], best, ms);
+             p.seq_id[slot], flt, best, ms);
   best = block_best(best, sh_b);
   ms = block_ms(ms, sh_m);
   if (threadIdx.x == 0) {
@@ -205,18 +335,24 @@ __global__ __launch_bounds__(kEpiThreads) void draft_epilogue_kernel(Params p, S
   }
 }
 
-// ln-sum-exp and argmax of every validation row
+// ln-sum-exp (over the row's filter) and argmax of every validation row
 __global__ __launch_bounds__(kEpiThreads) void verify_stats_kernel(Params p, SampleArgs a, int R) {
   __shared__ Best sh_b[kEpiWaves];
   __shared__ MaxSum sh_m[kEpiWaves];
   int m = blockIdx.x, b = m / R, r = m % R;
   int slot = p.step_slots[b];
   const float *logits = p.verify_logits + ((size_t)slot * (1 + p.k) + r) * p.V;
+  __shared__ SelectShared sh_sel;
   bool greedy = a.temperature == 0.f;
   float inv_t = greedy ? 1.f : 1.f / a.temperature;
+  const RowFilter flt = select_top_k(logits, p.V, greedy ? 0 : a.top_k, sh_sel);
+  if (threadIdx.x == 0) {
+    p.flt_key_p[slot * (kMaxK + 1) + r] = flt.key;
+    p.flt_tie_p[slot * (kMaxK + 1) + r] = flt.tie_max;
+  }
   Best best;
   MaxSum ms;
-  sample_row(logits, p.V, true, inv_t, 0, 0, 0, 0, 0, best, ms);
+  sample_row(logits, p.V, true, inv_t, 0, 0, 0, 0, 0, flt, best, ms);
   best = block_best(best, sh_b);
   ms = block_ms(ms, sh_m);
   if (threadIdx.x == 0) {
@@ -237,6 +373,19 @@ __global__ __launch_bounds__(kEpiThreads) void verify_decide_kernel(Params p, Sa
   const float *zp = p.logz_p + slot * (kMaxK + 1), *zd = p.logz_d + slot * (kMaxK + 1);
   const int32_t *drafts = p.drafts + slot * kMaxK;
   const uint32_t it = p.iter[slot], sid = p.seq_id[slot];
+  // row filters (top-k) found by the two statistics kernels; greedy never filters
+  auto filter_p = [&](int row) {
+    RowFilter f;
+    f.key = greedy ? 0u : p.flt_key_p[slot * (kMaxK + 1) + row];
+    f.tie_max = greedy ? V : p.flt_tie_p[slot * (kMaxK + 1) + row];
+    return f;
+  };
+  auto filter_d = [&](int row) {
+    RowFilter f;
+    f.key = greedy ? 0u : p.flt_key_d[slot * (kMaxK + 1) + row];
+    f.tie_max = greedy ? V : p.flt_tie_d[slot * (kMaxK + 1) + row];
+    return f;
+  };
 
   if (threadIdx.x == 0) {
     int acc = 0;
@@ -246,8 +395,10 @@ __global__ __launch_bounds__(kEpiThreads) void verify_decide_kernel(Params p, Sa
       if (greedy) {
         ok = x == p.argmax_p[slot * (kMaxK + 1) + (t - 1)];
       } else {
-        float lp = P[(size_t)(t - 1) * V + x] * inv_t - zp[t - 1];
-        float ld = Dl[(size_t)t * V + x] * inv_t - zd[t];
+        // a token outside a row's filter has probability zero there
+        const float pl = P[(size_t)(t - 1) * V + x], dl = Dl[(size_t)t * V + x];
+        float lp = kept(filter_p(t - 1), pl, x) ? pl * inv_t - zp[t - 1] : -INFINITY;
+        float ld = kept(filter_d(t), dl, x) ? dl * inv_t - zd[t] : -INFINITY;
         uint32_t rnd[4];
         philox4x32_10(0u, it, (uint32_t)t | (PURPOSE_ACCEPT << 8), sid, a.seed_lo, a.seed_hi, rnd);
         ok = logf(u01(rnd[0])) + ld < lp;
@@ -266,12 +417,13 @@ __global__ __launch_bounds__(kEpiThreads) void verify_decide_kernel(Params p, Sa
     Best best;
     MaxSum ms;
     sample_row(P + (size_t)k * V, V, false, inv_t, a.seed_lo, a.seed_hi, it, (uint32_t)(k + 1) | (PURPOSE_BONUS << 8),
-               sid, best, ms);
+               sid, filter_p(k), best, ms);
     y = block_best(best, sh_b).idx;
   } else {
     const float *pr = P + (size_t)acc * V, *dr = Dl + (size_t)(acc + 1) * V;
     const float z_p = zp[acc], z_d = zd[acc + 1];
     const uint32_t c2 = (uint32_t)(acc + 1) | (PURPOSE_RESIDUAL << 8);
+    const RowFilter fp = filter_p(acc), fd = filter_d(acc + 1);
     Best best;
     best.s = -INFINITY;
     best.idx = -1;
@@ -282,7 +434,9 @@ __global__ __launch_bounds__(kEpiThreads) void verify_decide_kernel(Params p, Sa
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         if (e < n) {
-          float w = expf(x[0][e] * inv_t - z_p) - expf(x[1][e] * inv_t - z_d);
+          const int j = q4 * 4 + e;
+          float w = (kept(fp, x[0][e], j) ? expf(x[0][e] * inv_t - z_p) : 0.f) -
+                    (kept(fd, x[1][e], j) ? expf(x[1][e] * inv_t - z_d) : 0.f);
           if (w > 0.f) {
             Best c;
             c.s = logf(w) + gumbel(u01(rnd[e]));
@@ -296,7 +450,7 @@ __global__ __launch_bounds__(kEpiThreads) void verify_decide_kernel(Params p, Sa
     if (best.idx < 0) {
       // residual empty through rounding: draw from p_t with the same counters
       MaxSum ms;
-      sample_row(pr, V, false, inv_t, a.seed_lo, a.seed_hi, it, c2, sid, best, ms);
+      sample_row(pr, V, false, inv_t, a.seed_lo, a.seed_hi, it, c2, sid, fp, best, ms);
       best = block_best(best, sh_b);
       if (threadIdx.x == 0) atomicAdd(p.fallbacks, 1);
     }

@@ -67,7 +67,7 @@ struct pass_ctx {
   // optional timing of the dominant kernel (the gate/up GEMM): one event pair per layer
   // captured (model call + epilogue) graphs, keyed by everything that is baked into the launches:
   // mode, batch, attention grid width, sampling arguments
-  typedef std::tuple<int, int, int, uint32_t, uint32_t, uint32_t, int> GraphKey;
+  typedef std::tuple<int, int, int, uint32_t, uint32_t, uint32_t, int, int> GraphKey;
   std::map<GraphKey, hipGraphExec_t> graphs;
   int opt_kernel_timing = 0;
   std::vector<hipEvent_t> kev;
@@ -143,6 +143,8 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   P.gen = A.take<int32_t>(S * P.gen_cap);
   P.logz_d = A.take<float>(S * (kMaxK + 1)); P.logz_p = A.take<float>(S * (kMaxK + 1));
   P.argmax_p = A.take<int32_t>(S * (kMaxK + 1));
+  P.flt_key_d = A.take<uint32_t>(S * (kMaxK + 1)); P.flt_key_p = A.take<uint32_t>(S * (kMaxK + 1));
+  P.flt_tie_d = A.take<int32_t>(S * (kMaxK + 1)); P.flt_tie_p = A.take<int32_t>(S * (kMaxK + 1));
   P.fallbacks = A.take<int32_t>(1);
   P.block_table = A.take<int32_t>(S * pps);
   P.draft_logits = A.take<float>(S * (1 + c.k) * V);
@@ -328,7 +330,7 @@ int check_slots(pass_ctx *c, const int32_t *slots, int n_slots, int want_state) 
 int check_sampling(pass_ctx *c, const pass_sampling *sp) {
   if (!sp) return fail(c, PASS_EINVAL, "null sampling parameters");
   if (!(sp->temperature >= 0.f) || !isfinite(sp->temperature)) return fail(c, PASS_EINVAL, "temperature must be >= 0");
-  if (sp->top_k != 0) return fail(c, PASS_EINVAL, "top_k is reserved and must be 0");
+  if (sp->top_k < 0) return fail(c, PASS_EINVAL, "top_k must be >= 0 (0 = no filter)");
   return PASS_OK;
 }
 
@@ -338,6 +340,7 @@ SampleArgs sample_args(const pass_sampling *sp, int commit) {
   a.seed_lo = (uint32_t)sp->seed;
   a.seed_hi = (uint32_t)(sp->seed >> 32);
   a.commit = commit;
+  a.top_k = sp->top_k;
   return a;
 }
 
@@ -381,7 +384,7 @@ int issue_call(pass_ctx *c, int mode, const int32_t *slots, int B, const pass_sa
   const int S = choose_splits(c, B, R, max_keys_of(c, slots, B, mode == MODE_DRAFT ? R : R + 1));
   uint32_t tbits;
   memcpy(&tbits, &sp->temperature, 4);
-  pass_ctx::GraphKey key(mode, B, S, tbits, (uint32_t)sp->seed, (uint32_t)(sp->seed >> 32), commit);
+  pass_ctx::GraphKey key(mode, B, S, tbits, (uint32_t)sp->seed, (uint32_t)(sp->seed >> 32), commit, sp->top_k);
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     if (c->graphs.size() >= 64) {  // bound the cache: drop everything, recapture on demand

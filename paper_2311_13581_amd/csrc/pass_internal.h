@@ -55,6 +55,8 @@ struct Params {
   int32_t *gen;       // [slot][gen_cap]: every generated token since the prefill
   float *logz_d, *logz_p;  // [slot][kMaxK+1]: ln sum exp(logit/T) of each draft / verify row
   int32_t *argmax_p;       // [slot][kMaxK+1]
+  uint32_t *flt_key_d, *flt_key_p;  // [slot][kMaxK+1]: top-k filter of each draft / verify row (threshold key,
+  int32_t *flt_tie_d, *flt_tie_p;   //   highest index kept among the logits equal to the threshold)
   int32_t *fallbacks;      // [1]: residual numerically empty after a reject
   int32_t *block_table;    // [slot][pages_per_seq]
   float *draft_logits, *verify_logits;  // [slot][1+k][V]
@@ -92,6 +94,7 @@ struct SampleArgs {
   float temperature;
   uint32_t seed_lo, seed_hi;
   int commit;  // 0: compute but leave the sequence state untouched (timing replays)
+  int top_k;   // 0: no filter; K: sample from the K largest logits of a row only
 };
 
 // ---- launchers (each checks nothing but launches; shapes are validated by the caller) ----

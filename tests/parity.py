@@ -44,20 +44,20 @@ class StepStats:
                 f"accepted={self.accepted} resyncs={self.resyncs} max_rel_err={self.max_rel_err:.2e}")
 
 
-def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st):
+def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st, top_k=0):
     """One draft + verify on both sides.  Returns (tokens the oracle added, in_sync)."""
     k = gpu.k
     inv_t = 1.0 if temp == 0 else 1.0 / temp
     kv0 = oseq.kv_len
-    o_first, o_drafts = oseq.draft(temp, seed)
-    g_first, g_drafts = gpu.draft([slot], temp, seed)
+    o_first, o_drafts = oseq.draft(temp, seed, top_k=top_k)
+    g_first, g_drafts = gpu.draft([slot], temp, seed, top_k)
     ol, gl = oseq.logits(0), gpu.get_logits(slot, 0)
     err_d = logits_error(gl, ol, tol, f"draft it={it}")
     st.max_rel_err = max(st.max_rel_err, err_d / np.abs(ol).max())
     tau = err_d * inv_t * 1.01 + (0.0 if temp == 0 else F32_ARITH)
     same = True
     for t in range(k + 1):
-        tok, stable = O.sample_softmax(ol[t], temp, seed, seq_id, it, t, O.DRAFT, tau)
+        tok, stable = O.sample_softmax(ol[t], temp, seed, seq_id, it, t, O.DRAFT, tau, top_k)
         o_tok = o_first if t == 0 else o_drafts[t - 1]
         g_tok = g_first[0] if t == 0 else g_drafts[0, t - 1]
         assert tok == o_tok
@@ -68,11 +68,11 @@ def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st):
             st.unstable += 1
             same &= g_tok == tok
     assert gpu.seq_len(slot)[0] == kv0 + 1 == oseq.kv_len
-    o_a, o_out = oseq.verify(temp, seed)
+    o_a, o_out = oseq.verify(temp, seed, top_k=top_k)
     added = [o_first] + [int(x) for x in o_out]
     if not same:
         return added, False
-    g_a, g_out = gpu.verify([slot], temp, seed)
+    g_a, g_out = gpu.verify([slot], temp, seed, top_k)
     pl, gpl = oseq.logits(1), gpu.get_logits(slot, 1)
     err_v = logits_error(gpl, pl, tol, f"verify it={it}")
     st.max_rel_err = max(st.max_rel_err, err_v / np.abs(pl).max())
@@ -80,7 +80,7 @@ def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st):
     a = 0
     chain_stable = True
     for t in range(1, k + 1):  # replay the accept chain with stability flags
-        acc, stable = O.accept(pl[t - 1], ol[t], o_drafts[t - 1], temp, seed, seq_id, it, t, tau)
+        acc, stable = O.accept(pl[t - 1], ol[t], o_drafts[t - 1], temp, seed, seq_id, it, t, tau, top_k)
         st.compared += 1
         if not stable:
             st.unstable += 1
@@ -94,9 +94,9 @@ def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st):
     elif g_a[0] != a:
         return added, False
     if a < k:
-        y, stable, _ = O.sample_residual(pl[a], ol[a + 1], temp, seed, seq_id, it, a + 1, tau)
+        y, stable, _ = O.sample_residual(pl[a], ol[a + 1], temp, seed, seq_id, it, a + 1, tau, top_k)
     else:
-        y, stable = O.sample_softmax(pl[k], temp, seed, seq_id, it, k + 1, O.BONUS, tau)
+        y, stable = O.sample_softmax(pl[k], temp, seed, seq_id, it, k + 1, O.BONUS, tau, top_k)
     assert y == o_out[-1]
     st.compared += 1
     assert np.array_equal(g_out[0, :a], o_out[:a])
@@ -112,7 +112,8 @@ def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st):
     return added, True
 
 
-def stepwise_parity(gpu, omodel, slot, seq_id, prompt, n_iters, temp, seed, tol, max_len=256, stats=None):
+def stepwise_parity(gpu, omodel, slot, seq_id, prompt, n_iters, temp, seed, tol, max_len=256, stats=None,
+                    top_k=0):
     """Drive one sequence through draft / verify on both sides, comparing the logits of every
     call and every decision.  A difference on a stable decision fails.  When an unstable decision
     differs, both sides restart from the oracle's token history (a resync, counted)."""
@@ -125,7 +126,7 @@ def stepwise_parity(gpu, omodel, slot, seq_id, prompt, n_iters, temp, seed, tol,
         oseq.prefill(hist)
         it = 0
         while done < n_iters:
-            added, in_sync = _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st)
+            added, in_sync = _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st, top_k)
             hist += added
             done += 1
             it += 1

@@ -154,6 +154,9 @@ def test_error_paths():
         g.draft([0, 0], 1.0, 1)
     assert e.value.code == -1
     with pytest.raises(binding.PassError) as e:
+        g.draft([0], 1.0, 1, -3)  # negative top-k
+    assert e.value.code == -1
+    with pytest.raises(binding.PassError) as e:
         g.generate([0], 64, 1.0, 1)  # runs out of positions
     assert e.value.code == -3
     g.prefill(0, [1, 2, 3])  # the slot is usable again after the failure
@@ -216,9 +219,10 @@ def test_7b_layer_shapes_two_layers():
     g = _gpu(w.shape, W, w.k, max_seq_len=128, page_size=64)
     m = O.Model(w.shape, W, w.k)
     prompt = synth.make_prompts(w)[0][:37]
-    for temp in (0.0, 0.8):
-        st = parity.stepwise_parity(g, m, 0, 1, prompt, 2, temp, 99, parity.LOGIT_TOL[synth.BF16], max_len=128)
-        print(temp, st)
+    for temp, top_k in ((0.0, 0), (0.8, 0), (0.8, 10)):
+        st = parity.stepwise_parity(g, m, 0, 1, prompt, 2, temp, 99, parity.LOGIT_TOL[synth.BF16], max_len=128,
+                                    top_k=top_k)
+        print(temp, top_k, st)
         assert st.iterations == 2
     g.close()
 
@@ -266,3 +270,54 @@ def test_matrix_core_attention(temp, plen):
         assert st.iterations == 6 and st.resyncs == 0 and st.max_rel_err < 1e-3
         g.close()
 
+
+
+@pytest.mark.parametrize("w", [TINY, TINY_BF16, MFMA_HD128], ids=["fp32", "bf16", "mfma"])
+@pytest.mark.parametrize("top_k", [1, 10, 25, 100000])
+def test_top_k_sampling_stepwise(w, top_k):
+    """Top-k sampling (the paper's sampler: k = 10, 25) in both epilogues: every decision of 16
+    iterations against the oracle; K = 1 is greedy in effect, K above the vocabulary no filter."""
+    g, m, _ = _both(w, w.k, max_seq_len=256, page_size=64 if w is MFMA_HD128 else 16)
+    prompt = synth.make_prompts(w)[0]
+    st = parity.stepwise_parity(g, m, 0, 5, prompt, 16, 0.8, 4242, parity.LOGIT_TOL[w.shape.dtype], top_k=top_k)
+    print(top_k, st)
+    assert st.iterations == 16
+    if w.shape.dtype == synth.F32:
+        assert st.resyncs == 0 and st.unstable <= 2
+    g.close()
+
+
+def test_top_k_boundary_ties_keep_the_lower_indices():
+    """Exactly equal logits across the top-k boundary (LM-head rows repeated in blocks of 8): the
+    kept set is the K largest with ties to the lower index.  Checked on the GPU's own logits with
+    a stable sort: over many draws at a high temperature every sampled token lies in that set, and
+    every member of the set shows up."""
+    w = TINY
+    W = synth.make_weights(w.shape, 77, w.k, 8.0)
+    V = w.shape.vocab
+    lm = W["lm_head"].reshape(V, -1).copy()
+    lm[:] = lm[(np.arange(V) // 8) * 8]      # rows 8b..8b+7 all equal row 8b
+    W["lm_head"] = lm.reshape(W["lm_head"].shape)
+    g = _gpu(w.shape, W, w.k, max_seq_len=256)
+    K = 11                                    # one whole block of 8 and 3 of the next
+    prompt = synth.make_prompts(w)[0]
+    g.prefill(0, prompt, seq_id=0)
+    seen = [set() for _ in range(w.k + 1)]
+    kept = None
+    for seed in range(300):
+        first, drafts = g.draft([0], 50.0, seed, K)   # commits x_{n+1}; restart below keeps the rows the same
+        lg = g.get_logits(0, 0)
+        order = [np.argsort(-lg[r], kind="stable")[:K] for r in range(w.k + 1)]
+        if kept is None:
+            kept = [set(int(j) for j in o) for o in order]
+            for r in range(w.k + 1):          # the boundary really cuts a block of equal logits
+                srt = np.sort(lg[r])[::-1]
+                assert srt[K - 1] == srt[K]
+        toks = [int(first[0])] + [int(t) for t in drafts[0]]
+        for r, t in enumerate(toks):
+            assert t in kept[r], (seed, r, t)
+            seen[r].add(t)
+        g.prefill(0, prompt, seq_id=0)        # same context again: same logits, new seed
+    for r in range(w.k + 1):
+        assert seen[r] == kept[r]
+    g.close()
