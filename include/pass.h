@@ -160,7 +160,12 @@ int pass_seq_len(pass_ctx *ctx, int slot, int32_t *kv_len, int32_t *n_generated)
  * kernel and its transposed V pages; before pass_load_weights), "gemm_cfg" (launch shape of the decode-sized matrix-core GEMMs, process-wide:
  * kind * 10000 + wavefronts * 100 + unroll with kind 0 QKV, 1 Wo, 2 gate/up, 3 LM head, 4 down, wavefronts 4/8/16,
  * unroll 1/2/4; for calls with more than 8 rows 1000000 + kind * 10000 + wavefronts * 100 + blocks with
- * wavefronts 8/16 and blocks (strips of 16 output features per workgroup) 1/2/4), "kernel_timing" (1 = after every model call, launch the dominant kernel, the gate/up GEMM,
+ * wavefronts 8/16 and blocks (strips of 16 output features per workgroup) 1/2/4), "lookahead_rows" (look-ahead rows per call from now on, 0 .. k: the drafting call uses the first
+ * that many look-ahead embeddings, outputs and logits keep their k-sized layout with unused entries -1 /
+ * stale; the paper's sweep over the number of look-ahead tokens without reloading), "lookahead_token" (-1 =
+ * trained look-ahead embeddings; a token id = the drafting call appends that token's embedding instead, the
+ * paper's second baseline with a fixed [UNK] token; both only between iterations, else PASS_ESTATE),
+ * "kernel_timing" (1 = after every model call, launch the dominant kernel, the gate/up GEMM,
  * once per layer with that layer's weights on the call's rows, back to back between two HIP events on
  * the context's stream, and synchronise; the launches write workspaces only; setting the option resets
  * the counters pass_kernel_time reports).  Unknown names: PASS_EINVAL. */

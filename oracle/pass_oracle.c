@@ -41,6 +41,8 @@
  *     distribution and independent of summation order; ties go to the lowest index;
  *   - r is drawn from the open interval (0,1); the test is ln r + ln d(x) < ln p(x);
  *   - temperature 0 means greedy: every sample is an argmax (the one-hot limit of the rule);
+ *   - the second baseline (Baselines: a fixed [UNK] token in place of the trained look-ahead
+ *     embeddings) is the same algorithm with the embedding of one fixed token appended k times;
  *   - top-k sampling (Experimental setup: k = 10, and k = 25 for pass@10): the draft and the
  *     target distribution are each the softmax over the row's own k largest logits (ties at the
  *     boundary go to the lower index), zero elsewhere; the accept test and the residual use
@@ -69,6 +71,9 @@ typedef struct {
   int32_t dtype;    /* ORC_F32 / ORC_BF16: storage type of every model tensor */
   int32_t k;        /* number of look-ahead embeddings, L in Algorithm 1 */
   int32_t act_bf16; /* also round activations between matrix products to bfloat16 (see header) */
+  int32_t la_token; /* < 0: the drafting call appends the look-ahead embeddings (PaSS);
+                       >= 0: it appends the embedding of this fixed token k times instead (the
+                       paper's second baseline, Baselines: a fixed [UNK] token as look-ahead) */
 } orc_config;
 
 typedef struct {
@@ -347,6 +352,7 @@ static const void **dup_ptrs(const void *const *p, int n) {
 /* The oracle borrows the weight buffers: the caller keeps them alive until orc_model_free. */
 orc_model *orc_model_create(const orc_config *c, const orc_weights *w) {
   if (!c || !w || c->k < 0 || c->k > ORC_MAX_K || c->n_layers < 0 || (c->head_dim & 1)) return NULL;
+  if (c->la_token >= c->vocab) return NULL;
   orc_model *m = (orc_model *)calloc(1, sizeof(orc_model));
   m->c = *c;
   m->tok_emb = w->tok_emb; m->lm_head = w->lm_head;
@@ -574,7 +580,10 @@ int orc_draft(orc_seq *s, const orc_sampling *sp, double tau, int32_t *out_first
   if (s->kv_len + 1 + k > s->max_len) return ORC_ECAPACITY;
   int32_t ids[ORC_MAX_K + 1], la[ORC_MAX_K + 1];
   ids[0] = s->pending; la[0] = 0;
-  for (int t = 1; t <= k; ++t) { ids[t] = t - 1; la[t] = 1; }
+  for (int t = 1; t <= k; ++t) {
+    if (c->la_token >= 0) { ids[t] = c->la_token; la[t] = 0; }
+    else { ids[t] = t - 1; la[t] = 1; }
+  }
   int rc = orc_forward(s, 1 + k, ids, la, s->kv_len, s->draft_logits);
   if (rc) return rc;
   for (int t = 0; t <= k; ++t) {

@@ -27,7 +27,7 @@ class Config(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("d_ffn", C.c_int32), ("vocab", C.c_int32),
                 ("rms_eps", C.c_float), ("rope_base", C.c_float), ("dtype", C.c_int32),
-                ("k", C.c_int32), ("act_bf16", C.c_int32)]
+                ("k", C.c_int32), ("act_bf16", C.c_int32), ("la_token", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)
@@ -163,13 +163,13 @@ def sample_residual(p_logits, d_logits, temperature, seed=0, seq_id=0, iteration
 class Model:
     """Borrowed-weights transformer.  `weights` is the dict made by the synthetic generator."""
 
-    def __init__(self, shape, weights: dict, k: int, act_bf16: bool | None = None):
+    def __init__(self, shape, weights: dict, k: int, act_bf16: bool | None = None, la_token: int = -1):
         self.shape = shape
         self.k = k
         if act_bf16 is None:
             act_bf16 = False
         self.cfg = Config(shape.n_layers, shape.d_model, shape.n_heads, shape.head_dim, shape.d_ffn,
-                          shape.vocab, shape.rms_eps, shape.rope_base, shape.dtype, k, int(act_bf16))
+                          shape.vocab, shape.rms_eps, shape.rope_base, shape.dtype, k, int(act_bf16), int(la_token))
         self._keep = weights  # keep the numpy buffers alive
         w = Weights()
         for name in ("tok_emb", "lm_head", "final_norm", "lookahead"):

@@ -151,6 +151,8 @@ class Pass:
 
     def set_option(self, name: str, value: int):
         self._check(self.lib.pass_set_option(self.h, name.encode(), int(value)))
+        if name == "lookahead_rows":
+            self.k_act = int(value)  # rows 1 .. k_act of drafts / logits are live, the rest padding
 
     def load_weights(self, weights: dict):
         """weights: dict of numpy arrays (host) or torch CUDA tensors (device), plain layout."""

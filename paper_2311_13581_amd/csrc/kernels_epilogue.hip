@@ -365,11 +365,11 @@ __global__ __launch_bounds__(kEpiThreads) void verify_decide_kernel(Params p, Sa
   __shared__ Best sh_b[kEpiWaves];
   __shared__ int sh_a;
   const int slot = p.step_slots[blockIdx.x];
-  const int k = p.k, V = p.V;
+  const int k = p.k_act, V = p.V;  // rows of this call; the logits buffers keep the stride 1 + p.k
   const bool greedy = a.temperature == 0.f;
   const float inv_t = greedy ? 1.f : 1.f / a.temperature;
-  const float *P = p.verify_logits + (size_t)slot * (1 + k) * V;
-  const float *Dl = p.draft_logits + (size_t)slot * (1 + k) * V;
+  const float *P = p.verify_logits + (size_t)slot * (1 + p.k) * V;
+  const float *Dl = p.draft_logits + (size_t)slot * (1 + p.k) * V;
   const float *zp = p.logz_p + slot * (kMaxK + 1), *zd = p.logz_d + slot * (kMaxK + 1);
   const int32_t *drafts = p.drafts + slot * kMaxK;
   const uint32_t it = p.iter[slot], sid = p.seq_id[slot];

@@ -101,7 +101,8 @@ __global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint
   } else if (r == 0) {
     src = tok_emb + (size_t)p.pending[slot] * p.d;
   } else if (mode == MODE_DRAFT) {
-    src = lookahead + (size_t)(r - 1) * p.d;
+    // look-ahead embedding r (Section 2.2.1), or the fixed token of the paper's second baseline
+    src = p.la_token >= 0 ? tok_emb + (size_t)p.la_token * p.d : lookahead + (size_t)(r - 1) * p.d;
   } else {
     src = tok_emb + (size_t)p.drafts[slot * kMaxK + (r - 1)] * p.d;
   }

@@ -67,7 +67,7 @@ struct pass_ctx {
   // optional timing of the dominant kernel (the gate/up GEMM): one event pair per layer
   // captured (model call + epilogue) graphs, keyed by everything that is baked into the launches:
   // mode, batch, attention grid width, sampling arguments
-  typedef std::tuple<int, int, int, uint32_t, uint32_t, uint32_t, int, int> GraphKey;
+  typedef std::tuple<int, int, int, uint32_t, uint32_t, uint32_t, int, int, int, int> GraphKey;
   std::map<GraphKey, hipGraphExec_t> graphs;
   int opt_kernel_timing = 0;
   std::vector<hipEvent_t> kev;
@@ -130,7 +130,7 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   Params P;
   memset(&P, 0, sizeof P);
   P.L = c.n_layers; P.d = c.d_model; P.H = c.n_heads; P.hd = c.head_dim; P.D = (int)D; P.F = c.d_ffn; P.V = c.vocab;
-  P.k = c.k; P.max_slots = c.max_slots; P.max_seq_len = c.max_seq_len; P.page_size = c.page_size;
+  P.k = c.k; P.k_act = c.k; P.la_token = -1; P.max_slots = c.max_slots; P.max_seq_len = c.max_seq_len; P.page_size = c.page_size;
   P.page_shift = __builtin_ctz(c.page_size); P.n_pages = np; P.pages_per_seq = pps;
   P.gen_cap = c.max_seq_len + kMaxK + 2;
   P.eps = c.rms_eps; P.rope_base = c.rope_base;
@@ -361,7 +361,7 @@ int max_keys_of(pass_ctx *c, const int32_t *slots, int B, int extra) {
 
 // the two halves of an iteration, without host synchronisation
 int issue_call_eager(pass_ctx *c, int mode, const int32_t *slots, int B, const pass_sampling *sp, int commit) {
-  const int R = 1 + c->cfg.k;
+  const int R = 1 + c->P.k_act;
   const bool draft = mode == MODE_DRAFT;
   int rc = run_step(c, mode, B, R, draft ? c->P.draft_logits : c->P.verify_logits,
                     max_keys_of(c, slots, B, draft ? R : R + 1), nullptr);
@@ -380,11 +380,11 @@ int issue_call_eager(pass_ctx *c, int mode, const int32_t *slots, int B, const p
 int issue_call(pass_ctx *c, int mode, const int32_t *slots, int B, const pass_sampling *sp, int commit) {
   // the null stream cannot be captured: graphs need a stream of their own
   if (!c->opt_graph || c->opt_kernel_timing || c->stream == nullptr) return issue_call_eager(c, mode, slots, B, sp, commit);
-  const int R = 1 + c->cfg.k;
+  const int R = 1 + c->P.k_act;
   const int S = choose_splits(c, B, R, max_keys_of(c, slots, B, mode == MODE_DRAFT ? R : R + 1));
   uint32_t tbits;
   memcpy(&tbits, &sp->temperature, 4);
-  pass_ctx::GraphKey key(mode, B, S, tbits, (uint32_t)sp->seed, (uint32_t)(sp->seed >> 32), commit, sp->top_k);
+  pass_ctx::GraphKey key(mode, B, S, tbits, (uint32_t)sp->seed, (uint32_t)(sp->seed >> 32), commit, sp->top_k, c->P.k_act, c->P.la_token);
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     if (c->graphs.size() >= 64) {  // bound the cache: drop everything, recapture on demand
@@ -625,7 +625,7 @@ int pass_draft(pass_ctx *c, const int32_t *slots, int n_slots, const pass_sampli
     s.state = 2;
     if (out_first) out_first[b] = r[3];
     if (out_drafts)
-      for (int t = 0; t < k; ++t) out_drafts[b * k + t] = r[4 + t];
+      for (int t = 0; t < k; ++t) out_drafts[b * k + t] = t < c->P.k_act ? r[4 + t] : -1;
   }
   return PASS_OK;
 }
@@ -712,7 +712,7 @@ int pass_generate(pass_ctx *c, const int32_t *slots, int n_slots, int max_new, c
       Slot &s = c->slots[slots[b]];
       if (r[1] != s.n_gen) {  // the slot was live in this iteration
         st.iterations += 1;
-        st.drafts_proposed += k;
+        st.drafts_proposed += c->P.k_act;
         st.drafts_accepted += r[2];
       }
       s.kv_len = r[0];
@@ -762,7 +762,7 @@ int pass_run_iterations(pass_ctx *c, const int32_t *slots, int n_slots, int n_it
       const int32_t *r = c->report_host + b * kReportStride;
       Slot &s = c->slots[slots[b]];
       st.iterations += 1;
-      st.drafts_proposed += k;
+      st.drafts_proposed += c->P.k_act;
       st.drafts_accepted += r[2];
       st.tokens_out += r[1] - s.n_gen;
       s.kv_len = r[0];
@@ -811,6 +811,18 @@ int pass_set_option(pass_ctx *c, const char *name, int value) {
       return fail(c, PASS_EINVAL, "gemm_cfg: kind 0..4, wavefronts 4/8/16, unroll 1/2/4");
     for (auto &g : c->graphs) (void)hipGraphExecDestroy(g.second);  // captured launches carry the old shape
     c->graphs.clear();
+    return PASS_OK;
+  }
+  if (!strcmp(name, "lookahead_rows") || !strcmp(name, "lookahead_token")) {
+    for (const Slot &s : c->slots)
+      if (s.state == 2) return fail(c, PASS_ESTATE, "%s cannot change between a drafting and a validation call", name);
+    if (!strcmp(name, "lookahead_rows")) {
+      if (value < 0 || value > c->cfg.k) return fail(c, PASS_EINVAL, "lookahead_rows: 0 .. k (%d)", c->cfg.k);
+      c->P.k_act = value;
+    } else {
+      if (value < -1 || value >= c->cfg.vocab) return fail(c, PASS_EINVAL, "lookahead_token: -1 (embeddings) or a token id");
+      c->P.la_token = value;
+    }
     return PASS_OK;
   }
   if (!strcmp(name, "kernel_timing")) {

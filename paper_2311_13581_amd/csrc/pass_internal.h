@@ -44,6 +44,8 @@ __device__ __forceinline__ void store_f(bf16_t *p, size_t i, float v) { p[i].bit
 struct Params {
   // shape
   int L, d, H, hd, D, F, V, k;
+  int k_act;     // look-ahead rows per call right now (0 .. k; buffers keep their stride 1 + k)
+  int la_token;  // < 0: drafting rows are the look-ahead embeddings; >= 0: this token's embedding, k_act times
   int max_slots, max_seq_len, page_size, page_shift, n_pages, pages_per_seq;
   int gen_cap;
   int v_transposed;  // V pages hold [head][dim][page_size] (matrix-core attention) instead of [head][page_size][dim]

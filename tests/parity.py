@@ -46,12 +46,12 @@ class StepStats:
 
 def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st, top_k=0):
     """One draft + verify on both sides.  Returns (tokens the oracle added, in_sync)."""
-    k = gpu.k
+    k = getattr(gpu, "k_act", gpu.k)  # look-ahead rows of this call (buffers are sized for gpu.k)
     inv_t = 1.0 if temp == 0 else 1.0 / temp
     kv0 = oseq.kv_len
     o_first, o_drafts = oseq.draft(temp, seed, top_k=top_k)
     g_first, g_drafts = gpu.draft([slot], temp, seed, top_k)
-    ol, gl = oseq.logits(0), gpu.get_logits(slot, 0)
+    ol, gl = oseq.logits(0), gpu.get_logits(slot, 0)[:k + 1]
     err_d = logits_error(gl, ol, tol, f"draft it={it}")
     st.max_rel_err = max(st.max_rel_err, err_d / np.abs(ol).max())
     tau = err_d * inv_t * 1.01 + (0.0 if temp == 0 else F32_ARITH)
@@ -73,7 +73,7 @@ def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st, top_k=0):
     if not same:
         return added, False
     g_a, g_out = gpu.verify([slot], temp, seed, top_k)
-    pl, gpl = oseq.logits(1), gpu.get_logits(slot, 1)
+    pl, gpl = oseq.logits(1), gpu.get_logits(slot, 1)[:k + 1]
     err_v = logits_error(gpl, pl, tol, f"verify it={it}")
     st.max_rel_err = max(st.max_rel_err, err_v / np.abs(pl).max())
     tau = max(err_d, err_v) * inv_t * 1.01 + (0.0 if temp == 0 else F32_ARITH)

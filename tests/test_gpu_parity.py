@@ -321,3 +321,46 @@ def test_top_k_boundary_ties_keep_the_lower_indices():
     for r in range(w.k + 1):
         assert seen[r] == kept[r]
     g.close()
+
+
+def test_lookahead_rows_change_at_run_time():
+    """One loaded model (k = 6), the number of look-ahead rows per call switched by option: every
+    setting must equal an oracle model built with that many look-ahead embeddings (the paper's sweep
+    over the number of look-ahead tokens, without reloading)."""
+    from paper_2311_13581_amd import binding
+    w = synth.scaled(TINY, k=6)
+    W = synth.make_weights(w.shape, 31, 6, 6.0)
+    g = _gpu(w.shape, W, 6)
+    prompt = np.random.default_rng(9).integers(0, w.shape.vocab, 29).astype(np.int32)
+    for k_act in (0, 2, 6, 3):
+        g.set_option("lookahead_rows", k_act)
+        m = O.Model(w.shape, W, k_act)
+        st = parity.stepwise_parity(g, m, 0, 2, prompt, 8, 0.9, 321, 1e-4)
+        print(k_act, st)
+        assert st.iterations == 8 and st.resyncs == 0
+    g.prefill(0, prompt)
+    g.draft([0], 0.0, 1)
+    with pytest.raises(binding.PassError) as e:   # not between a drafting and a validation call
+        g.set_option("lookahead_rows", 1)
+    assert e.value.code == -2
+    g.verify([0], 0.0, 1)
+    with pytest.raises(binding.PassError) as e:
+        g.set_option("lookahead_rows", 7)
+    assert e.value.code == -1
+    g.close()
+
+
+@pytest.mark.parametrize("w", [TINY, MFMA_HD128], ids=["fp32", "mfma"])
+def test_fixed_token_as_lookahead(w):
+    """The paper's second baseline: a fixed token's embedding appended instead of the trained
+    look-ahead embeddings ("lookahead_token" option), against the oracle in the same mode."""
+    unk = 3
+    g, _, W = _both(w, w.k, max_seq_len=256, page_size=64 if w is MFMA_HD128 else 16)
+    g.set_option("lookahead_token", unk)
+    m = O.Model(w.shape, W, w.k, la_token=unk)
+    prompt = synth.make_prompts(w)[0]
+    for temp in (0.0, 1.0):
+        st = parity.stepwise_parity(g, m, 0, 4, prompt, 10, temp, 77, parity.LOGIT_TOL[w.shape.dtype])
+        print(temp, st)
+        assert st.iterations == 10
+    g.close()

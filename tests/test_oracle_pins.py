@@ -611,3 +611,29 @@ def test_topk_pass_keeps_the_greedy_and_bookkeeping_invariants():
         n_tok += 1 + len(out)
         assert 0 <= acc <= 2 and len(out) == acc + 1
         assert c.kv_len == n_tok - 1
+
+
+# ------------------------------------------------------------------------------------------
+# fixed token as look-ahead (Baselines: [UNK] instead of trained look-ahead embeddings)
+# ------------------------------------------------------------------------------------------
+def test_fixed_token_lookahead_feeds_token_rows_and_stays_lossless():
+    """With la_token set, the drafting call's rows are (last token, that token k times): logits
+    equal the library composition on exactly that sequence; greedy decoding still equals greedy
+    auto-regressive decoding; the trained-embedding rows are not used."""
+    w = TINY
+    k, unk = 3, 7
+    W = synth.make_weights(w.shape, 12, k, 8.0)
+    m = O.Model(w.shape, W, k, la_token=unk)
+    prompt = synth.make_prompts(w)[0]
+    s = m.sequence(128)
+    s.prefill(prompt)
+    s.draft(0.0, 1)
+    ref = torch_ref.forward_full(w.shape, W, np.array(list(prompt) + [unk] * k), 0).numpy()[-(k + 1):]
+    got = s.logits(0)
+    assert np.abs(got - ref).max() < 1e-4 * np.abs(ref).max()
+    pass_rows = torch_ref.forward_full(w.shape, W, prompt, k).numpy()[-(k + 1):]
+    assert np.abs(got[1:] - pass_rows[1:]).max() > 1e-2 * np.abs(ref).max()   # really a different input
+    a, b = m.sequence(160), O.Model(w.shape, W, 0).sequence(160)
+    a.prefill(prompt)
+    b.prefill(prompt)
+    assert np.array_equal(a.generate(40, 0.0, 3)[0], b.generate_ar(40, 0.0, 3))
