@@ -70,6 +70,7 @@ struct pass_ctx {
   typedef std::tuple<int, int, int, uint32_t, uint32_t, uint32_t, int, int, int, int> GraphKey;
   std::map<GraphKey, hipGraphExec_t> graphs;
   int opt_kernel_timing = 0;
+  int opt_prefill_chunk = 64;
   std::vector<hipEvent_t> kev;
   double kernel_ms = 0;
   int64_t kernel_launches = 0;
@@ -584,7 +585,7 @@ int pass_prefill(pass_ctx *c, int slot, uint32_t seq_id, const int32_t *prompt, 
   if ((rc = poke(c, ptrs, vals))) return rc;
   if (n > 1) {
     HIP_TRY(c, hipMemcpyAsync(c->prompt_buf, prompt, sizeof(int32_t) * (n - 1), hipMemcpyHostToDevice, c->stream));
-    const int chunk = 32;
+    const int chunk = c->opt_prefill_chunk;  // rows per pass over the weights
     for (int done = 0; done < n - 1; done += chunk) {
       int R = std::min(chunk, n - 1 - done);
       ptrs = {P.kv_len + slot};
@@ -823,6 +824,11 @@ int pass_set_option(pass_ctx *c, const char *name, int value) {
       if (value < -1 || value >= c->cfg.vocab) return fail(c, PASS_EINVAL, "lookahead_token: -1 (embeddings) or a token id");
       c->P.la_token = value;
     }
+    return PASS_OK;
+  }
+  if (!strcmp(name, "prefill_chunk")) {
+    if (value < 1 || value > kMaxRows) return fail(c, PASS_EINVAL, "prefill_chunk: 1 .. %d", kMaxRows);
+    c->opt_prefill_chunk = value;
     return PASS_OK;
   }
   if (!strcmp(name, "kernel_timing")) {
