@@ -164,7 +164,7 @@ void launch_assemble_mfma(const Params &p, const void *tok_emb, const void *look
 // ---------------------------------------------------------------------------------------------
 // The streaming GEMM
 // ---------------------------------------------------------------------------------------------
-enum { EPI_QKV = 0, EPI_RESID = 1, EPI_GATEUP = 2, EPI_LOGITS = 3 };
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_GATEUP = 2, EPI_LOGITS = 3, EPI_PARTIAL = 4 };
 
 struct GemmArgs {
   const u32x4 *W;             // packed weight tiles
@@ -173,6 +173,8 @@ struct GemmArgs {
   int layer;
   const uint16_t *gain_next;  // RESID: gain of the norm that follows
   float *logits;              // LOGITS: base of the [slot][1+k][V] logits
+  int kt_split;               // PARTIAL: k-tiles per workgroup row (blockIdx.y picks the slice of K); else 0
+  float *partial;             // PARTIAL: [gridDim.y][kMaxRows][N] sums over the slice of K
 };
 
 // MT = number of 8-row groups (one MFMA column block each); NB = output blocks per workgroup (a
@@ -184,14 +186,16 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
   constexpr int kGemmWaves = WAVES;
   constexpr int PER = (EPI == EPI_GATEUP) ? 2 : 1;  // strips per block
   constexpr int NS = NB * PER;
-  constexpr bool NORM = (EPI != EPI_RESID);
+  constexpr bool NORM = (EPI != EPI_RESID && EPI != EPI_PARTIAL);
   static_assert(WAVES * NS <= 32 && NB <= WAVES, "reduction buffer must fit the static LDS limit");
   __shared__ floatx4 red[kGemmWaves][NS][64];  // one 8-row group at a time
   __shared__ float red_ss[kGemmWaves][MT][8];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int ml = lane & 15, g = lane >> 4;  // ml: MFMA column = pseudo-row; g: k-group of 8
-  const int KT = a.K >> 5;
+  const int KT = a.K >> 5;                                        // k-tiles of the whole K (strip stride)
+  const int KTl = (EPI == EPI_PARTIAL) ? a.kt_split : KT;         // k-tiles this workgroup walks
+  const int kbase = (EPI == EPI_PARTIAL) ? blockIdx.y * KTl : 0;  // first of them
   const int strip0 = blockIdx.x * NS;
 
   floatx4 acc[NS][MT];
@@ -211,9 +215,9 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     int m = mt * 8 + (ml & 7);
-    xoff[mt] = (m < a.M) ? (mt * KT * 64 + lane) * 16 : 0x40000000;
+    xoff[mt] = (m < a.M) ? ((mt * KT + kbase) * 64 + lane) * 16 : 0x40000000;
   }
-  const u32x4 *wp = a.W + (size_t)strip0 * KT * 64 + lane;
+  const u32x4 *wp = a.W + ((size_t)strip0 * KT + kbase) * 64 + lane;
 
   auto load_a = [&](u32x4 (&dst)[U][NS], int kt0) {
 #pragma unroll
@@ -243,7 +247,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
   // full trips: k-tiles kt0 + u * WAVES, u < U, with kt0 = wave + trip * WAVES * U (interleaved
   // over the wavefronts, so the workgroup walks its strip front to back)
   const int trip_tiles = kGemmWaves * U;
-  const int n_trips = KT / trip_tiles;
+  const int n_trips = KTl / trip_tiles;
   if (n_trips > 0) {
     // Both operands of trip t+1 are requested during trip t, activations first, so a trip only
     // ever waits for requests that have had a whole trip to complete.
@@ -266,7 +270,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
     mma(a_cur, b_cur);
   }
   // tail: the k-tiles that do not fill a trip, one per wavefront and step (wavefront-uniform bound)
-  for (int kt = n_trips * trip_tiles + wave; kt < KT; kt += kGemmWaves) {
+  for (int kt = n_trips * trip_tiles + wave; kt < KTl; kt += kGemmWaves) {
     u32x4 bv[MT];
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) bv[mt] = __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[mt] + kt * 1024, 0, 0);
@@ -343,6 +347,10 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
         }
         store_split4(p.act_x, m, p.F, f0, t);
       }
+    } else if constexpr (EPI == EPI_PARTIAL) {
+      // sums over this workgroup's slice of K; the slices are added up by resid_reduce_kernel
+      if (live)
+        *(floatx4 *)(a.partial + ((size_t)blockIdx.y * kMaxRows + m) * p.d + strip * 16 + 4 * g) = y[0];
     } else if constexpr (EPI == EPI_RESID) {
       int n = strip * 16 + 4 * g;
       float ss = 0.f;
@@ -492,21 +500,93 @@ static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hi
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Residual projections (Wo, down) of calls with more than 8 rows.  N = d gives only d/16 strips,
+// one per compute unit at best, and every workgroup would have to pull all M activation rows
+// through its L1: that traffic, not HBM, bounds the kernel.  So K is cut into KS slices across
+// workgroups that each own 4 strips (an activation tile fetched is used 4 times); the slices'
+// sums go to a workspace and this kernel adds them in slice order (deterministic), then does what
+// the fused epilogue does: residual add into h, (hi, lo) of h * gain of the next norm, per-strip
+// partial sums of h^2.  One workgroup per strip of 16 features: thread = (row, 4 features).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void resid_reduce_kernel(Params p, const float *partial, int KS, int M,
+                                                           const uint16_t *gain_next) {
+  const int strip = blockIdx.x, m = threadIdx.x >> 2, n = strip * 16 + (threadIdx.x & 3) * 4;
+  float ss = 0.f;
+  if (m < M) {
+    float *hp = p.h + (size_t)m * p.d + n;
+    floatx4 hv = *(floatx4 *)hp;
+    floatx4 part[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks)  // all slices requested at once (index clamped, surplus dropped)
+      part[ks] = *(const floatx4 *)(partial + ((size_t)min(ks, KS - 1) * kMaxRows + m) * p.d + n);
+    floatx4 y = part[0];
+#pragma unroll
+    for (int ks = 1; ks < 8; ++ks)
+      if (ks < KS) y += part[ks];
+    hv += y;
+    *(floatx4 *)hp = hv;
+    float t[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      t[r] = hv[r] * bf16_to_f32(gain_next[n + r]);
+      ss += hv[r] * hv[r];
+    }
+    store_split4(p.xg, m, p.d, n, t);
+  }
+  ss += __shfl_xor(ss, 1);
+  ss += __shfl_xor(ss, 2);
+  if ((threadIdx.x & 3) == 0) p.ssq[(size_t)strip * kMaxRows + m] = ss;  // rows >= M get 0
+}
+
+// wavefronts per workgroup, strips per workgroup and K slices of the split residual GEMM
+constexpr int kSplitWaves = 8, kSplitBlocks = 4;
+static int g_split_ks = 4;  // override: gemm_cfg 2000000 + slices (0 = never split)
+
+int set_gemm_split(int ks) {
+  if (ks < 0 || ks > 8) return -1;
+  g_split_ks = ks;
+  return 0;
+}
+
+static bool launch_resid_split(const Params &p, const GemmArgs &a0, int mt, hipStream_t s) {
+  const int n_strips = p.d / 16, KT = a0.K >> 5, KS = g_split_ks;
+  if (KS < 2 || n_strips % kSplitBlocks != 0 || KT % KS != 0) return false;
+  if ((size_t)KS * p.d > (size_t)2 * p.F) return false;  // the slices' sums borrow the generic path's gate/up workspace
+  GemmArgs a = a0;
+  a.kt_split = KT / KS;
+  a.partial = p.gu;
+  dim3 grid(n_strips / kSplitBlocks, KS);
+  constexpr int T = kSplitWaves * 64;
+  switch (mt) {
+    case 2: gemm_mfma_kernel<2, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    case 3: gemm_mfma_kernel<3, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    case 4: gemm_mfma_kernel<4, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    case 5: gemm_mfma_kernel<5, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    case 6: gemm_mfma_kernel<6, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    case 7: gemm_mfma_kernel<7, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    default: gemm_mfma_kernel<8, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+  }
+  resid_reduce_kernel<<<n_strips, 256, 0, s>>>(p, a.partial, KS, a.M, a.gain_next);
+  return true;
+}
+
 void launch_gemm_qkv(const Params &p, const void *W, int layer, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, layer, nullptr, nullptr};
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, layer, nullptr, nullptr, 0, nullptr};
   launch_gemm_epi<EPI_QKV>(p, a, 3 * p.D / 16, s);
 }
 void launch_gemm_resid(const Params &p, const void *W, const uint16_t *X, int K, const void *gain_next, int M,
                        hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, X, M, K, 0, (const uint16_t *)gain_next, nullptr};
+  GemmArgs a{(const u32x4 *)W, X, M, K, 0, (const uint16_t *)gain_next, nullptr, 0, nullptr};
+  if (M > 8 && launch_resid_split(p, a, (M + 7) / 8, s)) return;
   launch_gemm_epi<EPI_RESID>(p, a, p.d / 16, s, K == p.F ? 4 : 1);  // the down projection has its own shape
 }
 void launch_gemm_gateup(const Params &p, const void *W, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, nullptr};
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, nullptr, 0, nullptr};
   launch_gemm_epi<EPI_GATEUP>(p, a, 2 * p.F / 16, s);
 }
 void launch_gemm_logits(const Params &p, const void *W, float *logits, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, logits};
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, logits, 0, nullptr};
   launch_gemm_epi<EPI_LOGITS>(p, a, p.V / 16, s);
 }
 

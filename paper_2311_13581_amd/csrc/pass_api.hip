@@ -804,7 +804,9 @@ int pass_set_option(pass_ctx *c, const char *name, int value) {
   if (!c || !name) return PASS_EINVAL;
   if (!strcmp(name, "graph")) { c->opt_graph = value; return PASS_OK; }
   if (!strcmp(name, "gemm_cfg")) {
-    if (value >= 1000000) {
+    if (value >= 2000000) {
+      if (set_gemm_split(value - 2000000)) return fail(c, PASS_EINVAL, "gemm_cfg (split residual GEMM): 0 .. 8 slices of K");
+    } else if (value >= 1000000) {
       int v = value - 1000000;
       if (set_gemm_config_big(v / 10000, (v / 100) % 100, v % 100))
         return fail(c, PASS_EINVAL, "gemm_cfg (more than 8 rows): kind 0..4, wavefronts 8/16, blocks 1/2/4");

@@ -135,6 +135,7 @@ __device__ __forceinline__ size_t xs_index(int m, int K, int k) {
 constexpr int kXsLoOffset = 64;  // elements from a hi half to its lo half
 
 int set_gemm_config_big(int kind, int waves, int blocks);  // calls with more than 8 rows
+int set_gemm_split(int ks);  // K slices of the split residual GEMMs (0 = never split)
 int set_gemm_config(int kind, int waves, int unroll);  // kind: 0 QKV, 1 Wo, 2 gate/up, 3 LM head, 4 down
 void launch_gemm_logits(const Params &p, const void *W, float *logits, int M, hipStream_t s);
 
