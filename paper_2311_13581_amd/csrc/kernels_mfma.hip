@@ -288,11 +288,20 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
   // Lane (ml & 7) covers row mt*8 + (ml & 7); the two halves of the columns take alternate partials.
   if constexpr (NORM) {
     const int NP = p.d / 16;
-#pragma unroll
+    // requested in batches of 8 through a buffer descriptor (indices past the end read as zero):
+    // one trip to L2 per batch instead of one per partial
+    const __amdgpu_buffer_rsrc_t sr = __builtin_amdgcn_make_buffer_rsrc((void *)p.ssq, 0, NP * kMaxRows * 4, 0x00020000);
     for (int mt = 0; mt < MT; ++mt) {
       float ss = 0.f;
-      for (int i = wave * 8 + g * 2 + (ml >> 3); i < NP; i += kGemmWaves * 8)
-        ss += p.ssq[(size_t)i * kMaxRows + mt * 8 + (ml & 7)];
+      for (int i0 = wave * 8 + g * 2 + (ml >> 3); i0 < NP; i0 += kGemmWaves * 64) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          v[u] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+              sr, ((i0 + u * kGemmWaves * 8) * kMaxRows + mt * 8 + (ml & 7)) * 4, 0, 0));
+#pragma unroll
+        for (int u = 0; u < 8; ++u) ss += v[u];
+      }
       ss += __shfl_xor(ss, 8);
       ss += __shfl_xor(ss, 16);
       ss += __shfl_xor(ss, 32);
