@@ -194,13 +194,6 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-__device__ __forceinline__ void split_plan_mfma(int n_keys, int &n_splits, int &chunk) {
-  int steps = (n_keys + 127) / 128;                    // 128 keys = one step of a 4-wavefront workgroup
-  int per = (steps + kMaxSplits - 1) / kMaxSplits;     // steps per split
-  chunk = per * 128;
-  n_splits = (n_keys + chunk - 1) / chunk;
-}
-
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void attn_split_mfma_kernel(Params p, int layer, int R) {
   constexpr int HD = 128, RQ = kAttnRowsPerGroup;
   __shared__ float s_m[4][RQ], s_l[4][RQ];
@@ -216,7 +209,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   const int pos0 = p.row_pos[m0];
   const int n_keys = pos0 + nr;
   int n_splits, chunk;
-  split_plan_mfma(n_keys, n_splits, chunk);
+  split_plan_mfma(n_keys, p.H, n_splits, chunk);
   if (split >= n_splits) return;
   const int k_lo = split * chunk;
   const int k_hi = min(n_keys, k_lo + chunk);
@@ -369,7 +362,7 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R, int m
   int n_keys = p.row_pos[b * R + r0] + min(RQ, R - r0);  // as the split kernel: position of the group's first row
   int n_splits, chunk;
   if (mfma_plan)
-    split_plan_mfma(n_keys, n_splits, chunk);
+    split_plan_mfma(n_keys, p.H, n_splits, chunk);
   else
     split_plan(n_keys, n_splits, chunk);
   size_t pi = ((size_t)m * p.H + head) * kMaxSplits;

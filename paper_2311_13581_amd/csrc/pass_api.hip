@@ -245,7 +245,11 @@ int choose_splits(const pass_ctx *c, int B, int R, int max_keys) {
   // grid width only: each row group cuts its own keys by a rule of its own length (split_plan in
   // the attention kernel); workgroups beyond a group's split count exit at once
   (void)B; (void)R;
-  if (c->P.v_transposed) return std::max(1, std::min(kMaxSplits, (max_keys + 127) / 128));
+  if (c->P.v_transposed) {  // the longest sequence's split count (shorter ones have no more)
+    int n_splits, chunk;
+    split_plan_mfma(std::max(1, max_keys), c->P.H, n_splits, chunk);
+    return n_splits;
+  }
   return std::max(1, std::min(kMaxSplits, (max_keys + 63) / 64));
 }
 

@@ -14,6 +14,20 @@ constexpr int kMaxK = PASS_MAX_K;
 constexpr int kMaxRows = PASS_MAX_ROWS;
 constexpr int kAttnRowsPerGroup = 8;  // queries one attention workgroup carries in registers
 constexpr int kMaxSplits = 32;
+constexpr int kAttnResident = 768;  // matrix-core attention workgroups resident on the chip (256 CUs x 3)
+
+// How the matrix-core attention kernel cuts a row group's keys into splits: a function of the
+// sequence's own key count and of the model (number of heads) only, so that a sequence's
+// arithmetic cannot depend on what else is batched.  A split is 128 keys (one step of a
+// 4-wavefront workgroup) until splits x heads no longer fit the chip at once: then the steps per
+// split grow, because a second round of workgroups costs more than a second step inside one.
+__host__ __device__ inline void split_plan_mfma(int n_keys, int n_heads, int &n_splits, int &chunk) {
+  const int steps = (n_keys + 127) / 128;
+  int per = (steps + kMaxSplits - 1) / kMaxSplits;  // steps per split
+  while (((steps + per - 1) / per) * n_heads > kAttnResident && per < steps) ++per;
+  chunk = per * 128;
+  n_splits = (n_keys + chunk - 1) / chunk;
+}
 
 // bfloat16 storage type: raw bits, converted with shifts (round-to-nearest-even on store)
 struct bf16_t {
