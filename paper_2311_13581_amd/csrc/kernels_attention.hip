@@ -353,9 +353,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 // A kernel of its own: handing partials between workgroups inside one kernel needs device-scope
 // fences, which on this multi-die part write back and invalidate the per-die L2s and cost far more
 // than a launch.
-template <int HD, int OUT>
-__global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R, int mfma_plan) {
-  int m = blockIdx.x, head = blockIdx.y, dim = threadIdx.x;
+// Q = 1: HD threads, one per dimension, walk all splits.  Q = 4 (more than 8 splits): 4 * HD
+// threads, quarter q takes splits 8q .. 8q+7 (one batch of requests each), the quarters' triples
+// are merged through LDS in quarter order.  Both give the same bits for up to 8 splits.
+template <int HD, int OUT, int Q>
+__global__ __launch_bounds__(HD * Q) void attn_combine_kernel(Params p, int R, int mfma_plan) {
+  __shared__ float sm[Q], sl[Q], sv[Q][HD];
+  const int m = blockIdx.x, head = blockIdx.y, dim = threadIdx.x % HD, q = threadIdx.x / HD;
   // the row's group and its split plan, recomputed exactly as the split kernel did
   constexpr int RQ = kAttnRowsPerGroup;
   int b = m / R, r = m % R, r0 = (r / RQ) * RQ;
@@ -369,7 +373,8 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R, int m
   // eight splits at a time: their triples are requested together (indices clamped, surplus
   // dropped) and merged into the running triple in split order
   float m_n = -INFINITY, l_n = 0.f, v = 0.f;
-  for (int s0 = 0; s0 < n_splits; s0 += 8) {
+  const int s_begin = (Q == 1) ? 0 : q * 8, s_end = (Q == 1) ? n_splits : min(n_splits, q * 8 + 8);
+  for (int s0 = s_begin; s0 < s_end; s0 += 8) {
     float pm[8], pl[8], pa[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
@@ -381,18 +386,35 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R, int m
     float m_new = m_n;
 #pragma unroll
     for (int u = 0; u < 8; ++u)
-      if (s0 + u < n_splits) m_new = fmaxf(m_new, pm[u]);
+      if (s0 + u < s_end) m_new = fmaxf(m_new, pm[u]);
     const float f0 = (m_n == -INFINITY) ? 0.f : __expf(m_n - m_new);
     l_n *= f0;
     v *= f0;
 #pragma unroll
     for (int u = 0; u < 8; ++u)
-      if (s0 + u < n_splits) {
+      if (s0 + u < s_end) {
         const float f = (pm[u] == -INFINITY) ? 0.f : __expf(pm[u] - m_new);
         l_n += pl[u] * f;
         v += pa[u] * f;
       }
     m_n = m_new;
+  }
+  if constexpr (Q > 1) {
+    if (dim == 0) { sm[q] = m_n; sl[q] = l_n; }
+    sv[q][dim] = v;
+    __syncthreads();
+    if (q != 0) return;
+    float m_all = sm[0];
+#pragma unroll
+    for (int i = 1; i < Q; ++i) m_all = fmaxf(m_all, sm[i]);
+    l_n = 0.f;
+    v = 0.f;
+#pragma unroll
+    for (int i = 0; i < Q; ++i) {
+      const float f = (sm[i] == -INFINITY) ? 0.f : __expf(sm[i] - m_all);
+      l_n += sl[i] * f;
+      v += sv[i][dim] * f;
+    }
   }
   float o = v / l_n;
   if (OUT == 1) {
@@ -406,16 +428,29 @@ __global__ __launch_bounds__(HD) void attn_combine_kernel(Params p, int R, int m
   }
 }
 
+template <int HD>
+static void launch_combine(const Params &p, dim3 cgrid, int R, int n_splits, int out_split, int mfma_plan,
+                           hipStream_t s) {
+  if (n_splits > 8) {
+    if (out_split)
+      attn_combine_kernel<HD, 1, 4><<<cgrid, HD * 4, 0, s>>>(p, R, mfma_plan);
+    else
+      attn_combine_kernel<HD, 0, 4><<<cgrid, HD * 4, 0, s>>>(p, R, mfma_plan);
+  } else {
+    if (out_split)
+      attn_combine_kernel<HD, 1, 1><<<cgrid, HD, 0, s>>>(p, R, mfma_plan);
+    else
+      attn_combine_kernel<HD, 0, 1><<<cgrid, HD, 0, s>>>(p, R, mfma_plan);
+  }
+}
+
 void launch_attention(const Params &p, int dtype, int layer, int B, int R, int n_splits, int out_split,
                       hipStream_t s) {
   int groups = B * ((R + kAttnRowsPerGroup - 1) / kAttnRowsPerGroup);
   dim3 grid(n_splits, p.H, groups), cgrid(B * R, p.H);
   if (p.v_transposed) {  // bf16, head_dim 128, page_size % 32 == 0: matrix-core kernel
     attn_split_mfma_kernel<<<grid, 256, 0, s>>>(p, layer, R);
-    if (out_split)
-      attn_combine_kernel<128, 1><<<cgrid, 128, 0, s>>>(p, R, 1);
-    else
-      attn_combine_kernel<128, 0><<<cgrid, 128, 0, s>>>(p, R, 1);
+    launch_combine<128>(p, cgrid, R, n_splits, out_split, 1, s);
     return;
   }
   if (p.hd == 128) {
@@ -423,19 +458,13 @@ void launch_attention(const Params &p, int dtype, int layer, int B, int R, int n
       attn_split_kernel<float, 128><<<grid, 256, 0, s>>>(p, layer, R);
     else
       attn_split_kernel<bf16_t, 128><<<grid, 256, 0, s>>>(p, layer, R);
-    if (out_split)
-      attn_combine_kernel<128, 1><<<cgrid, 128, 0, s>>>(p, R, 0);
-    else
-      attn_combine_kernel<128, 0><<<cgrid, 128, 0, s>>>(p, R, 0);
+    launch_combine<128>(p, cgrid, R, n_splits, out_split, 0, s);
   } else {
     if (dtype == PASS_F32)
       attn_split_kernel<float, 64><<<grid, 256, 0, s>>>(p, layer, R);
     else
       attn_split_kernel<bf16_t, 64><<<grid, 256, 0, s>>>(p, layer, R);
-    if (out_split)
-      attn_combine_kernel<64, 1><<<cgrid, 64, 0, s>>>(p, R, 0);
-    else
-      attn_combine_kernel<64, 0><<<cgrid, 64, 0, s>>>(p, R, 0);
+    launch_combine<64>(p, cgrid, R, n_splits, out_split, 0, s);
   }
 }
 

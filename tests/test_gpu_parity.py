@@ -364,3 +364,18 @@ def test_fixed_token_as_lookahead(w):
         print(temp, st)
         assert st.iterations == 10
     g.close()
+
+
+@pytest.mark.parametrize("attn", [0, 1], ids=["matrix-core", "lane-per-key"])
+def test_attention_over_many_splits(attn):
+    """A context of 1100+ keys: more than 8 splits (the merge kernel's four-quarter form) and, for
+    the lane-per-key kernel, chunks longer than one step; logits and decisions against the oracle."""
+    w = MFMA_HD128
+    W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
+    m = O.Model(w.shape, W, w.k)
+    prompt = np.random.default_rng(12).integers(0, w.shape.vocab, 1100).astype(np.int32)
+    g = _gpu(w.shape, W, w.k, max_seq_len=1280, page_size=64, options={"attention": attn})
+    st = parity.stepwise_parity(g, m, 0, 3, prompt, 3, 0.9, 31, parity.LOGIT_TOL[synth.BF16], max_len=1280)
+    print(attn, st)
+    assert st.iterations == 3 and st.max_rel_err < 1e-3
+    g.close()
