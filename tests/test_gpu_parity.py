@@ -379,3 +379,41 @@ def test_attention_over_many_splits(attn):
     print(attn, st)
     assert st.iterations == 3 and st.max_rel_err < 1e-3
     g.close()
+
+
+@pytest.mark.parametrize("w", [TINY, MFMA_HD128], ids=["fp32", "mfma"])
+def test_maximum_lookahead_count(w):
+    """k = 15 (the most the interface takes): 16 rows per call, so the attention kernels see two
+    row groups per sequence and the second group's causal bound starts 8 positions later."""
+    w = synth.scaled(w, k=15)
+    g, m, _ = _both(w, 15, seed=19, max_seq_len=384, page_size=64 if w.shape.head_dim == 128 else 16)
+    prompt = np.random.default_rng(4).integers(0, w.shape.vocab, 83).astype(np.int32)
+    for temp in (0.0, 1.2):
+        st = parity.stepwise_parity(g, m, 0, 6, prompt, 6, temp, 2024, parity.LOGIT_TOL[w.shape.dtype], max_len=384)
+        print(temp, st)
+        assert st.iterations == 6
+    g.close()
+
+
+def test_maximum_rows_per_call():
+    """8 slots x (1+7) rows = 64 rows, the most one call carries (eight 8-row MFMA groups): every
+    slot against the oracle, free running, with ragged prompts."""
+    w = synth.scaled(MFMA_SMALL, k=7)
+    W = synth.make_weights(w.shape, 23, 7, 8.0)
+    lens = [5, 64, 33, 90, 17, 129, 48, 71]
+    prompts = [np.random.default_rng(40 + i).integers(0, w.shape.vocab, n).astype(np.int32) for i, n in enumerate(lens)]
+    g = _gpu(w.shape, W, 7, max_slots=8, max_seq_len=256, page_size=16)
+    for i, p in enumerate(prompts):
+        g.prefill(i, p, seq_id=200 + i)
+    toks, stats = g.generate(list(range(8)), 20, 1.0, 808)
+    m = O.Model(w.shape, W, 7)
+    for i, p in enumerate(prompts):
+        s = m.sequence(256, seq_id=200 + i)
+        s.prefill(p)
+        ref, acc, stable = s.generate(20, 1.0, 808, tau=2e-2 * 40 + parity.F32_ARITH)
+        parity.generate_parity(toks[i], ref, acc, stable)
+    st = parity.stepwise_parity(g, m, 3, 203, prompts[3], 4, 1.0, 808, parity.LOGIT_TOL[synth.BF16])
+    print(stats, st)
+    with pytest.raises(Exception):  # a ninth slot does not exist
+        g.prefill(8, prompts[0])
+    g.close()
