@@ -417,3 +417,24 @@ def test_maximum_rows_per_call():
     with pytest.raises(Exception):  # a ninth slot does not exist
         g.prefill(8, prompts[0])
     g.close()
+
+
+@pytest.mark.parametrize("w", [TINY, MFMA_SMALL], ids=["fp32", "mfma"])
+def test_degenerate_inputs(w):
+    """The smallest inputs the interface takes: a prompt of one token (nothing cached before the
+    first call), a generation of zero tokens, an empty slot list (an error, not a crash)."""
+    from paper_2311_13581_amd import binding
+    g, m, _ = _both(w, w.k, max_seq_len=128)
+    st = parity.stepwise_parity(g, m, 0, 9, np.array([5], np.int32), 6, 0.0, 3, parity.LOGIT_TOL[w.shape.dtype],
+                                max_len=128)
+    assert st.iterations == 6
+    g.prefill(0, [7], seq_id=1)
+    toks, stats = g.generate([0], 0, 1.0, 1)
+    assert toks.shape == (1, 0) and stats["iterations"] == 0 and g.seq_len(0) == (0, 0)
+    with pytest.raises(binding.PassError) as e:
+        g.draft([], 1.0, 1)
+    assert e.value.code == -1
+    with pytest.raises(binding.PassError) as e:
+        g.prefill(0, [])
+    assert e.value.code == -1
+    g.close()
