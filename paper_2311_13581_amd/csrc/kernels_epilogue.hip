@@ -27,10 +27,10 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
                                               uint32_t k1, uint32_t (&out)[4]) {
 #pragma unroll
   for (int i = 0; i < 10; ++i) {
-    uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-    uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-    uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
-    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+    // one 32 x 32 -> 64 bit multiply per product (v_mad_u64_u32) instead of a high and a low one
+    const uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+    const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+    c0 = n0; c1 = (uint32_t)p1; c2 = n2; c3 = (uint32_t)p0;
     k0 += 0x9E3779B9u;
     k1 += 0xBB67AE85u;
   }
@@ -39,7 +39,10 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 
 // top 23 bits -> (bits + 0.5) * 2^-23, in (0,1), exact in fp32
 __device__ __forceinline__ float u01(uint32_t x) { return ((float)(x >> 9) + 0.5f) * (1.0f / 8388608.0f); }
-__device__ __forceinline__ float gumbel(float u) { return -logf(-logf(u)); }
+// The per-element transcendentals use the hardware exp2 / log2 (absolute error around 1e-6 on
+// the scores in play), inside the fp32 margin the decision comparison allows; the ln-sum-exp
+// totals, the accept test and the merges of partial sums, a handful of values per row, stay precise.
+__device__ __forceinline__ float gumbel(float u) { return -__logf(-__logf(u)); }
 
 struct Best {
   float s;
@@ -85,7 +88,7 @@ __device__ __forceinline__ MaxSum wave_ms(MaxSum v) {
   return v;
 }
 
-constexpr int kEpiThreads = 512;
+constexpr int kEpiThreads = 1024;
 constexpr int kEpiWaves = kEpiThreads / 64;
 
 __device__ Best block_best(Best v, Best *sh) {
@@ -281,10 +284,10 @@ __device__ void sample_row(const float *logits, int V, bool greedy, float inv_t,
         float l = x[0][e];
         float a = l * inv_t;
         if (a > ms.m) {
-          ms.s = (ms.m == -INFINITY) ? 1.f : ms.s * expf(ms.m - a) + 1.f;
+          ms.s = (ms.m == -INFINITY) ? 1.f : ms.s * __expf(ms.m - a) + 1.f;
           ms.m = a;
         } else {
-          ms.s += expf(a - ms.m);
+          ms.s += __expf(a - ms.m);
         }
         Best c;
         c.s = greedy ? l : a + gumbel(u01(rnd[e]));
@@ -435,11 +438,11 @@ __global__ __launch_bounds__(kEpiThreads) void verify_decide_kernel(Params p, Sa
       for (int e = 0; e < 4; ++e) {
         if (e < n) {
           const int j = q4 * 4 + e;
-          float w = (kept(fp, x[0][e], j) ? expf(x[0][e] * inv_t - z_p) : 0.f) -
-                    (kept(fd, x[1][e], j) ? expf(x[1][e] * inv_t - z_d) : 0.f);
+          float w = (kept(fp, x[0][e], j) ? __expf(x[0][e] * inv_t - z_p) : 0.f) -
+                    (kept(fd, x[1][e], j) ? __expf(x[1][e] * inv_t - z_d) : 0.f);
           if (w > 0.f) {
             Best c;
-            c.s = logf(w) + gumbel(u01(rnd[e]));
+            c.s = __logf(w) + gumbel(u01(rnd[e]));
             c.idx = q4 * 4 + e;
             best = better(best, c);
           }
