@@ -424,7 +424,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
 // Launch shape of the decode-sized GEMMs (one 8-row group): wavefronts per workgroup and k-tiles
 // per trip, per epilogue kind.  Defaults chosen by sweeping the benchmark on MI355X; the "gemm_cfg"
 // option of the library overrides them (value = kind * 10000 + wavefronts * 100 + unroll).
-static int g_cfg_waves[5] = {8, 0, 4, 16, 0};  // QKV, Wo, gate/up, LM head, down; 0 = by strip count (below)
+static int g_cfg_waves[5] = {0, 0, 4, 16, 0};  // QKV, Wo, gate/up, LM head, down; 0 = by strip count (below)
 static int g_cfg_unroll[5] = {1, 1, 1, 2, 1};
 // Calls with more than 8 rows: wavefronts and output blocks per workgroup
 // (override: 1000000 + kind * 10000 + wavefronts * 100 + blocks).
@@ -482,10 +482,11 @@ static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hi
   int mt = (a.M + 7) / 8;
   if (mt == 1) {
     const int grid = n_blocks;
-    // Residual projections have one strip per 16 model dimensions: when the strips fill the 256
-    // compute units evenly (d = 4096) one 16-wavefront workgroup per unit is best; otherwise
-    // (d = 5120: 320 strips) 8-wavefront workgroups, of which a unit holds several, balance better.
-    const int w = g_cfg_waves[kind] ? g_cfg_waves[kind] : (n_blocks % 256 == 0 ? 16 : 8);
+    // QKV and the residual projections: when the strips fill the 256 compute units evenly
+    // (d = 4096: 768 and 256 strips) coarse workgroups are best (8 and 16 wavefronts); otherwise
+    // (d = 5120: 960 and 320 strips) finer ones, of which a unit holds several, balance better.
+    const bool even = n_blocks % 256 == 0;
+    const int w = g_cfg_waves[kind] ? g_cfg_waves[kind] : (kind == 0 ? (even ? 8 : 4) : (even ? 16 : 8));
     const int u = g_cfg_unroll[kind];
     switch (w * 10 + u) {
       case 161: launch_one<EPI, 16, 1>(p, a, grid, s); break;
