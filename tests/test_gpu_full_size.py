@@ -139,3 +139,36 @@ def test_config5_13b_long_prompt_runs_and_is_deterministic():
     kv, ng = g.seq_len(0)
     assert kv == len(prompt) - 1 + ng
     g.close()
+
+
+def test_config2_model_with_the_papers_sampler_stays_inside_the_top_k():
+    """The 7B model as benchmarked, sampled as in the paper's experiments (top-k 10, temperature
+    0.8): every token a call emits lies among the 10 largest logits of its own row (checked with
+    numpy on the logits the call produced), accepted drafts lie in both rows' sets, and the run is
+    deterministic."""
+    w = synth.WORKLOADS["7b_k4_greedy"]
+    prompt = synth.make_prompts(w)[0]
+    K, temp, seed = 10, 0.8, 2023
+    g = _gpu_dev(w, w.k, 1, 512 + 64)
+    history = []
+    for rep in range(2):
+        g.prefill(0, prompt, seq_id=5)
+        out = []
+        for it in range(6):
+            first, drafts = g.draft([0], temp, seed, K)
+            dl = g.get_logits(0, 0)
+            top_d = [set(np.argsort(-dl[r], kind="stable")[:K].tolist()) for r in range(w.k + 1)]
+            assert int(first[0]) in top_d[0]
+            for t in range(w.k):
+                assert int(drafts[0, t]) in top_d[t + 1]
+            n_acc, toks = g.verify([0], temp, seed, K)
+            pl = g.get_logits(0, 1)
+            top_p = [set(np.argsort(-pl[r], kind="stable")[:K].tolist()) for r in range(w.k + 1)]
+            a = int(n_acc[0])
+            for t in range(a):                       # accepted drafts have p > 0: inside the target's set too
+                assert int(toks[0, t]) == int(drafts[0, t]) and int(toks[0, t]) in top_p[t]
+            assert int(toks[0, a]) in top_p[a]       # residual draw or extra token: inside row a's set
+            out += [int(first[0])] + [int(x) for x in toks[0, :a + 1]]
+        history.append(out)
+    assert history[0] == history[1]
+    g.close()
