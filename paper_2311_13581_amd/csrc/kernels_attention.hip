@@ -5,8 +5,12 @@
 // K/V byte is read once for all rows of a group: that is the premise of the method (Section 2.2:
 // a few extra tokens cost about as much as one because decoding is bound by memory traffic).
 //
+// Two split kernels, one merge kernel.  The matrix-core kernel (bf16 cache, head_dim 128, V pages
+// transposed; described at its definition) carries the benchmarked configurations; the
+// lane-per-key kernel below carries fp32 caches, head_dim 64 and odd page sizes.
+//
 // Grid: (split, head, group).  A group is up to 8 consecutive rows of one slot.  Within the
-// workgroup (4 wavefronts) 16 lanes share one key: each lane holds hd/16 dimensions, so a key or
+// workgroup (4 wavefronts) of the lane-per-key kernel 16 lanes share one key: each lane holds hd/16 dimensions, so a key or
 // value row is fetched as 16 adjacent 16-byte loads.  An iteration covers 64 keys: every 16-lane
 // group requests the K and V chunks of 4 keys before it computes on any of them.  The 16-lane dot
 // product is reduced with DPP row operations (no LDS traffic).  The 16 lane groups merge their

@@ -186,19 +186,19 @@ void launch_rope_kv(const Params &p, int dtype, int layer, int M, hipStream_t s)
 }
 
 // act = silu(gate) * up
-__global__ __launch_bounds__(256) void silu_mul_kernel(const float *gu, float *act, int F, int round_bf16) {
+__global__ __launch_bounds__(256) void silu_mul_kernel(const float *gu, float *act, int F) {
   int m = blockIdx.y;
   int f = blockIdx.x * 256 + threadIdx.x;
   if (f < F) {
     float g = gu[(size_t)m * 2 * F + f], u = gu[(size_t)m * 2 * F + F + f];
     float v = g / (1.0f + __expf(-g)) * u;
-    act[(size_t)m * F + f] = round_bf16 ? bf16_to_f32(f32_to_bf16(v)) : v;
+    act[(size_t)m * F + f] = v;
   }
 }
 
-void launch_silu_mul(const Params &p, int round_bf16, int M, hipStream_t s) {
+void launch_silu_mul(const Params &p, int M, hipStream_t s) {
   dim3 grid((p.F + 255) / 256, M);
-  silu_mul_kernel<<<grid, 256, 0, s>>>(p.gu, p.act, p.F, round_bf16);
+  silu_mul_kernel<<<grid, 256, 0, s>>>(p.gu, p.act, p.F);
 }
 
 // ---------------------------------------------------------------------------------------------

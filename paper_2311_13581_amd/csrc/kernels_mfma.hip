@@ -6,9 +6,12 @@
 // order of v_mfma_f32_16x16x32_bf16's A operand, so that one wavefront fetches a tile as 64
 // adjacent 16-byte loads (1 KB, fully coalesced) and a strip of 16 output features is one
 // contiguous run of K/32 KB.  The M <= 64 activation rows are the B operand (rows padded to 16
-// per MFMA).  A workgroup of 16 wavefronts owns one strip (two for gate/up) and splits K among
-// its wavefronts; the next trip's weight tiles are requested before the current trip computes;
-// partial tiles are reduced through LDS in a fixed order (deterministic).
+// per MFMA).  A workgroup of 4 to 16 wavefronts owns one strip (a gate and an up strip for
+// gate/up; up to four strips for calls with more than 8 rows) and splits K among its wavefronts;
+// the next trip's weight tiles are requested before the current trip computes; partial tiles are
+// reduced through LDS in a fixed order (deterministic).  No workgroup shares weights with another,
+// and the activation rows (tens of KB) sit in every XCD's L2, so the block-to-XCD mapping needs
+// no special order.
 //
 // Activations keep fp32-like precision although the matrix core takes bf16: every activation x
 // is carried as a pair (hi, lo) of bf16 values, hi = bf16(x), lo = bf16(x - hi).  Eight rows fill
@@ -38,7 +41,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kGemmWaves = 16;  // default wavefronts per workgroup
 
 // ---------------------------------------------------------------------------------------------
 // Weight repacking: plain [N][K] bf16 -> tiles [strip][K/32][64 lanes][8], lane l of a tile holds

@@ -288,7 +288,7 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
     launch_gemm_generic(dt, P.attn, w.wo, P.h, M, P.d, P.D, P.d, nullptr, 1, s);
     launch_rmsnorm(P, dt, P.h, w.ffn_norm, P.xn, M, s);
     launch_gemm_generic(dt, P.xn, w.wgu, P.gu, M, 2 * P.F, P.d, 2 * P.F, nullptr, 0, s);
-    launch_silu_mul(P, 0, M, s);
+    launch_silu_mul(P, M, s);
     launch_gemm_generic(dt, P.act, w.wdown, P.h, M, P.d, P.F, P.d, nullptr, 1, s);
   }
   if (logits_base) {

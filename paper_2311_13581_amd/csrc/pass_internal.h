@@ -121,7 +121,7 @@ void launch_rmsnorm(const Params &p, int dtype, const float *x, const void *gain
 void launch_gemm_generic(int dtype, const float *X, const void *W, float *out, int M, int N, int K, int ldc,
                          const int32_t *rowmap, int accumulate, hipStream_t s);
 void launch_rope_kv(const Params &p, int dtype, int layer, int M, hipStream_t s);
-void launch_silu_mul(const Params &p, int round_bf16, int M, hipStream_t s);
+void launch_silu_mul(const Params &p, int M, hipStream_t s);
 // attention (both paths).  out_split: 0 = fp32 into p.attn, 1 = (hi, lo) bf16 pairs into p.attn_x
 void launch_attention(const Params &p, int dtype, int layer, int B, int R, int n_splits, int out_split,
                       hipStream_t s);
