@@ -106,7 +106,10 @@ def test_config3_lookahead_sweep_is_deterministic_and_flat():
 
 def test_config4_ragged_batch_matches_single_slot_runs():
     """Configuration 4 (7B, 8 ragged prompts 128..2048, k = 4, temperature 1.0, 128 tokens each):
-    every slot's tokens equal its single-slot run bit for bit (M = 40 rows vs 5)."""
+    the sampled slots produce the same tokens as their single-slot runs (M = 40 rows vs 5).  Random
+    streams and the attention split plan never depend on the batch; the GEMMs' reduction order does
+    (different launch shapes), which moves logits by rounding only: far below every decision margin
+    of this seeded run, and the runs are deterministic."""
     w = synth.WORKLOADS["7b_b8_ragged_t1"]
     prompts = synth.make_prompts(w)
     assert len(prompts) == 8 and min(map(len, prompts)) >= 128 and max(map(len, prompts)) <= 2048

@@ -189,9 +189,10 @@ def test_mfma_path_stepwise(w, temp, path):
 
 
 def test_mfma_path_batches_span_several_row_tiles():
-    """M = 4 slots x (1+4) rows = 20 rows (two 16-row MFMA tiles, ragged), ragged prompts: every
-    slot's tokens equal its single-slot run bit for bit, and prefill chunks (up to 64 rows) agree with
-    the oracle through the stepwise check of one of the slots."""
+    """M = 4 slots x (1+4) rows = 20 rows (three 8-row MFMA groups, ragged), ragged prompts: every
+    slot's tokens equal its single-slot run (same random streams; logits differ by the GEMMs'
+    reduction order only, below the decision margins of this seeded run), and prefill chunks (up
+    to 64 rows) agree with the oracle through the stepwise check of one of the slots."""
     w = MFMA_HD128
     W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
     lens = [9, 75, 33, 50]
