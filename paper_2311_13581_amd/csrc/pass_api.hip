@@ -474,6 +474,10 @@ int pass_create(const pass_config *cfg, void *hip_stream, void *device_arena, si
   }
   launch_fill_i32(c->P.gen_limit, INT_MAX, S, c->stream);
   launch_fill_i32(c->P.step_slots, 0, kMaxRows, c->stream);
+  // row tables: entries past a call's row count are never meant to be read, but start in bounds
+  launch_fill_i32(c->P.row_pos, 0, kMaxRows, c->stream);
+  launch_fill_i32(c->P.row_slot, 0, kMaxRows, c->stream);
+  launch_fill_i32(c->P.row_out, 0, kMaxRows, c->stream);
   // rotary frequencies theta_i = base^(-2i/hd), in double (the angle pos * theta_i is formed in double too)
   std::vector<double> theta(cfg->head_dim / 2);
   for (int i = 0; i < cfg->head_dim / 2; ++i) theta[i] = pow((double)cfg->rope_base, -2.0 * i / (double)cfg->head_dim);
