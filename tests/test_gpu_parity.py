@@ -439,3 +439,29 @@ def test_degenerate_inputs(w):
         g.prefill(0, [])
     assert e.value.code == -1
     g.close()
+
+
+def test_page_pool_limits_and_reuse():
+    """A K/V page pool smaller than max_slots x pages per sequence: a prompt that does not fit the
+    free pages is refused (capacity error, nothing half-done), releasing a slot returns its pages,
+    and a sequence living on recycled, out-of-order pages still matches the oracle."""
+    from paper_2311_13581_amd import binding
+    w = TINY
+    W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
+    g = binding.Pass(binding.make_config(w.shape, w.k, 2, 128, 16, n_pages=9))
+    g.load_weights(W)
+    m = O.Model(w.shape, W, w.k)
+    rng = np.random.default_rng(8)
+    long_p, short_p = rng.integers(0, w.shape.vocab, 100).astype(np.int32), rng.integers(0, w.shape.vocab, 40).astype(np.int32)
+    g.prefill(0, long_p, seq_id=1)                      # 7 of 9 pages
+    with pytest.raises(binding.PassError) as e:
+        g.prefill(1, short_p, seq_id=2)                 # needs 3 more
+    assert e.value.code == -3
+    g.draft([0], 0.0, 1)                                # slot 0 is untouched by the failure
+    g.verify([0], 0.0, 1)
+    g.release(0)
+    st = parity.stepwise_parity(g, m, 1, 2, short_p, 5, 0.8, 17, 1e-4, max_len=128)   # recycled pages, reversed order
+    assert st.iterations == 5 and st.resyncs == 0
+    st = parity.stepwise_parity(g, m, 0, 3, long_p[:60], 3, 0.8, 17, 1e-4, max_len=128)
+    assert st.iterations == 3
+    g.close()
