@@ -143,7 +143,11 @@ int pass_generate(pass_ctx *ctx, const int32_t *slots, int n_slots, int max_new,
 
 /* The body of Algorithm 1's loop exactly n_iters times for a batch of slots (no length target):
  * the serving-loop primitive.  Tokens accumulate in the per-slot token buffer; out_stats (may be
- * NULL) counts them.  Errors: PASS_ECAPACITY when a slot cannot take another iteration. */
+ * NULL) counts them.  Iteration i + 1 is issued before the report of iteration i has been read (the
+ * device never waits for the host; K/V pages are provided for an upper bound of the lengths
+ * meanwhile); on return, also with an error, the host's view of the slots is exact again.
+ * Errors: PASS_ECAPACITY when a slot cannot take another iteration (every iteration that fits has
+ * been run). */
 int pass_run_iterations(pass_ctx *ctx, const int32_t *slots, int n_slots, int n_iters,
                         const pass_sampling *sp, pass_stats *out_stats);
 

@@ -64,6 +64,8 @@ struct pass_ctx {
   int32_t *report_host = nullptr;       // pinned
   int32_t *block_table_host = nullptr;  // pinned mirror of P.block_table
   hipEvent_t ev[3];
+  hipEvent_t ev2[2][4];  // run_iterations: per in-flight iteration, start / middle / end of the calls and report landed
+  int kv_slack = 0;      // positions an unreported iteration may have added to every running slot
   // optional timing of the dominant kernel (the gate/up GEMM): one event pair per layer
   // captured (model call + epilogue) graphs, keyed by everything that is baked into the launches:
   // mode, batch, attention grid width, sampling arguments
@@ -163,7 +165,7 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   size_t pool_elems = (size_t)c.n_layers * np * c.n_heads * c.page_size * c.head_dim;
   P.k_pool = A.take<char>(pool_elems * esz); P.v_pool = A.take<char>(pool_elems * esz);
   int32_t *prompt_buf = A.take<int32_t>(c.max_seq_len);
-  int32_t *report_dev = A.take<int32_t>(S * kReportStride);
+  int32_t *report_dev = A.take<int32_t>(2 * S * kReportStride);  // two reports: one may still be in flight
 
   void *tok_emb = A.take<char>(V * d * esz), *lm_head = A.take<char>(V * d * esz);
   void *final_norm = A.take<char>(d * esz), *lookahead = A.take<char>((size_t)(c.k ? c.k : 1) * d * esz);
@@ -360,7 +362,7 @@ int fetch_report(pass_ctx *c, int B) {
 
 int max_keys_of(pass_ctx *c, const int32_t *slots, int B, int extra) {
   int mk = 1;
-  for (int b = 0; b < B; ++b) mk = std::max(mk, c->slots[slots[b]].kv_len + extra);
+  for (int b = 0; b < B; ++b) mk = std::max(mk, c->slots[slots[b]].kv_len + c->kv_slack + extra);
   return mk;
 }
 
@@ -451,7 +453,7 @@ int pass_create(const pass_config *cfg, void *hip_stream, void *device_arena, si
     delete c;
     return PASS_EDEVICE;
   };
-  hipError_t e = hipHostMalloc((void **)&c->report_host, sizeof(int32_t) * S * kReportStride, hipHostMallocDefault);
+  hipError_t e = hipHostMalloc((void **)&c->report_host, sizeof(int32_t) * 2 * S * kReportStride, hipHostMallocDefault);
   if (e != hipSuccess) return die(e);
   e = hipHostMalloc((void **)&c->block_table_host, sizeof(int32_t) * S * c->P.pages_per_seq, hipHostMallocDefault);
   if (e != hipSuccess) return die(e);
@@ -460,6 +462,11 @@ int pass_create(const pass_config *cfg, void *hip_stream, void *device_arena, si
     e = hipEventCreate(&ev);
     if (e != hipSuccess) return die(e);
   }
+  for (auto &set : c->ev2)
+    for (auto &ev : set) {
+      e = hipEventCreate(&ev);
+      if (e != hipSuccess) return die(e);
+    }
   // per-slot state starts at zero; block table at page 0 (valid memory, never read before set)
   size_t state_ints = (size_t)((char *)c->P.gen - (char *)c->P.kv_len) / 4;
   launch_fill_i32(c->P.kv_len, 0, state_ints, c->stream);
@@ -750,25 +757,21 @@ int pass_run_iterations(pass_ctx *c, const int32_t *slots, int n_slots, int n_it
   pass_stats st;
   memset(&st, 0, sizeof st);
   if ((rc = set_step_slots(c, slots, n_slots))) return rc;
-  for (int it = 0; it < n_iters; ++it) {
-    for (int b = 0; b < n_slots; ++b) {
-      Slot &s = c->slots[slots[b]];
-      if (s.kv_len + 2 + k > c->cfg.max_seq_len) return fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]);
-      if ((rc = ensure_pages(c, slots[b], s.kv_len + 2 + k))) return rc;
-    }
-    HIP_TRY(c, hipEventRecord(c->ev[0], c->stream));
-    if ((rc = issue_draft(c, slots, n_slots, sp, 1))) return rc;
-    HIP_TRY(c, hipEventRecord(c->ev[1], c->stream));
-    if ((rc = issue_verify(c, slots, n_slots, sp, 1))) return rc;
-    HIP_TRY(c, hipEventRecord(c->ev[2], c->stream));
-    if ((rc = fetch_report(c, n_slots))) return rc;
+  // Iteration it + 1 is issued before the report of iteration it is read, so the device never
+  // waits for the host.  Until a report lands the host only knows an upper bound of every
+  // sequence's length (an iteration adds at most k + 2 positions): pages are provided and the
+  // attention grid is sized for that bound; the exact lengths live on the device.
+  const size_t rep_ints = (size_t)c->cfg.max_slots * kReportStride;
+  const int grow = c->P.k_act + 2;
+  auto retire = [&](int par) -> int {
+    HIP_TRY(c, hipEventSynchronize(c->ev2[par][3]));
     float ms_d = 0, ms_v = 0;
-    HIP_TRY(c, hipEventElapsedTime(&ms_d, c->ev[0], c->ev[1]));
-    HIP_TRY(c, hipEventElapsedTime(&ms_v, c->ev[1], c->ev[2]));
+    HIP_TRY(c, hipEventElapsedTime(&ms_d, c->ev2[par][0], c->ev2[par][1]));
+    HIP_TRY(c, hipEventElapsedTime(&ms_v, c->ev2[par][1], c->ev2[par][2]));
     st.draft_ms += ms_d;
     st.verify_ms += ms_v;
     for (int b = 0; b < n_slots; ++b) {
-      const int32_t *r = c->report_host + b * kReportStride;
+      const int32_t *r = c->report_host + par * rep_ints + b * kReportStride;
       Slot &s = c->slots[slots[b]];
       st.iterations += 1;
       st.drafts_proposed += c->P.k_act;
@@ -777,9 +780,44 @@ int pass_run_iterations(pass_ctx *c, const int32_t *slots, int n_slots, int n_it
       s.kv_len = r[0];
       s.n_gen = r[1];
     }
+    return PASS_OK;
+  };
+  int pending = -1;  // parity of the iteration whose report has not been read, or -1
+  auto bail = [&](int code) {  // leave the host's view of the slots exact before returning
+    if (pending >= 0) (void)retire(pending);
+    pending = -1;
+    c->kv_slack = 0;
+    return code;
+  };
+  for (int it = 0; it < n_iters; ++it) {
+    const int par = it & 1;
+    for (int b = 0; b < n_slots; ++b) {
+      Slot &s = c->slots[slots[b]];
+      if (pending >= 0 && s.kv_len + grow + 2 + k > c->cfg.max_seq_len) {  // the bound no longer fits: use exact lengths
+        if ((rc = retire(pending))) return bail(rc);
+        pending = -1;
+      }
+      const int ub = s.kv_len + (pending >= 0 ? grow : 0);
+      if (ub + 2 + k > c->cfg.max_seq_len) return bail(fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]));
+      if ((rc = ensure_pages(c, slots[b], ub + 2 + k))) return bail(rc);
+    }
+    c->kv_slack = pending >= 0 ? grow : 0;
+    HIP_TRY(c, hipEventRecord(c->ev2[par][0], c->stream));
+    if ((rc = issue_draft(c, slots, n_slots, sp, 1))) return bail(rc);
+    HIP_TRY(c, hipEventRecord(c->ev2[par][1], c->stream));
+    if ((rc = issue_verify(c, slots, n_slots, sp, 1))) return bail(rc);
+    HIP_TRY(c, hipEventRecord(c->ev2[par][2], c->stream));
+    gather_report_kernel<<<1, 64, 0, c->stream>>>(c->P, n_slots, c->report_dev + par * rep_ints);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipMemcpyAsync(c->report_host + par * rep_ints, c->report_dev + par * rep_ints,
+                              sizeof(int32_t) * n_slots * kReportStride, hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipEventRecord(c->ev2[par][3], c->stream));
+    if (pending >= 0 && (rc = retire(pending))) { pending = par; return bail(rc); }
+    pending = par;
   }
+  rc = bail(PASS_OK);
   if (out_stats) *out_stats = st;
-  return PASS_OK;
+  return rc;
 }
 
 int pass_kernel_time(pass_ctx *c, double *total_ms, int64_t *launches) {
@@ -890,6 +928,8 @@ void pass_destroy(pass_ctx *c) {
   if (!c) return;
   (void)hipStreamSynchronize(c->stream);
   for (auto &ev : c->ev) (void)hipEventDestroy(ev);
+  for (auto &set : c->ev2)
+    for (auto &ev : set) (void)hipEventDestroy(ev);
   for (auto &ev : c->kev) (void)hipEventDestroy(ev);
   for (auto &g : c->graphs) (void)hipGraphExecDestroy(g.second);
   if (c->report_host) (void)hipHostFree(c->report_host);

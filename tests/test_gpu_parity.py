@@ -465,3 +465,61 @@ def test_page_pool_limits_and_reuse():
     st = parity.stepwise_parity(g, m, 0, 3, long_p[:60], 3, 0.8, 17, 1e-4, max_len=128)
     assert st.iterations == 3
     g.close()
+
+
+@pytest.mark.parametrize("w", [TINY, MFMA_HD128], ids=["fp32", "mfma"])
+def test_run_iterations_equals_stepwise_calls(w):
+    """pass_run_iterations issues iteration i+1 before it has read the report of iteration i (it
+    works with an upper bound of the sequence lengths meanwhile); the sequences must end up exactly
+    where the same number of draft / verify calls, each synchronised, leaves them: same lengths,
+    same token counts, same logits of the last two calls.  High temperature, so accepted drafts
+    make the lengths grow unevenly; two ragged slots; enough iterations to cross page boundaries."""
+    w = synth.scaled(w, k=3)
+    W = synth.make_weights(w.shape, 5, 3, 1.0)
+    page = 64 if w.shape.head_dim == 128 else 16
+    prompts = [np.random.default_rng(i).integers(0, w.shape.vocab, n).astype(np.int32) for i, n in enumerate((9, 58))]
+    res = []
+    for mode in ("iterations", "stepwise"):
+        g = _gpu(w.shape, W, 3, max_slots=2, max_seq_len=256, page_size=page)
+        for i, p in enumerate(prompts):
+            g.prefill(i, p, seq_id=50 + i)
+        if mode == "iterations":
+            st = g.run_iterations([0, 1], 17, 3.0, 1234)
+            assert st["iterations"] == 34 and st["drafts_proposed"] == 3 * 34
+        else:
+            acc = 0
+            for _ in range(17):
+                g.draft([0, 1], 3.0, 1234)
+                a, _t = g.verify([0, 1], 3.0, 1234)
+                acc += int(a.sum())
+        res.append((g.seq_len(0), g.seq_len(1), g.get_logits(0, 0), g.get_logits(1, 1),
+                    st["drafts_accepted"] if mode == "iterations" else acc))
+        g.close()
+    assert res[0][0] == res[1][0] and res[0][1] == res[1][1]
+    assert np.array_equal(res[0][2], res[1][2]) and np.array_equal(res[0][3], res[1][3])
+    assert res[0][4] == res[1][4] and res[0][4] > 0
+
+
+def test_run_iterations_stops_exactly_where_stepwise_calls_stop():
+    """Near the end of a sequence's room the look-ahead bound of pass_run_iterations no longer fits
+    and it falls back to exact lengths: it must run as many iterations as synchronised calls can,
+    report the capacity error, and leave the same state."""
+    from paper_2311_13581_amd import binding
+    w = synth.scaled(TINY, k=3)
+    W = synth.make_weights(w.shape, 5, 3, 1.0)
+    prompt = np.random.default_rng(1).integers(0, w.shape.vocab, 9).astype(np.int32)
+    state = []
+    for mode in ("iterations", "stepwise"):
+        g = _gpu(w.shape, W, 3, max_seq_len=64)
+        g.prefill(0, prompt, seq_id=3)
+        with pytest.raises(binding.PassError) as e:
+            if mode == "iterations":
+                g.run_iterations([0], 1000, 3.0, 99)
+            else:
+                for _ in range(1000):
+                    g.draft([0], 3.0, 99)
+                    g.verify([0], 3.0, 99)
+        assert e.value.code == -3
+        state.append(g.seq_len(0))
+        g.close()
+    assert state[0] == state[1] and state[0][0] + 2 + 3 > 64
