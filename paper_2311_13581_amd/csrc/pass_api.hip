@@ -57,11 +57,11 @@ struct pass_ctx {
   bool use_mfma = false;  // matrix-core path active (set by pass_load_weights)
   int opt_graph = 0, opt_path = 0, opt_attn = 0;
   // device scratch
-  int32_t *prompt_buf, *report_dev;
+  int32_t *prompt_buf;
   // host
   std::vector<Slot> slots;
   std::vector<int> free_pages;
-  int32_t *report_host = nullptr;       // pinned
+  int32_t *report_host = nullptr;       // pinned, written by the report kernel; two reports (one may be in flight)
   int32_t *block_table_host = nullptr;  // pinned mirror of P.block_table
   hipEvent_t ev[3];
   hipEvent_t ev2[2][4];  // run_iterations: per in-flight iteration, start / middle / end of the calls and report landed
@@ -165,7 +165,6 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   size_t pool_elems = (size_t)c.n_layers * np * c.n_heads * c.page_size * c.head_dim;
   P.k_pool = A.take<char>(pool_elems * esz); P.v_pool = A.take<char>(pool_elems * esz);
   int32_t *prompt_buf = A.take<int32_t>(c.max_seq_len);
-  int32_t *report_dev = A.take<int32_t>(2 * S * kReportStride);  // two reports: one may still be in flight
 
   void *tok_emb = A.take<char>(V * d * esz), *lm_head = A.take<char>(V * d * esz);
   void *final_norm = A.take<char>(d * esz), *lookahead = A.take<char>((size_t)(c.k ? c.k : 1) * d * esz);
@@ -180,7 +179,7 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   if (D * d > stage) stage = D * d;
   void *staging = A.take<char>(stage * esz);
   if (ctx) {
-    ctx->P = P; ctx->esz = esz; ctx->prompt_buf = prompt_buf; ctx->report_dev = report_dev;
+    ctx->P = P; ctx->esz = esz; ctx->prompt_buf = prompt_buf;
     ctx->tok_emb = tok_emb; ctx->lm_head = lm_head; ctx->final_norm = final_norm; ctx->lookahead = lookahead;
     ctx->layers = layers; ctx->staging = staging; ctx->staging_bytes = stage * esz;
   }
@@ -352,10 +351,9 @@ SampleArgs sample_args(const pass_sampling *sp, int commit) {
 }
 
 int fetch_report(pass_ctx *c, int B) {
-  gather_report_kernel<<<1, 64, 0, c->stream>>>(c->P, B, c->report_dev);
+  // the kernel stores straight into the pinned (device-visible, coherent) host buffer: no copy
+  gather_report_kernel<<<1, 64, 0, c->stream>>>(c->P, B, c->report_host);
   HIP_TRY(c, hipGetLastError());
-  HIP_TRY(c, hipMemcpyAsync(c->report_host, c->report_dev, sizeof(int32_t) * B * kReportStride, hipMemcpyDeviceToHost,
-                            c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   return PASS_OK;
 }
@@ -807,10 +805,8 @@ int pass_run_iterations(pass_ctx *c, const int32_t *slots, int n_slots, int n_it
     HIP_TRY(c, hipEventRecord(c->ev2[par][1], c->stream));
     if ((rc = issue_verify(c, slots, n_slots, sp, 1))) return bail(rc);
     HIP_TRY(c, hipEventRecord(c->ev2[par][2], c->stream));
-    gather_report_kernel<<<1, 64, 0, c->stream>>>(c->P, n_slots, c->report_dev + par * rep_ints);
+    gather_report_kernel<<<1, 64, 0, c->stream>>>(c->P, n_slots, c->report_host + par * rep_ints);
     HIP_TRY(c, hipGetLastError());
-    HIP_TRY(c, hipMemcpyAsync(c->report_host + par * rep_ints, c->report_dev + par * rep_ints,
-                              sizeof(int32_t) * n_slots * kReportStride, hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipEventRecord(c->ev2[par][3], c->stream));
     if (pending >= 0 && (rc = retire(pending))) { pending = par; return bail(rc); }
     pending = par;
