@@ -781,38 +781,44 @@ int pass_run_iterations(pass_ctx *c, const int32_t *slots, int n_slots, int n_it
     return PASS_OK;
   };
   int pending = -1;  // parity of the iteration whose report has not been read, or -1
-  auto bail = [&](int code) {  // leave the host's view of the slots exact before returning
-    if (pending >= 0) (void)retire(pending);
-    pending = -1;
-    c->kv_slack = 0;
-    return code;
-  };
-  for (int it = 0; it < n_iters; ++it) {
-    const int par = it & 1;
-    for (int b = 0; b < n_slots; ++b) {
-      Slot &s = c->slots[slots[b]];
-      if (pending >= 0 && s.kv_len + grow + 2 + k > c->cfg.max_seq_len) {  // the bound no longer fits: use exact lengths
-        if ((rc = retire(pending))) return bail(rc);
-        pending = -1;
+  auto loop = [&]() -> int {
+    for (int it = 0; it < n_iters; ++it) {
+      const int par = it & 1;
+      int rc2;
+      for (int b = 0; b < n_slots; ++b) {
+        Slot &s = c->slots[slots[b]];
+        if (pending >= 0 && s.kv_len + grow + 2 + k > c->cfg.max_seq_len) {  // the bound no longer fits: use exact lengths
+          const int was = pending;
+          pending = -1;
+          if ((rc2 = retire(was))) return rc2;
+        }
+        const int ub = s.kv_len + (pending >= 0 ? grow : 0);
+        if (ub + 2 + k > c->cfg.max_seq_len) return fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]);
+        if ((rc2 = ensure_pages(c, slots[b], ub + 2 + k))) return rc2;
       }
-      const int ub = s.kv_len + (pending >= 0 ? grow : 0);
-      if (ub + 2 + k > c->cfg.max_seq_len) return bail(fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]));
-      if ((rc = ensure_pages(c, slots[b], ub + 2 + k))) return bail(rc);
+      c->kv_slack = pending >= 0 ? grow : 0;
+      HIP_TRY(c, hipEventRecord(c->ev2[par][0], c->stream));
+      if ((rc2 = issue_draft(c, slots, n_slots, sp, 1))) return rc2;
+      HIP_TRY(c, hipEventRecord(c->ev2[par][1], c->stream));
+      if ((rc2 = issue_verify(c, slots, n_slots, sp, 1))) return rc2;
+      HIP_TRY(c, hipEventRecord(c->ev2[par][2], c->stream));
+      gather_report_kernel<<<1, 64, 0, c->stream>>>(c->P, n_slots, c->report_host + par * rep_ints);
+      HIP_TRY(c, hipGetLastError());
+      HIP_TRY(c, hipEventRecord(c->ev2[par][3], c->stream));
+      const int was = pending;
+      pending = par;
+      if (was >= 0 && (rc2 = retire(was))) return rc2;
     }
-    c->kv_slack = pending >= 0 ? grow : 0;
-    HIP_TRY(c, hipEventRecord(c->ev2[par][0], c->stream));
-    if ((rc = issue_draft(c, slots, n_slots, sp, 1))) return bail(rc);
-    HIP_TRY(c, hipEventRecord(c->ev2[par][1], c->stream));
-    if ((rc = issue_verify(c, slots, n_slots, sp, 1))) return bail(rc);
-    HIP_TRY(c, hipEventRecord(c->ev2[par][2], c->stream));
-    gather_report_kernel<<<1, 64, 0, c->stream>>>(c->P, n_slots, c->report_host + par * rep_ints);
-    HIP_TRY(c, hipGetLastError());
-    HIP_TRY(c, hipEventRecord(c->ev2[par][3], c->stream));
-    if (pending >= 0 && (rc = retire(pending))) { pending = par; return bail(rc); }
-    pending = par;
+    return PASS_OK;
+  };
+  rc = loop();
+  // whatever happened, leave the host's view of the slots exact
+  if (pending >= 0) {
+    int rc2 = retire(pending);
+    if (!rc) rc = rc2;
   }
-  rc = bail(PASS_OK);
-  if (out_stats) *out_stats = st;
+  c->kv_slack = 0;
+  if (!rc && out_stats) *out_stats = st;
   return rc;
 }
 
