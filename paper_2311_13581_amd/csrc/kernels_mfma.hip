@@ -430,8 +430,8 @@ static int g_cfg_waves[5] = {0, 0, 4, 16, 0};  // QKV, Wo, gate/up, LM head, dow
 static int g_cfg_unroll[5] = {1, 1, 1, 2, 1};
 // Calls with more than 8 rows: wavefronts and output blocks per workgroup
 // (override: 1000000 + kind * 10000 + wavefronts * 100 + blocks).
-static int g_big_waves[5] = {8, 16, 8, 8, 16};
-static int g_big_blocks[5] = {4, 1, 1, 4, 1};
+static int g_big_waves[5] = {8, 16, 4, 8, 16};
+static int g_big_blocks[5] = {4, 1, 2, 4, 1};
 
 int set_gemm_config(int kind, int waves, int unroll) {
   if (kind < 0 || kind > 4) return -1;
@@ -444,7 +444,7 @@ int set_gemm_config(int kind, int waves, int unroll) {
 
 int set_gemm_config_big(int kind, int waves, int blocks) {
   if (kind < 0 || kind > 4) return -1;
-  if (waves != 8 && waves != 16) return -1;
+  if (waves != 4 && waves != 8 && waves != 16) return -1;
   if (blocks != 1 && blocks != 2 && blocks != 4) return -1;
   g_big_waves[kind] = waves;
   g_big_blocks[kind] = blocks;
@@ -512,6 +512,9 @@ static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hi
     case 81: launch_big<EPI, 8, 1>(p, a, n_blocks, mt, s); break;
     case 82: launch_big<EPI, 8, 2>(p, a, n_blocks, mt, s); break;
     case 84: launch_big<EPI, 8, 4>(p, a, n_blocks, mt, s); break;
+    case 41: launch_big<EPI, 4, 1>(p, a, n_blocks, mt, s); break;
+    case 42: launch_big<EPI, 4, 2>(p, a, n_blocks, mt, s); break;
+    case 44: launch_big<EPI, 4, 4>(p, a, n_blocks, mt, s); break;
     default: launch_big<EPI, 16, 1>(p, a, n_blocks, mt, s); break;
   }
 }
