@@ -172,7 +172,13 @@ int pass_seq_len(pass_ctx *ctx, int slot, int32_t *kv_len, int32_t *n_generated)
  * "kernel_timing" (1 = after every model call, launch the dominant kernel, the gate/up GEMM,
  * once per layer with that layer's weights on the call's rows, back to back between two HIP events on
  * the context's stream, and synchronise; the launches write workspaces only; setting the option resets
- * the counters pass_kernel_time reports).  Unknown names: PASS_EINVAL. */
+ * the counters pass_kernel_time reports), "prefill_chunk" (1 .. PASS_MAX_ROWS: prompt rows per pass over the
+ * weights when the prompt goes through the decode kernels), "prefill_tiled" (-1 = prompts of more than
+ * PASS_MAX_ROWS rows take the tiled, compute-bound prompt pass when the model runs on the matrix-core
+ * path with the matrix-core attention kernel, 0 = never, 1 = every prompt does), "prefill_rows" (a
+ * multiple of 128 up to min(2048, max_seq_len rounded up): prompt rows per pass of the tiled prompt
+ * pass), "prefill_tile" (0, 16 or 24: query rows per attention workgroup of the tiled prompt pass).
+ * Unknown names: PASS_EINVAL. */
 int pass_set_option(pass_ctx *ctx, const char *name, int value);
 
 /* Timed replay of one drafting-shaped step on the given slots without changing any sequence

@@ -70,29 +70,14 @@ void launch_pack_tiles(const uint16_t *src, uint16_t *dst, int N, int K, int str
 }
 
 // ---------------------------------------------------------------------------------------------
-// Activation rows as (hi, lo) bf16 pairs in MFMA column order: x = hi + lo up to 2^-17 relative
-// ---------------------------------------------------------------------------------------------
-
-// four consecutive features of row m
-__device__ __forceinline__ void store_split4(uint16_t *xs, int m, int K, int k, const float (&v)[4]) {
-  uint2 ph, pl;
-  ph.x = pack2_bf16(v[0], v[1]);
-  ph.y = pack2_bf16(v[2], v[3]);
-  pl.x = pack2_bf16(v[0] - __uint_as_float(ph.x << 16), v[1] - __uint_as_float(ph.x & 0xffff0000u));
-  pl.y = pack2_bf16(v[2] - __uint_as_float(ph.y << 16), v[3] - __uint_as_float(ph.y & 0xffff0000u));
-  uint16_t *hp = xs + xs_index(m, K, k);
-  *(uint2 *)hp = ph;
-  *(uint2 *)(hp + kXsLoOffset) = pl;
-}
-
-// ---------------------------------------------------------------------------------------------
 // Row assembly for the matrix-core path: h (fp32), (hi, lo) of h * gain of the first norm,
 // partial sums of h^2 (partial 0 carries the whole row, the others are zero), rotary table,
 // row tables.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint16_t *tok_emb,
                                                             const uint16_t *lookahead, const uint16_t *gain0,
-                                                            int mode, int R) {
+                                                            int mode, int R, int ssq_parts, int ssq_stride,
+                                                            int row_tables) {
   __shared__ float red[4];
   int m = blockIdx.x, b = m / R, r = m % R;
   int slot = p.step_slots[b];
@@ -140,9 +125,8 @@ __global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint
   for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
   __syncthreads();
-  const int NP = p.d / 16;
-  for (int i = threadIdx.x; i < NP; i += 256)
-    p.ssq[(size_t)i * kMaxRows + m] = (i == 0) ? (red[0] + red[1] + red[2] + red[3]) : 0.f;
+  for (int i = threadIdx.x; i < ssq_parts; i += 256)
+    p.ssq[(size_t)i * ssq_stride + m] = (i == 0) ? (red[0] + red[1] + red[2] + red[3]) : 0.f;
   int half = p.hd / 2;
   for (int i = threadIdx.x; i < half; i += 256) {
     double sn, cs;
@@ -150,7 +134,7 @@ __global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint
     p.rope_cos[(size_t)m * half + i] = (float)cs;
     p.rope_sin[(size_t)m * half + i] = (float)sn;
   }
-  if (threadIdx.x == 0) {
+  if (threadIdx.x == 0 && row_tables) {
     p.row_pos[m] = pos;
     p.row_slot[m] = slot;
     p.row_out[m] = slot * (1 + p.k) + r;
@@ -160,7 +144,14 @@ __global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint
 void launch_assemble_mfma(const Params &p, const void *tok_emb, const void *lookahead, const void *gain0, int mode,
                           int B, int R, hipStream_t s) {
   assemble_mfma_kernel<<<B * R, 256, 0, s>>>(p, (const uint16_t *)tok_emb, (const uint16_t *)lookahead,
-                                             (const uint16_t *)gain0, mode, R);
+                                             (const uint16_t *)gain0, mode, R, p.d / 16, kMaxRows, 1);
+}
+// the same rows for the tiled prefill: `ssq_parts` partial sums per row with row stride `ssq_stride`,
+// no row tables (one slot, consecutive positions)
+void launch_assemble_prefill(const Params &p, const void *tok_emb, const void *gain0, int R, int ssq_parts,
+                             int ssq_stride, hipStream_t s) {
+  assemble_mfma_kernel<<<R, 256, 0, s>>>(p, (const uint16_t *)tok_emb, nullptr, (const uint16_t *)gain0, MODE_PREFILL,
+                                         R, ssq_parts, ssq_stride, 0);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -1,0 +1,512 @@
+// Prompt pass ("initial prompt sequence" of Algorithm 1) as a compute-bound problem.
+//
+// The decode kernels stream every weight once per call of at most 64 rows; a prompt of thousands
+// of tokens pushed through them re-reads the model dozens of times and leaves the matrix cores
+// idle.  Here up to 2048 prompt rows go through each layer in one pass:
+//
+//   gemm_tile_kernel   a workgroup of 4 wavefronts computes 256 output features x 64 rows.  The activation tile of a k-step (rows x 32 features, as (hi, lo)
+//                      pairs) is staged once in LDS and read by all four wavefronts; every
+//                      wavefront streams the weight tiles of its own 4 strips straight into
+//                      registers, two k-steps ahead.  Accumulators (128 registers per lane)
+//                      stay in the register file for the whole K loop: no split of K, one fixed
+//                      summation order.  Same operand formats and the same fused epilogues as the
+//                      decode GEMM (RMSNorm scale, rotary embedding and K/V page writes, SiLU * up,
+//                      residual add with (hi, lo) of the next norm's input).
+//   attn_prefill_kernel causal attention of a block of 16 or 24 query rows of one head over the
+//                      paged cache, without a split of the keys across workgroups: the four
+//                      wavefronts take alternate 32-key steps and merge once at the end.  K and V
+//                      tiles are used for all row groups of the block.
+//
+// Workgroup -> tile mapping: consecutive workgroup ids go to different dies (XCDs), each with its
+// own L2.  Tiles are numbered row-tile fastest and handed out so that one die gets a contiguous
+// run of them: the row tiles that share a block of weights run on the same die at the same time
+// and the weights leave HBM once.
+#include "pass_internal.h"
+
+namespace pass {
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+// value of the lane 8 columns further in the same row of 16 (row_ror 8): lo half <-> hi half
+__device__ __forceinline__ float other_half(float v) { return dpp_mov<0x128>(v); }
+
+template <int I> struct ic { static constexpr int value = I; };
+
+enum { TILE_QKV = 0, TILE_RESID = 1, TILE_GATEUP = 2 };
+
+struct TileArgs {
+  const u32x4 *W;             // packed weight tiles [strip][K/32][64 lanes]
+  const uint16_t *X;          // activation rows as (hi, lo) tiles [ceil(M/8)][K/32][64 lanes][8]
+  int M, K, n_strips;
+  int layer;
+  const uint16_t *gain_next;  // RESID: gain of the norm that follows
+  int slot, pos0;             // QKV: the sequence and the position of row 0
+  int tiles_m, tiles_n;
+};
+
+constexpr int kTileStrips = 4;  // strips of 16 features per wavefront
+
+// MG = 8-row groups per workgroup tile (rows = 8 * MG)
+template <int EPI, int MG>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_tile_kernel(Params p, PrefillWs w, TileArgs a) {
+  constexpr int SW = kTileStrips;
+  constexpr int ROWS = MG * 8;
+  constexpr bool NORM = (EPI != TILE_RESID);
+  constexpr int BL = MG / 4;  // 16-byte chunks of the activation tile each thread stages per k-step
+  __shared__ u32x4 sB[2][MG][64];
+  __shared__ float s_inv[ROWS];
+  __shared__ float s_part[256];
+
+  // tile of this workgroup (see the note on dies at the top)
+  const int T = a.tiles_m * a.tiles_n, per_die = (T + 7) >> 3;
+  const int t = (blockIdx.x & 7) * per_die + (blockIdx.x >> 3);
+  if (t >= T) return;
+  const int tm = t % a.tiles_m, tn = t / a.tiles_m;
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int ml = lane & 15, g4 = lane >> 4;
+  const int KT = a.K >> 5;
+  const int m0 = tm * ROWS;
+  const int strip0 = (tn * 4 + wave) * SW;
+
+  // 1 / rms of the tile's rows from the producer's partial sums of h^2
+  if constexpr (NORM) {
+    constexpr int TG = 256 / ROWS;
+    const int row = tid % ROWS, tg = tid / ROWS;
+    float ss = 0.f;
+    if (m0 + row < a.M)
+      for (int i = tg; i < w.np; i += TG) ss += p.ssq[(size_t)i * w.rows + m0 + row];
+    s_part[tid] = ss;
+    __syncthreads();
+    if (tid < ROWS) {
+      float tot = 0.f;
+#pragma unroll
+      for (int j = 0; j < TG; ++j) tot += s_part[j * ROWS + tid];
+      s_inv[tid] = 1.0f / sqrtf(tot / (float)p.d + p.eps);
+    }
+    // published by the barriers of the main loop
+  }
+
+  floatx4 acc[SW][MG];
+#pragma unroll
+  for (int s = 0; s < SW; ++s)
+#pragma unroll
+    for (int g = 0; g < MG; ++g) acc[s][g] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  // activation tile: thread (wave, lane) stages lane slot `lane` of groups j * 4 + wave.  Loads go
+  // through a buffer descriptor; slots of rows >= M get an out-of-range offset and read as zero.
+  const int n_groups = (a.M + 7) >> 3;
+  const __amdgpu_buffer_rsrc_t xr =
+      __builtin_amdgcn_make_buffer_rsrc((void *)a.X, 0, n_groups * 16 * a.K * 2, 0x00020000);
+  int boff[BL];
+#pragma unroll
+  for (int j = 0; j < BL; ++j) {
+    const int grp = tm * MG + j * 4 + wave;
+    boff[j] = (grp * 8 + (lane & 7) < a.M) ? (grp * KT * 64 + lane) * 16 : 0x40000000;
+  }
+  // weight tiles of this wavefront's strips (strips past the end repeat the last one; their
+  // results are dropped)
+  const u32x4 *wp[SW];
+#pragma unroll
+  for (int s = 0; s < SW; ++s) wp[s] = a.W + (size_t)min(strip0 + s, a.n_strips - 1) * KT * 64 + lane;
+
+  u32x4 aR[3][SW], bR[BL];
+  auto load_a = [&](u32x4 (&dst)[SW], int kt) {
+#pragma unroll
+    for (int s = 0; s < SW; ++s) dst[s] = wp[s][(size_t)kt * 64];
+  };
+  auto load_b = [&](int kt) {
+#pragma unroll
+    for (int j = 0; j < BL; ++j) bR[j] = __builtin_amdgcn_raw_buffer_load_b128(xr, boff[j] + kt * 1024, 0, 0);
+  };
+  auto store_b = [&](int buf) {
+#pragma unroll
+    for (int j = 0; j < BL; ++j) sB[buf][j * 4 + wave][lane] = bR[j];
+  };
+  auto compute = [&](const u32x4 (&av)[SW], int buf) {
+    // four activation fragments in flight: the fragment of group g + 4 is requested from LDS as
+    // soon as group g has been issued
+    u32x4 b[4];
+#pragma unroll
+    for (int g = 0; g < 4; ++g) b[g] = sB[buf][g][lane];
+#pragma unroll
+    for (int g = 0; g < MG; ++g) {
+#pragma unroll
+      for (int s = 0; s < SW; ++s)
+        acc[s][g] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av[s]),
+                                                            __builtin_bit_cast(bf16x8, b[g & 3]), acc[s][g], 0, 0, 0);
+      if (g + 4 < MG) b[g & 3] = sB[buf][g + 4][lane];
+    }
+  };
+  // k-step kt: request the activation tile of step kt+1 and the weight tiles of step kt+2 (indices
+  // past the end repeat the last step: in bounds, never used), compute from LDS buffer kt & 1, then
+  // hand the activation tile over.  One barrier per step: a buffer is rewritten only after the
+  // barrier that follows its last reader.
+  auto step = [&](auto I, int kt) {
+    constexpr int i = decltype(I)::value;
+    load_b(min(kt + 1, KT - 1));
+    load_a(aR[(i + 2) % 3], min(kt + 2, KT - 1));
+    // the requests leave before the step computes (left alone, the instruction scheduler sinks
+    // them to the point of use and the step pays their whole latency), and no instruction moves
+    // from one step into the next
+    __builtin_amdgcn_sched_barrier(0);
+    compute(aR[i], kt & 1);
+    store_b((kt + 1) & 1);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  load_b(0);
+  load_a(aR[0], 0);
+  load_a(aR[1], min(1, KT - 1));
+  store_b(0);
+  __syncthreads();
+  int kt = 0;
+  for (; kt + 2 < KT; kt += 3) {
+    step(ic<0>{}, kt);
+    step(ic<1>{}, kt + 1);
+    step(ic<2>{}, kt + 2);
+  }
+  if (kt < KT) {
+    step(ic<0>{}, kt);
+    if (kt + 1 < KT) step(ic<1>{}, kt + 1);
+  }
+
+  // Epilogue.  After adding the lo columns to the hi columns, lane (ml < 8, g4) holds
+  // Y[m0 + 8g + ml][16 strip + 4 g4 .. + 3].
+  float ss_row[MG];  // RESID: this wavefront's sum of h^2 per row
+#pragma unroll
+  for (int g = 0; g < MG; ++g) {
+    const int m = m0 + g * 8 + (ml & 7);
+    const bool row_live = m < a.M && ml < 8;
+    float inv = 1.f;
+    if constexpr (NORM) inv = s_inv[g * 8 + (ml & 7)];
+    float ss = 0.f;
+    if constexpr (EPI == TILE_GATEUP) {
+#pragma unroll
+      for (int s = 0; s < SW; s += 2) {
+        floatx4 yg = acc[s][g], yu = acc[s + 1][g];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          yg[r] += other_half(yg[r]);
+          yu[r] += other_half(yu[r]);
+        }
+        if (row_live && strip0 + s + 1 < a.n_strips) {
+          const int f0 = ((strip0 + s) >> 1) * 16 + 4 * g4;
+          float tv[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            float gt = yg[r] * inv, up = yu[r] * inv;
+            tv[r] = gt / (1.0f + __expf(-gt)) * up;
+          }
+          store_split4(p.act_x, m, p.F, f0, tv);
+        }
+      }
+    } else {
+#pragma unroll
+      for (int s = 0; s < SW; ++s) {
+        floatx4 y = acc[s][g];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) y[r] += other_half(y[r]);
+        const int strip = strip0 + s;
+        const bool live = row_live && strip < a.n_strips;
+        const int n = strip * 16 + 4 * g4;
+        if constexpr (EPI == TILE_RESID) {
+          if (live) {
+            float *hp = p.h + (size_t)m * p.d + n;
+            floatx4 hv = *(floatx4 *)hp + y;
+            *(floatx4 *)hp = hv;
+            float tv[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              tv[r] = hv[r] * bf16_to_f32(a.gain_next[n + r]);
+              ss += hv[r] * hv[r];
+            }
+            store_split4(p.xg, m, p.d, n, tv);
+          }
+        } else {  // TILE_QKV
+          if (live) {
+            const int which = n / p.D;        // 0 q, 1 k, 2 v
+            const int c = n - which * p.D;    // column inside the projection
+            const int head = c / p.hd, dim = c - head * p.hd;
+            floatx4 v = y * inv;
+            if (which < 2) {
+              const int half = p.hd / 2;
+              const float *cs = p.rope_cos + (size_t)m * half + dim / 2;
+              const float *sn = p.rope_sin + (size_t)m * half + dim / 2;
+              const float x0 = v[0], x1 = v[1], x2 = v[2], x3 = v[3];
+              v[0] = x0 * cs[0] - x1 * sn[0];
+              v[1] = x0 * sn[0] + x1 * cs[0];
+              v[2] = x2 * cs[1] - x3 * sn[1];
+              v[3] = x2 * sn[1] + x3 * cs[1];
+            }
+            if (which == 0) {
+              *(floatx4 *)(w.q + (size_t)m * p.D + c) = v;
+            } else {
+              // K rows [page][head][pos][dim], V pages transposed [page][head][dim][pos]; bf16 storage
+              const int pos = a.pos0 + m;
+              const int page = p.block_table[(size_t)a.slot * p.pages_per_seq + (pos >> p.page_shift)];
+              const size_t hbase = ((size_t)a.layer * p.n_pages + page) * p.H + head;
+              const int off = pos & (p.page_size - 1);
+              if (which == 1) {
+                uint2 pk;
+                pk.x = pack2_bf16(v[0], v[1]);
+                pk.y = pack2_bf16(v[2], v[3]);
+                *(uint2 *)((uint16_t *)p.k_pool + (hbase * p.page_size + off) * p.hd + dim) = pk;
+              } else {
+                uint16_t *vp = (uint16_t *)p.v_pool + (hbase * p.hd + dim) * p.page_size + off;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) vp[(size_t)r * p.page_size] = f32_to_bf16(v[r]);
+              }
+            }
+          }
+        }
+      }
+    }
+    ss_row[g] = ss;
+  }
+  if constexpr (EPI == TILE_RESID) {
+    // partial sum of h^2 over this wavefront's 64 features, one per row: partial index = wavefront
+    // strip group (64 features), rows past M get 0
+    const int part = tn * 4 + wave;
+    if (part < w.np) {
+#pragma unroll
+      for (int g = 0; g < MG; ++g) {
+        float ss = ss_row[g];
+        ss += __shfl_xor(ss, 16);
+        ss += __shfl_xor(ss, 32);
+        if (lane < 8) p.ssq[(size_t)part * w.rows + m0 + g * 8 + lane] = ss;
+      }
+    }
+  }
+}
+
+template <int EPI>
+void launch_tile(const Params &p, const PrefillWs &w, TileArgs a, hipStream_t s) {
+  a.tiles_n = (a.n_strips + 4 * kTileStrips - 1) / (4 * kTileStrips);
+  a.tiles_m = (a.M + 63) / 64;
+  const int grid = ((a.tiles_m * a.tiles_n + 7) / 8) * 8;
+  gemm_tile_kernel<EPI, 8><<<grid, 256, 0, s>>>(p, w, a);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Causal attention of RG * 8 consecutive prompt rows of one head (bf16 cache, head_dim 128, V pages
+// transposed).  Operand layouts as in the decode kernel: scores S^T[key][col] = K[key][:] . Q[col][:]
+// with K rows as the MFMA A operand and the (hi, lo) halves of 8 scaled query rows as the 16
+// columns of the B operand; the probabilities of 8 consecutive keys, again as (hi, lo) columns,
+// feed O^T[dim][col] += V^T[dim][key] P[key][col].  A wavefront walks 32-key steps base = 32 * wave,
+// + 128, ...; wavefronts 1..3 leave (max, sum, accumulator) in LDS and wavefront 0 merges the four
+// in wavefront order, normalises and stores the rows as (hi, lo) pairs for the Wo GEMM.
+// ---------------------------------------------------------------------------------------------
+template <int RG>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_prefill_kernel(Params p, PrefillWs w, int layer, int slot, int pos0,
+                                                           int R) {
+  constexpr int HD = 128, RQ = 8 * RG;
+  __shared__ float s_m[3][RQ], s_l[3][RQ];
+  __shared__ float s_acc[3][RQ][HD];
+
+  const int blk = gridDim.x - 1 - blockIdx.x;  // blocks with the most keys first
+  const int head = blockIdx.y;
+  const int r0 = blk * RQ;
+  const int nr = min(RQ, R - r0);
+  const int k_hi = pos0 + r0 + nr;  // keys 0 .. k_hi - 1 are visible to the block's last row
+
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ml = lane & 15, g = lane >> 4;
+  const int row = ml & 7;
+  const uint16_t *kpool = (const uint16_t *)p.k_pool, *vpool = (const uint16_t *)p.v_pool;
+
+  // query fragments: column ml = hi (ml < 8) or lo half of row rg * 8 + (ml & 7), scaled by 1/sqrt(hd)
+  u32x4 qf[RG][4];
+  {
+    const float scale = rsqrtf((float)HD);
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) {
+      const int rr = rg * 8 + row;
+      const bool live = rr < nr;
+      const float *qp = w.q + (size_t)(r0 + (live ? rr : 0)) * p.D + head * HD + g * 8;
+      floatx4 raw[4][2];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        raw[j][0] = *(const floatx4 *)(qp + j * 32);
+        raw[j][1] = *(const floatx4 *)(qp + j * 32 + 4);
+      }
+      const float sc_q = live ? scale : 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          qf[rg][j][2 * h] = split2_bf16(raw[j][h][0] * sc_q, raw[j][h][1] * sc_q, ml < 8);
+          qf[rg][j][2 * h + 1] = split2_bf16(raw[j][h][2] * sc_q, raw[j][h][3] * sc_q, ml < 8);
+        }
+    }
+  }
+
+  floatx4 o[RG][8];
+  float m_run[RG], l_run[RG];
+#pragma unroll
+  for (int rg = 0; rg < RG; ++rg) {
+    m_run[rg] = -INFINITY;
+    l_run[rg] = 0.f;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) o[rg][db] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  for (int base = wave * 32; base < k_hi; base += 128) {
+    // one page holds the 32 keys (page_size is a multiple of 32); the lookup is wavefront-uniform
+    const int page = p.block_table[(size_t)slot * p.pages_per_seq + (base >> p.page_shift)];
+    const int poff = base & (p.page_size - 1);
+    const size_t hbase = ((size_t)layer * p.n_pages + page) * p.H + head;
+    const uint16_t *kp = kpool + (hbase * p.page_size + poff) * HD;   // K[key][dim]
+    const uint16_t *vp = vpool + hbase * HD * p.page_size + poff;     // Vt[dim][key]
+    u32x4 kt[2][4], vt[8];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int key = (ml >> 2) * 8 + t * 4 + (ml & 3);  // key slot ml of tile t
+#pragma unroll
+      for (int j = 0; j < 4; ++j) kt[t][j] = *(const u32x4 *)(kp + (size_t)key * HD + j * 32 + g * 8);
+    }
+#pragma unroll
+    for (int db = 0; db < 8; ++db) vt[db] = *(const u32x4 *)(vp + (size_t)(db * 16 + ml) * p.page_size + g * 8);
+    __builtin_amdgcn_sched_barrier(0);  // all sixteen requests leave before anything is computed
+
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) {
+      // a row group whose last row comes before this step's first key sees none of the step
+      if (base > pos0 + r0 + rg * 8 + 7) continue;
+      floatx4 sc[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        sc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kt[t][j]),
+                                                          __builtin_bit_cast(bf16x8, qf[rg][j]), sc[t], 0, 0, 0);
+      }
+      // lane (column ml, g) holds the scores of keys base + 8g + 4t + r; add the lo-half column
+      const int rr = rg * 8 + row;
+      float sv[8];
+      float m_blk = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float v = sc[t][r];
+          v += other_half(v);
+          const int key = base + 8 * g + 4 * t + r;
+          const bool ok = (rr < nr) && (key <= pos0 + r0 + rr);
+          v = ok ? v : -INFINITY;
+          sv[4 * t + r] = v;
+          m_blk = fmaxf(m_blk, v);
+        }
+      m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 16));
+      m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32));
+      const float m_new = fmaxf(m_run[rg], m_blk);
+      const float alpha = (m_run[rg] == -INFINITY) ? 0.f : __expf(m_run[rg] - m_new);
+      float pv[8], psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        pv[i] = (sv[i] == -INFINITY) ? 0.f : __expf(sv[i] - m_new);
+        psum += pv[i];
+      }
+      l_run[rg] = l_run[rg] * alpha + psum;
+      m_run[rg] = m_new;
+      const u32x4 pf = {split2_bf16(pv[0], pv[1], ml < 8), split2_bf16(pv[2], pv[3], ml < 8),
+                        split2_bf16(pv[4], pv[5], ml < 8), split2_bf16(pv[6], pv[7], ml < 8)};
+#pragma unroll
+      for (int db = 0; db < 8; ++db) {
+        o[rg][db] *= alpha;
+        o[rg][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[db]),
+                                                            __builtin_bit_cast(bf16x8, pf), o[rg][db], 0, 0, 0);
+      }
+    }
+  }
+
+  // per row: the sum of probabilities is spread over the four g groups; hi + lo column halves of
+  // the accumulator.  Lane (ml < 8, g) then holds dims db * 16 + 4g + r of row rg * 8 + ml.
+#pragma unroll
+  for (int rg = 0; rg < RG; ++rg) {
+    l_run[rg] += __shfl_xor(l_run[rg], 16);
+    l_run[rg] += __shfl_xor(l_run[rg], 32);
+#pragma unroll
+    for (int db = 0; db < 8; ++db)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) o[rg][db][r] += other_half(o[rg][db][r]);
+  }
+  if (wave > 0 && ml < 8) {
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) {
+      const int rr = rg * 8 + ml;
+      if (g == 0) { s_m[wave - 1][rr] = m_run[rg]; s_l[wave - 1][rr] = l_run[rg]; }
+#pragma unroll
+      for (int db = 0; db < 8; ++db) *(floatx4 *)&s_acc[wave - 1][rr][db * 16 + 4 * g] = o[rg][db];
+    }
+  }
+  __syncthreads();
+  if (wave == 0 && ml < 8) {
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) {
+      const int rr = rg * 8 + ml;
+      if (rr >= nr) continue;
+      float m_n = m_run[rg];
+#pragma unroll
+      for (int j = 0; j < 3; ++j) m_n = fmaxf(m_n, s_m[j][rr]);
+      // row rr always sees key 0, so m_n is finite
+      float f0 = (m_run[rg] == -INFINITY) ? 0.f : __expf(m_run[rg] - m_n);
+      float l_n = l_run[rg] * f0;
+      floatx4 acc[8];
+#pragma unroll
+      for (int db = 0; db < 8; ++db) acc[db] = o[rg][db] * f0;
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const float mj = s_m[j][rr];
+        const float f = (mj == -INFINITY) ? 0.f : __expf(mj - m_n);
+        l_n += s_l[j][rr] * f;
+#pragma unroll
+        for (int db = 0; db < 8; ++db) acc[db] += *(const floatx4 *)&s_acc[j][rr][db * 16 + 4 * g] * f;
+      }
+      const float inv_l = 1.0f / l_n;
+#pragma unroll
+      for (int db = 0; db < 8; ++db) {
+        const float tv[4] = {acc[db][0] * inv_l, acc[db][1] * inv_l, acc[db][2] * inv_l, acc[db][3] * inv_l};
+        store_split4(p.attn_x, r0 + rr, p.D, head * HD + db * 16 + 4 * g, tv);
+      }
+    }
+  }
+}
+
+}  // namespace
+
+void launch_prefill_qkv(const Params &p, const PrefillWs &w, const void *W, int layer, int slot, int pos0, int M,
+                        hipStream_t s) {
+  TileArgs a{(const u32x4 *)W, p.xg, M, p.d, 3 * p.D / 16, layer, nullptr, slot, pos0, 0, 0};
+  launch_tile<TILE_QKV>(p, w, a, s);
+}
+void launch_prefill_resid(const Params &p, const PrefillWs &w, const void *W, const uint16_t *X, int K,
+                          const void *gain_next, int M, hipStream_t s) {
+  TileArgs a{(const u32x4 *)W, X, M, K, p.d / 16, 0, (const uint16_t *)gain_next, 0, 0, 0, 0};
+  launch_tile<TILE_RESID>(p, w, a, s);
+}
+void launch_prefill_gateup(const Params &p, const PrefillWs &w, const void *W, int M, hipStream_t s) {
+  TileArgs a{(const u32x4 *)W, p.xg, M, p.d, 2 * p.F / 16, 0, nullptr, 0, 0, 0, 0};
+  launch_tile<TILE_GATEUP>(p, w, a, s);
+}
+void launch_prefill_attention(const Params &p, const PrefillWs &w, int layer, int slot, int pos0, int R,
+                              hipStream_t s) {
+  if (w.attn_rows == 16) {
+    dim3 grid((R + 15) / 16, p.H);
+    attn_prefill_kernel<2><<<grid, 256, 0, s>>>(p, w, layer, slot, pos0, R);
+  } else {
+    dim3 grid((R + 23) / 24, p.H);
+    attn_prefill_kernel<3><<<grid, 256, 0, s>>>(p, w, layer, slot, pos0, R);
+  }
+}
+
+}  // namespace pass

@@ -73,6 +73,9 @@ struct pass_ctx {
   std::map<GraphKey, hipGraphExec_t> graphs;
   int opt_kernel_timing = 0;
   int opt_prefill_chunk = 64;
+  int opt_prefill_tiled = -1;  // -1: prompts of more than kMaxRows rows take the tiled pass; 0 never; 1 always
+  Params PP;                   // P with the row buffers of the tiled prompt pass
+  PrefillWs pws;
   std::vector<hipEvent_t> kev;
   double kernel_ms = 0;
   int64_t kernel_launches = 0;
@@ -177,11 +180,29 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   size_t stage = V * d;
   if (F * d > stage) stage = F * d;
   if (D * d > stage) stage = D * d;
-  void *staging = A.take<char>(stage * esz);
+  size_t stage_bytes = stage * esz;
+  // The staging area doubles as the row buffers of the tiled prompt pass (weights are staged only
+  // while they are loaded): h, (hi, lo) of the normed rows, q, (hi, lo) of the attention output and
+  // of silu(gate) * up, partial sums of h^2, rotary table.
+  PrefillWs W;
+  memset(&W, 0, sizeof W);
+  W.rows = std::min(kPrefillRows, (c.max_seq_len + 127) / 128 * 128);
+  W.np = (int)((d + 63) / 64);
+  const size_t R = W.rows;
+  const size_t ws_bytes = R * 4 * (d + d + D + D + F + W.np + c.head_dim) + 8 * 256;
+  if (ws_bytes > stage_bytes) stage_bytes = ws_bytes;
+  void *staging = A.take<char>(stage_bytes);
   if (ctx) {
     ctx->P = P; ctx->esz = esz; ctx->prompt_buf = prompt_buf;
     ctx->tok_emb = tok_emb; ctx->lm_head = lm_head; ctx->final_norm = final_norm; ctx->lookahead = lookahead;
-    ctx->layers = layers; ctx->staging = staging; ctx->staging_bytes = stage * esz;
+    ctx->layers = layers; ctx->staging = staging; ctx->staging_bytes = stage_bytes;
+    Arena S2{(char *)staging, 0};
+    Params PP = P;
+    PP.h = S2.take<float>(R * d); PP.xg = S2.take<uint16_t>(2 * R * d);
+    W.q = S2.take<float>(R * D); PP.attn_x = S2.take<uint16_t>(2 * R * D); PP.act_x = S2.take<uint16_t>(2 * R * F);
+    PP.ssq = S2.take<float>(R * W.np);
+    PP.rope_cos = S2.take<float>(R * c.head_dim / 2); PP.rope_sin = S2.take<float>(R * c.head_dim / 2);
+    ctx->PP = PP; ctx->pws = W;
   }
   return (A.off + 255) & ~(size_t)255;
 }
@@ -317,6 +338,29 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
     c->kernel_ms += ms;
     c->kernel_launches += P.L;
   }
+  return PASS_OK;
+}
+
+// Prompt rows [pos0, pos0 + R) of one slot through all layers, R <= pws.rows, tiled kernels.
+// No LM head: the last prompt token stays pending and goes through the first draft call.
+int run_prefill_tiled(pass_ctx *c, int slot, int pos0, int R, const int32_t *ids) {
+  Params P = c->P;
+  const Params &B = c->PP;
+  P.h = B.h; P.xg = B.xg; P.attn_x = B.attn_x; P.act_x = B.act_x; P.ssq = B.ssq;
+  P.rope_cos = B.rope_cos; P.rope_sin = B.rope_sin;
+  P.prefill_ids = const_cast<int32_t *>(ids);
+  const PrefillWs &W = c->pws;
+  hipStream_t s = c->stream;
+  launch_assemble_prefill(P, c->tok_emb, c->layers[0].attn_norm, R, W.np, W.rows, s);
+  for (int l = 0; l < P.L; ++l) {
+    const LayerW &w = c->layers[l];
+    launch_prefill_qkv(P, W, w.wqkv, l, slot, pos0, R, s);
+    launch_prefill_attention(P, W, l, slot, pos0, R, s);
+    launch_prefill_resid(P, W, w.wo, P.attn_x, P.D, w.ffn_norm, R, s);
+    launch_prefill_gateup(P, W, w.wgu, R, s);
+    launch_prefill_resid(P, W, w.wdown, P.act_x, P.F, l + 1 < P.L ? c->layers[l + 1].attn_norm : c->final_norm, R, s);
+  }
+  HIP_TRY(c, hipGetLastError());
   return PASS_OK;
 }
 
@@ -598,13 +642,21 @@ int pass_prefill(pass_ctx *c, int slot, uint32_t seq_id, const int32_t *prompt, 
   if ((rc = poke(c, ptrs, vals))) return rc;
   if (n > 1) {
     HIP_TRY(c, hipMemcpyAsync(c->prompt_buf, prompt, sizeof(int32_t) * (n - 1), hipMemcpyHostToDevice, c->stream));
-    const int chunk = c->opt_prefill_chunk;  // rows per pass over the weights
+    // long prompts on the matrix-core path: tiled kernels, up to pws.rows rows per pass over the
+    // weights; otherwise the decode kernels, prefill_chunk rows per pass
+    const bool tiled = c->use_mfma && c->P.v_transposed &&
+                       (c->opt_prefill_tiled == 1 || (c->opt_prefill_tiled < 0 && n - 1 > kMaxRows));
+    const int chunk = tiled ? c->pws.rows : c->opt_prefill_chunk;
     for (int done = 0; done < n - 1; done += chunk) {
       int R = std::min(chunk, n - 1 - done);
       ptrs = {P.kv_len + slot};
       vals = {done};
       if ((rc = poke(c, ptrs, vals))) return rc;
-      if ((rc = run_step(c, MODE_PREFILL, 1, R, nullptr, done + R, c->prompt_buf + done))) return rc;
+      if (tiled)
+        rc = run_prefill_tiled(c, slot, done, R, c->prompt_buf + done);
+      else
+        rc = run_step(c, MODE_PREFILL, 1, R, nullptr, done + R, c->prompt_buf + done);
+      if (rc) return rc;
     }
     ptrs = {P.kv_len + slot};
     vals = {n - 1};
@@ -879,6 +931,23 @@ int pass_set_option(pass_ctx *c, const char *name, int value) {
   if (!strcmp(name, "prefill_chunk")) {
     if (value < 1 || value > kMaxRows) return fail(c, PASS_EINVAL, "prefill_chunk: 1 .. %d", kMaxRows);
     c->opt_prefill_chunk = value;
+    return PASS_OK;
+  }
+  if (!strcmp(name, "prefill_tiled")) {
+    if (value < -1 || value > 1) return fail(c, PASS_EINVAL, "prefill_tiled: -1 (by prompt length), 0 (never) or 1 (always)");
+    c->opt_prefill_tiled = value;
+    return PASS_OK;
+  }
+  if (!strcmp(name, "prefill_rows")) {
+    const int cap = std::min(kPrefillRows, (c->cfg.max_seq_len + 127) / 128 * 128);
+    if (value < 128 || value > cap || value % 128) return fail(c, PASS_EINVAL, "prefill_rows: a multiple of 128, 128 .. %d", cap);
+    c->pws.rows = value;
+    return PASS_OK;
+  }
+  if (!strcmp(name, "prefill_tile")) {
+    // query rows of an attention workgroup of the tiled prompt pass
+    if (value != 0 && value != 16 && value != 24) return fail(c, PASS_EINVAL, "prefill_tile: 0 (default), 16 or 24");
+    c->pws.attn_rows = value;
     return PASS_OK;
   }
   if (!strcmp(name, "kernel_timing")) {

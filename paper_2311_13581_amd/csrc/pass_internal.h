@@ -14,6 +14,7 @@ constexpr int kMaxK = PASS_MAX_K;
 constexpr int kMaxRows = PASS_MAX_ROWS;
 constexpr int kAttnRowsPerGroup = 8;  // queries one attention workgroup carries in registers
 constexpr int kMaxSplits = 32;
+constexpr int kPrefillRows = 2048;  // most prompt rows the tiled prompt pass takes through the weights at once
 constexpr int kAttnResident = 768;  // matrix-core attention workgroups resident on the chip (256 CUs x 3)
 
 // How the matrix-core attention kernel cuts a row group's keys into splits: a function of the
@@ -147,6 +148,36 @@ __device__ __forceinline__ size_t xs_index(int m, int K, int k) {
   return ((((size_t)(m >> 3) * (K >> 5) + (k >> 5)) * 64 + ((k >> 3) & 3) * 16 + (m & 7)) << 3) + (k & 7);
 }
 constexpr int kXsLoOffset = 64;  // elements from a hi half to its lo half
+// (hi, lo) of four consecutive features k .. k+3 of row m: x = hi + lo up to 2^-17 relative
+__device__ __forceinline__ void store_split4(uint16_t *xs, int m, int K, int k, const float (&v)[4]) {
+  uint2 ph, pl;
+  ph.x = pack2_bf16(v[0], v[1]);
+  ph.y = pack2_bf16(v[2], v[3]);
+  pl.x = pack2_bf16(v[0] - __uint_as_float(ph.x << 16), v[1] - __uint_as_float(ph.x & 0xffff0000u));
+  pl.y = pack2_bf16(v[2] - __uint_as_float(ph.y << 16), v[3] - __uint_as_float(ph.y & 0xffff0000u));
+  uint16_t *hp = xs + xs_index(m, K, k);
+  *(uint2 *)hp = ph;
+  *(uint2 *)(hp + kXsLoOffset) = pl;
+}
+
+// Tiled prompt pass (bf16 models on the matrix-core path with transposed V pages): up to `rows`
+// prompt rows per pass over the weights.  The kernels take a Params copy whose h, xg, ssq,
+// rope_cos, rope_sin, attn_x and act_x point at buffers of that many rows; the rest is here.
+struct PrefillWs {
+  int rows;       // capacity in rows (multiple of 128); also the row stride of the partial sums of h^2
+  int np;         // partial sums of h^2 per row: one per 64 features
+  int attn_rows;  // query rows of an attention workgroup: 16 or 24 (0 = 24)
+  float *q;       // [rows][D] rotated queries
+};
+void launch_assemble_prefill(const Params &p, const void *tok_emb, const void *gain0, int R, int ssq_parts,
+                             int ssq_stride, hipStream_t s);
+void launch_prefill_qkv(const Params &p, const PrefillWs &w, const void *W, int layer, int slot, int pos0, int M,
+                        hipStream_t s);
+void launch_prefill_attention(const Params &p, const PrefillWs &w, int layer, int slot, int pos0, int R,
+                              hipStream_t s);
+void launch_prefill_resid(const Params &p, const PrefillWs &w, const void *W, const uint16_t *X, int K,
+                          const void *gain_next, int M, hipStream_t s);
+void launch_prefill_gateup(const Params &p, const PrefillWs &w, const void *W, int M, hipStream_t s);
 
 int set_gemm_config_big(int kind, int waves, int blocks);  // calls with more than 8 rows
 int set_gemm_split(int ks);  // K slices of the split residual GEMMs (0 = never split)

@@ -273,6 +273,50 @@ def test_matrix_core_attention(temp, plen):
 
 
 
+@pytest.mark.parametrize("plen,attn_rows,rows", [(66, 0, 128), (130, 16, 128), (200, 24, 128), (300, 0, 128),
+                                                 (300, 16, 256), (37, 24, 128)])
+def test_tiled_prompt_pass(plen, attn_rows, rows):
+    """The compute-bound prompt pass (tiled GEMMs, unsplit causal attention): ragged row tiles (65,
+    129, 199, 299 rows against 64-row tiles; 36 rows forced through it), ragged feature tiles (148
+    gate/up strips against 16 per workgroup), an odd number of k-steps (37), several passes over the
+    weights (299 rows at 128 per pass: later passes attend to the earlier ones through the cache),
+    both attention block heights.  The first drafting and validation calls after it are compared
+    with the oracle, which prefills row by row."""
+    w = MFMA_HD128
+    W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
+    m = O.Model(w.shape, W, w.k)
+    prompt = np.random.default_rng(plen).integers(0, w.shape.vocab, plen).astype(np.int32)
+    g = _gpu(w.shape, W, w.k, max_seq_len=384, page_size=64,
+             options={"prefill_tiled": 1, "prefill_tile": attn_rows, "prefill_rows": rows})
+    st = parity.stepwise_parity(g, m, 0, 2, prompt, 3, 0.9, 777, parity.LOGIT_TOL[synth.BF16], max_len=384)
+    print(st)
+    assert st.iterations == 3 and st.resyncs == 0 and st.max_rel_err < 1e-3
+    g.close()
+
+
+def test_tiled_and_chunked_prompt_passes_fill_the_same_cache():
+    """Same prompt through the tiled pass and through the decode kernels in 64-row chunks: the logits
+    of the next call agree to rounding (different summation orders, same bf16 cache up to the last
+    bit of a few entries), and greedy generation continues with the same tokens."""
+    w = MFMA_HD128
+    W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
+    prompt = np.random.default_rng(5).integers(0, w.shape.vocab, 333).astype(np.int32)
+    out = {}
+    for tiled in (1, 0):
+        g = _gpu(w.shape, W, w.k, max_seq_len=512, page_size=64, options={"prefill_tiled": tiled})
+        g.prefill(0, prompt, seq_id=3)
+        g.draft([0], 0.0, 1)
+        lg = g.get_logits(0, 0).copy()
+        g.verify([0], 0.0, 1)
+        toks, _ = g.generate([0], 24, 0.0, 1)
+        out[tiled] = (lg, toks[0])
+        g.close()
+    err = np.abs(out[1][0] - out[0][0]).max() / np.abs(out[0][0]).max()
+    print("tiled vs chunked logits", err)
+    assert err < 1e-3
+    assert np.array_equal(out[1][1], out[0][1])
+
+
 @pytest.mark.parametrize("w", [TINY, TINY_BF16, MFMA_HD128], ids=["fp32", "bf16", "mfma"])
 @pytest.mark.parametrize("top_k", [1, 10, 25, 100000])
 def test_top_k_sampling_stepwise(w, top_k):
