@@ -5,9 +5,9 @@
 // idle.  Here up to 2048 prompt rows go through each layer in one pass:
 //
 //   gemm_tile_kernel   a workgroup of 4 wavefronts computes 256 output features x 64 rows.  The activation tile of a k-step (rows x 32 features, as (hi, lo)
-//                      pairs) is staged once in LDS and read by all four wavefronts; every
+//                      pairs) is staged once in LDS and read by all wavefronts; every
 //                      wavefront streams the weight tiles of its own 4 strips straight into
-//                      registers, two k-steps ahead.  Accumulators (128 registers per lane)
+//                      registers, three k-steps ahead.  Accumulators (128 registers per lane)
 //                      stay in the register file for the whole K loop: no split of K, one fixed
 //                      summation order.  Same operand formats and the same fused epilogues as the
 //                      decode GEMM (RMSNorm scale, rotary embedding and K/V page writes, SiLU * up,
@@ -18,9 +18,8 @@
 //                      tiles are used for all row groups of the block.
 //
 // Workgroup -> tile mapping: consecutive workgroup ids go to different dies (XCDs), each with its
-// own L2.  Tiles are numbered row-tile fastest and handed out so that one die gets a contiguous
-// run of them: the row tiles that share a block of weights run on the same die at the same time
-// and the weights leave HBM once.
+// own L2.  The 64 workgroups a die holds at a time are given a block of 8 x 8 tiles, so a weight
+// tile and an activation tile fetched into that L2 are each used by 8 workgroups.
 #include "pass_internal.h"
 
 namespace pass {
@@ -50,26 +49,35 @@ struct TileArgs {
   const uint16_t *gain_next;  // RESID: gain of the norm that follows
   int slot, pos0;             // QKV: the sequence and the position of row 0
   int tiles_m, tiles_n;
+  int blk_n, blk_m, blocks_m, n_blocks;  // blocks of tiles, one per die at a time
 };
 
 constexpr int kTileStrips = 4;  // strips of 16 features per wavefront
 
-// MG = 8-row groups per workgroup tile (rows = 8 * MG)
+// MG = 8-row groups per workgroup tile (rows = 8 * MG).
+// Two wavefronts per SIMD (256 registers each): above that budget the compiler moves the
+// accumulators to AGPRs and, the MFMA then not being tied to its accumulator, permutes them
+// every trip with hundreds of register copies.
 template <int EPI, int MG>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_tile_kernel(Params p, PrefillWs w, TileArgs a) {
   constexpr int SW = kTileStrips;
+  constexpr int NT = 256;
   constexpr int ROWS = MG * 8;
   constexpr bool NORM = (EPI != TILE_RESID);
   constexpr int BL = MG / 4;  // 16-byte chunks of the activation tile each thread stages per k-step
   __shared__ u32x4 sB[2][MG][64];
   __shared__ float s_inv[ROWS];
-  __shared__ float s_part[256];
+  __shared__ float s_part[NT];
 
-  // tile of this workgroup (see the note on dies at the top)
-  const int T = a.tiles_m * a.tiles_n, per_die = (T + 7) >> 3;
-  const int t = (blockIdx.x & 7) * per_die + (blockIdx.x >> 3);
-  if (t >= T) return;
-  const int tm = t % a.tiles_m, tn = t / a.tiles_m;
+  // tile of this workgroup (see the note on dies at the top): the `per` workgroups that one die
+  // holds at a time form a block of blk_n x blk_m tiles
+  const int per = a.blk_n * a.blk_m;
+  const int loc = blockIdx.x >> 3;
+  const int block = (loc / per) * 8 + (blockIdx.x & 7), within = loc % per;
+  if (block >= a.n_blocks) return;
+  const int tn = (block / a.blocks_m) * a.blk_n + within / a.blk_m;
+  const int tm = (block % a.blocks_m) * a.blk_m + within % a.blk_m;
+  if (tn >= a.tiles_n || tm >= a.tiles_m) return;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int ml = lane & 15, g4 = lane >> 4;
@@ -79,11 +87,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   // 1 / rms of the tile's rows from the producer's partial sums of h^2
   if constexpr (NORM) {
-    constexpr int TG = 256 / ROWS;
+    constexpr int TG = NT / ROWS;
     const int row = tid % ROWS, tg = tid / ROWS;
     float ss = 0.f;
-    if (m0 + row < a.M)
-      for (int i = tg; i < w.np; i += TG) ss += p.ssq[(size_t)i * w.rows + m0 + row];
+    if (m0 + row < a.M) {
+      // eight requests at a time (indices past the end repeat the last partial and are dropped)
+      for (int i0 = tg; i0 < w.np; i0 += 8 * TG) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = p.ssq[(size_t)min(i0 + u * TG, w.np - 1) * w.rows + m0 + row];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) ss += (i0 + u * TG < w.np) ? v[u] : 0.f;
+      }
+    }
     s_part[tid] = ss;
     __syncthreads();
     if (tid < ROWS) {
@@ -118,18 +134,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
   for (int s = 0; s < SW; ++s) wp[s] = a.W + (size_t)min(strip0 + s, a.n_strips - 1) * KT * 64 + lane;
 
-  u32x4 aR[3][SW], bR[BL];
+  constexpr int AD = 3;  // k-steps both operands are requested ahead
+  u32x4 aR[AD + 1][SW], bR[AD + 1][BL];
   auto load_a = [&](u32x4 (&dst)[SW], int kt) {
 #pragma unroll
     for (int s = 0; s < SW; ++s) dst[s] = wp[s][(size_t)kt * 64];
   };
-  auto load_b = [&](int kt) {
+  auto load_b = [&](u32x4 (&dst)[BL], int kt) {
 #pragma unroll
-    for (int j = 0; j < BL; ++j) bR[j] = __builtin_amdgcn_raw_buffer_load_b128(xr, boff[j] + kt * 1024, 0, 0);
+    for (int j = 0; j < BL; ++j) dst[j] = __builtin_amdgcn_raw_buffer_load_b128(xr, boff[j] + kt * 1024, 0, 0);
   };
-  auto store_b = [&](int buf) {
+  auto store_b = [&](int buf, const u32x4 (&src)[BL]) {
 #pragma unroll
-    for (int j = 0; j < BL; ++j) sB[buf][j * 4 + wave][lane] = bR[j];
+    for (int j = 0; j < BL; ++j) sB[buf][j * 4 + wave][lane] = src[j];
   };
   auto compute = [&](const u32x4 (&av)[SW], int buf) {
     // four activation fragments in flight: the fragment of group g + 4 is requested from LDS as
@@ -145,38 +162,53 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                                                             __builtin_bit_cast(bf16x8, b[g & 3]), acc[s][g], 0, 0, 0);
       if (g + 4 < MG) b[g & 3] = sB[buf][g + 4][lane];
     }
+    // the order above is the order wanted: left alone, the scheduler moves every LDS read down to
+    // its first use to save registers, and the wavefront then waits out the LDS latency once per
+    // group.  (0x100 = LDS read, 0x008 = MFMA.)
+    __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+    for (int g = 0; g < MG; ++g) {
+      __builtin_amdgcn_sched_group_barrier(0x008, SW, 0);
+      if (g + 4 < MG) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    }
   };
-  // k-step kt: request the activation tile of step kt+1 and the weight tiles of step kt+2 (indices
-  // past the end repeat the last step: in bounds, never used), compute from LDS buffer kt & 1, then
-  // hand the activation tile over.  One barrier per step: a buffer is rewritten only after the
-  // barrier that follows its last reader.
+  // k-step kt: request both operands of step kt+3 (indices past the end repeat the last step: in
+  // bounds, never used), hand the activation tile of step kt+1 (requested two steps ago) over to
+  // LDS buffer (kt+1) & 1, compute from buffer kt & 1.  Loads return in order, so a wait for any
+  // request also waits for everything requested before it: every wait here is for requests at
+  // least two steps old, and a step costs its MFMAs, not a trip to memory.  One barrier per step:
+  // a buffer is rewritten only after the barrier that follows its last reader, and read only
+  // after the barrier that follows its writers.
   auto step = [&](auto I, int kt) {
     constexpr int i = decltype(I)::value;
-    load_b(min(kt + 1, KT - 1));
-    load_a(aR[(i + 2) % 3], min(kt + 2, KT - 1));
+    load_b(bR[(i + AD) % (AD + 1)], min(kt + AD, KT - 1));
+    load_a(aR[(i + AD) % (AD + 1)], min(kt + AD, KT - 1));
     // the requests leave before the step computes (left alone, the instruction scheduler sinks
     // them to the point of use and the step pays their whole latency), and no instruction moves
     // from one step into the next
     __builtin_amdgcn_sched_barrier(0);
+    store_b((kt + 1) & 1, bR[(i + 1) % (AD + 1)]);
     compute(aR[i], kt & 1);
-    store_b((kt + 1) & 1);
     __syncthreads();
     __builtin_amdgcn_sched_barrier(0);
   };
-  load_b(0);
-  load_a(aR[0], 0);
-  load_a(aR[1], min(1, KT - 1));
-  store_b(0);
+#pragma unroll
+  for (int j = 0; j < AD; ++j) load_b(bR[j], min(j, KT - 1));
+#pragma unroll
+  for (int j = 0; j < AD; ++j) load_a(aR[j], min(j, KT - 1));
+  store_b(0, bR[0]);
   __syncthreads();
   int kt = 0;
-  for (; kt + 2 < KT; kt += 3) {
+  for (; kt + AD < KT; kt += AD + 1) {
     step(ic<0>{}, kt);
     step(ic<1>{}, kt + 1);
     step(ic<2>{}, kt + 2);
+    if constexpr (AD == 3) step(ic<3>{}, kt + 3);
   }
   if (kt < KT) {
     step(ic<0>{}, kt);
     if (kt + 1 < KT) step(ic<1>{}, kt + 1);
+    if (AD == 3 && kt + 2 < KT) step(ic<2>{}, kt + 2);
   }
 
   // Epilogue.  After adding the lo columns to the hi columns, lane (ml < 8, g4) holds
@@ -273,8 +305,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     ss_row[g] = ss;
   }
   if constexpr (EPI == TILE_RESID) {
-    // partial sum of h^2 over this wavefront's 64 features, one per row: partial index = wavefront
-    // strip group (64 features), rows past M get 0
+    // partial sum of h^2 over this wavefront's 64 features, one per row: partial index = group of
+    // 4 strips (64 features), rows past M get 0
     const int part = tn * 4 + wave;
     if (part < w.np) {
 #pragma unroll
@@ -292,7 +324,13 @@ template <int EPI>
 void launch_tile(const Params &p, const PrefillWs &w, TileArgs a, hipStream_t s) {
   a.tiles_n = (a.n_strips + 4 * kTileStrips - 1) / (4 * kTileStrips);
   a.tiles_m = (a.M + 63) / 64;
-  const int grid = ((a.tiles_m * a.tiles_n + 7) / 8) * 8;
+  // a die (32 compute units, two workgroups each) holds 64 workgroups: a block of 8 x 8 tiles
+  // re-reads the least per multiply-add (2048 features and 512 rows per die at a time)
+  a.blk_n = w.blk_n ? w.blk_n : 8;
+  a.blk_m = w.blk_m ? w.blk_m : 8;
+  a.blocks_m = (a.tiles_m + a.blk_m - 1) / a.blk_m;
+  a.n_blocks = a.blocks_m * ((a.tiles_n + a.blk_n - 1) / a.blk_n);
+  const int grid = ((a.n_blocks + 7) / 8) * 8 * a.blk_n * a.blk_m;
   gemm_tile_kernel<EPI, 8><<<grid, 256, 0, s>>>(p, w, a);
 }
 
@@ -486,16 +524,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
 void launch_prefill_qkv(const Params &p, const PrefillWs &w, const void *W, int layer, int slot, int pos0, int M,
                         hipStream_t s) {
-  TileArgs a{(const u32x4 *)W, p.xg, M, p.d, 3 * p.D / 16, layer, nullptr, slot, pos0, 0, 0};
+  TileArgs a{(const u32x4 *)W, p.xg, M, p.d, 3 * p.D / 16, layer, nullptr, slot, pos0, 0, 0, 0, 0, 0, 0};
   launch_tile<TILE_QKV>(p, w, a, s);
 }
 void launch_prefill_resid(const Params &p, const PrefillWs &w, const void *W, const uint16_t *X, int K,
                           const void *gain_next, int M, hipStream_t s) {
-  TileArgs a{(const u32x4 *)W, X, M, K, p.d / 16, 0, (const uint16_t *)gain_next, 0, 0, 0, 0};
+  TileArgs a{(const u32x4 *)W, X, M, K, p.d / 16, 0, (const uint16_t *)gain_next, 0, 0, 0, 0, 0, 0, 0, 0};
   launch_tile<TILE_RESID>(p, w, a, s);
 }
 void launch_prefill_gateup(const Params &p, const PrefillWs &w, const void *W, int M, hipStream_t s) {
-  TileArgs a{(const u32x4 *)W, p.xg, M, p.d, 2 * p.F / 16, 0, nullptr, 0, 0, 0, 0};
+  TileArgs a{(const u32x4 *)W, p.xg, M, p.d, 2 * p.F / 16, 0, nullptr, 0, 0, 0, 0, 0, 0, 0, 0};
   launch_tile<TILE_GATEUP>(p, w, a, s);
 }
 void launch_prefill_attention(const Params &p, const PrefillWs &w, int layer, int slot, int pos0, int R,

@@ -73,7 +73,7 @@ struct pass_ctx {
   std::map<GraphKey, hipGraphExec_t> graphs;
   int opt_kernel_timing = 0;
   int opt_prefill_chunk = 64;
-  int opt_prefill_tiled = -1;  // -1: prompts of more than kMaxRows rows take the tiled pass; 0 never; 1 always
+  int opt_prefill_tiled = -1;  // -1: prompts of more than 3 * kMaxRows rows take the tiled pass; 0 never; 1 always
   Params PP;                   // P with the row buffers of the tiled prompt pass
   PrefillWs pws;
   std::vector<hipEvent_t> kev;
@@ -643,9 +643,11 @@ int pass_prefill(pass_ctx *c, int slot, uint32_t seq_id, const int32_t *prompt, 
   if (n > 1) {
     HIP_TRY(c, hipMemcpyAsync(c->prompt_buf, prompt, sizeof(int32_t) * (n - 1), hipMemcpyHostToDevice, c->stream));
     // long prompts on the matrix-core path: tiled kernels, up to pws.rows rows per pass over the
-    // weights; otherwise the decode kernels, prefill_chunk rows per pass
+    // weights; otherwise the decode kernels, prefill_chunk rows per pass.  A tiled pass costs about
+    // as much as three passes of the decode kernels however few rows it carries (a workgroup walks
+    // all of K whatever the row count), so it takes over above three chunks.
     const bool tiled = c->use_mfma && c->P.v_transposed &&
-                       (c->opt_prefill_tiled == 1 || (c->opt_prefill_tiled < 0 && n - 1 > kMaxRows));
+                       (c->opt_prefill_tiled == 1 || (c->opt_prefill_tiled < 0 && n - 1 > 3 * kMaxRows));
     const int chunk = tiled ? c->pws.rows : c->opt_prefill_chunk;
     for (int done = 0; done < n - 1; done += chunk) {
       int R = std::min(chunk, n - 1 - done);
@@ -948,6 +950,13 @@ int pass_set_option(pass_ctx *c, const char *name, int value) {
     // query rows of an attention workgroup of the tiled prompt pass
     if (value != 0 && value != 16 && value != 24) return fail(c, PASS_EINVAL, "prefill_tile: 0 (default), 16 or 24");
     c->pws.attn_rows = value;
+    return PASS_OK;
+  }
+  if (!strcmp(name, "prefill_block")) {
+    const int bn = value / 100, bm = value % 100;
+    if (value < 0 || bn > 64 || bm > 64 || (bn == 0) != (bm == 0)) return fail(c, PASS_EINVAL, "prefill_block: tiles along the features * 100 + tiles along the rows (1 .. 64 each), or 0");
+    c->pws.blk_n = bn;
+    c->pws.blk_m = bm;
     return PASS_OK;
   }
   if (!strcmp(name, "kernel_timing")) {

@@ -166,6 +166,7 @@ __device__ __forceinline__ void store_split4(uint16_t *xs, int m, int K, int k, 
 struct PrefillWs {
   int rows;       // capacity in rows (multiple of 128); also the row stride of the partial sums of h^2
   int np;         // partial sums of h^2 per row: one per 64 features
+  int blk_n, blk_m;  // tiles (along the features, along the rows) of the block one die works on at a time; 0 = default
   int attn_rows;  // query rows of an attention workgroup: 16 or 24 (0 = 24)
   float *q;       // [rows][D] rotated queries
 };
