@@ -48,7 +48,7 @@ def prefill_report(shape, prompts, rows, seconds):
     return {"prompt_rows": rows, "ms": seconds * 1e3, "rows_per_s": rows / seconds,
             "matmul_TFLOPs": flops / seconds / 1e12, "mfma_issued_TFLOPs": issued / seconds / 1e12,
             "mfma_frac": issued / seconds / 1e12 / MFMA_BF16_PEAK_TFLOPS,
-            "pass": "tiled" if shape.dtype == 1 and max(len(p) for p in prompts) - 1 > 192 else "decode kernels in chunks"}
+            "pass": "tiled" if shape.dtype == 1 and max(len(p) for p in prompts) - 1 > 128 else "decode kernels in chunks"}
 
 
 def measured_traffic(workload_name):

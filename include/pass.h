@@ -174,12 +174,13 @@ int pass_seq_len(pass_ctx *ctx, int slot, int32_t *kv_len, int32_t *n_generated)
  * the context's stream, and synchronise; the launches write workspaces only; setting the option resets
  * the counters pass_kernel_time reports), "prefill_chunk" (1 .. PASS_MAX_ROWS: prompt rows per pass over the
  * weights when the prompt goes through the decode kernels), "prefill_tiled" (-1 = prompts of more than
- * 3 * PASS_MAX_ROWS rows take the tiled, compute-bound prompt pass when the model runs on the matrix-core
+ * 2 * PASS_MAX_ROWS rows take the tiled, compute-bound prompt pass when the model runs on the matrix-core
  * path with the matrix-core attention kernel, 0 = never, 1 = every prompt does), "prefill_rows" (a
  * multiple of 128 up to min(2048, max_seq_len rounded up): prompt rows per pass of the tiled prompt
  * pass), "prefill_tile" (0, 16 or 24: query rows per attention workgroup of the tiled prompt pass),
  * "prefill_block" (tiles along the features * 100 + tiles along the rows of the block of GEMM tiles one
- * die works on at a time; 0 = default 8 x 8).
+ * die works on at a time; 0 = default 8 x 8), "prefill_strips" (1, 2 or 4: strips of 16 features per wavefront
+ * in the GEMMs of the tiled prompt pass, gate/up at least 2; 0 = by row count).
  * Unknown names: PASS_EINVAL. */
 int pass_set_option(pass_ctx *ctx, const char *name, int value);
 

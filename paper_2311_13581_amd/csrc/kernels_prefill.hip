@@ -52,15 +52,15 @@ struct TileArgs {
   int blk_n, blk_m, blocks_m, n_blocks;  // blocks of tiles, one per die at a time
 };
 
-constexpr int kTileStrips = 4;  // strips of 16 features per wavefront
+constexpr int kTileStrips = 4;  // strips of 16 features per wavefront (fewer when the tiles would not fill the chip)
 
 // MG = 8-row groups per workgroup tile (rows = 8 * MG).
 // Two wavefronts per SIMD (256 registers each): above that budget the compiler moves the
 // accumulators to AGPRs and, the MFMA then not being tied to its accumulator, permutes them
 // every trip with hundreds of register copies.
-template <int EPI, int MG>
+// SW = strips of 16 features per wavefront: the tile is 64 * SW features x 8 * MG rows.
+template <int EPI, int MG, int SW>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void gemm_tile_kernel(Params p, PrefillWs w, TileArgs a) {
-  constexpr int SW = kTileStrips;
   constexpr int NT = 256;
   constexpr int ROWS = MG * 8;
   constexpr bool NORM = (EPI != TILE_RESID);
@@ -305,8 +305,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     ss_row[g] = ss;
   }
   if constexpr (EPI == TILE_RESID) {
-    // partial sum of h^2 over this wavefront's 64 features, one per row: partial index = group of
-    // 4 strips (64 features), rows past M get 0
+    // partial sum of h^2 over this wavefront's 16 * SW features, one per row: partial index =
+    // wavefront strip group, rows past M get 0
     const int part = tn * 4 + wave;
     if (part < w.np) {
 #pragma unroll
@@ -321,8 +321,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 }
 
 template <int EPI>
-void launch_tile(const Params &p, const PrefillWs &w, TileArgs a, hipStream_t s) {
-  a.tiles_n = (a.n_strips + 4 * kTileStrips - 1) / (4 * kTileStrips);
+void launch_tile(const Params &p, const PrefillWs &w, TileArgs a, int sw, hipStream_t s) {
+  a.tiles_n = (a.n_strips + 4 * sw - 1) / (4 * sw);
   a.tiles_m = (a.M + 63) / 64;
   // a die (32 compute units, two workgroups each) holds 64 workgroups: a block of 8 x 8 tiles
   // re-reads the least per multiply-add (2048 features and 512 rows per die at a time)
@@ -331,7 +331,22 @@ void launch_tile(const Params &p, const PrefillWs &w, TileArgs a, hipStream_t s)
   a.blocks_m = (a.tiles_m + a.blk_m - 1) / a.blk_m;
   a.n_blocks = a.blocks_m * ((a.tiles_n + a.blk_n - 1) / a.blk_n);
   const int grid = ((a.n_blocks + 7) / 8) * 8 * a.blk_n * a.blk_m;
-  gemm_tile_kernel<EPI, 8><<<grid, 256, 0, s>>>(p, w, a);
+  if constexpr (EPI != TILE_GATEUP) {  // (a gate/up wavefront needs a gate strip and its up strip)
+    if (sw == 1) { gemm_tile_kernel<EPI, 8, 1><<<grid, 256, 0, s>>>(p, w, a); return; }
+  }
+  if (sw == 2) { gemm_tile_kernel<EPI, 8, 2><<<grid, 256, 0, s>>>(p, w, a); return; }
+  gemm_tile_kernel<EPI, 8, kTileStrips><<<grid, 256, 0, s>>>(p, w, a);
+}
+
+// Strips per wavefront for a GEMM of n_strips strips on M rows: halved (down to `least`) until
+// there are at least 384 tiles for the chip's 512 workgroup slots (measured on 7B shapes: 384 wide
+// tiles beat 768 narrow ones, 256 do not beat 512).  Narrow tiles pull more operand bytes per
+// multiply-add, but a pass with few rows is bound by how many workgroups walk K side by side.
+int tile_strips(int n_strips, int M, int least) {
+  int sw = kTileStrips;
+  const int tiles_m = (M + 63) / 64;
+  while (sw > least && tiles_m * ((n_strips + 4 * sw - 1) / (4 * sw)) < 384) sw >>= 1;
+  return sw;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -522,19 +537,24 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
 }  // namespace
 
+// Strips per wavefront of the residual projections for a pass of M rows.  Fixes the number of
+// partial sums of h^2 per row (one per wavefront strip group), which the producer of the rows
+// must know.
+int prefill_resid_strips(const Params &p, int M) { return tile_strips(p.d / 16, M, 1); }
+
 void launch_prefill_qkv(const Params &p, const PrefillWs &w, const void *W, int layer, int slot, int pos0, int M,
                         hipStream_t s) {
   TileArgs a{(const u32x4 *)W, p.xg, M, p.d, 3 * p.D / 16, layer, nullptr, slot, pos0, 0, 0, 0, 0, 0, 0};
-  launch_tile<TILE_QKV>(p, w, a, s);
+  launch_tile<TILE_QKV>(p, w, a, w.resid_strips_opt ? w.resid_strips_opt : tile_strips(a.n_strips, M, 1), s);
 }
 void launch_prefill_resid(const Params &p, const PrefillWs &w, const void *W, const uint16_t *X, int K,
                           const void *gain_next, int M, hipStream_t s) {
   TileArgs a{(const u32x4 *)W, X, M, K, p.d / 16, 0, (const uint16_t *)gain_next, 0, 0, 0, 0, 0, 0, 0, 0};
-  launch_tile<TILE_RESID>(p, w, a, s);
+  launch_tile<TILE_RESID>(p, w, a, w.resid_strips, s);
 }
 void launch_prefill_gateup(const Params &p, const PrefillWs &w, const void *W, int M, hipStream_t s) {
   TileArgs a{(const u32x4 *)W, p.xg, M, p.d, 2 * p.F / 16, 0, nullptr, 0, 0, 0, 0, 0, 0, 0, 0};
-  launch_tile<TILE_GATEUP>(p, w, a, s);
+  launch_tile<TILE_GATEUP>(p, w, a, w.resid_strips_opt > 1 ? w.resid_strips_opt : tile_strips(a.n_strips, M, 2), s);
 }
 void launch_prefill_attention(const Params &p, const PrefillWs &w, int layer, int slot, int pos0, int R,
                               hipStream_t s) {

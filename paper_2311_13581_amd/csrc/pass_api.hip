@@ -73,7 +73,7 @@ struct pass_ctx {
   std::map<GraphKey, hipGraphExec_t> graphs;
   int opt_kernel_timing = 0;
   int opt_prefill_chunk = 64;
-  int opt_prefill_tiled = -1;  // -1: prompts of more than 3 * kMaxRows rows take the tiled pass; 0 never; 1 always
+  int opt_prefill_tiled = -1;  // -1: prompts of more than 2 * kMaxRows rows take the tiled pass; 0 never; 1 always
   Params PP;                   // P with the row buffers of the tiled prompt pass
   PrefillWs pws;
   std::vector<hipEvent_t> kev;
@@ -187,7 +187,7 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   PrefillWs W;
   memset(&W, 0, sizeof W);
   W.rows = std::min(kPrefillRows, (c.max_seq_len + 127) / 128 * 128);
-  W.np = (int)((d + 63) / 64);
+  W.np = (int)(d / 16);  // most partial sums of h^2 a row can have (one per strip)
   const size_t R = W.rows;
   const size_t ws_bytes = R * 4 * (d + d + D + D + F + W.np + c.head_dim) + 8 * 256;
   if (ws_bytes > stage_bytes) stage_bytes = ws_bytes;
@@ -349,7 +349,9 @@ int run_prefill_tiled(pass_ctx *c, int slot, int pos0, int R, const int32_t *ids
   P.h = B.h; P.xg = B.xg; P.attn_x = B.attn_x; P.act_x = B.act_x; P.ssq = B.ssq;
   P.rope_cos = B.rope_cos; P.rope_sin = B.rope_sin;
   P.prefill_ids = const_cast<int32_t *>(ids);
-  const PrefillWs &W = c->pws;
+  PrefillWs W = c->pws;
+  W.resid_strips = W.resid_strips_opt ? W.resid_strips_opt : prefill_resid_strips(P, R);
+  W.np = (P.d / 16 + W.resid_strips - 1) / W.resid_strips;
   hipStream_t s = c->stream;
   launch_assemble_prefill(P, c->tok_emb, c->layers[0].attn_norm, R, W.np, W.rows, s);
   for (int l = 0; l < P.L; ++l) {
@@ -644,10 +646,10 @@ int pass_prefill(pass_ctx *c, int slot, uint32_t seq_id, const int32_t *prompt, 
     HIP_TRY(c, hipMemcpyAsync(c->prompt_buf, prompt, sizeof(int32_t) * (n - 1), hipMemcpyHostToDevice, c->stream));
     // long prompts on the matrix-core path: tiled kernels, up to pws.rows rows per pass over the
     // weights; otherwise the decode kernels, prefill_chunk rows per pass.  A tiled pass costs about
-    // as much as three passes of the decode kernels however few rows it carries (a workgroup walks
-    // all of K whatever the row count), so it takes over above three chunks.
+    // as much as two passes of the decode kernels however few rows it carries (a workgroup walks
+    // all of K whatever the row count), so it takes over above two chunks.
     const bool tiled = c->use_mfma && c->P.v_transposed &&
-                       (c->opt_prefill_tiled == 1 || (c->opt_prefill_tiled < 0 && n - 1 > 3 * kMaxRows));
+                       (c->opt_prefill_tiled == 1 || (c->opt_prefill_tiled < 0 && n - 1 > 2 * kMaxRows));
     const int chunk = tiled ? c->pws.rows : c->opt_prefill_chunk;
     for (int done = 0; done < n - 1; done += chunk) {
       int R = std::min(chunk, n - 1 - done);
@@ -950,6 +952,11 @@ int pass_set_option(pass_ctx *c, const char *name, int value) {
     // query rows of an attention workgroup of the tiled prompt pass
     if (value != 0 && value != 16 && value != 24) return fail(c, PASS_EINVAL, "prefill_tile: 0 (default), 16 or 24");
     c->pws.attn_rows = value;
+    return PASS_OK;
+  }
+  if (!strcmp(name, "prefill_strips")) {
+    if (value != 0 && value != 1 && value != 2 && value != 4) return fail(c, PASS_EINVAL, "prefill_strips: 0 (by row count), 1, 2 or 4");
+    c->pws.resid_strips_opt = value;
     return PASS_OK;
   }
   if (!strcmp(name, "prefill_block")) {

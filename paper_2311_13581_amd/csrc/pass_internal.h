@@ -165,7 +165,9 @@ __device__ __forceinline__ void store_split4(uint16_t *xs, int m, int K, int k, 
 // rope_cos, rope_sin, attn_x and act_x point at buffers of that many rows; the rest is here.
 struct PrefillWs {
   int rows;       // capacity in rows (multiple of 128); also the row stride of the partial sums of h^2
-  int np;         // partial sums of h^2 per row: one per 64 features
+  int np;         // partial sums of h^2 per row of this pass: one per resid_strips strips of 16 features
+  int resid_strips;  // strips per wavefront of the residual projections in this pass (prefill_resid_strips)
+  int resid_strips_opt;  // 1, 2 or 4: strips per wavefront of every GEMM fixed by the caller (gate/up: at least 2); 0 = by row count
   int blk_n, blk_m;  // tiles (along the features, along the rows) of the block one die works on at a time; 0 = default
   int attn_rows;  // query rows of an attention workgroup: 16 or 24 (0 = 24)
   float *q;       // [rows][D] rotated queries
@@ -179,6 +181,7 @@ void launch_prefill_attention(const Params &p, const PrefillWs &w, int layer, in
 void launch_prefill_resid(const Params &p, const PrefillWs &w, const void *W, const uint16_t *X, int K,
                           const void *gain_next, int M, hipStream_t s);
 void launch_prefill_gateup(const Params &p, const PrefillWs &w, const void *W, int M, hipStream_t s);
+int prefill_resid_strips(const Params &p, int M);
 
 int set_gemm_config_big(int kind, int waves, int blocks);  // calls with more than 8 rows
 int set_gemm_split(int ks);  // K slices of the split residual GEMMs (0 = never split)
