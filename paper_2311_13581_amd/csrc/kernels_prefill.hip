@@ -473,12 +473,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       m_run[rg] = m_new;
       const u32x4 pf = {split2_bf16(pv[0], pv[1], ml < 8), split2_bf16(pv[2], pv[3], ml < 8),
                         split2_bf16(pv[4], pv[5], ml < 8), split2_bf16(pv[6], pv[7], ml < 8)};
+      // once the running maxima have settled alpha is 1 in every lane: skip the rescaling then
+      // (multiplying by 1.0f changes nothing, so the result is the same either way)
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
-      for (int db = 0; db < 8; ++db) {
-        o[rg][db] *= alpha;
+        for (int db = 0; db < 8; ++db) o[rg][db] *= alpha;
+      }
+#pragma unroll
+      for (int db = 0; db < 8; ++db)
         o[rg][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[db]),
                                                             __builtin_bit_cast(bf16x8, pf), o[rg][db], 0, 0, 0);
-      }
     }
   }
 
