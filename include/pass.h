@@ -111,7 +111,12 @@ int pass_load_weights(pass_ctx *ctx, const pass_weights *w, int on_device);
 /* Start a sequence in `slot` (frees what the slot held).  prompt: host, n >= 1 token ids.
  * Computes K/V of prompt[0..n-2]; prompt[n-1] becomes the pending token, so the first
  * drafting call is already a parallel one (Algorithm 1 starts from the prompt x_0..x_t).
- * seq_id selects the sequence's random streams. */
+ * seq_id selects the sequence's random streams.  Prompts of more than 2 * PASS_MAX_ROWS rows on
+ * the matrix-core path go through tiled, compute-bound kernels, up to 2048 rows per pass over the
+ * weights; shorter ones (and every prompt on the generic path) through the decode kernels,
+ * PASS_MAX_ROWS rows per pass ("prefill_*" options).  Returns when the cache is filled.
+ * Errors: PASS_EINVAL (slot, token ids), PASS_ESTATE (no weights), PASS_ECAPACITY (the prompt
+ * plus one call's rows exceed max_seq_len, or the page pool is exhausted). */
 int pass_prefill(pass_ctx *ctx, int slot, uint32_t seq_id, const int32_t *prompt, int n);
 
 /* Release a slot's pages. */

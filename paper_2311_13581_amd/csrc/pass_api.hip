@@ -115,7 +115,6 @@ bool config_ok(const pass_config *c, std::string *why) {
   if (c->max_slots < 1 || (1 + c->k) * c->max_slots > kMaxRows) return bad("(1+k)*max_slots exceeds PASS_MAX_ROWS");
   if (c->max_seq_len < 2 + c->k) return bad("max_seq_len too small");
   if (c->max_seq_len > 65536) return bad("max_seq_len above 65536");
-  if (c->max_seq_len > 65536) return bad("max_seq_len above 65536");
   if (c->page_size < 16 || (c->page_size & (c->page_size - 1))) return bad("page_size must be a power of two >= 16");
   if (c->n_pages < 0) return bad("n_pages negative");
   if (!(c->rms_eps > 0) || !(c->rope_base > 1)) return bad("rms_eps / rope_base");

@@ -47,19 +47,42 @@ def test_7b_full_depth_short_context_vs_oracle():
     g.close()
 
 
-def test_long_context_single_layer_vs_oracle():
-    """One 7B-shaped layer, 1100-token prompt (18 pages, several attention splits, 35 prefill
-    chunks), k = 4, temperature 0.8: the attention path at long context against the oracle."""
+@pytest.mark.parametrize("tiled", [1, 0], ids=["tiled-prompt-pass", "chunked-prompt-pass"])
+def test_long_context_single_layer_vs_oracle(tiled):
+    """One 7B-shaped layer, 1100-token prompt (18 pages, several attention splits), k = 4,
+    temperature 0.8: the prompt pass (tiled kernels at the 7B tile counts, 18 ragged row tiles; or
+    the decode kernels in 18 chunks of 64 rows) and the attention path at long context against the
+    oracle, which prefills row by row."""
     w = synth.scaled(synth.WORKLOADS["7b_ksweep_t0.8"], n_layers=1, vocab=2048)
     W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
     from paper_2311_13581_amd import binding
-    g = binding.Pass(binding.make_config(w.shape, w.k, 1, 1280, 64))
+    g = binding.Pass(binding.make_config(w.shape, w.k, 1, 1280, 64), {"prefill_tiled": tiled})
     g.load_weights(W)
     m = O.Model(w.shape, W, w.k)
     prompt = synth.make_prompts(w)[0][:1100]
     st = parity.stepwise_parity(g, m, 0, 4, prompt, 2, 0.8, 31337, parity.LOGIT_TOL[synth.BF16], max_len=1280)
     print(st, flush=True)
     assert st.iterations == 2 and st.resyncs <= 1
+    g.close()
+
+
+def test_tiled_and_chunked_prompt_passes_agree_at_full_size():
+    """Configuration 3's prompt (2048 tokens) through eight 7B layers, tiled against chunked prompt
+    pass: the logits of the first drafting call agree to rounding (summation orders differ; the
+    chunked pass is checked against the oracle above and on the small models)."""
+    w = synth.scaled(synth.WORKLOADS["7b_ksweep_t0.8"], n_layers=8)
+    g = _gpu_dev(w, w.k, 1, 2304)
+    prompt = synth.make_prompts(w)[0]
+    lg = {}
+    for tiled in (1, 0):
+        g.set_option("prefill_tiled", tiled)
+        g.prefill(0, prompt, seq_id=1)
+        g.draft([0], 0.0, 1)
+        lg[tiled] = g.get_logits(0, 0).copy()
+        g.verify([0], 0.0, 1)
+    err = np.abs(lg[1] - lg[0]).max() / np.abs(lg[0]).max()
+    print("tiled vs chunked, 2047 rows, 8 layers: logits rel err", err, flush=True)
+    assert err < 2e-3
     g.close()
 
 
