@@ -168,6 +168,7 @@ struct GemmArgs {
   float *logits;              // LOGITS: base of the [slot][1+k][V] logits
   int kt_split;               // PARTIAL: k-tiles per workgroup row (blockIdx.y picks the slice of K); else 0
   float *partial;             // PARTIAL: [gridDim.y][kMaxRows][N] sums over the slice of K
+  int n_strips;               // strips of the matrix (NB = 3: the last workgroup may own fewer blocks)
 };
 
 // MT = number of 8-row groups (one MFMA column block each); NB = output blocks per workgroup (a
@@ -211,13 +212,18 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
     xoff[mt] = (m < a.M) ? ((mt * KT + kbase) * 64 + lane) * 16 : 0x40000000;
   }
   const u32x4 *wp = a.W + ((size_t)strip0 * KT + kbase) * 64 + lane;
+  // strip s of this workgroup, relative to strip0.  NB = 3 does not divide every matrix: strips
+  // past the end repeat the last one (in bounds; their results are dropped in the epilogue)
+  int soff[NS];
+#pragma unroll
+  for (int s = 0; s < NS; ++s) soff[s] = (NB == 3) ? min(s, a.n_strips - 1 - strip0) : s;
 
   auto load_a = [&](u32x4 (&dst)[U][NS], int kt0) {
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
       for (int s = 0; s < NS; ++s)
-        dst[u][s] = __builtin_nontemporal_load(wp + ((size_t)s * KT + kt0 + u * kGemmWaves) * 64);
+        dst[u][s] = __builtin_nontemporal_load(wp + ((size_t)soff[s] * KT + kt0 + u * kGemmWaves) * 64);
   };
   auto load_b = [&](u32x4 (&dst)[U][MT], int kt0) {
 #pragma unroll
@@ -269,7 +275,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
     for (int mt = 0; mt < MT; ++mt) bv[mt] = __builtin_amdgcn_raw_buffer_load_b128(xr, xoff[mt] + kt * 1024, 0, 0);
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
-      u32x4 av = __builtin_nontemporal_load(wp + ((size_t)s * KT + kt) * 64);
+      u32x4 av = __builtin_nontemporal_load(wp + ((size_t)soff[s] * KT + kt) * 64);
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt)
         acc[s][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av),
@@ -313,6 +319,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
     if (wave >= NB) continue;
     const int blk = wave;
     const int strip = strip0 + blk * PER;
+    if (NB == 3 && strip >= a.n_strips) continue;  // this workgroup's last block does not exist
     floatx4 y[PER];
 #pragma unroll
     for (int s = 0; s < PER; ++s) {
@@ -420,9 +427,12 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
 static int g_cfg_waves[5] = {0, 0, 4, 16, 0};  // QKV, Wo, gate/up, LM head, down; 0 = by strip count (below)
 static int g_cfg_unroll[5] = {1, 1, 1, 2, 1};
 // Calls with more than 8 rows: wavefronts and output blocks per workgroup
-// (override: 1000000 + kind * 10000 + wavefronts * 100 + blocks).
+// (override: 1000000 + kind * 10000 + wavefronts * 100 + blocks).  Such a call is bound by what
+// one compute unit can pull through its vector memory path, and every workgroup pulls all M
+// activation rows whatever it owns of the weights: best is one workgroup per compute unit with
+// as many blocks as that leaves it (QKV: 768 strips = 256 x 3; gate/up: 688 pairs = 230 x 3).
 static int g_big_waves[5] = {8, 16, 4, 8, 16};
-static int g_big_blocks[5] = {4, 1, 2, 4, 1};
+static int g_big_blocks[5] = {3, 1, 3, 4, 1};
 
 int set_gemm_config(int kind, int waves, int unroll) {
   if (kind < 0 || kind > 4) return -1;
@@ -436,7 +446,7 @@ int set_gemm_config(int kind, int waves, int unroll) {
 int set_gemm_config_big(int kind, int waves, int blocks) {
   if (kind < 0 || kind > 4) return -1;
   if (waves != 4 && waves != 8 && waves != 16) return -1;
-  if (blocks != 1 && blocks != 2 && blocks != 4) return -1;
+  if (blocks < 1 || blocks > 4) return -1;
   g_big_waves[kind] = waves;
   g_big_blocks[kind] = blocks;
   return 0;
@@ -453,7 +463,7 @@ static void launch_big(const Params &p, const GemmArgs &a, int n_blocks, int mt,
   if constexpr (W * NB * PER > 32) {
     launch_big<EPI, 8, 1>(p, a, n_blocks, mt, s);
   } else {
-    const int grid = n_blocks / NB;
+    const int grid = (n_blocks + NB - 1) / NB;
     constexpr int T = W * 64;
     constexpr int U2 = (NB == 1 && W == 16) ? 2 : 1;  // two k-tiles per trip while registers allow
     switch (mt) {
@@ -496,13 +506,16 @@ static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hi
   }
   int w = g_big_waves[kind], nb = g_big_blocks[kind];
   if (mt == 8 && nb == 4) nb = 2;                 // 64 rows x 4 blocks does not fit the register file
-  while (nb > 1 && n_blocks % nb != 0) nb >>= 1;  // a workgroup's blocks must all exist
+  if (nb == 3 && mt * PER > 10) nb = 2;           // nor do 3 blocks of more than 40 rows (gate/up) / 80
+  while (nb != 3 && nb > 1 && n_blocks % nb != 0) nb >>= 1;  // a workgroup's blocks must all exist (3: the kernel copes)
   switch (w * 10 + nb) {
     case 161: launch_big<EPI, 16, 1>(p, a, n_blocks, mt, s); break;
     case 162: launch_big<EPI, 16, 2>(p, a, n_blocks, mt, s); break;
     case 81: launch_big<EPI, 8, 1>(p, a, n_blocks, mt, s); break;
     case 82: launch_big<EPI, 8, 2>(p, a, n_blocks, mt, s); break;
     case 84: launch_big<EPI, 8, 4>(p, a, n_blocks, mt, s); break;
+    case 83: launch_big<EPI, 8, 3>(p, a, n_blocks, mt, s); break;
+    case 43: launch_big<EPI, 4, 3>(p, a, n_blocks, mt, s); break;
     case 41: launch_big<EPI, 4, 1>(p, a, n_blocks, mt, s); break;
     case 42: launch_big<EPI, 4, 2>(p, a, n_blocks, mt, s); break;
     case 44: launch_big<EPI, 4, 4>(p, a, n_blocks, mt, s); break;
@@ -582,21 +595,21 @@ static bool launch_resid_split(const Params &p, const GemmArgs &a0, int mt, hipS
 }
 
 void launch_gemm_qkv(const Params &p, const void *W, int layer, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, layer, nullptr, nullptr, 0, nullptr};
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, layer, nullptr, nullptr, 0, nullptr, 3 * p.D / 16};
   launch_gemm_epi<EPI_QKV>(p, a, 3 * p.D / 16, s);
 }
 void launch_gemm_resid(const Params &p, const void *W, const uint16_t *X, int K, const void *gain_next, int M,
                        hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, X, M, K, 0, (const uint16_t *)gain_next, nullptr, 0, nullptr};
+  GemmArgs a{(const u32x4 *)W, X, M, K, 0, (const uint16_t *)gain_next, nullptr, 0, nullptr, p.d / 16};
   if (M > 8 && launch_resid_split(p, a, (M + 7) / 8, s)) return;
   launch_gemm_epi<EPI_RESID>(p, a, p.d / 16, s, K == p.F ? 4 : 1);  // the down projection has its own shape
 }
 void launch_gemm_gateup(const Params &p, const void *W, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, nullptr, 0, nullptr};
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, nullptr, 0, nullptr, 2 * p.F / 16};
   launch_gemm_epi<EPI_GATEUP>(p, a, 2 * p.F / 16, s);
 }
 void launch_gemm_logits(const Params &p, const void *W, float *logits, int M, hipStream_t s) {
-  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, logits, 0, nullptr};
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, logits, 0, nullptr, p.V / 16};
   launch_gemm_epi<EPI_LOGITS>(p, a, p.V / 16, s);
 }
 
