@@ -33,6 +33,8 @@
 //   LOGITS  : RMSNorm scale, fp32 logits into the slot's logits rows
 // RMSNorm has no kernel: the producer stores (hi, lo) of h * gain and partial sums of h^2; the
 // consumer multiplies its accumulators by rsqrt(mean(h^2) + eps), which commutes with the GEMM.
+#include <algorithm>
+
 #include "pass_internal.h"
 
 namespace pass {
@@ -432,7 +434,7 @@ static int g_cfg_unroll[5] = {1, 1, 1, 2, 1};
 // activation rows whatever it owns of the weights: best is one workgroup per compute unit with
 // as many blocks as that leaves it (QKV: 768 strips = 256 x 3; gate/up: 688 pairs = 230 x 3).
 static int g_big_waves[5] = {8, 16, 4, 8, 16};
-static int g_big_blocks[5] = {3, 1, 3, 4, 1};
+static int g_big_blocks[5] = {0, 1, 0, 4, 1};  // 0 = as many as leave one workgroup per compute unit
 
 int set_gemm_config(int kind, int waves, int unroll) {
   if (kind < 0 || kind > 4) return -1;
@@ -446,7 +448,7 @@ int set_gemm_config(int kind, int waves, int unroll) {
 int set_gemm_config_big(int kind, int waves, int blocks) {
   if (kind < 0 || kind > 4) return -1;
   if (waves != 4 && waves != 8 && waves != 16) return -1;
-  if (blocks < 1 || blocks > 4) return -1;
+  if (blocks < 0 || blocks > 4) return -1;
   g_big_waves[kind] = waves;
   g_big_blocks[kind] = blocks;
   return 0;
@@ -505,6 +507,7 @@ static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hi
     return;
   }
   int w = g_big_waves[kind], nb = g_big_blocks[kind];
+  if (nb == 0) nb = std::min(PER == 2 ? 3 : 4, (n_blocks + 255) / 256);  // 7B: QKV 768 / 256 = 3, gate/up 688 pairs -> 3
   if (mt == 8 && nb == 4) nb = 2;                 // 64 rows x 4 blocks does not fit the register file
   if (nb == 3 && mt * PER > 10) nb = 2;           // nor do 3 blocks of more than 40 rows (gate/up) / 80
   while (nb != 3 && nb > 1 && n_blocks % nb != 0) nb >>= 1;  // a workgroup's blocks must all exist (3: the kernel copes)
