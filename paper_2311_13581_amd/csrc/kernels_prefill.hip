@@ -4,9 +4,10 @@
 // of tokens pushed through them re-reads the model dozens of times and leaves the matrix cores
 // idle.  Here up to 2048 prompt rows go through each layer in one pass:
 //
-//   gemm_tile_kernel   a workgroup of 4 wavefronts computes 256 output features x 64 rows.  The activation tile of a k-step (rows x 32 features, as (hi, lo)
+//   gemm_tile_kernel   a workgroup of 4 wavefronts computes 256 (or 128, 64) output features x 64
+//                      rows.  The activation tile of a k-step (rows x 32 features, as (hi, lo)
 //                      pairs) is staged once in LDS and read by all wavefronts; every
-//                      wavefront streams the weight tiles of its own 4 strips straight into
+//                      wavefront streams the weight tiles of its own strips straight into
 //                      registers, three k-steps ahead.  Accumulators (128 registers per lane)
 //                      stay in the register file for the whole K loop: no split of K, one fixed
 //                      summation order.  Same operand formats and the same fused epilogues as the
