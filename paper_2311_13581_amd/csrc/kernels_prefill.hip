@@ -13,7 +13,7 @@
 //                      summation order.  Same operand formats and the same fused epilogues as the
 //                      decode GEMM (RMSNorm scale, rotary embedding and K/V page writes, SiLU * up,
 //                      residual add with (hi, lo) of the next norm's input).
-//   attn_prefill_kernel causal attention of a block of 16 or 24 query rows of one head over the
+//   attn_prefill_kernel causal attention of a block of 32 (or 16) query rows of one head over the
 //                      paged cache, without a split of the keys across workgroups: the four
 //                      wavefronts take alternate 32-key steps and merge once at the end.  K and V
 //                      tiles are used for all row groups of the block.
@@ -351,18 +351,24 @@ int tile_strips(int n_strips, int M, int least) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Causal attention of RG * 8 consecutive prompt rows of one head (bf16 cache, head_dim 128, V pages
-// transposed).  Operand layouts as in the decode kernel: scores S^T[key][col] = K[key][:] . Q[col][:]
-// with K rows as the MFMA A operand and the (hi, lo) halves of 8 scaled query rows as the 16
-// columns of the B operand; the probabilities of 8 consecutive keys, again as (hi, lo) columns,
-// feed O^T[dim][col] += V^T[dim][key] P[key][col].  A wavefront walks 32-key steps base = 32 * wave,
-// + 128, ...; wavefronts 1..3 leave (max, sum, accumulator) in LDS and wavefront 0 merges the four
-// in wavefront order, normalises and stores the rows as (hi, lo) pairs for the Wo GEMM.
+// Causal attention of RG * 16 consecutive prompt rows of one head (bf16 cache, head_dim 128, V pages
+// transposed).  Scores S^T[key][row] = K[key][:] . Q[row][:] with K rows as the MFMA A operand (key
+// order inside the two 16-key tiles chosen so that a lane ends up with 8 consecutive keys) and 16
+// query rows as the columns of the B operand; the probabilities of 8 consecutive keys feed
+// O^T[dim][row] += V^T[dim][key] P[key][row] with one 16-byte load of the transposed V page as A
+// operand.  Queries and probabilities keep fp32-like precision as (hi, lo) bf16 pairs; unlike the
+// decode kernel, which puts the two halves of 8 rows side by side in the 16 columns, the halves go
+// into separate MFMAs here: S = K q_hi + K q_lo accumulate into one score tile, the softmax runs
+// once per (row, key) (side by side it runs in the hi and in the lo column, and that vector
+// arithmetic, not the matrix cores, bounds the kernel), and P_hi, P_lo are two B operands that
+// accumulate into one output tile.  A wavefront walks 32-key steps base = 32 * wave, + 128, ...
+// with online softmax; wavefronts 1..3 leave (max, sum, accumulator) in LDS and wavefront 0 merges
+// the four in wavefront order, normalises and stores the rows as (hi, lo) pairs for the Wo GEMM.
 // ---------------------------------------------------------------------------------------------
-template <int RG>
+template <int RG>  // groups of 16 rows per workgroup
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_prefill_kernel(Params p, PrefillWs w, int layer, int slot, int pos0,
-                                                           int R) {
-  constexpr int HD = 128, RQ = 8 * RG;
+                                                                                                       int R) {
+  constexpr int HD = 128, RQ = 16 * RG;
   __shared__ float s_m[3][RQ], s_l[3][RQ];
   __shared__ float s_acc[3][RQ][HD];
 
@@ -374,16 +380,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int ml = lane & 15, g = lane >> 4;
-  const int row = ml & 7;
   const uint16_t *kpool = (const uint16_t *)p.k_pool, *vpool = (const uint16_t *)p.v_pool;
 
-  // query fragments: column ml = hi (ml < 8) or lo half of row rg * 8 + (ml & 7), scaled by 1/sqrt(hd)
-  u32x4 qf[RG][4];
+  // query fragments: column ml = row rg * 16 + ml, scaled by 1/sqrt(hd), as separate hi and lo operands
+  u32x4 qh[RG][4], ql[RG][4];
   {
     const float scale = rsqrtf((float)HD);
 #pragma unroll
     for (int rg = 0; rg < RG; ++rg) {
-      const int rr = rg * 8 + row;
+      const int rr = rg * 16 + ml;
       const bool live = rr < nr;
       const float *qp = w.q + (size_t)(r0 + (live ? rr : 0)) * p.D + head * HD + g * 8;
       floatx4 raw[4][2];
@@ -397,8 +402,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-          qf[rg][j][2 * h] = split2_bf16(raw[j][h][0] * sc_q, raw[j][h][1] * sc_q, ml < 8);
-          qf[rg][j][2 * h + 1] = split2_bf16(raw[j][h][2] * sc_q, raw[j][h][3] * sc_q, ml < 8);
+          qh[rg][j][2 * h] = split2_bf16(raw[j][h][0] * sc_q, raw[j][h][1] * sc_q, true);
+          qh[rg][j][2 * h + 1] = split2_bf16(raw[j][h][2] * sc_q, raw[j][h][3] * sc_q, true);
+          ql[rg][j][2 * h] = split2_bf16(raw[j][h][0] * sc_q, raw[j][h][1] * sc_q, false);
+          ql[rg][j][2 * h + 1] = split2_bf16(raw[j][h][2] * sc_q, raw[j][h][3] * sc_q, false);
         }
     }
   }
@@ -434,29 +441,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
     for (int rg = 0; rg < RG; ++rg) {
       // a row group whose last row comes before this step's first key sees none of the step
-      if (base > pos0 + r0 + rg * 8 + 7) continue;
+      if (base > pos0 + r0 + rg * 16 + 15) continue;
       floatx4 sc[2];
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         sc[t] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < 4; ++j) {
           sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kt[t][j]),
-                                                          __builtin_bit_cast(bf16x8, qf[rg][j]), sc[t], 0, 0, 0);
+                                                          __builtin_bit_cast(bf16x8, qh[rg][j]), sc[t], 0, 0, 0);
+          sc[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kt[t][j]),
+                                                          __builtin_bit_cast(bf16x8, ql[rg][j]), sc[t], 0, 0, 0);
+        }
       }
-      // lane (column ml, g) holds the scores of keys base + 8g + 4t + r; add the lo-half column
-      const int rr = rg * 8 + row;
+      // lane (column ml, g) holds the scores of row rg * 16 + ml for keys base + 8g + 4t + r
+      const int rr = rg * 16 + ml;
       float sv[8];
       float m_blk = -INFINITY;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-          float v = sc[t][r];
-          v += other_half(v);
           const int key = base + 8 * g + 4 * t + r;
           const bool ok = (rr < nr) && (key <= pos0 + r0 + rr);
-          v = ok ? v : -INFINITY;
+          const float v = ok ? sc[t][r] : -INFINITY;
           sv[4 * t + r] = v;
           m_blk = fmaxf(m_blk, v);
         }
@@ -472,46 +480,48 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       }
       l_run[rg] = l_run[rg] * alpha + psum;
       m_run[rg] = m_new;
-      const u32x4 pf = {split2_bf16(pv[0], pv[1], ml < 8), split2_bf16(pv[2], pv[3], ml < 8),
-                        split2_bf16(pv[4], pv[5], ml < 8), split2_bf16(pv[6], pv[7], ml < 8)};
+      u32x4 ph, pl;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ph[i] = pack2_bf16(pv[2 * i], pv[2 * i + 1]);
+        pl[i] = pack2_bf16(pv[2 * i] - __uint_as_float(ph[i] << 16), pv[2 * i + 1] - __uint_as_float(ph[i] & 0xffff0000u));
+      }
       // once the running maxima have settled alpha is 1 in every lane: skip the rescaling then
-      // (multiplying by 1.0f changes nothing, so the result is the same either way)
       if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
 #pragma unroll
         for (int db = 0; db < 8; ++db) o[rg][db] *= alpha;
       }
 #pragma unroll
-      for (int db = 0; db < 8; ++db)
+      for (int db = 0; db < 8; ++db) {
         o[rg][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[db]),
-                                                            __builtin_bit_cast(bf16x8, pf), o[rg][db], 0, 0, 0);
+                                                            __builtin_bit_cast(bf16x8, ph), o[rg][db], 0, 0, 0);
+        o[rg][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vt[db]),
+                                                            __builtin_bit_cast(bf16x8, pl), o[rg][db], 0, 0, 0);
+      }
     }
   }
 
-  // per row: the sum of probabilities is spread over the four g groups; hi + lo column halves of
-  // the accumulator.  Lane (ml < 8, g) then holds dims db * 16 + 4g + r of row rg * 8 + ml.
+  // a row's sum of probabilities is spread over the four g groups; lane (ml, g) holds dims
+  // db * 16 + 4g + r of row rg * 16 + ml
 #pragma unroll
   for (int rg = 0; rg < RG; ++rg) {
     l_run[rg] += __shfl_xor(l_run[rg], 16);
     l_run[rg] += __shfl_xor(l_run[rg], 32);
-#pragma unroll
-    for (int db = 0; db < 8; ++db)
-#pragma unroll
-      for (int r = 0; r < 4; ++r) o[rg][db][r] += other_half(o[rg][db][r]);
   }
-  if (wave > 0 && ml < 8) {
+  if (wave > 0) {
 #pragma unroll
     for (int rg = 0; rg < RG; ++rg) {
-      const int rr = rg * 8 + ml;
+      const int rr = rg * 16 + ml;
       if (g == 0) { s_m[wave - 1][rr] = m_run[rg]; s_l[wave - 1][rr] = l_run[rg]; }
 #pragma unroll
       for (int db = 0; db < 8; ++db) *(floatx4 *)&s_acc[wave - 1][rr][db * 16 + 4 * g] = o[rg][db];
     }
   }
   __syncthreads();
-  if (wave == 0 && ml < 8) {
+  if (wave == 0) {
 #pragma unroll
     for (int rg = 0; rg < RG; ++rg) {
-      const int rr = rg * 8 + ml;
+      const int rr = rg * 16 + ml;
       if (rr >= nr) continue;
       float m_n = m_run[rg];
 #pragma unroll
@@ -565,10 +575,10 @@ void launch_prefill_attention(const Params &p, const PrefillWs &w, int layer, in
                               hipStream_t s) {
   if (w.attn_rows == 16) {
     dim3 grid((R + 15) / 16, p.H);
-    attn_prefill_kernel<2><<<grid, 256, 0, s>>>(p, w, layer, slot, pos0, R);
+    attn_prefill_kernel<1><<<grid, 256, 0, s>>>(p, w, layer, slot, pos0, R);
   } else {
-    dim3 grid((R + 23) / 24, p.H);
-    attn_prefill_kernel<3><<<grid, 256, 0, s>>>(p, w, layer, slot, pos0, R);
+    dim3 grid((R + 31) / 32, p.H);
+    attn_prefill_kernel<2><<<grid, 256, 0, s>>>(p, w, layer, slot, pos0, R);
   }
 }
 

@@ -949,7 +949,7 @@ int pass_set_option(pass_ctx *c, const char *name, int value) {
   }
   if (!strcmp(name, "prefill_tile")) {
     // query rows of an attention workgroup of the tiled prompt pass
-    if (value != 0 && value != 16 && value != 24) return fail(c, PASS_EINVAL, "prefill_tile: 0 (default), 16 or 24");
+    if (value != 0 && value != 16 && value != 32) return fail(c, PASS_EINVAL, "prefill_tile: 0 (default), 16 or 32");
     c->pws.attn_rows = value;
     return PASS_OK;
   }

@@ -273,8 +273,8 @@ def test_matrix_core_attention(temp, plen):
 
 
 
-@pytest.mark.parametrize("plen,attn_rows,rows,strips", [(66, 0, 128, 0), (130, 16, 128, 2), (200, 24, 128, 4),
-                                                        (300, 0, 128, 1), (300, 16, 256, 2), (37, 24, 128, 4)])
+@pytest.mark.parametrize("plen,attn_rows,rows,strips", [(66, 0, 128, 0), (130, 16, 128, 2), (200, 32, 128, 4),
+                                                        (300, 0, 128, 1), (300, 16, 256, 2), (37, 32, 128, 4)])
 def test_tiled_prompt_pass(plen, attn_rows, rows, strips):
     """The compute-bound prompt pass (tiled GEMMs, unsplit causal attention): ragged row tiles (65,
     129, 199, 299 rows against 64-row tiles; 36 rows forced through it), ragged feature tiles (148
