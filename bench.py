@@ -195,6 +195,11 @@ def main():
     k_avg_s = kms / max(kn, 1) * 1e-3
     k_bytes = gate_up_kernel_bytes(shape, M)
     achieved = k_bytes / k_avg_s / 1e9
+    # yardstick: a kernel that only reads as many bytes of the model, launched back to back like the
+    # kernel above (what streaming that many bytes once can at best take on this device)
+    plain_bytes = k_bytes // 16 * 16
+    g.plain_read(plain_bytes, 8)
+    plain_us = g.plain_read(plain_bytes, 4 * shape.n_layers)
 
     # the same model call with no look-ahead rows (k = 0): the paper's premise is that the (1+k)-row
     # step costs about what the one-row step costs (Section 2.2)
@@ -247,7 +252,8 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "gate_up_gemm_silu", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": measured_traffic(w.name) if not args.layers and k == w.k else None,
-                     "bytes_per_launch": k_bytes, "avg_launch_us": k_avg_s * 1e6, "launches_timed": kn},
+                     "bytes_per_launch": k_bytes, "avg_launch_us": k_avg_s * 1e6, "launches_timed": kn,
+                     "plain_read_of_same_bytes_us": plain_us, "plain_read_GBps": plain_bytes / plain_us / 1e3},
     }
     g.close()
     if args.calibrate_copy:

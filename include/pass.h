@@ -195,11 +195,20 @@ int pass_set_option(pass_ctx *ctx, const char *name, int value);
 int pass_time_step(pass_ctx *ctx, const int32_t *slots, int n_slots, int warmup, int iters,
                    double *out_ms);
 
-/* Message of the last failure on ctx; ctx == NULL: of the last failed pass_create. */
 /* Sum of the event-measured durations (ms) and the number of launches of the dominant kernel
  * since "kernel_timing" was last set. */
 int pass_kernel_time(pass_ctx *ctx, double *total_ms, int64_t *launches);
 
+/* Measurement yardstick: a kernel that only reads `bytes` bytes of the loaded model (16-byte
+ * non-temporal loads, every workgroup a contiguous segment, nothing computed or written) is launched
+ * `iters` times back to back on the context's stream, each launch on the next `bytes` of the weights
+ * (wrapping around), between two HIP events; *out_us = mean duration of a launch in microseconds.
+ * What a kernel that streams that many bytes once can at best take on this device.
+ * PASS_EINVAL: bytes not a multiple of 16, zero, or more than the model holds; iters < 1.
+ * PASS_ESTATE: no weights loaded. */
+int pass_plain_read(pass_ctx *ctx, size_t bytes, int iters, double *out_us);
+
+/* Message of the last failure on ctx; ctx == NULL: of the last failed pass_create. */
 const char *pass_last_error(pass_ctx *ctx);
 void pass_destroy(pass_ctx *ctx);
 

@@ -224,6 +224,31 @@ __global__ void fill_i32_kernel(int32_t *p, int32_t v, size_t n) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i < n) p[i] = v;
 }
+// Reads n16 16-byte words and drops them: the yardstick of pass_plain_read.  Every workgroup owns
+// a contiguous segment (the pattern that reads fastest on this device), 8 requests per thread in
+// flight.  `never` is 0: the store only keeps the loads alive.
+typedef uint32_t rd_u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(256) void plain_read_kernel(const rd_u32x4 *src, size_t n16, int never, uint32_t *sink) {
+  constexpr int U = 8;
+  const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+  const size_t lo = per * blockIdx.x, hi = min(n16, lo + per);
+  uint32_t acc = 0;
+  size_t i = lo + threadIdx.x;
+  for (; i + (U - 1) * 256 < hi; i += U * 256) {
+    rd_u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = __builtin_nontemporal_load(src + i + u * 256);
+#pragma unroll
+    for (int u = 0; u < U; ++u) acc ^= v[u][u & 3];
+  }
+  for (; i < hi; i += 256) acc ^= __builtin_nontemporal_load(src + i)[0];
+  if (never && acc == 0x9e3779b9u) *sink = acc;
+}
+
+void launch_plain_read(const void *src, size_t bytes, uint32_t *sink, hipStream_t s) {
+  plain_read_kernel<<<2048, 256, 0, s>>>((const rd_u32x4 *)src, bytes / 16, 0, sink);
+}
+
 void launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t s) {
   if (n == 0) return;
   // chunks of 2^30 elements keep the grid size inside 32 bits

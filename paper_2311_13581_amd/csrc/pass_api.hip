@@ -884,6 +884,29 @@ int pass_kernel_time(pass_ctx *c, double *total_ms, int64_t *launches) {
   return PASS_OK;
 }
 
+int pass_plain_read(pass_ctx *c, size_t bytes, int iters, double *out_us) {
+  if (!c) return PASS_EINVAL;
+  if (!c->weights_loaded) return fail(c, PASS_ESTATE, "weights not loaded");
+  // the model's tensors lie back to back in the arena, from the embedding table to the staging area
+  const char *base = (const char *)c->tok_emb;
+  const size_t span = (size_t)((const char *)c->staging - base);
+  if (!out_us || iters < 1 || bytes == 0 || bytes % 16 || bytes > span) return fail(c, PASS_EINVAL, "bad argument");
+  HIP_TRY(c, hipEventRecord(c->ev[0], c->stream));
+  size_t off = 0;
+  for (int i = 0; i < iters; ++i) {
+    if (off + bytes > span) off = 0;
+    launch_plain_read(base + off, bytes, (uint32_t *)c->P.fallbacks, c->stream);
+    off += bytes;
+  }
+  HIP_TRY(c, hipEventRecord(c->ev[1], c->stream));
+  HIP_TRY(c, hipGetLastError());
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  float ms = 0;
+  HIP_TRY(c, hipEventElapsedTime(&ms, c->ev[0], c->ev[1]));
+  *out_us = (double)ms * 1e3 / iters;
+  return PASS_OK;
+}
+
 int pass_get_logits(pass_ctx *c, int slot, int which, float *out) {
   if (!c) return PASS_EINVAL;
   if (slot < 0 || slot >= c->cfg.max_slots || !out || (which != 0 && which != 1)) return fail(c, PASS_EINVAL, "bad argument");

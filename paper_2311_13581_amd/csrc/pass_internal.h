@@ -131,6 +131,7 @@ void launch_draft_epilogue(const Params &p, const SampleArgs &a, int B, int R, h
 void launch_verify_epilogue(const Params &p, const SampleArgs &a, int B, int R, hipStream_t s);
 void launch_poke(int32_t *const *ptrs, const int32_t *vals, int n, hipStream_t s);
 void launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t s);
+void launch_plain_read(const void *src, size_t bytes, uint32_t *sink, hipStream_t s);
 
 // matrix-core path (bf16, 16x32 weight tiles)
 void launch_pack_tiles(const uint16_t *src, uint16_t *dst, int N, int K, int strip_off, int strip_stride,

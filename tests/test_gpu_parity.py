@@ -165,6 +165,26 @@ def test_error_paths():
     g.close()
 
 
+def test_plain_read_yardstick():
+    """pass_plain_read: argument checks, and a plausible duration for reading the tiny model."""
+    from paper_2311_13581_amd import binding
+    w = TINY
+    g = binding.Pass(binding.make_config(w.shape, w.k, 1, 64, 16))
+    with pytest.raises(binding.PassError) as e:
+        g.plain_read(4096, 2)  # no weights yet
+    assert e.value.code == -2
+    g.load_weights(synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale))
+    for bad in (0, 24, 1 << 40):
+        with pytest.raises(binding.PassError) as e:
+            g.plain_read(bad, 2)
+        assert e.value.code == -1
+    with pytest.raises(binding.PassError):
+        g.plain_read(4096, 0)
+    us = g.plain_read(1 << 20, 16)
+    assert 0.5 < us < 1000.0, us
+    g.close()
+
+
 # ---------------------------------------------------------------------------------------------
 # matrix-core (bf16 MFMA) path: shapes whose dimensions are multiples of the 16x32 weight tile
 # ---------------------------------------------------------------------------------------------
