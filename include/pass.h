@@ -182,7 +182,8 @@ int pass_seq_len(pass_ctx *ctx, int slot, int32_t *kv_len, int32_t *n_generated)
  * 2 * PASS_MAX_ROWS rows take the tiled, compute-bound prompt pass when the model runs on the matrix-core
  * path with the matrix-core attention kernel, 0 = never, 1 = every prompt does), "prefill_rows" (a
  * multiple of 128 up to min(2048, max_seq_len rounded up): prompt rows per pass of the tiled prompt
- * pass), "prefill_tile" (0, 16 or 32: query rows per attention workgroup of the tiled prompt pass),
+ * pass), "prefill_tile" (0, 16, 32 or 128: query rows per attention workgroup of the tiled prompt pass;
+ * 0 = 128 for passes of more than 512 rows, else 32),
  * "prefill_block" (tiles along the features * 100 + tiles along the rows of the block of GEMM tiles one
  * die works on at a time; 0 = default 8 x 8), "prefill_strips" (1, 2 or 4: strips of 16 features per wavefront
  * in the GEMMs of the tiled prompt pass, gate/up at least 2; 0 = by row count).

@@ -17,6 +17,8 @@
 //                      paged cache, without a split of the keys across workgroups: the four
 //                      wavefronts take alternate 32-key steps and merge once at the end.  K and V
 //                      tiles are used for all row groups of the block.
+//   attn_prefill_shared_kernel  the same for passes of more than 512 rows: 128 rows per workgroup,
+//                      the K and V tiles of a step fetched once into LDS for all four wavefronts.
 //
 // Workgroup -> tile mapping: consecutive workgroup ids go to different dies (XCDs), each with its
 // own L2.  The 64 workgroups a die holds at a time are given a block of 8 x 8 tiles, so a weight
@@ -550,6 +552,214 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Long prompts: the same attention with the K/V tiles shared by the workgroup.  In the kernel above
+// every block of 32 rows pulls all earlier keys through its compute unit's L1 on its own, and at
+// thousands of rows that traffic out of L2 bounds it.  Here a workgroup owns 128 rows, 32 per
+// wavefront; all four wavefronts walk the same 32-key steps, the step's K and V tiles (16 KB) are
+// fetched once, by all wavefronts together (each fetches 2 of the 8 K fragments and 2 of the 8 V
+// fragments, exactly as it would load them for itself), and laid down in LDS in fragment order, so
+// that every wavefront reads a fragment as 1 KB of consecutive 16-byte words.  Requests run two
+// steps ahead of their use (register ring, LDS double buffer, one barrier per step, as in
+// gemm_tile_kernel).  A wavefront skips the steps past its own last row but keeps fetching and
+// meeting the barriers.  No merge at the end: every wavefront owns its rows.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_prefill_shared_kernel(Params p, PrefillWs w, int layer, int slot,
+                                                                                                            int pos0, int R) {
+  constexpr int HD = 128, RG = 2, RW = 16 * RG, RQ = 4 * RW;  // 32 rows per wavefront, 128 per workgroup
+  __shared__ u32x4 sK[2][8][64], sV[2][8][64];
+
+  const int blk = gridDim.x - 1 - blockIdx.x;  // blocks with the most keys first
+  const int head = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int ml = lane & 15, g = lane >> 4;
+  const int r0w = blk * RQ + wave * RW;        // first row of this wavefront
+  const int nr = max(0, min(RW, R - r0w));     // its rows (0: the prompt ends before them)
+  const int k_all = pos0 + min(R, blk * RQ + RQ);  // keys visible to the workgroup's last row
+  const int k_own = pos0 + r0w + nr;               // keys visible to this wavefront's last row
+  const uint16_t *kpool = (const uint16_t *)p.k_pool, *vpool = (const uint16_t *)p.v_pool;
+
+  u32x4 qh[RG][4], ql[RG][4];
+  {
+    const float scale = rsqrtf((float)HD);
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) {
+      const int rr = rg * 16 + ml;
+      const bool live = rr < nr;
+      const float *qp = w.q + (size_t)(live ? r0w + rr : 0) * p.D + head * HD + g * 8;
+      floatx4 raw[4][2];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        raw[j][0] = *(const floatx4 *)(qp + j * 32);
+        raw[j][1] = *(const floatx4 *)(qp + j * 32 + 4);
+      }
+      const float sc_q = live ? scale : 0.f;
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          qh[rg][j][2 * h] = split2_bf16(raw[j][h][0] * sc_q, raw[j][h][1] * sc_q, true);
+          qh[rg][j][2 * h + 1] = split2_bf16(raw[j][h][2] * sc_q, raw[j][h][3] * sc_q, true);
+          ql[rg][j][2 * h] = split2_bf16(raw[j][h][0] * sc_q, raw[j][h][1] * sc_q, false);
+          ql[rg][j][2 * h + 1] = split2_bf16(raw[j][h][2] * sc_q, raw[j][h][3] * sc_q, false);
+        }
+    }
+  }
+
+  floatx4 o[RG][8];
+  float m_run[RG], l_run[RG];
+#pragma unroll
+  for (int rg = 0; rg < RG; ++rg) {
+    m_run[rg] = -INFINITY;
+    l_run[rg] = 0.f;
+#pragma unroll
+    for (int db = 0; db < 8; ++db) o[rg][db] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  const int n_steps = (k_all + 31) >> 5;
+  // this wavefront's share of a step's tiles: K fragments 2 * wave, 2 * wave + 1 (fragment t * 4 + j:
+  // 16 keys of tile t x dims j * 32 ..), V fragments of dim blocks 2 * wave, 2 * wave + 1
+  u32x4 rK[3][2], rV[3][2];
+  auto fetch = [&](u32x4 (&dk)[2], u32x4 (&dv)[2], int step) __attribute__((always_inline)) {
+    const int base = step << 5;
+    const int page = p.block_table[(size_t)slot * p.pages_per_seq + (base >> p.page_shift)];
+    const int poff = base & (p.page_size - 1);
+    const size_t hbase = ((size_t)layer * p.n_pages + page) * p.H + head;
+    const uint16_t *kp = kpool + (hbase * p.page_size + poff) * HD;   // K[key][dim]
+    const uint16_t *vp = vpool + hbase * HD * p.page_size + poff;     // Vt[dim][key]
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int f = wave * 2 + i, t = f >> 2, j = f & 3;
+      const int key = (ml >> 2) * 8 + t * 4 + (ml & 3);  // key slot ml of tile t
+      dk[i] = *(const u32x4 *)(kp + (size_t)key * HD + j * 32 + g * 8);
+      dv[i] = *(const u32x4 *)(vp + (size_t)(f * 16 + ml) * p.page_size + g * 8);
+    }
+  };
+  auto put = [&](int buf, const u32x4 (&dk)[2], const u32x4 (&dv)[2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      sK[buf][wave * 2 + i][lane] = dk[i];
+      sV[buf][wave * 2 + i][lane] = dv[i];
+    }
+  };
+  auto compute = [&](int buf, int base) __attribute__((always_inline)) {
+    if (base >= k_own) return;  // past this wavefront's last row
+    floatx4 sc[RG][2];
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg)
+#pragma unroll
+      for (int t = 0; t < 2; ++t) sc[rg][t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const u32x4 kf = sK[buf][t * 4 + j][lane];
+#pragma unroll
+        for (int rg = 0; rg < RG; ++rg) {
+          sc[rg][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf),
+                                                              __builtin_bit_cast(bf16x8, qh[rg][j]), sc[rg][t], 0, 0, 0);
+          sc[rg][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kf),
+                                                              __builtin_bit_cast(bf16x8, ql[rg][j]), sc[rg][t], 0, 0, 0);
+        }
+      }
+    u32x4 ph[RG], pl[RG];
+    float alpha[RG];
+#pragma unroll
+    for (int rg = 0; rg < RG; ++rg) {
+      const int rr = rg * 16 + ml;
+      float sv[8];
+      float m_blk = -INFINITY;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int key = base + 8 * g + 4 * t + r;
+          const bool ok = (rr < nr) && (key <= pos0 + r0w + rr);
+          const float v = ok ? sc[rg][t][r] : -INFINITY;
+          sv[4 * t + r] = v;
+          m_blk = fmaxf(m_blk, v);
+        }
+      m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 16));
+      m_blk = fmaxf(m_blk, __shfl_xor(m_blk, 32));
+      const float m_new = fmaxf(m_run[rg], m_blk);
+      alpha[rg] = (m_run[rg] == -INFINITY) ? 0.f : __expf(m_run[rg] - m_new);
+      float pv[8], psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        pv[i] = (sv[i] == -INFINITY) ? 0.f : __expf(sv[i] - m_new);
+        psum += pv[i];
+      }
+      l_run[rg] = l_run[rg] * alpha[rg] + psum;
+      m_run[rg] = m_new;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        ph[rg][i] = pack2_bf16(pv[2 * i], pv[2 * i + 1]);
+        pl[rg][i] = pack2_bf16(pv[2 * i] - __uint_as_float(ph[rg][i] << 16),
+                               pv[2 * i + 1] - __uint_as_float(ph[rg][i] & 0xffff0000u));
+      }
+      // once the running maxima have settled alpha is 1 in every lane: skip the rescaling then
+      if (__builtin_amdgcn_ballot_w64(alpha[rg] != 1.0f) != 0) {
+#pragma unroll
+        for (int db = 0; db < 8; ++db) o[rg][db] *= alpha[rg];
+      }
+    }
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      const u32x4 vf = sV[buf][db][lane];
+#pragma unroll
+      for (int rg = 0; rg < RG; ++rg) {
+        o[rg][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
+                                                            __builtin_bit_cast(bf16x8, ph[rg]), o[rg][db], 0, 0, 0);
+        o[rg][db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf),
+                                                            __builtin_bit_cast(bf16x8, pl[rg]), o[rg][db], 0, 0, 0);
+      }
+    }
+  };
+  // step s: request the tiles of step s+2 (past the end: the last step again, in bounds, unused),
+  // lay the tiles of step s+1 (requested a step ago) down in LDS buffer (s+1) & 1, compute from
+  // buffer s & 1.  A buffer is rewritten only after the barrier that follows its last reader.
+  auto step = [&](auto I, int st) __attribute__((always_inline)) {
+    constexpr int i = decltype(I)::value;
+    fetch(rK[(i + 2) % 3], rV[(i + 2) % 3], min(st + 2, n_steps - 1));
+    __builtin_amdgcn_sched_barrier(0);
+    put((st + 1) & 1, rK[(i + 1) % 3], rV[(i + 1) % 3]);
+    compute(st & 1, st << 5);
+    __syncthreads();
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  fetch(rK[0], rV[0], 0);
+  fetch(rK[1], rV[1], min(1, n_steps - 1));
+  put(0, rK[0], rV[0]);
+  __syncthreads();
+  int st = 0;
+  for (; st + 2 < n_steps; st += 3) {
+    step(ic<0>{}, st);
+    step(ic<1>{}, st + 1);
+    step(ic<2>{}, st + 2);
+  }
+  if (st < n_steps) {
+    step(ic<0>{}, st);
+    if (st + 1 < n_steps) step(ic<1>{}, st + 1);
+  }
+
+  // lane (ml, g) holds dims db * 16 + 4g + r of row rg * 16 + ml; a row's sum of probabilities is
+  // spread over the four g groups
+#pragma unroll
+  for (int rg = 0; rg < RG; ++rg) {
+    const int rr = rg * 16 + ml;
+    float l = l_run[rg];
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+    if (rr >= nr) continue;
+    const float inv_l = 1.0f / l;  // every live row sees key 0
+#pragma unroll
+    for (int db = 0; db < 8; ++db) {
+      const float tv[4] = {o[rg][db][0] * inv_l, o[rg][db][1] * inv_l, o[rg][db][2] * inv_l, o[rg][db][3] * inv_l};
+      store_split4(p.attn_x, r0w + rr, p.D, head * HD + db * 16 + 4 * g, tv);
+    }
+  }
+}
+
 }  // namespace
 
 // Strips per wavefront of the residual projections for a pass of M rows.  Fixes the number of
@@ -573,7 +783,12 @@ void launch_prefill_gateup(const Params &p, const PrefillWs &w, const void *W, i
 }
 void launch_prefill_attention(const Params &p, const PrefillWs &w, int layer, int slot, int pos0, int R,
                               hipStream_t s) {
-  if (w.attn_rows == 16) {
+  // 128 rows per workgroup with shared K/V tiles once a pass is long enough for the traffic out of
+  // L2 to matter (measured: equal at 512 rows, -4 % of the pass at 2048, -7 % at 4096)
+  if (w.attn_rows == 128 || (w.attn_rows == 0 && R > 512)) {
+    dim3 grid((R + 127) / 128, p.H);
+    attn_prefill_shared_kernel<<<grid, 256, 0, s>>>(p, w, layer, slot, pos0, R);
+  } else if (w.attn_rows == 16) {
     dim3 grid((R + 15) / 16, p.H);
     attn_prefill_kernel<1><<<grid, 256, 0, s>>>(p, w, layer, slot, pos0, R);
   } else {

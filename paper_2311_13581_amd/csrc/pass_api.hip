@@ -972,7 +972,7 @@ int pass_set_option(pass_ctx *c, const char *name, int value) {
   }
   if (!strcmp(name, "prefill_tile")) {
     // query rows of an attention workgroup of the tiled prompt pass
-    if (value != 0 && value != 16 && value != 32) return fail(c, PASS_EINVAL, "prefill_tile: 0 (default), 16 or 32");
+    if (value != 0 && value != 16 && value != 32 && value != 128) return fail(c, PASS_EINVAL, "prefill_tile: 0 (default), 16, 32 or 128");
     c->pws.attn_rows = value;
     return PASS_OK;
   }

@@ -170,7 +170,7 @@ struct PrefillWs {
   int resid_strips;  // strips per wavefront of the residual projections in this pass (prefill_resid_strips)
   int resid_strips_opt;  // 1, 2 or 4: strips per wavefront of every GEMM fixed by the caller (gate/up: at least 2); 0 = by row count
   int blk_n, blk_m;  // tiles (along the features, along the rows) of the block one die works on at a time; 0 = default
-  int attn_rows;  // query rows of an attention workgroup: 16 or 32 (0 = 32)
+  int attn_rows;  // query rows of an attention workgroup: 16, 32 or 128 (0 = 128 for passes of more than 512 rows, else 32)
   float *q;       // [rows][D] rotated queries
 };
 void launch_assemble_prefill(const Params &p, const void *tok_emb, const void *gain0, int R, int ssq_parts,

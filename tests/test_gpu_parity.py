@@ -294,13 +294,15 @@ def test_matrix_core_attention(temp, plen):
 
 
 @pytest.mark.parametrize("plen,attn_rows,rows,strips", [(66, 0, 128, 0), (130, 16, 128, 2), (200, 32, 128, 4),
-                                                        (300, 0, 128, 1), (300, 16, 256, 2), (37, 32, 128, 4)])
+                                                        (300, 128, 128, 1), (300, 16, 256, 2), (37, 32, 128, 4),
+                                                        (300, 128, 384, 0), (150, 128, 128, 0)])
 def test_tiled_prompt_pass(plen, attn_rows, rows, strips):
     """The compute-bound prompt pass (tiled GEMMs, unsplit causal attention): ragged row tiles (65,
     129, 199, 299 rows against 64-row tiles; 36 rows forced through it), ragged feature tiles (148
     gate/up strips against 16 per workgroup), an odd number of k-steps (37), several passes over the
     weights (299 rows at 128 per pass: later passes attend to the earlier ones through the cache),
-    both attention block heights, every width of the residual projections' tiles.  The first drafting and validation calls after it are compared
+    every attention block height (128: the kernel with K/V tiles shared through LDS, with ragged
+    last blocks and wavefronts without rows), every width of the residual projections' tiles.  The first drafting and validation calls after it are compared
     with the oracle, which prefills row by row."""
     w = MFMA_HD128
     W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
