@@ -293,23 +293,26 @@ def test_matrix_core_attention(temp, plen):
 
 
 
-@pytest.mark.parametrize("plen,attn_rows,rows,strips", [(66, 0, 128, 0), (130, 16, 128, 2), (200, 32, 128, 4),
-                                                        (300, 128, 128, 1), (300, 16, 256, 2), (37, 32, 128, 4),
-                                                        (300, 128, 384, 0), (150, 128, 128, 0)])
-def test_tiled_prompt_pass(plen, attn_rows, rows, strips):
+@pytest.mark.parametrize("plen,attn_rows,rows,strips,block", [
+    (66, 0, 128, 0, 0), (130, 16, 128, 2, 203), (200, 32, 128, 4, 101), (300, 128, 128, 1, 1602),
+    (300, 16, 256, 2, 364), (37, 32, 128, 4, 0), (300, 128, 384, 0, 6401), (150, 128, 128, 0, 0)])
+def test_tiled_prompt_pass(plen, attn_rows, rows, strips, block):
     """The compute-bound prompt pass (tiled GEMMs, unsplit causal attention): ragged row tiles (65,
     129, 199, 299 rows against 64-row tiles; 36 rows forced through it), ragged feature tiles (148
     gate/up strips against 16 per workgroup), an odd number of k-steps (37), several passes over the
     weights (299 rows at 128 per pass: later passes attend to the earlier ones through the cache),
     every attention block height (128: the kernel with K/V tiles shared through LDS, with ragged
-    last blocks and wavefronts without rows), every width of the residual projections' tiles.  The first drafting and validation calls after it are compared
-    with the oracle, which prefills row by row."""
+    last blocks and wavefronts without rows), every width of the GEMM tiles, and blocks of tiles per
+    die from 1 x 1 to 64 x 1 (mostly empty blocks: every tile must still be computed exactly once).
+    The first drafting and validation calls after it are compared with the oracle, which prefills row
+    by row."""
     w = MFMA_HD128
     W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
     m = O.Model(w.shape, W, w.k)
     prompt = np.random.default_rng(plen).integers(0, w.shape.vocab, plen).astype(np.int32)
     g = _gpu(w.shape, W, w.k, max_seq_len=384, page_size=64,
-             options={"prefill_tiled": 1, "prefill_tile": attn_rows, "prefill_rows": rows, "prefill_strips": strips})
+             options={"prefill_tiled": 1, "prefill_tile": attn_rows, "prefill_rows": rows, "prefill_strips": strips,
+                      "prefill_block": block})
     st = parity.stepwise_parity(g, m, 0, 2, prompt, 3, 0.9, 777, parity.LOGIT_TOL[synth.BF16], max_len=384)
     print(st)
     assert st.iterations == 3 and st.resyncs == 0 and st.max_rel_err < 1e-3
