@@ -160,6 +160,18 @@ int pass_run_iterations(pass_ctx *ctx, const int32_t *slots, int n_slots, int n_
  * validation (which = 1) call, copied to host memory. */
 int pass_get_logits(pass_ctx *ctx, int slot, int which, float *out);
 
+/* Parity hook for the random numbers of Algorithm 1 ("sample", "r ~ U[0,1]"): the uniform variates
+ * the device epilogues attach to vocabulary indices first .. first + n - 1 of one (seed, sequence id,
+ * iteration, row, purpose), computed by the epilogues' own generator (Philox4x32-10, key = seed,
+ * counter = (index / 4, iteration, row | purpose << 8, sequence id), word index % 4; top 23 bits ->
+ * (bits + 0.5) * 2^-23) and copied to the host array out[n].  purpose: 0 drafting draw, 1 accept test
+ * (index 0 only is used by the method), 2 residual draw, 3 bonus draw.  The values pass through the
+ * buffer of the validation call's logits: pass_get_logits(.., 1, ..) is stale afterwards until the
+ * next validation call; sequence state is untouched.  PASS_EINVAL: row > 255, purpose > 3, first not
+ * a multiple of 4, first + n beyond 2^32, out NULL. */
+int pass_rng_uniforms(pass_ctx *ctx, uint64_t seed, uint32_t seq_id, uint32_t iteration, uint32_t row,
+                      uint32_t purpose, uint32_t first, size_t n, float *out);
+
 /* kv_len and number of generated tokens of a slot (either pointer may be NULL). */
 int pass_seq_len(pass_ctx *ctx, int slot, int32_t *kv_len, int32_t *n_generated);
 

@@ -170,6 +170,12 @@ double orc_uniform(uint64_t seed, uint32_t seq_id, uint32_t iteration, uint32_t 
   return ((double)(out[j & 3] >> 9) + 0.5) * (1.0 / 8388608.0);
 }
 
+/* out[i] = orc_uniform(.., first + i) for i < n: the same variates, many at a time, for tests. */
+void orc_uniforms(uint64_t seed, uint32_t seq_id, uint32_t iteration, uint32_t row, uint32_t purpose,
+                  uint32_t first, size_t n, double *out) {
+  for (size_t i = 0; i < n; ++i) out[i] = orc_uniform(seed, seq_id, iteration, row, purpose, first + (uint32_t)i);
+}
+
 static inline double gumbel(double u) { return -log(-log(u)); }
 
 /* ------------------------------------------------------------------------------------------ */

@@ -62,6 +62,8 @@ def lib():
         L.orc_philox4x32_10.argtypes = [C.POINTER(C.c_uint32)] * 3
         L.orc_uniform.restype = C.c_double
         L.orc_uniform.argtypes = [C.c_uint64] + [C.c_uint32] * 5
+        L.orc_uniforms.restype = None
+        L.orc_uniforms.argtypes = [C.c_uint64] + [C.c_uint32] * 5 + [C.c_size_t, C.POINTER(C.c_double)]
         fp = C.POINTER(C.c_float)
         ip = C.POINTER(C.c_int32)
         L.orc_sample_softmax.argtypes = [fp, C.c_int, C.c_double, C.c_int, C.POINTER(Ctr), C.c_double, ip]
@@ -124,6 +126,13 @@ def philox4x32_10(ctr, key):
 
 def uniform(seed, seq_id, iteration, row, purpose, j) -> float:
     return lib().orc_uniform(seed, seq_id, iteration, row, purpose, j)
+
+
+def uniforms(seed, seq_id, iteration, row, purpose, first, n) -> np.ndarray:
+    """uniform(.., j) for j = first .. first + n - 1."""
+    out = np.empty(n, dtype=np.float64)
+    lib().orc_uniforms(seed, seq_id, iteration, row, purpose, first, n, out.ctypes.data_as(C.POINTER(C.c_double)))
+    return out
 
 
 def _ctr(seed, seq_id, iteration, row, purpose):

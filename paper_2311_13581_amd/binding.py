@@ -17,7 +17,7 @@ PASS_F32, PASS_BF16 = 0, 1
 MAX_K, MAX_ROWS = 15, 64
 
 SYMBOLS = ["pass_arena_bytes", "pass_create", "pass_load_weights", "pass_prefill", "pass_release",
-           "pass_draft", "pass_verify", "pass_generate", "pass_run_iterations", "pass_kernel_time", "pass_plain_read", "pass_get_logits", "pass_seq_len",
+           "pass_draft", "pass_verify", "pass_generate", "pass_run_iterations", "pass_kernel_time", "pass_plain_read", "pass_rng_uniforms", "pass_get_logits", "pass_seq_len",
            "pass_set_option", "pass_time_step", "pass_last_error", "pass_destroy"]
 
 
@@ -84,6 +84,8 @@ def load_library():
     L.pass_run_iterations.argtypes = [C.c_void_p, ip, C.c_int, C.c_int, C.POINTER(PassSampling), C.POINTER(PassStats)]
     L.pass_kernel_time.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     L.pass_plain_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_double)]
+    L.pass_rng_uniforms.argtypes = [C.c_void_p, C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint32,
+                                    C.c_size_t, C.POINTER(C.c_float)]
     L.pass_get_logits.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_float)]
     L.pass_seq_len.argtypes = [C.c_void_p, C.c_int, ip, ip]
     L.pass_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int]
@@ -232,6 +234,12 @@ class Pass:
         us = C.c_double(0)
         self._check(self.lib.pass_plain_read(self.h, nbytes, iters, C.byref(us)))
         return us.value
+
+    def rng_uniforms(self, seed: int, seq_id: int, iteration: int, row: int, purpose: int, first: int, n: int) -> np.ndarray:
+        out = np.empty(n, dtype=np.float32)
+        self._check(self.lib.pass_rng_uniforms(self.h, seed, seq_id, iteration, row, purpose, first, n,
+                                               out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
 
     def get_logits(self, slot: int, which: int) -> np.ndarray:
         out = np.empty((self.k + 1, self.vocab), dtype=np.float32)

@@ -485,4 +485,24 @@ void launch_verify_epilogue(const Params &p, const SampleArgs &a, int B, int R, 
   verify_decide_kernel<<<B, kEpiThreads, 0, s>>>(p, a);
 }
 
+// The uniforms the epilogues attach to indices j0 .. j0 + n of one (sequence, iteration, row,
+// purpose): the same generator and the same bits-to-float step as the draws above use.
+__global__ void rng_uniforms_kernel(float *out, uint32_t j0, int n, uint32_t k0, uint32_t k1, uint32_t c1, uint32_t c2,
+                                    uint32_t c3) {
+  const int q = blockIdx.x * blockDim.x + threadIdx.x;  // quad of indices within the chunk; j0 % 4 == 0
+  if (q * 4 >= n) return;
+  uint32_t rnd[4];
+  philox4x32_10(j0 / 4 + (uint32_t)q, c1, c2, c3, k0, k1, rnd);
+#pragma unroll
+  for (int e = 0; e < 4; ++e)
+    if (q * 4 + e < n) out[q * 4 + e] = u01(rnd[e]);
+}
+
+void launch_rng_uniforms(float *out, uint32_t j0, int n, uint64_t seed, uint32_t seq_id, uint32_t iteration,
+                         uint32_t row, uint32_t purpose, hipStream_t s) {
+  const int quads = (n + 3) / 4;
+  rng_uniforms_kernel<<<(quads + 255) / 256, 256, 0, s>>>(out, j0, n, (uint32_t)seed, (uint32_t)(seed >> 32), iteration,
+                                                         row | (purpose << 8), seq_id);
+}
+
 }  // namespace pass

@@ -907,6 +907,25 @@ int pass_plain_read(pass_ctx *c, size_t bytes, int iters, double *out_us) {
   return PASS_OK;
 }
 
+int pass_rng_uniforms(pass_ctx *c, uint64_t seed, uint32_t seq_id, uint32_t iteration, uint32_t row, uint32_t purpose,
+                      uint32_t first, size_t n, float *out) {
+  if (!c) return PASS_EINVAL;
+  if (!out || row > 255u || purpose > 3u || first % 4u || (uint64_t)first + n > ((uint64_t)1 << 32))
+    return fail(c, PASS_EINVAL, "bad argument");
+  // staged through the validation call's logits, in pieces of that buffer's size
+  const size_t cap = ((size_t)c->cfg.max_slots * (1 + c->cfg.k) * c->cfg.vocab) & ~(size_t)3;
+  if (cap == 0) return fail(c, PASS_ECAPACITY, "no staging room");
+  for (size_t done = 0; done < n;) {
+    const size_t m = std::min(cap, n - done);
+    launch_rng_uniforms(c->P.verify_logits, first + (uint32_t)done, (int)m, seed, seq_id, iteration, row, purpose, c->stream);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipMemcpyAsync(out + done, c->P.verify_logits, m * sizeof(float), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    done += m;
+  }
+  return PASS_OK;
+}
+
 int pass_get_logits(pass_ctx *c, int slot, int which, float *out) {
   if (!c) return PASS_EINVAL;
   if (slot < 0 || slot >= c->cfg.max_slots || !out || (which != 0 && which != 1)) return fail(c, PASS_EINVAL, "bad argument");

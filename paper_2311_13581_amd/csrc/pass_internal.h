@@ -132,6 +132,8 @@ void launch_verify_epilogue(const Params &p, const SampleArgs &a, int B, int R, 
 void launch_poke(int32_t *const *ptrs, const int32_t *vals, int n, hipStream_t s);
 void launch_fill_i32(int32_t *p, int32_t v, size_t n, hipStream_t s);
 void launch_plain_read(const void *src, size_t bytes, uint32_t *sink, hipStream_t s);
+void launch_rng_uniforms(float *out, uint32_t j0, int n, uint64_t seed, uint32_t seq_id, uint32_t iteration,
+                         uint32_t row, uint32_t purpose, hipStream_t s);
 
 // matrix-core path (bf16, 16x32 weight tiles)
 void launch_pack_tiles(const uint16_t *src, uint16_t *dst, int N, int K, int strip_off, int strip_stride,

@@ -165,6 +165,33 @@ def test_error_paths():
     g.close()
 
 
+def test_device_uniforms_equal_the_oracles_on_a_million_counters():
+    """The epilogues' generator (Philox4x32-10 and the bits-to-float step) against the oracle's, bit for
+    bit: 2^20 + 3 consecutive vocabulary indices of one stream (more than the staging buffer holds, so
+    several pieces and a ragged tail), then every purpose, rows at both ends, keys and counters with high
+    bits set, and a start far into the index range."""
+    from paper_2311_13581_amd import binding
+    w = TINY
+    g = binding.Pass(binding.make_config(w.shape, w.k, 1, 64, 16))
+    n = (1 << 20) + 3
+    got = g.rng_uniforms(0x0123456789ABCDEF, 7, 5, 2, 0, 0, n)
+    want = O.uniforms(0x0123456789ABCDEF, 7, 5, 2, 0, 0, n)
+    assert got.dtype == np.float32 and np.array_equal(got.astype(np.float64), want)
+    assert 0.0 < got.min() and got.max() < 1.0
+    for seed, sid, it, row, purpose, first in [(0, 0, 0, 0, 0, 0), (1, 2, 3, 4, 1, 0), (2 ** 64 - 1, 2 ** 32 - 1, 2 ** 32 - 1, 255, 3, 8),
+                                              (5 << 32, 1 << 31, 1 << 31, 15, 2, 2 ** 32 - 4096), (9, 3, 1, 1, 2, 31996)]:
+        m = 4093 if first < 2 ** 32 - 4096 else 4096
+        got = g.rng_uniforms(seed, sid, it, row, purpose, first, m)
+        assert np.array_equal(got.astype(np.float64), O.uniforms(seed, sid, it, row, purpose, first, m)), (seed, row, purpose)
+    for bad in [dict(row=256), dict(purpose=4), dict(first=2), dict(first=2 ** 32 - 4, n=5)]:
+        a = dict(seed=1, seq_id=0, iteration=0, row=0, purpose=0, first=0, n=4)
+        a.update(bad)
+        with pytest.raises(binding.PassError) as e:
+            g.rng_uniforms(**a)
+        assert e.value.code == -1
+    g.close()
+
+
 def test_plain_read_yardstick():
     """pass_plain_read: argument checks, and a plausible duration for reading the tiny model."""
     from paper_2311_13581_amd import binding

@@ -62,6 +62,13 @@ def test_uniform_counter_layout():
     assert base == ((out[5 & 3] >> 9) + 0.5) / 2 ** 23
 
 
+def test_bulk_uniforms_are_the_single_uniforms():
+    """The many-at-a-time helper the GPU test uses returns uniform(.., j), also from an unaligned start."""
+    for first in (0, 6, 4096):
+        got = O.uniforms(77, 9, 11, 3, 2, first, 41)
+        assert list(got) == [O.uniform(77, 9, 11, 3, 2, first + i) for i in range(41)]
+
+
 def test_bf16_round_matches_torch():
     rng = np.random.default_rng(0)
     xs = np.concatenate([rng.standard_normal(2000), rng.standard_normal(2000) * 1e-3,
