@@ -364,45 +364,42 @@ template <int HD, int OUT, int Q>
 __global__ __launch_bounds__(HD * Q) void attn_combine_kernel(Params p, int R, int mfma_plan) {
   __shared__ float sm[Q], sl[Q], sv[Q][HD];
   const int m = blockIdx.x, head = blockIdx.y, dim = threadIdx.x % HD, q = threadIdx.x / HD;
-  // the row's group and its split plan, recomputed exactly as the split kernel did
+  // One batch of eight splits per thread, requested before the plan is known so that the lookup of the
+  // row's position and the partials share one round trip to memory: slots 0 .. kMaxSplits - 1 of a
+  // (row, head) always exist, those beyond the plan hold stale values that are never used.
+  static_assert(Q * 8 <= kMaxSplits, "a quarter's eight slots must exist");
   constexpr int RQ = kAttnRowsPerGroup;
-  int b = m / R, r = m % R, r0 = (r / RQ) * RQ;
-  int n_keys = p.row_pos[b * R + r0] + min(RQ, R - r0);  // as the split kernel: position of the group's first row
+  const int b = m / R, r = m % R, r0 = (r / RQ) * RQ;
+  const int pos0 = p.row_pos[b * R + r0];  // position of the group's first row
+  const size_t pi = ((size_t)m * p.H + head) * kMaxSplits;
+  const int s_begin = (Q == 1) ? 0 : q * 8;
+  float pm[8], pl[8], pa[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) {
+    pm[u] = p.part_m[pi + s_begin + u];
+    pl[u] = p.part_l[pi + s_begin + u];
+    pa[u] = p.part_acc[(pi + s_begin + u) * HD + dim];
+  }
+  // the split plan of the row's group, recomputed exactly as the split kernel did
+  const int n_keys = pos0 + min(RQ, R - r0);
   int n_splits, chunk;
   if (mfma_plan)
     split_plan_mfma(n_keys, p.H, n_splits, chunk);
   else
     split_plan(n_keys, n_splits, chunk);
-  size_t pi = ((size_t)m * p.H + head) * kMaxSplits;
-  // eight splits at a time: their triples are requested together (indices clamped, surplus
-  // dropped) and merged into the running triple in split order
+  const int s_end = min(n_splits, s_begin + 8);
+  // merged in split order
   float m_n = -INFINITY, l_n = 0.f, v = 0.f;
-  const int s_begin = (Q == 1) ? 0 : q * 8, s_end = (Q == 1) ? n_splits : min(n_splits, q * 8 + 8);
-  for (int s0 = s_begin; s0 < s_end; s0 += 8) {
-    float pm[8], pl[8], pa[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int s = min(s0 + u, n_splits - 1);
-      pm[u] = p.part_m[pi + s];
-      pl[u] = p.part_l[pi + s];
-      pa[u] = p.part_acc[(pi + s) * HD + dim];
+  for (int u = 0; u < 8; ++u)
+    if (s_begin + u < s_end) m_n = fmaxf(m_n, pm[u]);
+#pragma unroll
+  for (int u = 0; u < 8; ++u)
+    if (s_begin + u < s_end) {
+      const float f = (pm[u] == -INFINITY) ? 0.f : __expf(pm[u] - m_n);
+      l_n += pl[u] * f;
+      v += pa[u] * f;
     }
-    float m_new = m_n;
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (s0 + u < s_end) m_new = fmaxf(m_new, pm[u]);
-    const float f0 = (m_n == -INFINITY) ? 0.f : __expf(m_n - m_new);
-    l_n *= f0;
-    v *= f0;
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (s0 + u < s_end) {
-        const float f = (pm[u] == -INFINITY) ? 0.f : __expf(pm[u] - m_new);
-        l_n += pl[u] * f;
-        v += pa[u] * f;
-      }
-    m_n = m_new;
-  }
   if constexpr (Q > 1) {
     if (dim == 0) { sm[q] = m_n; sl[q] = l_n; }
     sv[q][dim] = v;
