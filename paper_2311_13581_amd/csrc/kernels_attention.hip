@@ -209,12 +209,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   const int r0 = (grp_id % groups_per_slot) * RQ;
   const int nr = min(RQ, R - r0);
   const int m0 = b * R + r0;
+  // Requests that depend on each other come in three rounds and no more: (slot, position), then
+  // (page of the first step, query rows), then the first step's K and V.  The slot takes part in the
+  // first branch only so that the compiler requests it together with the position instead of after
+  // that branch.
   const int slot = p.row_slot[m0];
   const int pos0 = p.row_pos[m0];
   const int n_keys = pos0 + nr;
   int n_splits, chunk;
   split_plan_mfma(n_keys, p.H, n_splits, chunk);
-  if (split >= n_splits) return;
+  if (slot < 0 || split >= n_splits) return;
   const int k_lo = split * chunk;
   const int k_hi = min(n_keys, k_lo + chunk);
 
@@ -224,8 +228,28 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   const int row = ml & 7;  // query row of this lane's column (both column halves)
   const uint16_t *kpool = (const uint16_t *)p.k_pool, *vpool = (const uint16_t *)p.v_pool;
 
+  u32x4_t kt[2][4], vt[8];
+  // requests the K tiles and V rows of the 32 keys from `at` on (one page holds them: page_size is a
+  // multiple of 32; the lookup is wavefront-uniform)
+  auto request = [&](int at) __attribute__((always_inline)) {
+    const int page = p.block_table[(size_t)slot * p.pages_per_seq + (at >> p.page_shift)];
+    const int poff = at & (p.page_size - 1);
+    const size_t hbase = ((size_t)layer * p.n_pages + page) * p.H + head;
+    const uint16_t *kp = kpool + (hbase * p.page_size + poff) * HD;   // K[key][dim]
+    const uint16_t *vp = vpool + hbase * HD * p.page_size + poff;     // Vt[dim][key]
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int key = (ml >> 2) * 8 + t * 4 + (ml & 3);  // key slot ml of tile t
+#pragma unroll
+      for (int j = 0; j < 4; ++j) kt[t][j] = *(const u32x4_t *)(kp + (size_t)key * HD + j * 32 + g * 8);
+    }
+#pragma unroll
+    for (int db = 0; db < 8; ++db) vt[db] = *(const u32x4_t *)(vp + (size_t)(db * 16 + ml) * p.page_size + g * 8);
+  };
+
   // query fragment: column ml = hi (ml < 8) or lo (ml >= 8) half of row (ml & 7), scaled by 1/sqrt(hd)
   u32x4_t qf[4];
+  int base = k_lo + wave * 32;
   {
     const float scale = rsqrtf((float)HD);
     const bool live = row < nr;
@@ -238,6 +262,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
       raw[j][0] = *(const f32x4_t *)(qp + j * 32);
       raw[j][1] = *(const f32x4_t *)(qp + j * 32 + 4);
     }
+    // the first step's K and V leave before the query rows are waited for (a wavefront without keys
+    // in this split asks for the split's first keys, which exist, and skips the loop)
+    request(base < k_hi ? base : k_lo);
+    __builtin_amdgcn_sched_barrier(0);
     const float sc_q = live ? scale : 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
@@ -253,27 +281,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   for (int db = 0; db < 8; ++db) o[db] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   float m_run = -INFINITY, l_run = 0.f;
 
-  for (int base = k_lo + wave * 32; base < k_hi; base += 128) {
-    // one page holds the 32 keys (page_size is a multiple of 32); the lookup is wavefront-uniform
-    const int page = p.block_table[(size_t)slot * p.pages_per_seq + (base >> p.page_shift)];
-    const int poff = base & (p.page_size - 1);
-    const size_t hbase = ((size_t)layer * p.n_pages + page) * p.H + head;
-    const uint16_t *kp = kpool + (hbase * p.page_size + poff) * HD;   // K[key][dim]
-    const uint16_t *vp = vpool + hbase * HD * p.page_size + poff;     // Vt[dim][key]
-    u32x4_t kt[2][4], vt[8];
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-      const int key = (ml >> 2) * 8 + t * 4 + (ml & 3);  // key slot ml of tile t
-#pragma unroll
-      for (int j = 0; j < 4; ++j) kt[t][j] = *(const u32x4_t *)(kp + (size_t)key * HD + j * 32 + g * 8);
-    }
-#pragma unroll
-    for (int db = 0; db < 8; ++db) vt[db] = *(const u32x4_t *)(vp + (size_t)(db * 16 + ml) * p.page_size + g * 8);
-    // all sixteen requests leave before anything is computed: left alone, the instruction
-    // scheduler moves the V requests behind the score MFMAs to save registers, and the block
-    // pays two trips to memory in a row
-    __builtin_amdgcn_sched_barrier(0);
-
+  for (; base < k_hi; base += 128) {
+    // (the step's sixteen requests are in flight: those of the first step since before the loop,
+    // those of a later step since the end of the step before it)
     f32x4_t sc[2];
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
@@ -317,6 +327,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
       o[db] *= alpha;
       o[db] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, vt[db]),
                                                       __builtin_bit_cast(bf16x8_t, pf), o[db], 0, 0, 0);
+    }
+    if (base + 128 < k_hi) {
+      request(base + 128);
+      // all sixteen requests leave before anything is computed: left alone, the instruction
+      // scheduler moves the V requests behind the score MFMAs to save registers, and the step
+      // pays two trips to memory in a row
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 
