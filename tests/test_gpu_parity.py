@@ -478,6 +478,22 @@ def test_attention_over_many_splits(attn):
     g.close()
 
 
+def test_attention_splits_of_several_steps():
+    """32 heads and 3150 keys: 25 steps of 128 keys x 32 heads are more workgroups than the chip holds at
+    once, so the split plan gives every workgroup two steps (the second step's K/V is requested at the
+    end of the first) and 13 splits go through the merge kernel's four-quarter form; a narrow model
+    (d_model 256 against an attention width of 4096) keeps the oracle's row-by-row prompt pass short."""
+    shape = synth.ModelShape(1, 256, 32, 128, 704, 512, dtype=synth.BF16)
+    W = synth.make_weights(shape, 77, 2, 8.0)
+    m = O.Model(shape, W, 2)
+    prompt = np.random.default_rng(5).integers(0, shape.vocab, 3150).astype(np.int32)
+    g = _gpu(shape, W, 2, max_seq_len=3328, page_size=64)
+    st = parity.stepwise_parity(g, m, 0, 1, prompt, 3, 0.9, 4711, parity.LOGIT_TOL[synth.BF16], max_len=3328)
+    print(st)
+    assert st.iterations == 3 and st.max_rel_err < 1e-3
+    g.close()
+
+
 @pytest.mark.parametrize("w", [TINY, MFMA_HD128], ids=["fp32", "mfma"])
 def test_maximum_lookahead_count(w):
     """k = 15 (the most the interface takes): 16 rows per call, so the attention kernels see two
