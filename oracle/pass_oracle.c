@@ -473,7 +473,7 @@ int orc_forward(orc_seq *s, int R, const int32_t *ids, const int32_t *la, int po
   double *t0 = (double *)malloc(sizeof(double) * Rz * d);
   double *g = (double *)malloc(sizeof(double) * Rz * F);
   double *u = (double *)malloc(sizeof(double) * Rz * F);
-  double *sc = (double *)malloc(sizeof(double) * (size_t)(pos0 + R));
+  double *sc_all = (double *)malloc(sizeof(double) * Rz * H * (size_t)(pos0 + R)); /* scores of each (row, head) */
 
   /* row assembly: token embedding or look-ahead embedding (Section 2.2.1) */
   for (int r = 0; r < R; ++r) {
@@ -498,9 +498,13 @@ int orc_forward(orc_seq *s, int R, const int32_t *ids, const int32_t *la, int po
       memcpy(vc + (size_t)(pos0 + r) * D, vv + (size_t)r * D, sizeof(double) * D);
     }
     double scale = 1.0 / sqrt((double)hd);
+    /* heads are independent: the threads share them out (as they share the output features of a
+     * matrix product); every (row, head) runs the same operations in the same order on any thread */
+#pragma omp parallel for schedule(static) collapse(2)
     for (int r = 0; r < R; ++r) {
-      int nk = pos0 + r + 1; /* keys at positions 0 .. pos0+r */
       for (int hh = 0; hh < H; ++hh) {
+        int nk = pos0 + r + 1; /* keys at positions 0 .. pos0+r */
+        double *sc = sc_all + ((size_t)r * H + hh) * (size_t)(pos0 + R);
         const double *qv = q + (size_t)r * D + (size_t)hh * hd;
         double mx = -INFINITY;
         for (int j = 0; j < nk; ++j) {
@@ -543,7 +547,7 @@ int orc_forward(orc_seq *s, int R, const int32_t *ids, const int32_t *la, int po
     for (size_t i = 0; i < Rz * V; ++i) logits_out[i] = (float)lg[i];
     free(lg);
   }
-  free(h); free(xn); free(q); free(kk); free(vv); free(ao); free(t0); free(g); free(u); free(sc);
+  free(h); free(xn); free(q); free(kk); free(vv); free(ao); free(t0); free(g); free(u); free(sc_all);
   return ORC_OK;
 }
 
@@ -739,6 +743,30 @@ void orc_seq_read_kv(const orc_seq *s, int which, int layer, int pos, double *ou
 }
 /* overwrite the pending token and state: lets a test put a sequence in a chosen situation */
 void orc_seq_set_pending(orc_seq *s, int32_t tok) { s->pending = tok; }
+
+/* Start `dst` from the state `src` is in between iterations: cached K/V, length, pending token,
+ * iteration and token counters (not the sequence id).  Both must belong to models of the same
+ * layer shapes and weights (they may differ in the number of look-ahead embeddings, which the
+ * prompt pass never touches): a sweep over the number of look-ahead rows prefills once. */
+int orc_seq_copy_state(orc_seq *dst, const orc_seq *src) {
+  if (!dst || !src || src->state != 1) return ORC_EINVAL;
+  const orc_config *a = &dst->m->c, *b = &src->m->c;
+  if (a->n_layers != b->n_layers || a->n_heads != b->n_heads || a->head_dim != b->head_dim ||
+      a->d_model != b->d_model || a->dtype != b->dtype)
+    return ORC_EINVAL;
+  if (src->kv_len + 1 + a->k > dst->max_len) return ORC_ECAPACITY;
+  size_t D = (size_t)a->n_heads * a->head_dim;
+  for (int l = 0; l < a->n_layers; ++l) {
+    memcpy(dst->kc + (size_t)l * dst->max_len * D, src->kc + (size_t)l * src->max_len * D, sizeof(double) * D * src->kv_len);
+    memcpy(dst->vc + (size_t)l * dst->max_len * D, src->vc + (size_t)l * src->max_len * D, sizeof(double) * D * src->kv_len);
+  }
+  dst->kv_len = src->kv_len;
+  dst->pending = src->pending;
+  dst->state = 1;
+  dst->iteration = src->iteration;
+  dst->n_generated = src->n_generated;
+  return ORC_OK;
+}
 /* overwrite the stored draft (tokens and logits) before a verify call: the verify half is then
  * the speculative-sampling rule of Algorithm 2 with an arbitrary draft distribution */
 void orc_seq_set_draft(orc_seq *s, const int32_t *drafts, const float *draft_logits) {

@@ -93,6 +93,7 @@ def lib():
         L.orc_seq_read_kv.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double)]
         L.orc_seq_set_pending.argtypes = [C.c_void_p, C.c_int32]
         L.orc_seq_set_draft.argtypes = [C.c_void_p, ip, fp]
+        L.orc_seq_copy_state.argtypes = [C.c_void_p, C.c_void_p]
     return _lib
 
 
@@ -300,6 +301,10 @@ class Sequence:
         out = np.zeros(s.n_heads * s.head_dim, dtype=np.float64)
         lib().orc_seq_read_kv(self.handle, which, layer, pos, out.ctypes.data_as(C.POINTER(C.c_double)))
         return out
+
+    def copy_state_from(self, other: "Sequence"):
+        """Take over the cache, length, pending token and counters of `other` (between iterations)."""
+        _check(lib().orc_seq_copy_state(self.handle, other.handle), "copy_state")
 
     def set_pending(self, tok):
         lib().orc_seq_set_pending(self.handle, int(tok))
