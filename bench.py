@@ -147,7 +147,7 @@ def main():
     max_len = max(len(p) for p in prompts) + (k + 2) * total_iters + k + 2
     g = binding.Pass(binding.make_config(shape, k, w.batch, max_len, 64), {"path": args.path, "graph": args.graph})
     for cfg in args.gemm_cfg:
-        g.set_option("gemm_cfg", cfg)
+        g.set_option("tune.gemm_cfg", cfg)
     for opt in args.option:
         name, val = opt.split("=")
         g.set_option(name, int(val))

@@ -172,33 +172,49 @@ int pass_get_logits(pass_ctx *ctx, int slot, int which, float *out);
 int pass_rng_uniforms(pass_ctx *ctx, uint64_t seed, uint32_t seq_id, uint32_t iteration, uint32_t row,
                       uint32_t purpose, uint32_t first, size_t n, float *out);
 
+/* Tokens first .. first + n - 1 of everything the slot's sequence has generated since its prefill
+ * (by pass_draft / pass_verify, pass_generate or pass_run_iterations), copied to the host array
+ * out[n].  An iteration of Algorithm 1 adds 2 .. k + 2 tokens, so pass_generate may commit up to
+ * k + 1 tokens beyond max_new to the sequence (and to the cache): they are part of the sequence,
+ * the next call continues after them, and this call is how the caller reads them.
+ * PASS_EINVAL: bad slot, first < 0, n < 0, out NULL; PASS_ESTATE: empty slot; PASS_ECAPACITY:
+ * first + n exceeds the number of generated tokens (pass_seq_len). */
+int pass_get_tokens(pass_ctx *ctx, int slot, int first, int n, int32_t *out);
+
+/* Introspection hook for the split-KV attention of the matrix-core path (no context, no GPU): how a
+ * group of query rows that sees n_keys cached positions of a model with n_heads heads is cut into
+ * splits (*n_splits workgroups of *chunk_keys keys each; a function of the sequence's own length
+ * only, so its arithmetic cannot depend on what else is batched), and *grid_splits, the grid width
+ * the host launches for calls whose longest group has at most n_keys keys (never less than any
+ * shorter group's split count).  Any output pointer may be NULL.  PASS_EINVAL: n_keys or n_heads < 1. */
+int pass_attention_plan(int n_heads, int n_keys, int *n_splits, int *chunk_keys, int *grid_splits);
+
 /* kv_len and number of generated tokens of a slot (either pointer may be NULL). */
 int pass_seq_len(pass_ctx *ctx, int slot, int32_t *kv_len, int32_t *n_generated);
 
-/* Options: "graph" (1 = replay each model call and its epilogue as a captured HIP graph; ignored
- * when the context runs on the null stream, which cannot be captured), "path" (0 = auto, 1 = force the generic
- * kernels; before pass_load_weights), "attention" (0 = auto, 1 = never use the matrix-core attention
- * kernel and its transposed V pages; before pass_load_weights), "gemm_cfg" (launch shape of the decode-sized matrix-core GEMMs, process-wide:
- * kind * 10000 + wavefronts * 100 + unroll with kind 0 QKV, 1 Wo, 2 gate/up, 3 LM head, 4 down, wavefronts 4/8/16,
- * unroll 1/2/4; for calls with more than 8 rows 1000000 + kind * 10000 + wavefronts * 100 + blocks with
- * wavefronts 8/16 and blocks (strips of 16 output features per workgroup) 1/2/4), "lookahead_rows" (look-ahead rows per call from now on, 0 .. k: the drafting call uses the first
- * that many look-ahead embeddings, outputs and logits keep their k-sized layout with unused entries -1 /
- * stale; the paper's sweep over the number of look-ahead tokens without reloading), "lookahead_token" (-1 =
- * trained look-ahead embeddings; a token id = the drafting call appends that token's embedding instead, the
- * paper's second baseline with a fixed [UNK] token; both only between iterations, else PASS_ESTATE),
- * "kernel_timing" (1 = after every model call, launch the dominant kernel, the gate/up GEMM,
- * once per layer with that layer's weights on the call's rows, back to back between two HIP events on
- * the context's stream, and synchronise; the launches write workspaces only; setting the option resets
- * the counters pass_kernel_time reports), "prefill_chunk" (1 .. PASS_MAX_ROWS: prompt rows per pass over the
- * weights when the prompt goes through the decode kernels), "prefill_tiled" (-1 = prompts of more than
- * 2 * PASS_MAX_ROWS rows take the tiled, compute-bound prompt pass when the model runs on the matrix-core
- * path with the matrix-core attention kernel, 0 = never, 1 = every prompt does), "prefill_rows" (a
- * multiple of 128 up to min(2048, max_seq_len rounded up): prompt rows per pass of the tiled prompt
- * pass), "prefill_tile" (0, 16, 32 or 128: query rows per attention workgroup of the tiled prompt pass;
- * 0 = 128 for passes of more than 512 rows, else 32),
- * "prefill_block" (tiles along the features * 100 + tiles along the rows of the block of GEMM tiles one
- * die works on at a time; 0 = default 8 x 8), "prefill_strips" (1, 2 or 4: strips of 16 features per wavefront
- * in the GEMMs of the tiled prompt pass, gate/up at least 2; 0 = by row count).
+/* Options:
+ *   "graph"            1 = replay each model call and its epilogue as a captured HIP graph; ignored when the
+ *                      context runs on the null stream, which cannot be captured
+ *   "path"             0 = auto, 1 = force the generic kernels; before pass_load_weights
+ *   "attention"        0 = auto, 1 = never use the matrix-core attention kernel and its transposed V pages;
+ *                      before pass_load_weights
+ *   "lookahead_rows"   look-ahead rows per call from now on, 0 .. k: the drafting call uses the first that many
+ *                      look-ahead embeddings; outputs and logits keep their k-sized layout with unused entries
+ *                      -1 / stale (the paper's sweep over the number of look-ahead tokens without reloading)
+ *   "lookahead_token"  -1 = trained look-ahead embeddings; a token id = the drafting call appends that token's
+ *                      embedding instead (the paper's second baseline with a fixed [UNK] token).  Both only
+ *                      between iterations, else PASS_ESTATE
+ *   "kernel_timing"    1 = after every model call, launch the dominant kernel, the gate/up GEMM, once per layer
+ *                      with that layer's weights on the call's rows, back to back between two HIP events on the
+ *                      context's stream, and synchronise; the launches write workspaces only; setting the option
+ *                      resets the counters pass_kernel_time reports
+ *   "prefill_chunk"    1 .. PASS_MAX_ROWS: prompt rows per pass over the weights when the prompt goes through
+ *                      the decode kernels
+ *   "prefill_tiled"    -1 = prompts of more than 2 * PASS_MAX_ROWS rows take the tiled, compute-bound prompt pass
+ *                      when the model runs on the matrix-core path with the matrix-core attention kernel,
+ *                      0 = never, 1 = every prompt does
+ * Names that start with "tune." are sweep knobs of the kernels' launch shapes for development; they are not part
+ * of this interface and may change (they are listed where pass_set_option is defined).
  * Unknown names: PASS_EINVAL. */
 int pass_set_option(pass_ctx *ctx, const char *name, int value);
 

@@ -18,7 +18,7 @@ MAX_K, MAX_ROWS = 15, 64
 
 SYMBOLS = ["pass_arena_bytes", "pass_create", "pass_load_weights", "pass_prefill", "pass_release",
            "pass_draft", "pass_verify", "pass_generate", "pass_run_iterations", "pass_kernel_time", "pass_plain_read", "pass_rng_uniforms", "pass_get_logits", "pass_seq_len",
-           "pass_set_option", "pass_time_step", "pass_last_error", "pass_destroy"]
+           "pass_set_option", "pass_attention_plan", "pass_get_tokens", "pass_time_step", "pass_last_error", "pass_destroy"]
 
 
 class PassConfig(C.Structure):
@@ -62,7 +62,7 @@ def load_library():
     global _lib
     if _lib is not None:
         return _lib
-    path = os.environ.get("PASS_HIP_LIBRARY", LIB_PATH)  # development: compare two builds in one run
+    path = LIB_PATH
     if not os.path.exists(path):
         raise FileNotFoundError(f"{path} is not built: run `python -m paper_2311_13581_amd.build` "
                                 "(there is no fallback path)")
@@ -89,6 +89,8 @@ def load_library():
     L.pass_get_logits.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_float)]
     L.pass_seq_len.argtypes = [C.c_void_p, C.c_int, ip, ip]
     L.pass_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int]
+    L.pass_get_tokens.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, ip]
+    L.pass_attention_plan.argtypes = [C.c_int, C.c_int, ip, ip, ip]
     L.pass_time_step.argtypes = [C.c_void_p, ip, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double)]
     L.pass_last_error.restype = C.c_char_p
     L.pass_last_error.argtypes = [C.c_void_p]
@@ -245,6 +247,11 @@ class Pass:
         out = np.empty((self.k + 1, self.vocab), dtype=np.float32)
         self._check(self.lib.pass_get_logits(self.h, slot, which, out.ctypes.data_as(C.POINTER(C.c_float))))
         return out
+
+    def get_tokens(self, slot: int, first: int, n: int) -> np.ndarray:
+        out = np.empty(max(1, n), dtype=np.int32)
+        self._check(self.lib.pass_get_tokens(self.h, slot, first, n, _ip(out)))
+        return out[:n]
 
     def seq_len(self, slot: int):
         a, b = C.c_int32(0), C.c_int32(0)

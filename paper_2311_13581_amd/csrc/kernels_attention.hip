@@ -83,8 +83,9 @@ __global__ __launch_bounds__(256) void attn_split_kernel(Params p, int layer, in
   const int b = g / groups_per_slot;
   const int r0 = (g % groups_per_slot) * RQ;
   const int nr = min(RQ, R - r0);
-  const int slot = p.step_slots[b];
-  const int pos0 = p.kv_len[slot] + r0;  // position of the group's first row
+  const int slot = p.row_slot[b * R + r0];
+  if (slot < 0) return;  // dead rows (beyond the slot's capacity): the merge kernel writes zeros
+  const int pos0 = p.row_pos[b * R + r0];  // position of the group's first row
   const int n_keys = pos0 + nr;
   int n_splits, chunk;
   split_plan(n_keys, n_splits, chunk);
@@ -388,6 +389,7 @@ __global__ __launch_bounds__(HD * Q) void attn_combine_kernel(Params p, int R, i
   constexpr int RQ = kAttnRowsPerGroup;
   const int b = m / R, r = m % R, r0 = (r / RQ) * RQ;
   const int pos0 = p.row_pos[b * R + r0];  // position of the group's first row
+  const bool dead = p.row_slot[m] < 0;     // no split kernel ran for this row: its output is zero
   const size_t pi = ((size_t)m * p.H + head) * kMaxSplits;
   const int s_begin = (Q == 1) ? 0 : q * 8;
   float pm[8], pl[8], pa[8];
@@ -434,7 +436,7 @@ __global__ __launch_bounds__(HD * Q) void attn_combine_kernel(Params p, int R, i
       v += sv[i][dim] * f;
     }
   }
-  float o = v / l_n;
+  float o = dead ? 0.f : v / l_n;
   if (OUT == 1) {
     // (hi, lo) pair in the tiled activation layout of the matrix-core GEMMs
     uint16_t hi = f32_to_bf16(o);

@@ -17,16 +17,17 @@ __global__ __launch_bounds__(256) void assemble_kernel(Params p, const T *tok_em
   int m = blockIdx.x, b = m / R, r = m % R;
   int slot = p.step_slots[b];
   int pos = p.kv_len[slot] + r;
+  const bool dead = row_is_dead(p, mode, slot, R);
   const T *src;
   if (mode == MODE_PREFILL) {
     src = tok_emb + (size_t)p.prefill_ids[r] * p.d;
   } else if (r == 0) {
-    src = tok_emb + (size_t)p.pending[slot] * p.d;
+    src = tok_emb + (size_t)clamp_token(p, p.pending[slot]) * p.d;
   } else if (mode == MODE_DRAFT) {
     // look-ahead embedding r (Section 2.2.1), or the fixed token of the paper's second baseline
     src = p.la_token >= 0 ? tok_emb + (size_t)p.la_token * p.d : lookahead + (size_t)(r - 1) * p.d;
   } else {
-    src = tok_emb + (size_t)p.drafts[slot * kMaxK + (r - 1)] * p.d;
+    src = tok_emb + (size_t)clamp_token(p, p.drafts[slot * kMaxK + (r - 1)]) * p.d;
   }
   float *dst = p.h + (size_t)m * p.d;
   for (int i = threadIdx.x; i < p.d; i += blockDim.x) dst[i] = load_f(src, i);
@@ -38,8 +39,8 @@ __global__ __launch_bounds__(256) void assemble_kernel(Params p, const T *tok_em
     p.rope_sin[(size_t)m * half + i] = (float)sn;
   }
   if (threadIdx.x == 0) {
-    p.row_pos[m] = pos;
-    p.row_slot[m] = slot;
+    p.row_pos[m] = dead ? 0 : pos;
+    p.row_slot[m] = dead ? -1 : slot;
     p.row_out[m] = slot * (1 + p.k) + r;
   }
 }
@@ -169,6 +170,7 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(Params p, int layer) {
     float q0 = q[e], q1 = q[e + 1];
     q[e] = q0 * cs - q1 * sn;
     q[e + 1] = q0 * sn + q1 * cs;
+    if (slot < 0) continue;  // a dead row (see row_is_dead) has no place in the cache
     float k0 = kk[e], k1 = kk[e + 1];
     size_t off = kv_offset(p, layer, slot, pos, h) + 2 * i;
     store_f(kpool, off, k0 * cs - k1 * sn);

@@ -84,16 +84,17 @@ __global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint
   int m = blockIdx.x, b = m / R, r = m % R;
   int slot = p.step_slots[b];
   int pos = p.kv_len[slot] + r;
+  const bool dead = row_is_dead(p, mode, slot, R);
   const uint16_t *src;
   if (mode == MODE_PREFILL) {
     src = tok_emb + (size_t)p.prefill_ids[r] * p.d;
   } else if (r == 0) {
-    src = tok_emb + (size_t)p.pending[slot] * p.d;
+    src = tok_emb + (size_t)clamp_token(p, p.pending[slot]) * p.d;
   } else if (mode == MODE_DRAFT) {
     // look-ahead embedding r (Section 2.2.1), or the fixed token of the paper's second baseline
     src = p.la_token >= 0 ? tok_emb + (size_t)p.la_token * p.d : lookahead + (size_t)(r - 1) * p.d;
   } else {
-    src = tok_emb + (size_t)p.drafts[slot * kMaxK + (r - 1)] * p.d;
+    src = tok_emb + (size_t)clamp_token(p, p.drafts[slot * kMaxK + (r - 1)]) * p.d;
   }
   // eight consecutive features per thread and trip: one 16-byte load of the embedding row and of
   // the gain, two 16-byte stores of h, one 16-byte store each of the hi and the lo tile slots
@@ -137,8 +138,8 @@ __global__ __launch_bounds__(256) void assemble_mfma_kernel(Params p, const uint
     p.rope_sin[(size_t)m * half + i] = (float)sn;
   }
   if (threadIdx.x == 0 && row_tables) {
-    p.row_pos[m] = pos;
-    p.row_slot[m] = slot;
+    p.row_pos[m] = dead ? 0 : pos;
+    p.row_slot[m] = dead ? -1 : slot;
     p.row_out[m] = slot * (1 + p.k) + r;
   }
 }
@@ -399,7 +400,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
         }
         if (which == 0) {
           *(floatx4 *)(p.qkv + (size_t)m * 3 * p.D + c) = v;
-        } else {
+        } else if (p.row_slot[m] >= 0) {  // a dead row (see row_is_dead) has no place in the cache
           // the cache is bf16 storage: the one place besides the weights where values are rounded
           uint16_t *pool = (uint16_t *)(which == 1 ? p.k_pool : p.v_pool);
           if (which == 2 && p.v_transposed) {
@@ -423,34 +424,40 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
   }
 }
 
-// Launch shape of the decode-sized GEMMs (one 8-row group): wavefronts per workgroup and k-tiles
-// per trip, per epilogue kind.  Defaults chosen by sweeping the benchmark on MI355X; the "gemm_cfg"
-// option of the library overrides them (value = kind * 10000 + wavefronts * 100 + unroll).
-static int g_cfg_waves[5] = {0, 0, 4, 16, 0};  // QKV, Wo, gate/up, LM head, down; 0 = by strip count (below)
-static int g_cfg_unroll[5] = {1, 1, 1, 2, 1};
-// Calls with more than 8 rows: wavefronts and output blocks per workgroup
-// (override: 1000000 + kind * 10000 + wavefronts * 100 + blocks).  Such a call is bound by what
-// one compute unit can pull through its vector memory path, and every workgroup pulls all M
-// activation rows whatever it owns of the weights: best is one workgroup per compute unit with
-// as many blocks as that leaves it (QKV: 768 strips = 256 x 3; gate/up: 688 pairs = 230 x 3).
-static int g_big_waves[5] = {8, 16, 4, 8, 16};
-static int g_big_blocks[5] = {0, 1, 0, 4, 1};  // 0 = as many as leave one workgroup per compute unit
+// Launch shape of the decode-sized GEMMs: GemmTuning (a member of the context, so two contexts
+// never share a setting).  Defaults chosen by sweeping the benchmark on MI355X.
+GemmTuning::GemmTuning()
+    : waves{0, 0, 4, 16, 0},       // QKV, Wo, gate/up, LM head, down; 0 = by strip count (launch_gemm_epi)
+      unroll{1, 1, 1, 2, 1},
+      // Calls with more than 8 rows are bound by what one compute unit can pull through its vector
+      // memory path, and every workgroup pulls all M activation rows whatever it owns of the
+      // weights: best is one workgroup per compute unit with as many blocks as that leaves it
+      // (QKV: 768 strips = 256 x 3; gate/up: 688 pairs = 230 x 3).
+      big_waves{8, 16, 4, 8, 16},
+      big_blocks{0, 1, 0, 4, 1},   // 0 = as many as leave one workgroup per compute unit
+      split_ks(4) {}
 
-int set_gemm_config(int kind, int waves, int unroll) {
+int GemmTuning::set(int kind, int w, int u) {
   if (kind < 0 || kind > 4) return -1;
-  if (waves != 4 && waves != 8 && waves != 16) return -1;
-  if (unroll != 1 && unroll != 2 && unroll != 4) return -1;
-  g_cfg_waves[kind] = waves;
-  g_cfg_unroll[kind] = unroll;
+  if (w != 4 && w != 8 && w != 16) return -1;
+  if (u != 1 && u != 2 && u != 4) return -1;
+  waves[kind] = w;
+  unroll[kind] = u;
   return 0;
 }
 
-int set_gemm_config_big(int kind, int waves, int blocks) {
+int GemmTuning::set_big(int kind, int w, int blocks) {
   if (kind < 0 || kind > 4) return -1;
-  if (waves != 4 && waves != 8 && waves != 16) return -1;
+  if (w != 4 && w != 8 && w != 16) return -1;
   if (blocks < 0 || blocks > 4) return -1;
-  g_big_waves[kind] = waves;
-  g_big_blocks[kind] = blocks;
+  big_waves[kind] = w;
+  big_blocks[kind] = blocks;
+  return 0;
+}
+
+int GemmTuning::set_split(int ks) {
+  if (ks < 0 || ks > 8) return -1;
+  split_ks = ks;
   return 0;
 }
 
@@ -481,7 +488,8 @@ static void launch_big(const Params &p, const GemmArgs &a, int n_blocks, int mt,
 }
 
 template <int EPI>
-static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hipStream_t s, int kind = EPI) {
+static void launch_gemm_epi(const Params &p, const GemmTuning &tn, const GemmArgs &a, int n_strips, hipStream_t s,
+                            int kind = EPI) {
   constexpr int PER = (EPI == EPI_GATEUP) ? 2 : 1;
   const int n_blocks = n_strips / PER;
   int mt = (a.M + 7) / 8;
@@ -491,8 +499,8 @@ static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hi
     // (d = 4096: 768 and 256 strips) coarse workgroups are best (8 and 16 wavefronts); otherwise
     // (d = 5120: 960 and 320 strips) finer ones, of which a unit holds several, balance better.
     const bool even = n_blocks % 256 == 0;
-    const int w = g_cfg_waves[kind] ? g_cfg_waves[kind] : (kind == 0 ? (even ? 8 : 4) : (even ? 16 : 8));
-    const int u = g_cfg_unroll[kind];
+    const int w = tn.waves[kind] ? tn.waves[kind] : (kind == 0 ? (even ? 8 : 4) : (even ? 16 : 8));
+    const int u = tn.unroll[kind];
     switch (w * 10 + u) {
       case 161: launch_one<EPI, 16, 1>(p, a, grid, s); break;
       case 162: launch_one<EPI, 16, 2>(p, a, grid, s); break;
@@ -506,7 +514,7 @@ static void launch_gemm_epi(const Params &p, const GemmArgs &a, int n_strips, hi
     }
     return;
   }
-  int w = g_big_waves[kind], nb = g_big_blocks[kind];
+  int w = tn.big_waves[kind], nb = tn.big_blocks[kind];
   if (nb == 0) nb = std::min(PER == 2 ? 3 : 4, (n_blocks + 255) / 256);  // 7B: QKV 768 / 256 = 3, gate/up 688 pairs -> 3
   if (mt == 8 && nb == 4) nb = 2;                 // 64 rows x 4 blocks does not fit the register file
   if (nb == 3 && mt * PER > 10) nb = 2;           // nor do 3 blocks of more than 40 rows (gate/up) / 80
@@ -565,18 +573,11 @@ __global__ __launch_bounds__(256) void resid_reduce_kernel(Params p, const float
   if ((threadIdx.x & 3) == 0) p.ssq[(size_t)strip * kMaxRows + m] = ss;  // rows >= M get 0
 }
 
-// wavefronts per workgroup, strips per workgroup and K slices of the split residual GEMM
+// wavefronts per workgroup and strips per workgroup of the split residual GEMM (K slices: GemmTuning)
 constexpr int kSplitWaves = 8, kSplitBlocks = 4;
-static int g_split_ks = 4;  // override: gemm_cfg 2000000 + slices (0 = never split)
 
-int set_gemm_split(int ks) {
-  if (ks < 0 || ks > 8) return -1;
-  g_split_ks = ks;
-  return 0;
-}
-
-static bool launch_resid_split(const Params &p, const GemmArgs &a0, int mt, hipStream_t s) {
-  const int n_strips = p.d / 16, KT = a0.K >> 5, KS = g_split_ks;
+static bool launch_resid_split(const Params &p, const GemmTuning &tn, const GemmArgs &a0, int mt, hipStream_t s) {
+  const int n_strips = p.d / 16, KT = a0.K >> 5, KS = tn.split_ks;
   if (KS < 2 || n_strips % kSplitBlocks != 0 || KT % KS != 0) return false;
   if ((size_t)KS * p.d > (size_t)2 * p.F) return false;  // the slices' sums borrow the generic path's gate/up workspace
   GemmArgs a = a0;
@@ -597,23 +598,23 @@ static bool launch_resid_split(const Params &p, const GemmArgs &a0, int mt, hipS
   return true;
 }
 
-void launch_gemm_qkv(const Params &p, const void *W, int layer, int M, hipStream_t s) {
+void launch_gemm_qkv(const Params &p, const GemmTuning &tn, const void *W, int layer, int M, hipStream_t s) {
   GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, layer, nullptr, nullptr, 0, nullptr, 3 * p.D / 16};
-  launch_gemm_epi<EPI_QKV>(p, a, 3 * p.D / 16, s);
+  launch_gemm_epi<EPI_QKV>(p, tn, a, 3 * p.D / 16, s);
 }
-void launch_gemm_resid(const Params &p, const void *W, const uint16_t *X, int K, const void *gain_next, int M,
-                       hipStream_t s) {
+void launch_gemm_resid(const Params &p, const GemmTuning &tn, const void *W, const uint16_t *X, int K,
+                       const void *gain_next, int M, hipStream_t s) {
   GemmArgs a{(const u32x4 *)W, X, M, K, 0, (const uint16_t *)gain_next, nullptr, 0, nullptr, p.d / 16};
-  if (M > 8 && launch_resid_split(p, a, (M + 7) / 8, s)) return;
-  launch_gemm_epi<EPI_RESID>(p, a, p.d / 16, s, K == p.F ? 4 : 1);  // the down projection has its own shape
+  if (M > 8 && launch_resid_split(p, tn, a, (M + 7) / 8, s)) return;
+  launch_gemm_epi<EPI_RESID>(p, tn, a, p.d / 16, s, K == p.F ? 4 : 1);  // the down projection has its own shape
 }
-void launch_gemm_gateup(const Params &p, const void *W, int M, hipStream_t s) {
+void launch_gemm_gateup(const Params &p, const GemmTuning &tn, const void *W, int M, hipStream_t s) {
   GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, nullptr, 0, nullptr, 2 * p.F / 16};
-  launch_gemm_epi<EPI_GATEUP>(p, a, 2 * p.F / 16, s);
+  launch_gemm_epi<EPI_GATEUP>(p, tn, a, 2 * p.F / 16, s);
 }
-void launch_gemm_logits(const Params &p, const void *W, float *logits, int M, hipStream_t s) {
+void launch_gemm_logits(const Params &p, const GemmTuning &tn, const void *W, float *logits, int M, hipStream_t s) {
   GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, logits, 0, nullptr, p.V / 16};
-  launch_gemm_epi<EPI_LOGITS>(p, a, p.V / 16, s);
+  launch_gemm_epi<EPI_LOGITS>(p, tn, a, p.V / 16, s);
 }
 
 }  // namespace pass

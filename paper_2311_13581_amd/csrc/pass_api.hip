@@ -72,6 +72,7 @@ struct pass_ctx {
   typedef std::tuple<int, int, int, uint32_t, uint32_t, uint32_t, int, int, int, int> GraphKey;
   std::map<GraphKey, hipGraphExec_t> graphs;
   int opt_kernel_timing = 0;
+  GemmTuning tuning;  // launch shapes of the decode GEMMs (captured graphs carry them: cleared when it changes)
   int opt_prefill_chunk = 64;
   int opt_prefill_tiled = -1;  // -1: prompts of more than 2 * kMaxRows rows take the tiled pass; 0 never; 1 always
   Params PP;                   // P with the row buffers of the tiled prompt pass
@@ -266,11 +267,8 @@ int choose_splits(const pass_ctx *c, int B, int R, int max_keys) {
   // grid width only: each row group cuts its own keys by a rule of its own length (split_plan in
   // the attention kernel); workgroups beyond a group's split count exit at once
   (void)B; (void)R;
-  if (c->P.v_transposed) {  // the longest sequence's split count (shorter ones have no more)
-    int n_splits, chunk;
-    split_plan_mfma(std::max(1, max_keys), c->P.H, n_splits, chunk);
-    return n_splits;
-  }
+  if (c->P.v_transposed)  // the most splits any group of at most max_keys keys can have (the plan is not monotone)
+    return max_splits_mfma(std::max(1, max_keys), c->P.H);
   return std::max(1, std::min(kMaxSplits, (max_keys + 63) / 64));
 }
 
@@ -290,14 +288,14 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
     launch_assemble_mfma(P, c->tok_emb, c->lookahead, c->layers[0].attn_norm, mode, B, R, s);
     for (int l = 0; l < P.L; ++l) {
       const LayerW &w = c->layers[l];
-      launch_gemm_qkv(P, w.wqkv, l, M, s);
+      launch_gemm_qkv(P, c->tuning, w.wqkv, l, M, s);
       launch_attention(P, dt, l, B, R, S, 1, s);
-      launch_gemm_resid(P, w.wo, P.attn_x, P.D, w.ffn_norm, M, s);
-      launch_gemm_gateup(P, w.wgu, M, s);
-      launch_gemm_resid(P, w.wdown, P.act_x, P.F,
+      launch_gemm_resid(P, c->tuning, w.wo, P.attn_x, P.D, w.ffn_norm, M, s);
+      launch_gemm_gateup(P, c->tuning, w.wgu, M, s);
+      launch_gemm_resid(P, c->tuning, w.wdown, P.act_x, P.F,
                         l + 1 < P.L ? c->layers[l + 1].attn_norm : c->final_norm, M, s);
     }
-    if (logits_base) launch_gemm_logits(P, c->lm_head, logits_base, M, s);
+    if (logits_base) launch_gemm_logits(P, c->tuning, c->lm_head, logits_base, M, s);
   } else {
   launch_assemble(P, dt, c->tok_emb, c->lookahead, mode, B, R, s);
   for (int l = 0; l < P.L; ++l) {
@@ -325,7 +323,7 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
     HIP_TRY(c, hipEventRecord(c->kev[0], s));
     for (int l = 0; l < P.L; ++l) {
       if (c->use_mfma)
-        launch_gemm_gateup(P, c->layers[l].wgu, M, s);
+        launch_gemm_gateup(P, c->tuning, c->layers[l].wgu, M, s);
       else
         launch_gemm_generic(dt, P.xn, c->layers[l].wgu, P.gu, M, 2 * P.F, P.d, 2 * P.F, nullptr, 0, s);
     }
@@ -936,6 +934,29 @@ int pass_get_logits(pass_ctx *c, int slot, int which, float *out) {
   return PASS_OK;
 }
 
+int pass_get_tokens(pass_ctx *c, int slot, int first, int n, int32_t *out) {
+  if (!c) return PASS_EINVAL;
+  if (slot < 0 || slot >= c->cfg.max_slots || first < 0 || n < 0 || !out) return fail(c, PASS_EINVAL, "bad argument");
+  if (c->slots[slot].state == 0) return fail(c, PASS_ESTATE, "slot %d is empty", slot);
+  if ((int64_t)first + n > c->slots[slot].n_gen)
+    return fail(c, PASS_ECAPACITY, "slot %d has generated %d tokens", slot, c->slots[slot].n_gen);
+  if (n == 0) return PASS_OK;
+  HIP_TRY(c, hipMemcpyAsync(out, c->P.gen + (size_t)slot * c->P.gen_cap + first, sizeof(int32_t) * n,
+                            hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PASS_OK;
+}
+
+int pass_attention_plan(int n_heads, int n_keys, int *n_splits, int *chunk_keys, int *grid_splits) {
+  if (n_heads < 1 || n_keys < 1) return PASS_EINVAL;
+  int ns, ch;
+  split_plan_mfma(n_keys, n_heads, ns, ch);
+  if (n_splits) *n_splits = ns;
+  if (chunk_keys) *chunk_keys = ch;
+  if (grid_splits) *grid_splits = max_splits_mfma(n_keys, n_heads);
+  return PASS_OK;
+}
+
 int pass_seq_len(pass_ctx *c, int slot, int32_t *kv_len, int32_t *n_generated) {
   if (!c) return PASS_EINVAL;
   if (slot < 0 || slot >= c->cfg.max_slots) return fail(c, PASS_EINVAL, "slot %d out of range", slot);
@@ -948,15 +969,26 @@ int pass_seq_len(pass_ctx *c, int slot, int32_t *kv_len, int32_t *n_generated) {
 int pass_set_option(pass_ctx *c, const char *name, int value) {
   if (!c || !name) return PASS_EINVAL;
   if (!strcmp(name, "graph")) { c->opt_graph = value; return PASS_OK; }
-  if (!strcmp(name, "gemm_cfg")) {
+  // "tune.*": sweep knobs for development, not part of the stable interface (listed here only)
+  //   tune.gemm_cfg       launch shape of the decode-sized matrix-core GEMMs of this context:
+  //                       kind * 10000 + wavefronts * 100 + unroll (kind 0 QKV, 1 Wo, 2 gate/up, 3 LM head, 4 down;
+  //                       wavefronts 4/8/16; unroll 1/2/4); calls with more than 8 rows: 1000000 + kind * 10000 +
+  //                       wavefronts * 100 + blocks (strips of 16 output features per workgroup, 0..4);
+  //                       2000000 + K slices of the split residual GEMM (0 = never split)
+  //   tune.prefill_rows   prompt rows per pass of the tiled prompt pass (a multiple of 128)
+  //   tune.prefill_tile   query rows per attention workgroup of the tiled prompt pass (0, 16, 32, 128)
+  //   tune.prefill_block  tiles along the features * 100 + tiles along the rows of the block of GEMM tiles one die
+  //                       works on at a time (0 = default 8 x 8)
+  //   tune.prefill_strips strips of 16 features per wavefront in the tiled GEMMs (0 = by row count, 1, 2, 4)
+  if (!strcmp(name, "tune.gemm_cfg")) {
     if (value >= 2000000) {
-      if (set_gemm_split(value - 2000000)) return fail(c, PASS_EINVAL, "gemm_cfg (split residual GEMM): 0 .. 8 slices of K");
+      if (c->tuning.set_split(value - 2000000)) return fail(c, PASS_EINVAL, "tune.gemm_cfg (split residual GEMM): 0 .. 8 slices of K");
     } else if (value >= 1000000) {
       int v = value - 1000000;
-      if (set_gemm_config_big(v / 10000, (v / 100) % 100, v % 100))
-        return fail(c, PASS_EINVAL, "gemm_cfg (more than 8 rows): kind 0..4, wavefronts 8/16, blocks 1/2/4");
-    } else if (set_gemm_config(value / 10000, (value / 100) % 100, value % 100))
-      return fail(c, PASS_EINVAL, "gemm_cfg: kind 0..4, wavefronts 4/8/16, unroll 1/2/4");
+      if (c->tuning.set_big(v / 10000, (v / 100) % 100, v % 100))
+        return fail(c, PASS_EINVAL, "tune.gemm_cfg (more than 8 rows): kind 0..4, wavefronts 4/8/16, blocks 0..4");
+    } else if (c->tuning.set(value / 10000, (value / 100) % 100, value % 100))
+      return fail(c, PASS_EINVAL, "tune.gemm_cfg: kind 0..4, wavefronts 4/8/16, unroll 1/2/4");
     for (auto &g : c->graphs) (void)hipGraphExecDestroy(g.second);  // captured launches carry the old shape
     c->graphs.clear();
     return PASS_OK;
@@ -983,26 +1015,26 @@ int pass_set_option(pass_ctx *c, const char *name, int value) {
     c->opt_prefill_tiled = value;
     return PASS_OK;
   }
-  if (!strcmp(name, "prefill_rows")) {
+  if (!strcmp(name, "tune.prefill_rows")) {
     const int cap = std::min(kPrefillRows, (c->cfg.max_seq_len + 127) / 128 * 128);
-    if (value < 128 || value > cap || value % 128) return fail(c, PASS_EINVAL, "prefill_rows: a multiple of 128, 128 .. %d", cap);
+    if (value < 128 || value > cap || value % 128) return fail(c, PASS_EINVAL, "tune.prefill_rows: a multiple of 128, 128 .. %d", cap);
     c->pws.rows = value;
     return PASS_OK;
   }
-  if (!strcmp(name, "prefill_tile")) {
+  if (!strcmp(name, "tune.prefill_tile")) {
     // query rows of an attention workgroup of the tiled prompt pass
-    if (value != 0 && value != 16 && value != 32 && value != 128) return fail(c, PASS_EINVAL, "prefill_tile: 0 (default), 16, 32 or 128");
+    if (value != 0 && value != 16 && value != 32 && value != 128) return fail(c, PASS_EINVAL, "tune.prefill_tile: 0 (default), 16, 32 or 128");
     c->pws.attn_rows = value;
     return PASS_OK;
   }
-  if (!strcmp(name, "prefill_strips")) {
-    if (value != 0 && value != 1 && value != 2 && value != 4) return fail(c, PASS_EINVAL, "prefill_strips: 0 (by row count), 1, 2 or 4");
+  if (!strcmp(name, "tune.prefill_strips")) {
+    if (value != 0 && value != 1 && value != 2 && value != 4) return fail(c, PASS_EINVAL, "tune.prefill_strips: 0 (by row count), 1, 2 or 4");
     c->pws.resid_strips_opt = value;
     return PASS_OK;
   }
-  if (!strcmp(name, "prefill_block")) {
+  if (!strcmp(name, "tune.prefill_block")) {
     const int bn = value / 100, bm = value % 100;
-    if (value < 0 || bn > 64 || bm > 64 || (bn == 0) != (bm == 0)) return fail(c, PASS_EINVAL, "prefill_block: tiles along the features * 100 + tiles along the rows (1 .. 64 each), or 0");
+    if (value < 0 || bn > 64 || bm > 64 || (bn == 0) != (bm == 0)) return fail(c, PASS_EINVAL, "tune.prefill_block: tiles along the features * 100 + tiles along the rows (1 .. 64 each), or 0");
     c->pws.blk_n = bn;
     c->pws.blk_m = bm;
     return PASS_OK;

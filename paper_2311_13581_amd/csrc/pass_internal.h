@@ -29,6 +29,19 @@ __host__ __device__ inline void split_plan_mfma(int n_keys, int n_heads, int &n_
   chunk = per * 128;
   n_splits = (n_keys + chunk - 1) / chunk;
 }
+// The plan is not monotone in the key count: when the steps per split grow, the split count drops
+// (32 heads: 3072 keys give 24 splits, 3073 give 13).  A launch that serves row groups of several
+// lengths, or whose host only knows an upper bound of the lengths, therefore sizes its grid for the
+// largest split count any length up to that bound can have; surplus workgroups exit at once.
+inline int max_splits_mfma(int max_keys, int n_heads) {
+  int best = 1;
+  for (int steps = 1; (steps - 1) * 128 < max_keys; ++steps) {  // within one step count the last key count has most splits
+    int n_splits, chunk;
+    split_plan_mfma(steps * 128 < max_keys ? steps * 128 : max_keys, n_heads, n_splits, chunk);
+    if (n_splits > best) best = n_splits;
+  }
+  return best;
+}
 
 // bfloat16 storage type: raw bits, converted with shifts (round-to-nearest-even on store)
 struct bf16_t {
@@ -107,6 +120,19 @@ __device__ __forceinline__ size_t kv_offset(const Params &p, int layer, int slot
   return ((((size_t)layer * p.n_pages + page) * p.H + head) * p.page_size + off) * (size_t)p.hd;
 }
 
+// A slot whose rows would lie beyond max_seq_len is dead for this call: pass_generate keeps a slot
+// that has reached its token target stepping with the batch (its state is frozen, its outputs are
+// dropped), and such a slot may sit within k positions of its capacity.  Its rows take part in the
+// matrix products (rows are independent) but write no K/V, read no cache (their attention output is
+// zero) and so never index the block table past the slot's own entries.  The host never lets a
+// live slot get there (PASS_ECAPACITY first).
+__device__ __forceinline__ bool row_is_dead(const Params &p, int mode, int slot, int R) {
+  return mode != MODE_PREFILL && p.kv_len[slot] + R > p.max_seq_len;
+}
+// token ids read back from device state index the embedding table: keep them inside it whatever a
+// dead row's sampler produced
+__device__ __forceinline__ int clamp_token(const Params &p, int t) { return t < 0 ? 0 : (t >= p.V ? p.V - 1 : t); }
+
 struct SampleArgs {
   float temperature;
   uint32_t seed_lo, seed_hi;
@@ -140,10 +166,21 @@ void launch_pack_tiles(const uint16_t *src, uint16_t *dst, int N, int K, int str
                        hipStream_t s);
 void launch_assemble_mfma(const Params &p, const void *tok_emb, const void *lookahead, const void *gain0, int mode,
                           int B, int R, hipStream_t s);
-void launch_gemm_qkv(const Params &p, const void *W, int layer, int M, hipStream_t s);
-void launch_gemm_resid(const Params &p, const void *W, const uint16_t *X, int K, const void *gain_next, int M,
-                       hipStream_t s);
-void launch_gemm_gateup(const Params &p, const void *W, int M, hipStream_t s);
+// Launch shapes of the decode-sized matrix-core GEMMs, per context.  kind: 0 QKV, 1 Wo, 2 gate/up,
+// 3 LM head, 4 down.  The "tune.gemm_cfg" option writes it (see pass_set_option in pass_api.hip).
+struct GemmTuning {
+  int waves[5], unroll[5];          // calls of up to 8 rows: wavefronts per workgroup (0 = by strip count), k-tiles per trip
+  int big_waves[5], big_blocks[5];  // calls with more than 8 rows: wavefronts and output blocks per workgroup
+  int split_ks;                     // K slices of the split residual GEMMs (0 = never split)
+  GemmTuning();
+  int set(int kind, int w, int u);            // wavefronts 4/8/16, k-tiles per trip 1/2/4; -1 = rejected
+  int set_big(int kind, int w, int blocks);   // wavefronts 4/8/16, blocks 0..4
+  int set_split(int ks);                      // 0..8
+};
+void launch_gemm_qkv(const Params &p, const GemmTuning &tn, const void *W, int layer, int M, hipStream_t s);
+void launch_gemm_resid(const Params &p, const GemmTuning &tn, const void *W, const uint16_t *X, int K,
+                       const void *gain_next, int M, hipStream_t s);
+void launch_gemm_gateup(const Params &p, const GemmTuning &tn, const void *W, int M, hipStream_t s);
 // (hi, lo) activation buffers of the matrix-core path, K features per row, tiled like the MFMA B
 // operand: [m / 8][K / 32][64 lanes][8 features]; lane = (k / 8 % 4) * 16 + m % 8 for the hi half,
 // 8 lanes further for the lo half.  Element index of the hi half of feature k of row m:
@@ -186,9 +223,6 @@ void launch_prefill_resid(const Params &p, const PrefillWs &w, const void *W, co
 void launch_prefill_gateup(const Params &p, const PrefillWs &w, const void *W, int M, hipStream_t s);
 int prefill_resid_strips(const Params &p, int M);
 
-int set_gemm_config_big(int kind, int waves, int blocks);  // calls with more than 8 rows
-int set_gemm_split(int ks);  // K slices of the split residual GEMMs (0 = never split)
-int set_gemm_config(int kind, int waves, int unroll);  // kind: 0 QKV, 1 Wo, 2 gate/up, 3 LM head, 4 down
-void launch_gemm_logits(const Params &p, const void *W, float *logits, int M, hipStream_t s);
+void launch_gemm_logits(const Params &p, const GemmTuning &tn, const void *W, float *logits, int M, hipStream_t s);
 
 }  // namespace pass

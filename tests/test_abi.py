@@ -42,3 +42,28 @@ def test_struct_layouts_match_header_sizes():
     assert C.sizeof(binding.PassSampling) == 16
     assert C.sizeof(binding.PassStats) == 48
     assert C.sizeof(binding.PassWeights) == 13 * 8
+
+
+def test_attention_grid_covers_every_shorter_group():
+    """The split plan of the matrix-core attention is not monotone in the key count (32 heads: 3072 keys
+    give 24 splits, 3073 give 13).  A launch serves groups of several lengths and, in the pipelined
+    loop, only knows an upper bound of them: its grid must be at least as wide as the plan of every
+    length up to that bound, and the plan itself must cover all keys with at most 32 splits."""
+    lib = binding.load_library()
+    ns, ch, grid = C.c_int32(), C.c_int32(), C.c_int32()
+    for heads in (1, 4, 8, 32, 40, 64):
+        widest = 0
+        plans = []
+        for n in range(1, 16500):
+            assert lib.pass_attention_plan(heads, n, C.byref(ns), C.byref(ch), C.byref(grid)) == 0
+            assert 1 <= ns.value <= 32 and ch.value % 128 == 0
+            assert (ns.value - 1) * ch.value < n <= ns.value * ch.value  # every key in exactly one split, none empty
+            widest = max(widest, ns.value)
+            assert grid.value == widest, (heads, n)  # the running maximum: no shorter group has more splits
+            plans.append(ns.value)
+        if heads == 32:
+            assert plans[3072 - 1] == 24 and plans[3073 - 1] == 13  # the drop the grid width must survive
+        if heads == 40:
+            assert plans[2432 - 1] == 19 and plans[2433 - 1] == 10
+    assert lib.pass_attention_plan(0, 5, None, None, None) == -1
+    assert lib.pass_attention_plan(4, 0, None, None, None) == -1

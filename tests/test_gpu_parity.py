@@ -338,8 +338,8 @@ def test_tiled_prompt_pass(plen, attn_rows, rows, strips, block):
     m = O.Model(w.shape, W, w.k)
     prompt = np.random.default_rng(plen).integers(0, w.shape.vocab, plen).astype(np.int32)
     g = _gpu(w.shape, W, w.k, max_seq_len=384, page_size=64,
-             options={"prefill_tiled": 1, "prefill_tile": attn_rows, "prefill_rows": rows, "prefill_strips": strips,
-                      "prefill_block": block})
+             options={"prefill_tiled": 1, "tune.prefill_tile": attn_rows, "tune.prefill_rows": rows, "tune.prefill_strips": strips,
+                      "tune.prefill_block": block})
     st = parity.stepwise_parity(g, m, 0, 2, prompt, 3, 0.9, 777, parity.LOGIT_TOL[synth.BF16], max_len=384)
     print(st)
     assert st.iterations == 3 and st.resyncs == 0 and st.max_rel_err < 1e-3
