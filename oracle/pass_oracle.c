@@ -555,7 +555,13 @@ int orc_forward(orc_seq *s, int R, const int32_t *ids, const int32_t *la, int po
 /* PaSS loop (Algorithm 1)                                                                     */
 /* ------------------------------------------------------------------------------------------ */
 
-/* Cache K/V of prompt[0..n-2]; prompt[n-1] becomes the pending token. */
+/* Optional observer of long prompt passes (tests print a progress line from it): called after
+ * every chunk of rows with (rows done, rows in all).  No part of the computation. */
+static void (*g_progress)(int, int) = NULL;
+void orc_set_progress(void (*cb)(int, int)) { g_progress = cb; }
+
+/* Cache K/V of prompt[0..n-2]; prompt[n-1] becomes the pending token.  The rows go through the
+ * model 32 at a time (rows are independent of what shares their call: pinned bit for bit). */
 int orc_prefill(orc_seq *s, const int32_t *prompt, int n) {
   if (!s || !prompt || n < 1) return ORC_EINVAL;
   if (n - 1 + 1 + s->m->c.k > s->max_len) return ORC_ECAPACITY;
@@ -567,6 +573,7 @@ int orc_prefill(orc_seq *s, const int32_t *prompt, int n) {
     int rc = orc_forward(s, R, prompt + done, la, done, NULL);
     if (rc) return rc;
     done += R;
+    if (g_progress) g_progress(done, n - 1);
   }
   s->kv_len = n - 1;
   s->pending = prompt[n - 1];

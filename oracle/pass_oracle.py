@@ -50,6 +50,15 @@ class Ctr(C.Structure):
 
 
 _lib = None
+_PROGRESS = C.CFUNCTYPE(None, C.c_int, C.c_int)
+_progress_keep = None
+
+
+def set_progress(fn):
+    """fn(rows_done, rows_total) is called after every chunk of a prompt pass; None switches it off."""
+    global _progress_keep
+    _progress_keep = _PROGRESS(fn) if fn else _PROGRESS(0)
+    lib().orc_set_progress(_progress_keep)
 
 
 def lib():
@@ -94,6 +103,8 @@ def lib():
         L.orc_seq_set_pending.argtypes = [C.c_void_p, C.c_int32]
         L.orc_seq_set_draft.argtypes = [C.c_void_p, ip, fp]
         L.orc_seq_copy_state.argtypes = [C.c_void_p, C.c_void_p]
+        L.orc_set_progress.restype = None
+        L.orc_set_progress.argtypes = [_PROGRESS]
     return _lib
 
 

@@ -25,3 +25,26 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture(autouse=True)
+def _oracle_progress(request, capsys):
+    """The oracle's prompt pass over thousands of rows at 7B / 13B width takes minutes on the host
+    cores: print a line every 20 s past pytest's capture, so that a watcher sees the run is alive."""
+    if "gpu" not in request.keywords:
+        yield
+        return
+    import time
+
+    import pass_oracle as O
+    last = [time.time()]
+
+    def tick(done, total):
+        if time.time() - last[0] >= 20.0:
+            last[0] = time.time()
+            with capsys.disabled():
+                print(f"\n[{request.node.name}] oracle prompt pass {done}/{total} rows", flush=True)
+
+    O.set_progress(tick)
+    yield
+    O.set_progress(None)

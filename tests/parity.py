@@ -44,14 +44,10 @@ class StepStats:
                 f"accepted={self.accepted} resyncs={self.resyncs} max_rel_err={self.max_rel_err:.2e}")
 
 
-def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st, top_k=0):
-    """One draft + verify on both sides.  Returns (tokens the oracle added, in_sync)."""
-    k = getattr(gpu, "k_act", gpu.k)  # look-ahead rows of this call (buffers are sized for gpu.k)
+def _check_draft(st, it, k, temp, seed, seq_id, tol, top_k, ol, gl, o_first, o_drafts, g_first, g_drafts):
+    """Drafting call of one sequence: logits within tolerance, every stable decision identical.
+    Returns (all decisions identical, largest absolute logit difference)."""
     inv_t = 1.0 if temp == 0 else 1.0 / temp
-    kv0 = oseq.kv_len
-    o_first, o_drafts = oseq.draft(temp, seed, top_k=top_k)
-    g_first, g_drafts = gpu.draft([slot], temp, seed, top_k)
-    ol, gl = oseq.logits(0), gpu.get_logits(slot, 0)[:k + 1]
     err_d = logits_error(gl, ol, tol, f"draft it={it}")
     st.max_rel_err = max(st.max_rel_err, err_d / np.abs(ol).max())
     tau = err_d * inv_t * 1.01 + (0.0 if temp == 0 else F32_ARITH)
@@ -59,7 +55,7 @@ def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st, top_k=0):
     for t in range(k + 1):
         tok, stable = O.sample_softmax(ol[t], temp, seed, seq_id, it, t, O.DRAFT, tau, top_k)
         o_tok = o_first if t == 0 else o_drafts[t - 1]
-        g_tok = g_first[0] if t == 0 else g_drafts[0, t - 1]
+        g_tok = g_first if t == 0 else g_drafts[t - 1]
         assert tok == o_tok
         st.compared += 1
         if stable:
@@ -67,13 +63,13 @@ def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st, top_k=0):
         else:
             st.unstable += 1
             same &= g_tok == tok
-    assert gpu.seq_len(slot)[0] == kv0 + 1 == oseq.kv_len
-    o_a, o_out = oseq.verify(temp, seed, top_k=top_k)
-    added = [o_first] + [int(x) for x in o_out]
-    if not same:
-        return added, False
-    g_a, g_out = gpu.verify([slot], temp, seed, top_k)
-    pl, gpl = oseq.logits(1), gpu.get_logits(slot, 1)[:k + 1]
+    return same, err_d
+
+
+def _check_verify(st, it, k, temp, seed, seq_id, tol, top_k, ol, pl, gpl, err_d, o_drafts, o_a, o_out, g_a, g_out):
+    """Validation call of one sequence (g_out: the slot's k + 1 output entries).  Returns whether
+    the two sides took the same decisions (a difference on a stable decision fails)."""
+    inv_t = 1.0 if temp == 0 else 1.0 / temp
     err_v = logits_error(gpl, pl, tol, f"verify it={it}")
     st.max_rel_err = max(st.max_rel_err, err_v / np.abs(pl).max())
     tau = max(err_d, err_v) * inv_t * 1.01 + (0.0 if temp == 0 else F32_ARITH)
@@ -90,40 +86,114 @@ def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st, top_k=0):
         a += 1
     assert a == o_a
     if chain_stable:
-        assert g_a[0] == a, f"verify it={it}: gpu accepted {g_a[0]}, oracle {a}"
-    elif g_a[0] != a:
-        return added, False
+        assert g_a == a, f"verify it={it}: gpu accepted {g_a}, oracle {a}"
+    elif g_a != a:
+        return False
     if a < k:
         y, stable, _ = O.sample_residual(pl[a], ol[a + 1], temp, seed, seq_id, it, a + 1, tau, top_k)
     else:
         y, stable = O.sample_softmax(pl[k], temp, seed, seq_id, it, k + 1, O.BONUS, tau, top_k)
     assert y == o_out[-1]
     st.compared += 1
-    assert np.array_equal(g_out[0, :a], o_out[:a])
+    assert np.array_equal(g_out[:a], o_out[:a])
     if stable:
-        assert g_out[0, a] == y, f"verify it={it}: final token gpu {g_out[0, a]} != oracle {y} (a={a})"
+        assert g_out[a] == y, f"verify it={it}: final token gpu {g_out[a]} != oracle {y} (a={a})"
     else:
         st.unstable += 1
-        if g_out[0, a] != y:
-            return added, False
-    assert np.all(g_out[0, a + 1:] == -1)
-    assert gpu.seq_len(slot)[0] == kv0 + 2 + a == oseq.kv_len
+        if g_out[a] != y:
+            return False
+    assert np.all(g_out[a + 1:] == -1)
     st.accepted += a
+    return True
+
+
+def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st, top_k=0):
+    """One draft + verify on both sides.  Returns (tokens the oracle added, in_sync)."""
+    k = getattr(gpu, "k_act", gpu.k)  # look-ahead rows of this call (buffers are sized for gpu.k)
+    kv0 = oseq.kv_len
+    o_first, o_drafts = oseq.draft(temp, seed, top_k=top_k)
+    g_first, g_drafts = gpu.draft([slot], temp, seed, top_k)
+    ol, gl = oseq.logits(0), gpu.get_logits(slot, 0)[:k + 1]
+    same, err_d = _check_draft(st, it, k, temp, seed, seq_id, tol, top_k, ol, gl, o_first, o_drafts,
+                               g_first[0], g_drafts[0])
+    assert gpu.seq_len(slot)[0] == kv0 + 1 == oseq.kv_len
+    o_a, o_out = oseq.verify(temp, seed, top_k=top_k)
+    added = [o_first] + [int(x) for x in o_out]
+    if not same:
+        return added, False
+    g_a, g_out = gpu.verify([slot], temp, seed, top_k)
+    pl, gpl = oseq.logits(1), gpu.get_logits(slot, 1)[:k + 1]
+    if not _check_verify(st, it, k, temp, seed, seq_id, tol, top_k, ol, pl, gpl, err_d, o_drafts, o_a, o_out,
+                         int(g_a[0]), g_out[0]):
+        return added, False
+    assert gpu.seq_len(slot)[0] == kv0 + 2 + o_a == oseq.kv_len
     return added, True
 
 
+def batch_parity(gpu, omodel, slots, seq_ids, prompts, sampled, n_iters, temp, seed, tol, max_len, top_k=0):
+    """A batch of slots through draft / verify calls that carry every slot (the launch shapes of the
+    batch), with the sequences of the `sampled` slots run alone through the oracle: a sequence's
+    result does not depend on what shares its calls.  Every call's logits and decisions of the
+    sampled slots are compared as in stepwise_parity.  A sampled slot that parts ways on an
+    unstable decision is dropped from the comparison from then on (counted in `resyncs`).
+    Returns {slot: StepStats}."""
+    k = getattr(gpu, "k_act", gpu.k)
+    for sl, sid, p in zip(slots, seq_ids, prompts):
+        gpu.prefill(sl, p, seq_id=sid)
+    oseqs, stats, live = {}, {}, set(sampled)
+    for sl in sampled:
+        i = list(slots).index(sl)
+        oseqs[sl] = omodel.sequence(max_len, seq_id=seq_ids[i])
+        oseqs[sl].prefill(prompts[i])
+        stats[sl] = StepStats()
+    for it in range(n_iters):
+        g_first, g_drafts = gpu.draft(slots, temp, seed, top_k)
+        g_kv = {sl: gpu.seq_len(sl)[0] for sl in live}
+        pend = {}
+        for sl in sorted(live):
+            i, o, st = list(slots).index(sl), oseqs[sl], stats[sl]
+            kv0 = o.kv_len
+            o_first, o_drafts = o.draft(temp, seed, top_k=top_k)
+            ol, gl = o.logits(0), gpu.get_logits(sl, 0)[:k + 1]
+            same, err_d = _check_draft(st, it, k, temp, seed, seq_ids[i], tol, top_k, ol, gl, o_first, o_drafts,
+                                       g_first[i], g_drafts[i])
+            assert g_kv[sl] == kv0 + 1 == o.kv_len
+            o_a, o_out = o.verify(temp, seed, top_k=top_k)
+            pend[sl] = (same, err_d, ol, o_drafts, o_a, o_out, kv0)
+        g_a, g_out = gpu.verify(slots, temp, seed, top_k)
+        for sl in sorted(live):
+            i, o, st = list(slots).index(sl), oseqs[sl], stats[sl]
+            same, err_d, ol, o_drafts, o_a, o_out, kv0 = pend[sl]
+            st.iterations += 1
+            if same:
+                pl, gpl = o.logits(1), gpu.get_logits(sl, 1)[:k + 1]
+                same = _check_verify(st, it, k, temp, seed, seq_ids[i], tol, top_k, ol, pl, gpl, err_d, o_drafts,
+                                     o_a, o_out, int(g_a[i]), g_out[i])
+            if same:
+                assert gpu.seq_len(sl)[0] == kv0 + 2 + o_a == o.kv_len
+            else:
+                st.resyncs += 1
+                live.discard(sl)
+    return stats
+
+
 def stepwise_parity(gpu, omodel, slot, seq_id, prompt, n_iters, temp, seed, tol, max_len=256, stats=None,
-                    top_k=0):
+                    top_k=0, first_oseq=None):
     """Drive one sequence through draft / verify on both sides, comparing the logits of every
     call and every decision.  A difference on a stable decision fails.  When an unstable decision
-    differs, both sides restart from the oracle's token history (a resync, counted)."""
+    differs, both sides restart from the oracle's token history (a resync, counted).
+    first_oseq: an oracle sequence that already holds the prompt (same sequence id), used instead
+    of a fresh prompt pass of the oracle for the first round."""
     st = stats or StepStats()
     hist = [int(t) for t in prompt]
     done = 0
     while done < n_iters:
         gpu.prefill(slot, hist, seq_id=seq_id)
-        oseq = omodel.sequence(max_len, seq_id=seq_id)
-        oseq.prefill(hist)
+        if first_oseq is not None:
+            oseq, first_oseq = first_oseq, None
+        else:
+            oseq = omodel.sequence(max_len, seq_id=seq_id)
+            oseq.prefill(hist)
         it = 0
         while done < n_iters:
             added, in_sync = _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st, top_k)

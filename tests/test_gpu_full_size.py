@@ -27,26 +27,6 @@ def _gpu_dev(w, k, max_slots, max_seq_len, page_size=64):
     return g
 
 
-def test_7b_full_depth_short_context_vs_oracle():
-    """Configuration 2's model at full depth (32 layers, 13.2 GB of bf16 weights shared byte for byte
-    with the oracle), 9-token prompt, k = 4: logits of both calls and all decisions."""
-    from paper_2311_13581_amd import binding
-    w = synth.WORKLOADS["7b_k4_greedy"]
-    t0 = time.time()
-    W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
-    print("weights generated in %.0f s" % (time.time() - t0), flush=True)
-    g = binding.Pass(binding.make_config(w.shape, w.k, 1, 64, 64))
-    g.load_weights(W)
-    m = O.Model(w.shape, W, w.k)
-    prompt = synth.make_prompts(w)[0][:9]
-    t0 = time.time()
-    st = parity.stepwise_parity(g, m, 0, 0, prompt, 1, 0.0, synth.sampling_seed(w), parity.LOGIT_TOL[synth.BF16],
-                                max_len=64)
-    print(st, "oracle+gpu %.0f s" % (time.time() - t0), flush=True)
-    assert st.iterations == 1
-    g.close()
-
-
 @pytest.mark.parametrize("tiled", [1, 0], ids=["tiled-prompt-pass", "chunked-prompt-pass"])
 def test_long_context_single_layer_vs_oracle(tiled):
     """One 7B-shaped layer, 1100-token prompt (18 pages, several attention splits), k = 4,
@@ -124,7 +104,7 @@ def test_config3_lookahead_sweep_is_deterministic_and_flat():
         lat[k] = (st["draft_ms"] + st["verify_ms"]) / (2 * st["iterations"])
         g.close()
     print("call latency by k (ms):", {k: round(v, 3) for k, v in lat.items()}, flush=True)
-    assert lat[4] < 1.5 * lat[0]
+    assert lat[4] < 1.15 * lat[0]  # Section 2.2: a (1+k)-row call costs about what a one-row call costs (measured: 1.00 - 1.02)
 
 
 def test_config4_ragged_batch_matches_single_slot_runs():

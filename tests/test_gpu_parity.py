@@ -494,6 +494,94 @@ def test_attention_splits_of_several_steps():
     g.close()
 
 
+MANY_HEADS = synth.ModelShape(1, 256, 64, 128, 512, 512, dtype=synth.BF16)  # 64 heads: 12 steps x 64 = 768 workgroups
+
+
+def test_split_plan_breakpoint_inside_the_pipelined_loop():
+    """With 64 heads the split plan drops from 12 splits (1536 keys) to 7 (1537 keys).  A sequence
+    that crosses that length inside pass_run_iterations, where the host sizes the grid for an upper
+    bound of the length (up to k + 2 keys too many), must still get every split its own plan asks
+    for: greedy tokens against the oracle's, then the logits of one more synchronised iteration."""
+    shape, k = MANY_HEADS, 4
+    W = synth.make_weights(shape, 61, k, 10.0)
+    m = O.Model(shape, W, k)
+    prompt = np.random.default_rng(3).integers(0, shape.vocab, 1528).astype(np.int32)
+    g = _gpu(shape, W, k, max_seq_len=1664, page_size=64)
+    g.prefill(0, prompt, seq_id=8)
+    st = g.run_iterations([0], 8, 0.0, 17)
+    kv, ng = g.seq_len(0)
+    assert kv > 1536 + k + 2 and ng == st["tokens_out"]  # the sequence is past the breakpoint
+    toks = g.get_tokens(0, 0, ng)
+    s = m.sequence(1664, seq_id=8)
+    s.prefill(prompt)
+    ref, acc, stable = s.generate(ng, 0.0, 17, tau=1e-3 * 40)
+    n_same = parity.generate_parity(toks, ref, acc, stable)
+    print("identical prefix", n_same, "of", ng, "stable", stable)
+    assert n_same == ng
+    hist = list(prompt) + [int(t) for t in toks]
+    st2 = parity.stepwise_parity(g, m, 0, 8, np.array(hist[:1540], np.int32), 2, 0.0, 17, parity.LOGIT_TOL[synth.BF16],
+                                 max_len=1664)
+    print(st2)
+    assert st2.iterations == 2 and st2.max_rel_err < 1e-3
+    g.close()
+
+
+def test_split_plan_breakpoint_inside_one_batch():
+    """Two slots either side of the breakpoint in one call (1530 and 1545 cached keys with 64 heads:
+    12 and 7 splits): the grid must be as wide as the shorter sequence's plan.  Both slots against
+    the oracle, every call."""
+    shape, k = MANY_HEADS, 4
+    W = synth.make_weights(shape, 61, k, 10.0)
+    m = O.Model(shape, W, k)
+    prompts = [np.random.default_rng(30 + i).integers(0, shape.vocab, n).astype(np.int32) for i, n in enumerate((1531, 1546))]
+    g = _gpu(shape, W, k, max_slots=2, max_seq_len=1664, page_size=64)
+    stats = parity.batch_parity(g, m, [0, 1], [3, 4], prompts, [0, 1], 2, 0.9, 23, parity.LOGIT_TOL[synth.BF16], max_len=1664)
+    for sl in (0, 1):
+        print(sl, stats[sl])
+        assert stats[sl].iterations == 2 and stats[sl].max_rel_err < 1e-3 and stats[sl].resyncs == 0
+    g.close()
+
+
+@pytest.mark.parametrize("which,seed,len0", [("fp32", 2, 40), ("mfma", 5, 228)], ids=["fp32", "mfma"])
+def test_finished_slot_at_its_capacity_does_not_touch_its_neighbours(which, seed, len0):
+    """pass_generate keeps a slot that has reached its token target stepping with the batch.  In
+    these seeded runs (found with the oracle) slot 0 reaches 24 tokens two iterations before slot 1
+    and ends within k positions of max_seq_len: its rows then lie beyond its capacity and must
+    neither write K/V (its block-table row ends there; the next entries are slot 1's pages) nor
+    read any.  Both slots' tokens equal their single-slot runs and the oracle's."""
+    k, n_new, temp = 4, 24, 1.5
+    w = synth.scaled(TINY if which == "fp32" else MFMA_HD128, k=k)
+    page = 64 if w.shape.head_dim == 128 else 16
+    cap = 4 * page
+    W = synth.make_weights(w.shape, 29, k, 3.0)
+    rng = np.random.default_rng(2)
+    p0 = rng.integers(0, w.shape.vocab, cap).astype(np.int32)[:len0]
+    p1 = rng.integers(0, w.shape.vocab, 20).astype(np.int32)
+    g = _gpu(w.shape, W, k, max_slots=2, max_seq_len=cap, page_size=page)
+    single, iters, kv_end = {}, {}, {}
+    for slot, p, sid in ((0, p0, 1), (1, p1, 2)):
+        g.prefill(slot, p, seq_id=sid)
+        toks, st = g.generate([slot], n_new, temp, seed)
+        single[slot], iters[slot], kv_end[slot] = toks[0], st["iterations"], g.seq_len(slot)[0]
+    # the scenario: slot 0 is finished, beyond its capacity, while slot 1 still runs
+    assert iters[0] < iters[1] and kv_end[0] + 1 + k > cap, (iters, kv_end)
+    g.prefill(0, p0, seq_id=1)
+    g.prefill(1, p1, seq_id=2)
+    both, st = g.generate([0, 1], n_new, temp, seed)
+    assert st["iterations"] == iters[0] + iters[1]
+    assert np.array_equal(both[0], single[0]) and np.array_equal(both[1], single[1])
+    assert g.seq_len(0)[0] == kv_end[0] and g.seq_len(1)[0] == kv_end[1]
+    m = O.Model(w.shape, W, k)
+    tau = (2e-2 * 40 if w.shape.dtype == synth.BF16 else 1e-4 * 40) / temp + parity.F32_ARITH
+    for slot, p, sid in ((0, p0, 1), (1, p1, 2)):
+        s = m.sequence(cap + 8, seq_id=sid)
+        s.prefill(p)
+        ref, acc, stable = s.generate(n_new, temp, seed, tau=tau)
+        n_same = parity.generate_parity(both[slot], ref, acc, stable)
+        print(which, "slot", slot, "identical prefix", n_same, "stable", stable.all())
+    g.close()
+
+
 @pytest.mark.parametrize("w", [TINY, MFMA_HD128], ids=["fp32", "mfma"])
 def test_maximum_lookahead_count(w):
     """k = 15 (the most the interface takes): 16 rows per call, so the attention kernels see two

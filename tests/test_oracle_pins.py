@@ -235,6 +235,41 @@ def test_forward_matches_library_composition(shape, scale):
     assert np.abs(ref).max() > 0.1  # the comparison is not vacuous
 
 
+@pytest.mark.parametrize("dtype", [synth.F32, synth.BF16], ids=["fp32", "bf16"])
+def test_prompt_pass_across_chunk_boundaries_matches_library_composition(dtype):
+    """orc_prefill takes the prompt through the model 32 rows at a time: a 70-token prompt (two full
+    chunks and a ragged one) followed by a drafting call gives the logits of the full-sequence
+    recomputation from torch library routines; a sequence that takes over the cache of another
+    (orc_seq_copy_state, the look-ahead sweep's shortcut) continues bit for bit like it."""
+    shape = synth.ModelShape(2, 64, 4, 16, 96, 40, dtype=dtype)
+    k = 3
+    m, W = _model(shape, 33, k, 4.0, std=0.1)
+    prompt = np.random.default_rng(6).integers(0, shape.vocab, 70).astype(np.int32)
+    seen = []
+    O.set_progress(lambda done, total: seen.append((done, total)))
+    try:
+        s = m.sequence(96, seq_id=3)
+        s.prefill(prompt)
+    finally:
+        O.set_progress(None)
+    assert seen == [(32, 69), (64, 69), (69, 69)]
+    assert s.kv_len == 69 and s.pending == prompt[-1]
+    s2 = O.Model(shape, W, 2).sequence(80, seq_id=3)  # a model with another number of look-ahead rows
+    s2.copy_state_from(s)
+    s3 = m.sequence(96, seq_id=3)
+    s3.copy_state_from(s)
+    s.draft(0.7, 5)
+    ref = torch_ref.forward_full(shape, W, prompt, k).numpy()[-(k + 1):]
+    assert np.allclose(s.logits(0), ref, rtol=0, atol=1e-6 * np.abs(ref).max())
+    assert np.abs(ref).max() > 0.1
+    s3.draft(0.7, 5)
+    assert np.array_equal(s3.logits(0), s.logits(0))
+    assert s3.verify(0.7, 5)[0] == s.verify(0.7, 5)[0] and s3.kv_len == s.kv_len
+    s2.draft(0.7, 5)
+    ref2 = torch_ref.forward_full(shape, W, prompt, 2).numpy()[-3:]
+    assert np.allclose(s2.logits(0), ref2, rtol=0, atol=1e-6 * np.abs(ref2).max())
+
+
 def test_forward_closed_form_single_token():
     """One token at position 0: RoPE is the identity and attention over one key returns V, so the
     logits are a chain of matrix products that numpy evaluates directly."""

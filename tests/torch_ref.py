@@ -39,9 +39,9 @@ def forward_full(shape, W, ids, n_la):
         q = rope(F.linear(n1, to_t(W["wq"][l], dt)).view(T, H, hd))
         k = rope(F.linear(n1, to_t(W["wk"][l], dt)).view(T, H, hd))
         v = F.linear(n1, to_t(W["wv"][l], dt)).view(T, H, hd)
-        if dt == synth.BF16:  # the K/V cache of a bf16 model stores bf16 values
-            k = k.float().to(torch.bfloat16).double()
-            v = v.float().to(torch.bfloat16).double()
+        if dt == synth.BF16:  # the K/V cache of a bf16 model stores bf16 values (rounded once, from fp64)
+            k = k.to(torch.bfloat16).double()
+            v = v.to(torch.bfloat16).double()
         a = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None],
                                            v.transpose(0, 1)[None], is_causal=True)[0]
         x = x + F.linear(a.transpose(0, 1).reshape(T, H * hd), to_t(W["wo"][l], dt))
