@@ -207,6 +207,22 @@ def stepwise_parity(gpu, omodel, slot, seq_id, prompt, n_iters, temp, seed, tol,
     return st
 
 
+# Bounds of check_stats: about twice what the seeded runs of the test suite measure on MI355X.
+# fp32 models agree to 4e-7 of the row's largest logit; bf16 models of two or three layers to
+# 2e-4 (weights and K/V are the only rounded values: the rest is fp32 against fp64), the 7B width
+# with two layers to 5.5e-4, the 7B model at full depth to 1.3e-3.
+ERR_F32 = 2e-6
+ERR_BF16_SMALL = 4e-4
+ERR_BF16_7B_2L = 1.2e-3
+
+
+def check_stats(st, n_iters, max_err, max_unstable=2, max_resyncs=0):
+    """The run did what it was asked, and stayed as close to the oracle as such runs measure."""
+    assert st.iterations == n_iters, st
+    assert st.max_rel_err <= max_err, st
+    assert st.unstable <= max_unstable and st.resyncs <= max_resyncs, st
+
+
 def generate_parity(gpu_tokens, oracle_tokens, oracle_acc, oracle_stable):
     """Free-running comparison.  Returns the identical prefix length; a mismatch inside an
     iteration whose decisions the oracle reports stable (and with no unstable iteration before

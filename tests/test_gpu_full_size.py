@@ -42,7 +42,7 @@ def test_long_context_single_layer_vs_oracle(tiled):
     prompt = synth.make_prompts(w)[0][:1100]
     st = parity.stepwise_parity(g, m, 0, 4, prompt, 2, 0.8, 31337, parity.LOGIT_TOL[synth.BF16], max_len=1280)
     print(st, flush=True)
-    assert st.iterations == 2 and st.resyncs <= 1
+    parity.check_stats(st, 2, 4e-4, max_unstable=2)  # measured 1.1e-4 (tiled), 9.5e-5 (chunked), every decision stable
     g.close()
 
 

@@ -34,11 +34,7 @@ def test_tiny_stepwise(w, temp):
     seed = synth.sampling_seed(w)
     st = parity.stepwise_parity(g, m, 0, 7, prompt, 24, temp, seed, parity.LOGIT_TOL[w.shape.dtype])
     print(st)
-    assert st.iterations == 24
-    if w.shape.dtype == synth.F32:
-        assert st.max_rel_err < 1e-5 and st.unstable <= 1 and st.resyncs == 0
-    else:
-        assert st.resyncs <= 12
+    parity.check_stats(st, 24, parity.ERR_F32 if w.shape.dtype == synth.F32 else parity.ERR_BF16_SMALL, max_unstable=1)
     g.close()
 
 
@@ -56,7 +52,7 @@ def test_tiny_generate(w, temp):
     ref, acc, stable = s.generate(64, temp, seed, tau=tau)
     n_same = parity.generate_parity(toks[0], ref, acc, stable)
     print("identical prefix", n_same, stats)
-    assert n_same == 64 or not stable.all()
+    assert n_same == 64  # measured: all 64 tokens identical in both modes (fp32 model, margins far above 1e-4)
     assert stats["tokens_out"] == 64 and 2 * stats["iterations"] <= 64 + w.k + 1
     assert stats["drafts_proposed"] == w.k * stats["iterations"]
     kv, ng = g.seq_len(0)
@@ -73,7 +69,7 @@ def test_lookahead_counts_and_paging(k):
     prompt = np.random.default_rng(k).integers(0, w.shape.vocab, 75).astype(np.int32)
     st = parity.stepwise_parity(g, m, 0, 3, prompt, 10, 0.7, 99, 1e-4)
     print(st)
-    assert st.iterations == 10 and st.resyncs == 0
+    parity.check_stats(st, 10, parity.ERR_F32, max_unstable=1)
     g.close()
 
 
@@ -231,7 +227,7 @@ def test_mfma_path_stepwise(w, temp, path):
     prompt = synth.make_prompts(w)[0]
     st = parity.stepwise_parity(g, m, 0, 5, prompt, 16, temp, 4242, parity.LOGIT_TOL[synth.BF16])
     print(st)
-    assert st.iterations == 16 and st.resyncs <= 8
+    parity.check_stats(st, 16, parity.ERR_BF16_SMALL)
     g.close()
 
 
@@ -255,7 +251,7 @@ def test_mfma_path_batches_span_several_row_tiles():
     m = O.Model(w.shape, W, w.k)
     st = parity.stepwise_parity(g, m, 2, 2, prompts[1], 6, 0.9, 77, parity.LOGIT_TOL[synth.BF16])
     print(st, stats)
-    assert st.iterations == 6
+    parity.check_stats(st, 6, parity.ERR_BF16_SMALL)
     g.close()
 
 
@@ -271,7 +267,20 @@ def test_7b_layer_shapes_two_layers():
         st = parity.stepwise_parity(g, m, 0, 1, prompt, 2, temp, 99, parity.LOGIT_TOL[synth.BF16], max_len=128,
                                     top_k=top_k)
         print(temp, top_k, st)
-        assert st.iterations == 2
+        # greedy on a random model with a scaled LM head meets near-ties: unstable decisions are counted, and one resync was seen
+        parity.check_stats(st, 2, parity.ERR_BF16_7B_2L, max_unstable=12, max_resyncs=2)
+    # The paper's own implementation runs all in bfloat16.  The oracle's variant that also rounds the
+    # activations between matrix products (normalised rows, q, attention output, gated FFN rows) is
+    # not the reference here, but the HIP path must stay within the bf16 tolerance of it too.
+    mb = O.Model(w.shape, W, w.k, act_bf16=True)
+    sb = mb.sequence(128, seq_id=1)
+    sb.prefill(prompt)
+    sb.draft(0.0, 99)
+    g.prefill(0, prompt, seq_id=1)
+    g.draft([0], 0.0, 99)
+    err = parity.logits_error(g.get_logits(0, 0), sb.logits(0), parity.LOGIT_TOL[synth.BF16], "all-bf16-activation oracle")
+    print("against the oracle with bf16 activations: max |diff| %.3e of max |logit| %.3e" % (err, np.abs(sb.logits(0)).max()))
+    g.verify([0], 0.0, 99)
     g.close()
 
 
@@ -287,7 +296,7 @@ def test_graph_replay_equals_eager_launches():
     for graph in (1, 0):
         g = _gpu(w.shape, W, w.k, max_slots=2, options={"graph": graph})
         st = parity.stepwise_parity(g, m, 0, 9, prompt, 8, 1.0, 4242, parity.LOGIT_TOL[synth.BF16])
-        assert st.iterations == 8 and st.resyncs == 0
+        parity.check_stats(st, 8, parity.ERR_BF16_SMALL)
         toks = []
         for rep in range(3):  # same sequence three times: replays after replays
             g.prefill(1, prompt[:33], seq_id=rep)
@@ -315,7 +324,7 @@ def test_matrix_core_attention(temp, plen):
         g = _gpu(w.shape, W, w.k, max_seq_len=384, page_size=64, options={"attention": attn})
         st = parity.stepwise_parity(g, m, 0, 2, prompt, 6, temp, 777, parity.LOGIT_TOL[synth.BF16], max_len=384)
         print(attn, st)
-        assert st.iterations == 6 and st.resyncs == 0 and st.max_rel_err < 1e-3
+        parity.check_stats(st, 6, parity.ERR_BF16_SMALL)
         g.close()
 
 
@@ -342,7 +351,7 @@ def test_tiled_prompt_pass(plen, attn_rows, rows, strips, block):
                       "tune.prefill_block": block})
     st = parity.stepwise_parity(g, m, 0, 2, prompt, 3, 0.9, 777, parity.LOGIT_TOL[synth.BF16], max_len=384)
     print(st)
-    assert st.iterations == 3 and st.resyncs == 0 and st.max_rel_err < 1e-3
+    parity.check_stats(st, 3, parity.ERR_BF16_SMALL)
     g.close()
 
 
@@ -378,9 +387,8 @@ def test_top_k_sampling_stepwise(w, top_k):
     prompt = synth.make_prompts(w)[0]
     st = parity.stepwise_parity(g, m, 0, 5, prompt, 16, 0.8, 4242, parity.LOGIT_TOL[w.shape.dtype], top_k=top_k)
     print(top_k, st)
-    assert st.iterations == 16
-    if w.shape.dtype == synth.F32:
-        assert st.resyncs == 0 and st.unstable <= 2
+    # a top-k boundary adds decisions that sit near a tie by construction (measured: up to 5 unstable on the bf16 models)
+    parity.check_stats(st, 16, (parity.ERR_F32 if w.shape.dtype == synth.F32 else parity.ERR_BF16_SMALL), max_unstable=2 if w.shape.dtype == synth.F32 else 10)
     g.close()
 
 
@@ -434,7 +442,7 @@ def test_lookahead_rows_change_at_run_time():
         m = O.Model(w.shape, W, k_act)
         st = parity.stepwise_parity(g, m, 0, 2, prompt, 8, 0.9, 321, 1e-4)
         print(k_act, st)
-        assert st.iterations == 8 and st.resyncs == 0
+        parity.check_stats(st, 8, parity.ERR_F32, max_unstable=1)
     g.prefill(0, prompt)
     g.draft([0], 0.0, 1)
     with pytest.raises(binding.PassError) as e:   # not between a drafting and a validation call
@@ -459,7 +467,7 @@ def test_fixed_token_as_lookahead(w):
     for temp in (0.0, 1.0):
         st = parity.stepwise_parity(g, m, 0, 4, prompt, 10, temp, 77, parity.LOGIT_TOL[w.shape.dtype])
         print(temp, st)
-        assert st.iterations == 10
+        parity.check_stats(st, 10, (parity.ERR_F32 if w.shape.dtype == synth.F32 else parity.ERR_BF16_SMALL))
     g.close()
 
 
@@ -474,7 +482,7 @@ def test_attention_over_many_splits(attn):
     g = _gpu(w.shape, W, w.k, max_seq_len=1280, page_size=64, options={"attention": attn})
     st = parity.stepwise_parity(g, m, 0, 3, prompt, 3, 0.9, 31, parity.LOGIT_TOL[synth.BF16], max_len=1280)
     print(attn, st)
-    assert st.iterations == 3 and st.max_rel_err < 1e-3
+    parity.check_stats(st, 3, parity.ERR_BF16_SMALL)
     g.close()
 
 
@@ -490,7 +498,7 @@ def test_attention_splits_of_several_steps():
     g = _gpu(shape, W, 2, max_seq_len=3328, page_size=64)
     st = parity.stepwise_parity(g, m, 0, 1, prompt, 3, 0.9, 4711, parity.LOGIT_TOL[synth.BF16], max_len=3328)
     print(st)
-    assert st.iterations == 3 and st.max_rel_err < 1e-3
+    parity.check_stats(st, 3, parity.ERR_BF16_SMALL)
     g.close()
 
 
@@ -522,7 +530,7 @@ def test_split_plan_breakpoint_inside_the_pipelined_loop():
     st2 = parity.stepwise_parity(g, m, 0, 8, np.array(hist[:1540], np.int32), 2, 0.0, 17, parity.LOGIT_TOL[synth.BF16],
                                  max_len=1664)
     print(st2)
-    assert st2.iterations == 2 and st2.max_rel_err < 1e-3
+    parity.check_stats(st2, 2, parity.ERR_BF16_SMALL)
     g.close()
 
 
@@ -538,7 +546,7 @@ def test_split_plan_breakpoint_inside_one_batch():
     stats = parity.batch_parity(g, m, [0, 1], [3, 4], prompts, [0, 1], 2, 0.9, 23, parity.LOGIT_TOL[synth.BF16], max_len=1664)
     for sl in (0, 1):
         print(sl, stats[sl])
-        assert stats[sl].iterations == 2 and stats[sl].max_rel_err < 1e-3 and stats[sl].resyncs == 0
+        parity.check_stats(stats[sl], 2, parity.ERR_BF16_SMALL)
     g.close()
 
 
@@ -592,7 +600,7 @@ def test_maximum_lookahead_count(w):
     for temp in (0.0, 1.2):
         st = parity.stepwise_parity(g, m, 0, 6, prompt, 6, temp, 2024, parity.LOGIT_TOL[w.shape.dtype], max_len=384)
         print(temp, st)
-        assert st.iterations == 6
+        parity.check_stats(st, 6, (parity.ERR_F32 if w.shape.dtype == synth.F32 else parity.ERR_BF16_SMALL))
     g.close()
 
 
@@ -615,6 +623,7 @@ def test_maximum_rows_per_call():
         parity.generate_parity(toks[i], ref, acc, stable)
     st = parity.stepwise_parity(g, m, 3, 203, prompts[3], 4, 1.0, 808, parity.LOGIT_TOL[synth.BF16])
     print(stats, st)
+    parity.check_stats(st, 4, parity.ERR_BF16_SMALL)
     with pytest.raises(Exception):  # a ninth slot does not exist
         g.prefill(8, prompts[0])
     g.close()
@@ -628,7 +637,7 @@ def test_degenerate_inputs(w):
     g, m, _ = _both(w, w.k, max_seq_len=128)
     st = parity.stepwise_parity(g, m, 0, 9, np.array([5], np.int32), 6, 0.0, 3, parity.LOGIT_TOL[w.shape.dtype],
                                 max_len=128)
-    assert st.iterations == 6
+    parity.check_stats(st, 6, (parity.ERR_F32 if w.shape.dtype == synth.F32 else parity.ERR_BF16_SMALL))
     g.prefill(0, [7], seq_id=1)
     toks, stats = g.generate([0], 0, 1.0, 1)
     assert toks.shape == (1, 0) and stats["iterations"] == 0 and g.seq_len(0) == (0, 0)
@@ -661,9 +670,9 @@ def test_page_pool_limits_and_reuse():
     g.verify([0], 0.0, 1)
     g.release(0)
     st = parity.stepwise_parity(g, m, 1, 2, short_p, 5, 0.8, 17, 1e-4, max_len=128)   # recycled pages, reversed order
-    assert st.iterations == 5 and st.resyncs == 0
+    parity.check_stats(st, 5, parity.ERR_F32, max_unstable=1)
     st = parity.stepwise_parity(g, m, 0, 3, long_p[:60], 3, 0.8, 17, 1e-4, max_len=128)
-    assert st.iterations == 3
+    parity.check_stats(st, 3, parity.ERR_F32, max_unstable=1)
     g.close()
 
 
