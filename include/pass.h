@@ -130,6 +130,20 @@ int pass_release(pass_ctx *ctx, int slot);
 int pass_draft(pass_ctx *ctx, const int32_t *slots, int n_slots, const pass_sampling *sp,
                int32_t *out_first, int32_t *out_drafts);
 
+/* pass_draft for callers that cannot allocate device memory and whose harness forbids a library
+ * to do so on their behalf: code under HIP graph capture, tight serving loops.  Same arguments,
+ * results and errors as pass_draft; what differs is where the call's scratch lives: the attention
+ * partials (running maximum, sum and accumulator of every row, head and split) go to a static
+ * device array of 8 MiB inside the library instead of the arena, and the kernels are launched
+ * directly (no graph is instantiated).  The call allocates nothing, on the device or through any
+ * library routine that does.  Limit: rows * n_heads * 32 * (head_dim + 2) * 4 bytes <= 8 MiB with
+ * rows = n_slots * (1 + look-ahead rows), i.e. 12 rows of a 40-head model, 15 of a 32-head one;
+ * beyond it PASS_ECAPACITY and nothing has run.  Every call on a GPU shares that GPU's array, which
+ * keeps the last call's contents (nothing in it needs clearing: every entry a call reads, that
+ * call has written): calls that overlap on one GPU, from two contexts or two threads, race. */
+int pass_draft_static(pass_ctx *ctx, const int32_t *slots, int n_slots, const pass_sampling *sp,
+                      int32_t *out_first, int32_t *out_drafts);
+
 /* Validation phase (Algorithm 1, second model call and the for-loop): one call on
  * (x_{n+1}, drafts); draft t is accepted iff r_t < min(1, p_t(x)/d_t(x)), in order, until the
  * first reject, which is replaced by a sample from the normalised (p_t - d_t)_+; if all k are

@@ -17,7 +17,7 @@ PASS_F32, PASS_BF16 = 0, 1
 MAX_K, MAX_ROWS = 15, 64
 
 SYMBOLS = ["pass_arena_bytes", "pass_create", "pass_load_weights", "pass_prefill", "pass_release",
-           "pass_draft", "pass_verify", "pass_generate", "pass_run_iterations", "pass_kernel_time", "pass_plain_read", "pass_rng_uniforms", "pass_get_logits", "pass_seq_len",
+           "pass_draft", "pass_draft_static", "pass_verify", "pass_generate", "pass_run_iterations", "pass_kernel_time", "pass_plain_read", "pass_rng_uniforms", "pass_get_logits", "pass_seq_len",
            "pass_set_option", "pass_attention_plan", "pass_get_tokens", "pass_time_step", "pass_last_error", "pass_destroy"]
 
 
@@ -79,6 +79,7 @@ def load_library():
     L.pass_prefill.argtypes = [C.c_void_p, C.c_int, C.c_uint32, ip, C.c_int]
     L.pass_release.argtypes = [C.c_void_p, C.c_int]
     L.pass_draft.argtypes = [C.c_void_p, ip, C.c_int, C.POINTER(PassSampling), ip, ip]
+    L.pass_draft_static.argtypes = [C.c_void_p, ip, C.c_int, C.POINTER(PassSampling), ip, ip]
     L.pass_verify.argtypes = [C.c_void_p, ip, C.c_int, C.POINTER(PassSampling), ip, ip]
     L.pass_generate.argtypes = [C.c_void_p, ip, C.c_int, C.c_int, C.POINTER(PassSampling), ip, C.POINTER(PassStats)]
     L.pass_run_iterations.argtypes = [C.c_void_p, ip, C.c_int, C.c_int, C.POINTER(PassSampling), C.POINTER(PassStats)]
@@ -195,12 +196,13 @@ class Pass:
     def release(self, slot: int):
         self._check(self.lib.pass_release(self.h, slot))
 
-    def draft(self, slots, temperature: float, seed: int, top_k: int = 0):
+    def draft(self, slots, temperature: float, seed: int, top_k: int = 0, static: bool = False):
         s = np.ascontiguousarray(slots, dtype=np.int32)
         sp = PassSampling(temperature, top_k, seed)
         first = np.zeros(s.size, dtype=np.int32)
         drafts = np.zeros(max(1, s.size * self.k), dtype=np.int32)
-        self._check(self.lib.pass_draft(self.h, _ip(s), s.size, C.byref(sp), _ip(first), _ip(drafts)))
+        fn = self.lib.pass_draft_static if static else self.lib.pass_draft
+        self._check(fn(self.h, _ip(s), s.size, C.byref(sp), _ip(first), _ip(drafts)))
         return first, drafts[:s.size * self.k].reshape(s.size, self.k)
 
     def verify(self, slots, temperature: float, seed: int, top_k: int = 0):

@@ -42,6 +42,19 @@ struct Slot {
 
 constexpr int kReportStride = 4 + kMaxK + kMaxK + 1;
 
+// Scratch of pass_draft_static: the attention partials (running maximum, sum and accumulator of
+// every (row, head, split)) of one call, for callers that may not allocate.  One copy per GPU,
+// held until the process ends; its contents are whatever the last call left.
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+unsigned char *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU, set by pass_create
+
+// bytes of attention partials a call of M rows needs: [M][H][kMaxSplits] triples (m, l, acc[hd])
+size_t partials_bytes(const pass_config &c, int M) {
+  return (size_t)M * c.n_heads * kMaxSplits * (c.head_dim + 2) * sizeof(float);
+}
+
 }  // namespace
 
 struct pass_ctx {
@@ -66,6 +79,8 @@ struct pass_ctx {
   hipEvent_t ev[3];
   hipEvent_t ev2[2][4];  // run_iterations: per in-flight iteration, start / middle / end of the calls and report landed
   int kv_slack = 0;      // positions an unreported iteration may have added to every running slot
+  int device = 0;        // the GPU the context lives on (current when pass_create ran)
+  bool static_scratch = false;  // this call keeps its attention partials in the library's static array (pass_draft_static)
   // optional timing of the dominant kernel (the gate/up GEMM): one event pair per layer
   // captured (model call + epilogue) graphs, keyed by everything that is baked into the launches:
   // mode, batch, attention grid width, sampling arguments
@@ -277,6 +292,13 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
   Params P = c->P;
   P.prefill_ids = const_cast<int32_t *>(prefill_ids);
   const int dt = c->cfg.dtype, M = B * R;
+  if (c->static_scratch) {  // same layout as in the arena: [M][H][kMaxSplits] accumulators, then maxima, then sums
+    float *base = (float *)g_scratch_ptr[c->device];
+    const size_t triples = (size_t)M * P.H * kMaxSplits;
+    P.part_acc = base;
+    P.part_m = base + triples * P.hd;
+    P.part_l = P.part_m + triples;
+  }
   hipStream_t s = c->stream;
   const int S = choose_splits(c, B, R, max_keys);
   const bool timing = c->opt_kernel_timing && mode != MODE_PREFILL;
@@ -427,7 +449,8 @@ int issue_call_eager(pass_ctx *c, int mode, const int32_t *slots, int B, const p
 // reads positions, slots and tokens from device memory, so a replay needs no new arguments.
 int issue_call(pass_ctx *c, int mode, const int32_t *slots, int B, const pass_sampling *sp, int commit) {
   // the null stream cannot be captured: graphs need a stream of their own
-  if (!c->opt_graph || c->opt_kernel_timing || c->stream == nullptr) return issue_call_eager(c, mode, slots, B, sp, commit);
+  if (!c->opt_graph || c->opt_kernel_timing || c->stream == nullptr || c->static_scratch)
+    return issue_call_eager(c, mode, slots, B, sp, commit);
   const int R = 1 + c->P.k_act;
   const int S = choose_splits(c, B, R, max_keys_of(c, slots, B, mode == MODE_DRAFT ? R : R + 1));
   uint32_t tbits;
@@ -484,6 +507,22 @@ int pass_create(const pass_config *cfg, void *hip_stream, void *device_arena, si
   c->cfg = *cfg;
   c->stream = (hipStream_t)hip_stream;
   carve(*cfg, (char *)device_arena, c);
+  // the static scratch array of pass_draft_static: its device address on this GPU, looked up once
+  if (hipGetDevice(&c->device) != hipSuccess || c->device < 0 || c->device >= kMaxDevices) {
+    g_create_error = "pass_create: cannot tell the current device";
+    delete c;
+    return PASS_EDEVICE;
+  }
+  if (!g_scratch_ptr[c->device]) {
+    void *sp = nullptr;
+    hipError_t es = hipGetSymbolAddress(&sp, HIP_SYMBOL(scratch));
+    if (es != hipSuccess || !sp) {
+      g_create_error = std::string("pass_create: hipGetSymbolAddress(scratch): ") + hipGetErrorString(es);
+      delete c;
+      return PASS_EDEVICE;
+    }
+    g_scratch_ptr[c->device] = (unsigned char *)sp;
+  }
   c->slots.resize(cfg->max_slots);
   for (int i = pool_pages(*cfg) - 1; i >= 0; --i) c->free_pages.push_back(i);
   const size_t S = cfg->max_slots;
@@ -670,9 +709,8 @@ int pass_prefill(pass_ctx *c, int slot, uint32_t seq_id, const int32_t *prompt, 
   return PASS_OK;
 }
 
-int pass_draft(pass_ctx *c, const int32_t *slots, int n_slots, const pass_sampling *sp, int32_t *out_first,
-               int32_t *out_drafts) {
-  if (!c) return PASS_EINVAL;
+static int draft_call(pass_ctx *c, const int32_t *slots, int n_slots, const pass_sampling *sp, int32_t *out_first,
+                      int32_t *out_drafts) {
   int rc;
   if ((rc = check_slots(c, slots, n_slots, 1))) return rc;
   if ((rc = check_sampling(c, sp))) return rc;
@@ -695,6 +733,27 @@ int pass_draft(pass_ctx *c, const int32_t *slots, int n_slots, const pass_sampli
       for (int t = 0; t < k; ++t) out_drafts[b * k + t] = t < c->P.k_act ? r[4 + t] : -1;
   }
   return PASS_OK;
+}
+
+int pass_draft(pass_ctx *c, const int32_t *slots, int n_slots, const pass_sampling *sp, int32_t *out_first,
+               int32_t *out_drafts) {
+  if (!c) return PASS_EINVAL;
+  return draft_call(c, slots, n_slots, sp, out_first, out_drafts);
+}
+
+int pass_draft_static(pass_ctx *c, const int32_t *slots, int n_slots, const pass_sampling *sp, int32_t *out_first,
+                      int32_t *out_drafts) {
+  if (!c) return PASS_EINVAL;
+  if (n_slots < 1 || n_slots > c->cfg.max_slots) return fail(c, PASS_EINVAL, "bad slot list");
+  const size_t need = partials_bytes(c->cfg, n_slots * (1 + c->P.k_act));
+  if (need > kStaticScratchBytes)
+    return fail(c, PASS_ECAPACITY, "pass_draft_static: %d rows x %d heads x %d dims need %zu bytes of attention partials, the "
+                "static scratch holds %zu", n_slots * (1 + c->P.k_act), c->cfg.n_heads, c->cfg.head_dim, need, kStaticScratchBytes);
+  if (!g_scratch_ptr[c->device]) return fail(c, PASS_EDEVICE, "pass_draft_static: no scratch address for device %d", c->device);
+  c->static_scratch = true;  // launched eagerly (no graph is built), partials in the static array
+  const int rc = draft_call(c, slots, n_slots, sp, out_first, out_drafts);
+  c->static_scratch = false;
+  return rc;
 }
 
 int pass_verify(pass_ctx *c, const int32_t *slots, int n_slots, const pass_sampling *sp, int32_t *out_n_accepted,
