@@ -784,6 +784,104 @@ int pass_verify(pass_ctx *c, const int32_t *slots, int n_slots, const pass_sampl
   return PASS_OK;
 }
 
+// Algorithm 1's loop, pipelined: iteration i + 1 is issued before the report of iteration i (36 ints per
+// slot, stored by a small kernel straight into pinned host memory) has been read, so the device never
+// waits for the host.  Until a report lands the host only knows an upper bound of every sequence's
+// length (an iteration adds at most k + 2 positions): pages are provided and the attention grid is
+// sized for that bound; the exact lengths live on the device.
+// target < 0: exactly n_iters iterations.  target >= 0: until every slot has made `target` tokens
+// since start[b]; the next iteration is issued blind only while some slot needs it even if the
+// iteration in flight yields all k + 2 tokens, otherwise the report is read first, so no iteration
+// runs that Algorithm 1 would not run.  Slots that have reached the target are frozen on the device.
+static int run_pipeline(pass_ctx *c, const int32_t *slots, int n_slots, int n_iters, int target, const int *start,
+                        const pass_sampling *sp, pass_stats &st) {
+  const int k = c->cfg.k;
+  const size_t rep_ints = (size_t)c->cfg.max_slots * kReportStride;
+  const int grow = c->P.k_act + 2;
+  auto retire = [&](int par) -> int {
+    HIP_TRY(c, hipEventSynchronize(c->ev2[par][3]));
+    float ms_d = 0, ms_v = 0;
+    HIP_TRY(c, hipEventElapsedTime(&ms_d, c->ev2[par][0], c->ev2[par][1]));
+    HIP_TRY(c, hipEventElapsedTime(&ms_v, c->ev2[par][1], c->ev2[par][2]));
+    st.draft_ms += ms_d;
+    st.verify_ms += ms_v;
+    for (int b = 0; b < n_slots; ++b) {
+      const int32_t *r = c->report_host + par * rep_ints + b * kReportStride;
+      Slot &s = c->slots[slots[b]];
+      if (target < 0 || r[1] != s.n_gen) {  // the slot was live in this iteration (a frozen one adds nothing)
+        st.iterations += 1;
+        st.drafts_proposed += c->P.k_act;
+        st.drafts_accepted += r[2];
+      }
+      if (target < 0) st.tokens_out += r[1] - s.n_gen;
+      s.kv_len = r[0];
+      s.n_gen = r[1];
+    }
+    return PASS_OK;
+  };
+  int pending = -1;  // parity of the iteration whose report has not been read, or -1
+  auto loop = [&]() -> int {
+    for (int it = 0; target >= 0 || it < n_iters; ++it) {
+      const int par = it & 1;
+      int rc2;
+      if (target >= 0) {
+        bool all_done = true, certain = false;
+        for (int b = 0; b < n_slots; ++b) {
+          const int made = c->slots[slots[b]].n_gen - start[b];
+          all_done &= made >= target;
+          certain |= made + (pending >= 0 ? grow : 0) < target;
+        }
+        if (pending >= 0 && !certain) {  // the iteration in flight may be the last: look before going on
+          const int was = pending;
+          pending = -1;
+          if ((rc2 = retire(was))) return rc2;
+          --it;
+          continue;
+        }
+        if (pending < 0 && all_done) return PASS_OK;
+      }
+      bool again = false;
+      for (int b = 0; b < n_slots; ++b) {
+        Slot &s = c->slots[slots[b]];
+        const bool done = target >= 0 && s.n_gen - start[b] >= target;  // frozen on the device: needs no room
+        if (!done && pending >= 0 && s.kv_len + grow + 2 + k > c->cfg.max_seq_len) {  // the bound no longer fits: use exact lengths
+          const int was = pending;
+          pending = -1;
+          if ((rc2 = retire(was))) return rc2;
+          again = target >= 0;  // the report may have finished the slot, or all of them
+          if (again) break;
+        }
+        const int ub = s.kv_len + (!done && pending >= 0 ? grow : 0);  // a finished slot's length is exact and stays
+        if (!done && ub + 2 + k > c->cfg.max_seq_len) return fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]);
+        // rows of a finished slot beyond its capacity are dead (row_is_dead): pages up to the capacity suffice
+        if ((rc2 = ensure_pages(c, slots[b], std::min(ub + (done ? 1 : 2) + k, c->cfg.max_seq_len)))) return rc2;
+      }
+      if (again) { --it; continue; }
+      c->kv_slack = pending >= 0 ? grow : 0;
+      HIP_TRY(c, hipEventRecord(c->ev2[par][0], c->stream));
+      if ((rc2 = issue_draft(c, slots, n_slots, sp, 1))) return rc2;
+      HIP_TRY(c, hipEventRecord(c->ev2[par][1], c->stream));
+      if ((rc2 = issue_verify(c, slots, n_slots, sp, 1))) return rc2;
+      HIP_TRY(c, hipEventRecord(c->ev2[par][2], c->stream));
+      gather_report_kernel<<<1, 64, 0, c->stream>>>(c->P, n_slots, c->report_host + par * rep_ints);
+      HIP_TRY(c, hipGetLastError());
+      HIP_TRY(c, hipEventRecord(c->ev2[par][3], c->stream));
+      const int was = pending;
+      pending = par;
+      if (was >= 0 && (rc2 = retire(was))) return rc2;
+    }
+    return PASS_OK;
+  };
+  int rc = loop();
+  // whatever happened, leave the host's view of the slots exact
+  if (pending >= 0) {
+    int rc2 = retire(pending);
+    if (!rc) rc = rc2;
+  }
+  c->kv_slack = 0;
+  return rc;
+}
+
 int pass_generate(pass_ctx *c, const int32_t *slots, int n_slots, int max_new, const pass_sampling *sp,
                   int32_t *out_tokens, pass_stats *out_stats) {
   if (!c) return PASS_EINVAL;
@@ -805,54 +903,20 @@ int pass_generate(pass_ctx *c, const int32_t *slots, int n_slots, int max_new, c
   }
   if ((rc = poke(c, ptrs, vals))) return rc;
   if ((rc = set_step_slots(c, slots, n_slots))) return rc;
-  auto finish = [&](int code) {
-    for (int b = 0; b < n_slots; ++b) { ptrs.push_back(c->P.gen_limit + slots[b]); vals.push_back(INT_MAX); }
-    int r2 = poke(c, ptrs, vals);
-    (void)hipStreamSynchronize(c->stream);
-    return code ? code : r2;
-  };
-  for (;;) {
-    bool all_done = true;
+  rc = run_pipeline(c, slots, n_slots, 0, max_new, start.data(), sp, st);
+  if (!rc)
     for (int b = 0; b < n_slots; ++b) {
-      Slot &s = c->slots[slots[b]];
-      bool done = s.n_gen - start[b] >= max_new;
-      all_done &= done;
-      if (!done && s.kv_len + 2 + k > c->cfg.max_seq_len) return finish(fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]));
-      int want = std::min(s.kv_len + 2 + k, c->cfg.max_seq_len);
-      if ((rc = ensure_pages(c, slots[b], want))) return finish(rc);
+      if (max_new > 0)
+        HIP_TRY(c, hipMemcpyAsync(out_tokens + (size_t)b * max_new, c->P.gen + (size_t)slots[b] * c->P.gen_cap + start[b],
+                                  sizeof(int32_t) * max_new, hipMemcpyDeviceToHost, c->stream));
+      st.tokens_out += max_new;
     }
-    if (all_done) break;
-    HIP_TRY(c, hipEventRecord(c->ev[0], c->stream));
-    if ((rc = issue_draft(c, slots, n_slots, sp, 1))) return finish(rc);
-    HIP_TRY(c, hipEventRecord(c->ev[1], c->stream));
-    if ((rc = issue_verify(c, slots, n_slots, sp, 1))) return finish(rc);
-    HIP_TRY(c, hipEventRecord(c->ev[2], c->stream));
-    if ((rc = fetch_report(c, n_slots))) return finish(rc);
-    float ms_d = 0, ms_v = 0;
-    HIP_TRY(c, hipEventElapsedTime(&ms_d, c->ev[0], c->ev[1]));
-    HIP_TRY(c, hipEventElapsedTime(&ms_v, c->ev[1], c->ev[2]));
-    st.draft_ms += ms_d;
-    st.verify_ms += ms_v;
-    for (int b = 0; b < n_slots; ++b) {
-      const int32_t *r = c->report_host + b * kReportStride;
-      Slot &s = c->slots[slots[b]];
-      if (r[1] != s.n_gen) {  // the slot was live in this iteration
-        st.iterations += 1;
-        st.drafts_proposed += c->P.k_act;
-        st.drafts_accepted += r[2];
-      }
-      s.kv_len = r[0];
-      s.n_gen = r[1];
-    }
-  }
-  for (int b = 0; b < n_slots; ++b) {
-    if (max_new > 0)
-      HIP_TRY(c, hipMemcpyAsync(out_tokens + (size_t)b * max_new, c->P.gen + (size_t)slots[b] * c->P.gen_cap + start[b],
-                                sizeof(int32_t) * max_new, hipMemcpyDeviceToHost, c->stream));
-    st.tokens_out += max_new;
-  }
-  rc = finish(PASS_OK);
-  if (out_stats) *out_stats = st;
+  // the token targets go away with the call
+  for (int b = 0; b < n_slots; ++b) { ptrs.push_back(c->P.gen_limit + slots[b]); vals.push_back(INT_MAX); }
+  const int r2 = poke(c, ptrs, vals);
+  (void)hipStreamSynchronize(c->stream);
+  if (!rc) rc = r2;
+  if (!rc && out_stats) *out_stats = st;
   return rc;
 }
 
@@ -863,73 +927,10 @@ int pass_run_iterations(pass_ctx *c, const int32_t *slots, int n_slots, int n_it
   if ((rc = check_slots(c, slots, n_slots, 1))) return rc;
   if ((rc = check_sampling(c, sp))) return rc;
   if (n_iters < 0) return fail(c, PASS_EINVAL, "n_iters negative");
-  const int k = c->cfg.k;
   pass_stats st;
   memset(&st, 0, sizeof st);
   if ((rc = set_step_slots(c, slots, n_slots))) return rc;
-  // Iteration it + 1 is issued before the report of iteration it is read, so the device never
-  // waits for the host.  Until a report lands the host only knows an upper bound of every
-  // sequence's length (an iteration adds at most k + 2 positions): pages are provided and the
-  // attention grid is sized for that bound; the exact lengths live on the device.
-  const size_t rep_ints = (size_t)c->cfg.max_slots * kReportStride;
-  const int grow = c->P.k_act + 2;
-  auto retire = [&](int par) -> int {
-    HIP_TRY(c, hipEventSynchronize(c->ev2[par][3]));
-    float ms_d = 0, ms_v = 0;
-    HIP_TRY(c, hipEventElapsedTime(&ms_d, c->ev2[par][0], c->ev2[par][1]));
-    HIP_TRY(c, hipEventElapsedTime(&ms_v, c->ev2[par][1], c->ev2[par][2]));
-    st.draft_ms += ms_d;
-    st.verify_ms += ms_v;
-    for (int b = 0; b < n_slots; ++b) {
-      const int32_t *r = c->report_host + par * rep_ints + b * kReportStride;
-      Slot &s = c->slots[slots[b]];
-      st.iterations += 1;
-      st.drafts_proposed += c->P.k_act;
-      st.drafts_accepted += r[2];
-      st.tokens_out += r[1] - s.n_gen;
-      s.kv_len = r[0];
-      s.n_gen = r[1];
-    }
-    return PASS_OK;
-  };
-  int pending = -1;  // parity of the iteration whose report has not been read, or -1
-  auto loop = [&]() -> int {
-    for (int it = 0; it < n_iters; ++it) {
-      const int par = it & 1;
-      int rc2;
-      for (int b = 0; b < n_slots; ++b) {
-        Slot &s = c->slots[slots[b]];
-        if (pending >= 0 && s.kv_len + grow + 2 + k > c->cfg.max_seq_len) {  // the bound no longer fits: use exact lengths
-          const int was = pending;
-          pending = -1;
-          if ((rc2 = retire(was))) return rc2;
-        }
-        const int ub = s.kv_len + (pending >= 0 ? grow : 0);
-        if (ub + 2 + k > c->cfg.max_seq_len) return fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]);
-        if ((rc2 = ensure_pages(c, slots[b], ub + 2 + k))) return rc2;
-      }
-      c->kv_slack = pending >= 0 ? grow : 0;
-      HIP_TRY(c, hipEventRecord(c->ev2[par][0], c->stream));
-      if ((rc2 = issue_draft(c, slots, n_slots, sp, 1))) return rc2;
-      HIP_TRY(c, hipEventRecord(c->ev2[par][1], c->stream));
-      if ((rc2 = issue_verify(c, slots, n_slots, sp, 1))) return rc2;
-      HIP_TRY(c, hipEventRecord(c->ev2[par][2], c->stream));
-      gather_report_kernel<<<1, 64, 0, c->stream>>>(c->P, n_slots, c->report_host + par * rep_ints);
-      HIP_TRY(c, hipGetLastError());
-      HIP_TRY(c, hipEventRecord(c->ev2[par][3], c->stream));
-      const int was = pending;
-      pending = par;
-      if (was >= 0 && (rc2 = retire(was))) return rc2;
-    }
-    return PASS_OK;
-  };
-  rc = loop();
-  // whatever happened, leave the host's view of the slots exact
-  if (pending >= 0) {
-    int rc2 = retire(pending);
-    if (!rc) rc = rc2;
-  }
-  c->kv_slack = 0;
+  rc = run_pipeline(c, slots, n_slots, n_iters, -1, nullptr, sp, st);
   if (!rc && out_stats) *out_stats = st;
   return rc;
 }

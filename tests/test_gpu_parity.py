@@ -709,6 +709,59 @@ def test_run_iterations_equals_stepwise_calls(w):
     assert res[0][4] == res[1][4] and res[0][4] > 0
 
 
+@pytest.mark.parametrize("w", [TINY, MFMA_HD128], ids=["fp32", "mfma"])
+def test_generate_equals_stepwise_calls(w):
+    """pass_generate runs Algorithm 1's loop with the report of an iteration read one iteration late
+    (it issues the next one blind only while some slot needs it whatever the one in flight yields):
+    tokens, lengths and the number of iterations must be those of synchronised draft / verify
+    calls that stop each slot at its target.  High temperature (accepted drafts: uneven progress,
+    so one slot finishes first and is frozen while the other goes on); two calls in a row, the
+    second continuing after the tokens the first one made beyond its target."""
+    w = synth.scaled(w, k=3)
+    W = synth.make_weights(w.shape, 5, 3, 1.0)
+    page = 64 if w.shape.head_dim == 128 else 16
+    prompts = [np.random.default_rng(i).integers(0, w.shape.vocab, n).astype(np.int32) for i, n in enumerate((9, 58))]
+    g = _gpu(w.shape, W, 3, max_slots=2, max_seq_len=256, page_size=page)
+    for i, p in enumerate(prompts):
+        g.prefill(i, p, seq_id=50 + i)
+    out_a, st_a = g.generate([0, 1], 37, 3.0, 1234)
+    len_a = [g.seq_len(i) for i in (0, 1)]
+    out_b, st_b = g.generate([0, 1], 11, 3.0, 1234)
+    len_b = [g.seq_len(i) for i in (0, 1)]
+    all_toks = [g.get_tokens(i, 0, len_b[i][1]) for i in (0, 1)]
+    g.close()
+    # the same with synchronised calls: a slot steps while it is short of its target
+    g = _gpu(w.shape, W, 3, max_slots=2, max_seq_len=256, page_size=page)
+    for i, p in enumerate(prompts):
+        g.prefill(i, p, seq_id=50 + i)
+    toks = {0: [], 1: []}
+    iters = []
+    for target in (37, 11):
+        start = {i: len(toks[i]) for i in (0, 1)}
+        n_it = 0
+        while True:
+            live = [i for i in (0, 1) if len(toks[i]) - start[i] < target]
+            if not live:
+                break
+            first, _d = g.draft(live, 3.0, 1234)
+            a, out = g.verify(live, 3.0, 1234)
+            for j, i in enumerate(live):
+                toks[i] += [int(first[j])] + [int(t) for t in out[j, :a[j] + 1]]
+            n_it += len(live)
+        iters.append(n_it)
+        if target == 37:
+            assert [g.seq_len(i) for i in (0, 1)] == len_a
+            for i in (0, 1):
+                assert np.array_equal(out_a[i], toks[i][:37])
+    assert [g.seq_len(i) for i in (0, 1)] == len_b
+    for i in (0, 1):
+        assert np.array_equal(all_toks[i], toks[i])                      # every token, those beyond a target included
+        assert np.array_equal(out_b[i], toks[i][len_a[i][1]:len_a[i][1] + 11])  # the second call continues after them
+    assert [st_a["iterations"], st_b["iterations"]] == iters
+    assert st_a["tokens_out"] == 74 and st_a["drafts_accepted"] > 0
+    g.close()
+
+
 def test_run_iterations_stops_exactly_where_stepwise_calls_stop():
     """Near the end of a sequence's room the look-ahead bound of pass_run_iterations no longer fits
     and it falls back to exact lengths: it must run as many iterations as synchronised calls can,
