@@ -14,7 +14,8 @@
  *     (x_{n+1}, drafts), accept chain r < min(1, p/d), residual resampling from (p - d)_+,
  *     extra token when every draft is accepted.  Section 2.2 gives the two-phase structure,
  *     Section 2.2.1 the look-ahead embeddings appended after the sequence.
- *   - The verify half is the same rule as Algorithm 2 (speculative sampling, appendix).
+ *   - Algorithm 2 (appendix: speculative sampling with a separate drafting model): L sequential
+ *     single-row calls of the drafter, then the same validation call and accept / reject chain.
  *
  * Arithmetic: double precision everywhere, except where a storage format fixes the value:
  * weights are read in their storage type (fp32 or bfloat16), the K/V cache of a bfloat16 model
@@ -728,6 +729,98 @@ int orc_generate_ar(orc_seq *s, int max_new, const orc_sampling *sp, int32_t *ou
     out_tokens[i] = tok;
   }
   free(lg);
+  return ORC_OK;
+}
+
+/*
+ * One iteration of Algorithm 2 (appendix: speculative sampling with an auto-regressive target and an
+ * auto-regressive drafting model; the paper writes q for the target and p for the drafter there).
+ * `target` and `drafter` hold the same tokens (same length, same pending token x_n); L is the
+ * target model's k.
+ *   for t = 1..L: one single-row call of the drafter on the last token of (x_1..x_n, d_1..d_{t-1});
+ *                 draft d_t is sampled from its distribution (random stream: draft row t of the
+ *                 target sequence's iteration);
+ *   one call of the target on the rows (x_n, d_1..d_L): row t-1 is the target distribution for d_t;
+ *   accept d_t iff r < min(1, target_t(d_t) / drafter_t(d_t)) in order; the first reject is replaced
+ *   by a sample from the normalised (target_t - drafter_t)_+; if all L are accepted one more token is
+ *   sampled from the last row.
+ * That second half is Algorithm 1's validation phase on a draft that came from elsewhere, and it is
+ * run by the same function (orc_verify), with x_n in the place of x_{n+1}.  An iteration adds
+ * a + 1 tokens (1 .. L+1).  Afterwards both sequences again hold the same tokens: the drafter keeps
+ * the cache rows of x_n, d_1..d_a (when all L were accepted the row of d_L does not exist yet: one
+ * more single-row call makes it) and takes over the target's pending token.
+ * out_tokens: the a accepted drafts followed by the final token.  drafter_logits (may be NULL)
+ * receives the L rows of drafter logits, [L][vocab].
+ */
+int orc_sps_iteration(orc_seq *target, orc_seq *drafter, const orc_sampling *sp, double tau,
+                      int32_t *out_n_accepted, int32_t *out_tokens, float *drafter_logits) {
+  if (!target || !drafter || !sp || sp->top_k < 0 || sp->temperature < 0) return ORC_EINVAL;
+  if (target->state != 1 || drafter->state != 1) return ORC_ESTATE;
+  const int L = target->m->c.k, V = target->m->c.vocab;
+  if (drafter->m->c.vocab != V) return ORC_EINVAL;
+  if (drafter->kv_len != target->kv_len || drafter->pending != target->pending) return ORC_ESTATE;
+  if (target->kv_len + 1 + L > target->max_len || drafter->kv_len + 1 + L > drafter->max_len) return ORC_ECAPACITY;
+  const int n0 = drafter->kv_len;
+  int32_t la = 0;
+  /* drafting: L sequential single-row calls */
+  for (int t = 1; t <= L; ++t) {
+    int32_t id = drafter->pending;
+    float *row = target->draft_logits + (size_t)t * V; /* the slot orc_verify reads draft row t from */
+    int rc = orc_forward(drafter, 1, &id, &la, drafter->kv_len, row);
+    if (rc) return rc;
+    orc_ctr ctr = {sp->seed, target->seq_id, target->iteration, (uint32_t)t, ORC_DRAFT};
+    int tok = orc_sample_softmax(row, V, sp->temperature, sp->top_k, &ctr, tau, &target->draft_stable[t]);
+    target->drafts[t - 1] = tok;
+    drafter->kv_len += 1;
+    drafter->pending = tok;
+    if (drafter_logits) memcpy(drafter_logits + (size_t)(t - 1) * V, row, sizeof(float) * (size_t)V);
+  }
+  target->draft_stable[0] = 1;
+  /* validation: the target's one call on (x_n, drafts) and the accept / reject chain */
+  target->first = target->pending;
+  target->state = 2;
+  int32_t a = 0;
+  int32_t toks[ORC_MAX_K + 1];
+  int rc = orc_verify(target, sp, tau, &a, toks);
+  if (rc) return rc;
+  /* the drafter follows: rows of rejected drafts are dropped, a missing row is made */
+  if (a == L) {
+    int32_t id = drafter->pending; /* d_L (x_n itself when L = 0) */
+    rc = orc_forward(drafter, 1, &id, &la, drafter->kv_len, NULL);
+    if (rc) return rc;
+  }
+  drafter->kv_len = n0 + 1 + a;
+  drafter->pending = target->pending;
+  drafter->iteration += 1;
+  if (out_n_accepted) *out_n_accepted = a;
+  if (out_tokens) for (int t = 0; t <= a; ++t) out_tokens[t] = toks[t];
+  return ORC_OK;
+}
+
+/* Algorithm 2's while loop: iterate until at least max_new tokens exist, return the first max_new. */
+int orc_generate_sps(orc_seq *target, orc_seq *drafter, int max_new, const orc_sampling *sp, double tau,
+                     int32_t *out_tokens, int32_t *per_iter_accepted, int32_t *per_iter_stable, int max_iters,
+                     int32_t *out_iters) {
+  if (!target || !drafter || max_new < 0) return ORC_EINVAL;
+  int L = target->m->c.k, n = 0, it = 0;
+  int32_t buf[ORC_MAX_K + 1];
+  while (n < max_new) {
+    int32_t a;
+    int rc = orc_sps_iteration(target, drafter, sp, tau, &a, buf, NULL);
+    if (rc) return rc;
+    for (int i = 0; i <= a && n < max_new; ++i) out_tokens[n++] = buf[i];
+    if (it < max_iters) {
+      if (per_iter_accepted) per_iter_accepted[it] = a;
+      if (per_iter_stable) {
+        int st = target->final_stable;
+        for (int t = 1; t <= L; ++t) st &= target->draft_stable[t];
+        for (int t = 1; t <= a + 1 && t <= L; ++t) st &= target->accept_stable[t];
+        per_iter_stable[it] = st;
+      }
+    }
+    it += 1;
+  }
+  if (out_iters) *out_iters = it;
   return ORC_OK;
 }
 

@@ -103,6 +103,9 @@ def lib():
         L.orc_seq_set_pending.argtypes = [C.c_void_p, C.c_int32]
         L.orc_seq_set_draft.argtypes = [C.c_void_p, ip, fp]
         L.orc_seq_copy_state.argtypes = [C.c_void_p, C.c_void_p]
+        L.orc_sps_iteration.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(Sampling), C.c_double, ip, ip, fp]
+        L.orc_generate_sps.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.POINTER(Sampling), C.c_double, ip, ip, ip,
+                                       C.c_int, ip]
         L.orc_set_progress.restype = None
         L.orc_set_progress.argtypes = [_PROGRESS]
     return _lib
@@ -269,6 +272,30 @@ class Sequence:
         iters = C.c_int32(0)
         _check(lib().orc_generate(self.handle, max_new, C.byref(sp), tau, _ip(out), _ip(acc), _ip(stab),
                                   cap, C.byref(iters)), "generate")
+        n = iters.value
+        return out[:max_new].copy(), acc[:n].copy(), stab[:n].astype(bool)
+
+    # Algorithm 2 (two-model speculative sampling): self is the target ----------------------
+    def sps_iteration(self, drafter: "Sequence", temperature, seed, tau=0.0, top_k=0):
+        """One iteration with `drafter` (a sequence of a model with the same vocabulary holding the
+        same tokens).  Returns (accepted count, tokens added, drafter logits [k, vocab])."""
+        sp = Sampling(temperature, top_k, seed)
+        a = C.c_int32(0)
+        toks = np.zeros(self.k + 1, dtype=np.int32)
+        dl = np.zeros((max(1, self.k), self.vocab), dtype=np.float32)
+        _check(lib().orc_sps_iteration(self.handle, drafter.handle, C.byref(sp), tau, C.byref(a), _ip(toks), _fp(dl)),
+               "sps_iteration")
+        return int(a.value), toks[:a.value + 1].copy(), dl[:self.k]
+
+    def generate_sps(self, drafter: "Sequence", max_new, temperature, seed, tau=0.0, top_k=0):
+        sp = Sampling(temperature, top_k, seed)
+        out = np.zeros(max(1, max_new), dtype=np.int32)
+        cap = max_new + 2
+        acc = np.zeros(cap, dtype=np.int32)
+        stab = np.zeros(cap, dtype=np.int32)
+        iters = C.c_int32(0)
+        _check(lib().orc_generate_sps(self.handle, drafter.handle, max_new, C.byref(sp), tau, _ip(out), _ip(acc),
+                                      _ip(stab), cap, C.byref(iters)), "generate_sps")
         n = iters.value
         return out[:max_new].copy(), acc[:n].copy(), stab[:n].astype(bool)
 

@@ -679,3 +679,120 @@ def test_fixed_token_lookahead_feeds_token_rows_and_stays_lossless():
     a.prefill(prompt)
     b.prefill(prompt)
     assert np.array_equal(a.generate(40, 0.0, 3)[0], b.generate_ar(40, 0.0, 3))
+
+
+# ------------------------------------------------------------------------------------------
+# Algorithm 2 (appendix): speculative sampling with a separate drafting model
+# ------------------------------------------------------------------------------------------
+def _sps_pair(shape_t, shape_d, k, seed_t=51, seed_d=52, scale=4.0, std=0.02):
+    Wt = synth.make_weights(shape_t, seed_t, k, scale, std=std)
+    Wd = synth.make_weights(shape_d, seed_d, 1, scale, std=std)
+    return O.Model(shape_t, Wt, k), O.Model(shape_d, Wd, 0), Wt, Wd
+
+
+@pytest.mark.parametrize("k", [0, 1, 3, 5])
+def test_sps_greedy_equals_greedy_autoregressive_of_the_target(k):
+    """Greedy two-model speculative sampling is token-identical to greedy decoding of the target
+    model alone, whatever the drafting model proposes (one-hot limit of the accept rule), and both
+    sequences hold the same tokens after every iteration; an iteration adds 1 .. k+1 tokens."""
+    w = TINY
+    small = synth.ModelShape(1, 64, 2, 32, 96, w.shape.vocab, dtype=synth.F32)
+    mt, md, _, _ = _sps_pair(w.shape, small, k)
+    prompt = synth.make_prompts(w)[0]
+    t, d = mt.sequence(160, seq_id=3), md.sequence(160, seq_id=3)
+    t.prefill(prompt)
+    d.prefill(prompt)
+    toks = []
+    for _ in range(12):
+        n0 = t.kv_len
+        a, out, _dl = t.sps_iteration(d, 0.0, 7)
+        assert 0 <= a <= k and len(out) == a + 1
+        assert t.kv_len == n0 + 1 + a == d.kv_len and t.pending == d.pending == out[-1]
+        toks += [int(x) for x in out]
+    ref = mt.sequence(160, seq_id=3)
+    ref.prefill(prompt)
+    assert np.array_equal(toks, ref.generate_ar(len(toks), 0.0, 7))
+
+
+def test_sps_drafter_equal_to_target_accepts_every_draft():
+    """When the drafting model is the target model, draft t is drawn from exactly the distribution
+    row t-1 of the validation call scores it with, so every draft is accepted (r < 1): a = k in
+    every iteration.  A drafter conditioned one position off, or validation rows shifted by one,
+    would reject some."""
+    w = TINY
+    k = 4
+    W = synth.make_weights(w.shape, 9, k, 4.0)
+    mt, md = O.Model(w.shape, W, k), O.Model(w.shape, W, 0)
+    prompt = synth.make_prompts(w)[0]
+    t, d = mt.sequence(160, seq_id=1), md.sequence(160, seq_id=1)
+    t.prefill(prompt)
+    d.prefill(prompt)
+    for _ in range(6):
+        a, out, dl = t.sps_iteration(d, 0.8, 11)
+        assert a == k and len(out) == k + 1
+        # the drafter's rows are the target's rows of the same positions (same model, same context)
+        assert np.allclose(dl, t.logits(1)[:k], rtol=0, atol=1e-5)
+
+
+def test_sps_calls_feed_the_rows_algorithm_2_names():
+    """Drafter call t sees (x_1..x_n, d_1..d_{t-1}); the target call scores (x_n, d_1..d_k): logits of
+    both against the library reference on exactly those sequences, over two iterations (the second
+    starts from rolled-back caches on both sides)."""
+    shape_t = synth.ModelShape(2, 32, 2, 16, 48, 24, dtype=synth.F32)
+    shape_d = synth.ModelShape(1, 16, 1, 16, 24, 24, dtype=synth.F32)
+    k = 3
+    mt, md, Wt, Wd = _sps_pair(shape_t, shape_d, k, scale=3.0, std=0.1)
+    hist = [3, 1, 4, 1, 5, 9]
+    t, d = mt.sequence(48), md.sequence(48)
+    t.prefill(np.array(hist, np.int32))
+    d.prefill(np.array(hist, np.int32))
+    for it in range(2):
+        a, out, dl = t.sps_iteration(d, 1.0, 6)
+        # which drafts were proposed: the accepted ones are in out; rejected ones are not returned,
+        # so rebuild the drafted block from the drafter reference itself, row by row
+        block = list(hist)
+        for r in range(k):
+            ref_d = torch_ref.forward_full(shape_d, Wd, np.array(block), 0).numpy()[-1]
+            assert np.allclose(dl[r], ref_d, rtol=0, atol=1e-6 * np.abs(ref_d).max())
+            tok, _stable = O.sample_softmax(dl[r], 1.0, 6, 0, it, r + 1, O.DRAFT)
+            block.append(tok)
+        ref_t = torch_ref.forward_full(shape_t, Wt, np.array(block), 0).numpy()[-(k + 1):]
+        assert np.allclose(t.logits(1), ref_t, rtol=0, atol=1e-6 * np.abs(ref_t).max())
+        assert list(out[:a]) == block[len(hist):len(hist) + a]
+        hist = hist + [int(x) for x in out]
+
+
+def test_sps_output_law_is_the_target_models():
+    """Tiny vocabulary, many sequence ids: the joint law of the first three tokens of two-model
+    speculative sampling equals the chain rule of the TARGET model (probabilities from the torch
+    reference), although another model drafts; accept and reject branches are both hit."""
+    shape_t = MICRO
+    shape_d = synth.ModelShape(1, 16, 1, 16, 24, MICRO.vocab, dtype=synth.F32)
+    k, temp = 2, 0.9
+    mt, md, Wt, _ = _sps_pair(shape_t, shape_d, k, seed_t=31, seed_d=32, scale=3.0, std=0.08)
+    prompt = np.array([1, 5, 2, 7], np.int32)
+    V = shape_t.vocab
+
+    def probs(prefix):
+        lg = torch_ref.forward_full(shape_t, Wt, np.array(prefix), 0)[-1].numpy()
+        return scipy.special.softmax(lg / temp)
+    joint = np.zeros((V, V, V))
+    pa = probs(list(prompt))
+    for a in range(V):
+        pb = probs(list(prompt) + [a])
+        for b in range(V):
+            joint[a, b] = pa[a] * pb[b] * probs(list(prompt) + [a, b])
+    assert abs(joint.sum() - 1) < 1e-9
+    N = 30000
+    counts = np.zeros((V, V, V))
+    n_acc = np.zeros(k + 1)
+    for i in range(N):
+        t, d = mt.sequence(16, seq_id=i), md.sequence(16, seq_id=i)
+        t.prefill(prompt)
+        d.prefill(prompt)
+        toks, acc, _ = t.generate_sps(d, 3, temp, 2024)
+        counts[toks[0], toks[1], toks[2]] += 1
+        n_acc[acc[0]] += 1
+    assert n_acc[0] > 0.02 * N and n_acc[1:].sum() > 0.02 * N
+    assert _chi2_ok(counts.ravel(), joint.ravel())
+    assert _chi2_ok(counts.sum((1, 2)), joint.sum((1, 2)))
