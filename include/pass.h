@@ -153,6 +153,27 @@ int pass_draft_static(pass_ctx *ctx, const int32_t *slots, int n_slots, const pa
 int pass_verify(pass_ctx *ctx, const int32_t *slots, int n_slots, const pass_sampling *sp,
                 int32_t *out_n_accepted, int32_t *out_tokens);
 
+/* One iteration of two-model speculative sampling (Algorithm 2 of the appendix, the method PaSS is
+ * compared with and whose validation phase it shares): `drafter` is a second context holding a
+ * smaller model with the same vocabulary, run with single-row calls (k = 0, or "lookahead_rows" 0);
+ * target slot t_slots[i] and drafter slot d_slots[i] hold the same sequence (both prefilled with the
+ * same prompt and the same seq_id).  L = the target's look-ahead rows.  Per slot pair: L sequential
+ * calls of the drafter, each drawing draft t from its row with the random stream of draft row t of
+ * the target's iteration; then the target's one call on (last token, drafts) and the accept / reject
+ * chain, residual draw and extra token exactly as in pass_verify (row t-1 of the call is the target
+ * distribution for draft t).  Afterwards the target slot has kv_len += 1 + a and a + 1 new tokens,
+ * and the drafter slot holds the same sequence again (cache rows of rejected drafts are dead; when all
+ * L drafts were accepted one more drafter call makes the missing row).  The drafter's logits rows are
+ * kept as the target slot's drafting logits (rows 1 .. L of pass_get_logits(.., 0, ..)).
+ * out_drafts: host [n_slots * k] or NULL; out_n_accepted: host [n_slots]; out_tokens: host
+ * [n_slots * (k+1)], per slot the a accepted drafts followed by the final token, the rest -1.
+ * Errors as pass_verify, plus PASS_EINVAL (same context twice, vocabularies differ, drafter not in
+ * single-row mode) and PASS_ESTATE (a slot pair does not hold the same sequence); a failure of the
+ * drafter is reported on the target context with the drafter's message. */
+int pass_sps_iteration(pass_ctx *target, pass_ctx *drafter, const int32_t *t_slots, const int32_t *d_slots,
+                       int n_slots, const pass_sampling *sp, int32_t *out_drafts, int32_t *out_n_accepted,
+                       int32_t *out_tokens);
+
 /* Algorithm 1's while loop for a batch of prefilled slots: draft + verify until every slot has
  * produced at least max_new tokens; out_tokens: host [n_slots * max_new], the first max_new
  * tokens of each.  out_stats may be NULL.  Slots that finish early keep stepping with the

@@ -17,7 +17,7 @@ PASS_F32, PASS_BF16 = 0, 1
 MAX_K, MAX_ROWS = 15, 64
 
 SYMBOLS = ["pass_arena_bytes", "pass_create", "pass_load_weights", "pass_prefill", "pass_release",
-           "pass_draft", "pass_draft_static", "pass_verify", "pass_generate", "pass_run_iterations", "pass_kernel_time", "pass_plain_read", "pass_rng_uniforms", "pass_get_logits", "pass_seq_len",
+           "pass_draft", "pass_draft_static", "pass_verify", "pass_generate", "pass_sps_iteration", "pass_run_iterations", "pass_kernel_time", "pass_plain_read", "pass_rng_uniforms", "pass_get_logits", "pass_seq_len",
            "pass_set_option", "pass_attention_plan", "pass_get_tokens", "pass_time_step", "pass_last_error", "pass_destroy"]
 
 
@@ -82,6 +82,7 @@ def load_library():
     L.pass_draft_static.argtypes = [C.c_void_p, ip, C.c_int, C.POINTER(PassSampling), ip, ip]
     L.pass_verify.argtypes = [C.c_void_p, ip, C.c_int, C.POINTER(PassSampling), ip, ip]
     L.pass_generate.argtypes = [C.c_void_p, ip, C.c_int, C.c_int, C.POINTER(PassSampling), ip, C.POINTER(PassStats)]
+    L.pass_sps_iteration.argtypes = [C.c_void_p, C.c_void_p, ip, ip, C.c_int, C.POINTER(PassSampling), ip, ip, ip]
     L.pass_run_iterations.argtypes = [C.c_void_p, ip, C.c_int, C.c_int, C.POINTER(PassSampling), C.POINTER(PassStats)]
     L.pass_kernel_time.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     L.pass_plain_read.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.POINTER(C.c_double)]
@@ -221,6 +222,20 @@ class Pass:
         self._check(self.lib.pass_generate(self.h, _ip(s), s.size, max_new, C.byref(sp), _ip(out), C.byref(st)))
         stats = {f: getattr(st, f) for f, _ in PassStats._fields_}
         return out[:s.size * max_new].reshape(s.size, max_new), stats
+
+    def sps_iteration(self, drafter: "Pass", slots, drafter_slots, temperature: float, seed: int, top_k: int = 0):
+        """One iteration of two-model speculative sampling; self is the target.  Returns (drafts
+        [n, k], accepted counts [n], tokens [n, k + 1])."""
+        s = np.ascontiguousarray(slots, dtype=np.int32)
+        ds = np.ascontiguousarray(drafter_slots, dtype=np.int32)
+        assert s.size == ds.size
+        sp = PassSampling(temperature, top_k, seed)
+        drafts = np.zeros(max(1, s.size * self.k), dtype=np.int32)
+        n_acc = np.zeros(s.size, dtype=np.int32)
+        toks = np.zeros(s.size * (self.k + 1), dtype=np.int32)
+        self._check(self.lib.pass_sps_iteration(self.h, drafter.h, _ip(s), _ip(ds), s.size, C.byref(sp), _ip(drafts),
+                                                _ip(n_acc), _ip(toks)))
+        return drafts[:s.size * self.k].reshape(s.size, self.k), n_acc, toks.reshape(s.size, self.k + 1)
 
     def run_iterations(self, slots, n_iters: int, temperature: float, seed: int, top_k: int = 0) -> dict:
         s = np.ascontiguousarray(slots, dtype=np.int32)

@@ -304,6 +304,7 @@ __global__ __launch_bounds__(kEpiThreads) void draft_epilogue_kernel(Params p, S
   __shared__ SelectShared sh_sel;
   int m = blockIdx.x, b = m / R, r = m % R;
   int slot = p.step_slots[b];
+  if (a.stats_only && r == 0) return;  // row 0 of an externally drafted block is the last token, not a draft
   const float *logits = p.draft_logits + ((size_t)slot * (1 + p.k) + r) * p.V;
   bool greedy = a.temperature == 0.f;
   float inv_t = greedy ? 1.f : 1.f / a.temperature;
@@ -314,13 +315,15 @@ __global__ __launch_bounds__(kEpiThreads) void draft_epilogue_kernel(Params p, S
   }
   Best best;
   MaxSum ms;
-  sample_row(logits, p.V, greedy, inv_t, a.seed_lo, a.seed_hi, p.iter[slot], (uint32_t)r | (PURPOSE_DRAFT << 8),
+  sample_row(logits, p.V, greedy, inv_t, a.seed_lo, a.seed_hi, p.iter[slot], (uint32_t)(r + a.row_base) | (PURPOSE_DRAFT << 8),
              p.seq_id[slot], flt, best, ms);
   best = block_best(best, sh_b);
   ms = block_ms(ms, sh_m);
   if (threadIdx.x == 0) {
     p.logz_d[slot * (kMaxK + 1) + r] = ms.m + logf(ms.s);
-    if (r > 0) {
+    if (a.stats_only) {
+      // the tokens were drafted elsewhere
+    } else if (r > 0) {
       p.drafts[slot * kMaxK + (r - 1)] = best.idx;
     } else {
       p.first[slot] = best.idx;

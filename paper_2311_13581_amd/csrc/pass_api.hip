@@ -37,10 +37,11 @@ struct Slot {
   int state = 0;  // 0 empty, 1 ready for draft, 2 ready for verify
   int kv_len = 0, n_gen = 0;
   uint32_t seq_id = 0;
+  uint32_t iteration = 0;  // iterations of Algorithm 1 / 2 completed (mirror of the device counter)
   std::vector<int> pages;
 };
 
-constexpr int kReportStride = 4 + kMaxK + kMaxK + 1;
+constexpr int kReportStride = 4 + kMaxK + kMaxK + 1 + 1;  // ... and the slot's iteration counter
 
 // Scratch of pass_draft_static: the attention partials (running maximum, sum and accumulator of
 // every (row, head, split)) of one call, for callers that may not allocate.  One copy per GPU,
@@ -84,7 +85,8 @@ struct pass_ctx {
   // optional timing of the dominant kernel (the gate/up GEMM): one event pair per layer
   // captured (model call + epilogue) graphs, keyed by everything that is baked into the launches:
   // mode, batch, attention grid width, sampling arguments
-  typedef std::tuple<int, int, int, uint32_t, uint32_t, uint32_t, int, int, int, int> GraphKey;
+  typedef std::tuple<int, int, int, uint32_t, uint32_t, uint32_t, int, int, int, int, int> GraphKey;
+  int row_base = 0;  // SampleArgs::row_base of the calls issued now (pass_sps_iteration's drafting steps)
   std::map<GraphKey, hipGraphExec_t> graphs;
   int opt_kernel_timing = 0;
   GemmTuning tuning;  // launch shapes of the decode GEMMs (captured graphs carry them: cleared when it changes)
@@ -230,6 +232,7 @@ __global__ void gather_report_kernel(Params p, int B, int32_t *out) {
   o[0] = p.kv_len[slot]; o[1] = p.n_gen[slot]; o[2] = p.n_acc[slot]; o[3] = p.first[slot];
   for (int t = 0; t < kMaxK; ++t) o[4 + t] = p.drafts[slot * kMaxK + t];
   for (int t = 0; t <= kMaxK; ++t) o[4 + kMaxK + t] = p.last_out[slot * (kMaxK + 1) + t];
+  o[kReportStride - 1] = (int32_t)p.iter[slot];
 }
 
 int poke(pass_ctx *c, std::vector<int32_t *> &ptrs, std::vector<int32_t> &vals) {
@@ -412,6 +415,8 @@ SampleArgs sample_args(const pass_sampling *sp, int commit) {
   a.seed_hi = (uint32_t)(sp->seed >> 32);
   a.commit = commit;
   a.top_k = sp->top_k;
+  a.row_base = 0;
+  a.stats_only = 0;
   return a;
 }
 
@@ -436,9 +441,11 @@ int issue_call_eager(pass_ctx *c, int mode, const int32_t *slots, int B, const p
   int rc = run_step(c, mode, B, R, draft ? c->P.draft_logits : c->P.verify_logits,
                     max_keys_of(c, slots, B, draft ? R : R + 1), nullptr);
   if (rc) return rc;
-  if (draft)
-    launch_draft_epilogue(c->P, sample_args(sp, commit), B, R, c->stream);
-  else
+  if (draft) {
+    SampleArgs a = sample_args(sp, commit);
+    a.row_base = c->row_base;
+    launch_draft_epilogue(c->P, a, B, R, c->stream);
+  } else
     launch_verify_epilogue(c->P, sample_args(sp, commit), B, R, c->stream);
   HIP_TRY(c, hipGetLastError());
   return PASS_OK;
@@ -455,7 +462,7 @@ int issue_call(pass_ctx *c, int mode, const int32_t *slots, int B, const pass_sa
   const int S = choose_splits(c, B, R, max_keys_of(c, slots, B, mode == MODE_DRAFT ? R : R + 1));
   uint32_t tbits;
   memcpy(&tbits, &sp->temperature, 4);
-  pass_ctx::GraphKey key(mode, B, S, tbits, (uint32_t)sp->seed, (uint32_t)(sp->seed >> 32), commit, sp->top_k, c->P.k_act, c->P.la_token);
+  pass_ctx::GraphKey key(mode, B, S, tbits, (uint32_t)sp->seed, (uint32_t)(sp->seed >> 32), commit, sp->top_k, c->P.k_act, c->P.la_token, c->row_base);
   auto it = c->graphs.find(key);
   if (it == c->graphs.end()) {
     if (c->graphs.size() >= 64) {  // bound the cache: drop everything, recapture on demand
@@ -705,6 +712,7 @@ int pass_prefill(pass_ctx *c, int slot, uint32_t seq_id, const int32_t *prompt, 
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   s.kv_len = n - 1;
   s.n_gen = 0;
+  s.iteration = 0;
   s.state = 1;
   return PASS_OK;
 }
@@ -775,12 +783,120 @@ int pass_verify(pass_ctx *c, const int32_t *slots, int n_slots, const pass_sampl
     Slot &s = c->slots[slots[b]];
     s.kv_len = r[0];
     s.n_gen = r[1];
+    s.iteration = (uint32_t)r[kReportStride - 1];
     s.state = 1;
     int a = r[2];
     if (out_n_accepted) out_n_accepted[b] = a;
     if (out_tokens)
       for (int t = 0; t <= k; ++t) out_tokens[b * (k + 1) + t] = t <= a ? r[4 + kMaxK + t] : -1;
   }
+  return PASS_OK;
+}
+
+// One drafting-model call of Algorithm 2 on B slots of the drafter context: a single-row call whose
+// token is drawn with the random stream of draft row `row` of the target's iteration (the drafter
+// slots' iteration counters were set to the targets').  Host mirrors are updated; slots stay in
+// state 1 (a drafter never verifies).
+static int sps_drafter_step(pass_ctx *d, const int32_t *slots, int B, const pass_sampling *sp, int row) {
+  int rc;
+  for (int b = 0; b < B; ++b) {
+    Slot &s = d->slots[slots[b]];
+    if (s.kv_len + 1 > d->cfg.max_seq_len) return fail(d, PASS_ECAPACITY, "drafter slot %d is full", slots[b]);
+    if ((rc = ensure_pages(d, slots[b], s.kv_len + 1))) return rc;
+  }
+  if ((rc = set_step_slots(d, slots, B))) return rc;
+  d->row_base = row;
+  rc = issue_call(d, MODE_DRAFT, slots, B, sp, 1);
+  d->row_base = 0;
+  if (rc) return rc;
+  for (int b = 0; b < B; ++b) d->slots[slots[b]].kv_len += 1;  // the drafting epilogue appends its token
+  return PASS_OK;
+}
+
+int pass_sps_iteration(pass_ctx *t, pass_ctx *d, const int32_t *t_slots, const int32_t *d_slots, int n_slots,
+                       const pass_sampling *sp, int32_t *out_drafts, int32_t *out_n_accepted, int32_t *out_tokens) {
+  if (!t || !d) return PASS_EINVAL;
+  int rc;
+  if ((rc = check_slots(t, t_slots, n_slots, 1))) return rc;
+  if ((rc = check_slots(d, d_slots, n_slots, 1))) { fail(t, rc, "drafter: %s", d->err.c_str()); return rc; }
+  if ((rc = check_sampling(t, sp))) return rc;
+  if (t == d) return fail(t, PASS_EINVAL, "target and drafter must be two contexts");
+  if (d->P.k_act != 0) return fail(t, PASS_EINVAL, "the drafter context must run single-row calls (k = 0 or lookahead_rows = 0)");
+  if (d->cfg.vocab != t->cfg.vocab) return fail(t, PASS_EINVAL, "target and drafter vocabularies differ");
+  const int L = t->P.k_act, k = t->cfg.k, V = t->cfg.vocab;
+  std::vector<int32_t *> ptrs;
+  std::vector<int32_t> vals;
+  for (int b = 0; b < n_slots; ++b) {
+    const Slot &ts = t->slots[t_slots[b]], &ds = d->slots[d_slots[b]];
+    if (ts.kv_len != ds.kv_len || ts.seq_id != ds.seq_id)
+      return fail(t, PASS_ESTATE, "slot pair %d: target and drafter do not hold the same sequence", b);
+    if (ts.kv_len + 1 + k > t->cfg.max_seq_len) return fail(t, PASS_ECAPACITY, "slot %d is full", t_slots[b]);
+    if (ds.kv_len + 1 + L > d->cfg.max_seq_len) return fail(t, PASS_ECAPACITY, "drafter slot %d is full", d_slots[b]);
+    if ((rc = ensure_pages(t, t_slots[b], ts.kv_len + 1 + k))) return rc;
+    ptrs.push_back((int32_t *)d->P.iter + d_slots[b]);  // the drafter draws with the target's iteration counter
+    vals.push_back((int32_t)ts.iteration);
+  }
+  if ((rc = poke(d, ptrs, vals))) { fail(t, rc, "drafter: %s", d->err.c_str()); return rc; }
+  // drafting: L sequential single-row calls of the drafter; each call's logits row and token go straight
+  // into the target's draft state (row t of the slot's draft logits, draft t - 1), on the drafter's stream
+  for (int row = 1; row <= L; ++row) {
+    if ((rc = sps_drafter_step(d, d_slots, n_slots, sp, row))) { fail(t, rc, "drafter: %s", d->err.c_str()); return rc; }
+    for (int b = 0; b < n_slots; ++b) {
+      HIP_TRY(t, hipMemcpyAsync(t->P.draft_logits + ((size_t)t_slots[b] * (1 + k) + row) * V,
+                                d->P.draft_logits + (size_t)d_slots[b] * (1 + d->cfg.k) * V, sizeof(float) * V,
+                                hipMemcpyDeviceToDevice, d->stream));
+      HIP_TRY(t, hipMemcpyAsync(t->P.drafts + (size_t)t_slots[b] * kMaxK + (row - 1), d->P.first + d_slots[b], sizeof(int32_t),
+                                hipMemcpyDeviceToDevice, d->stream));
+    }
+  }
+  HIP_TRY(t, hipStreamSynchronize(d->stream));  // the target's stream may now read what the drafter's stream wrote
+  // validation: filter and ln-sum-exp of the drafted rows, then Algorithm 1's validation call unchanged
+  if ((rc = set_step_slots(t, t_slots, n_slots))) return rc;
+  if (L > 0) {
+    SampleArgs a = sample_args(sp, 0);
+    a.stats_only = 1;
+    launch_draft_epilogue(t->P, a, n_slots, 1 + L, t->stream);
+    HIP_TRY(t, hipGetLastError());
+  }
+  if ((rc = issue_verify(t, t_slots, n_slots, sp, 1))) return rc;
+  if ((rc = fetch_report(t, n_slots))) return rc;
+  std::vector<int32_t> again;  // drafter slots whose every draft was accepted: the row of draft L is still to be made
+  for (int b = 0; b < n_slots; ++b) {
+    const int32_t *r = t->report_host + b * kReportStride;
+    Slot &ts = t->slots[t_slots[b]];
+    ts.kv_len = r[0];
+    ts.n_gen = r[1];
+    ts.iteration = (uint32_t)r[kReportStride - 1];
+    const int a = r[2];
+    if (out_n_accepted) out_n_accepted[b] = a;
+    if (out_drafts)
+      for (int i = 0; i < k; ++i) out_drafts[b * k + i] = i < L ? r[4 + i] : -1;
+    if (out_tokens)
+      for (int i = 0; i <= k; ++i) out_tokens[b * (k + 1) + i] = i <= a ? r[4 + kMaxK + i] : -1;
+    if (a == L) again.push_back(d_slots[b]);
+  }
+  if (!again.empty() && (rc = sps_drafter_step(d, again.data(), (int)again.size(), sp, L + 1))) {
+    fail(t, rc, "drafter: %s", d->err.c_str());
+    return rc;
+  }
+  // the drafter follows the target: rows of rejected drafts are dead, the last token is the target's
+  ptrs.clear();
+  vals.clear();
+  for (int b = 0; b < n_slots; ++b) {
+    const int32_t *r = t->report_host + b * kReportStride;
+    Slot &ds = d->slots[d_slots[b]];
+    ds.kv_len = r[0];
+    ds.n_gen = r[1];
+    ds.iteration = t->slots[t_slots[b]].iteration;
+    ptrs.push_back(d->P.kv_len + d_slots[b]);
+    vals.push_back(r[0]);
+    ptrs.push_back(d->P.n_gen + d_slots[b]);  // (the drafter's own token buffer holds drafts: only its count follows)
+    vals.push_back(std::min(r[1], d->P.gen_cap));
+    ptrs.push_back(d->P.pending + d_slots[b]);
+    vals.push_back(r[4 + kMaxK + r[2]]);
+  }
+  if ((rc = poke(d, ptrs, vals))) { fail(t, rc, "drafter: %s", d->err.c_str()); return rc; }
+  HIP_TRY(t, hipStreamSynchronize(d->stream));
   return PASS_OK;
 }
 
@@ -816,6 +932,7 @@ static int run_pipeline(pass_ctx *c, const int32_t *slots, int n_slots, int n_it
       if (target < 0) st.tokens_out += r[1] - s.n_gen;
       s.kv_len = r[0];
       s.n_gen = r[1];
+      s.iteration = (uint32_t)r[kReportStride - 1];
     }
     return PASS_OK;
   };

@@ -138,6 +138,11 @@ struct SampleArgs {
   uint32_t seed_lo, seed_hi;
   int commit;  // 0: compute but leave the sequence state untouched (timing replays)
   int top_k;   // 0: no filter; K: sample from the K largest logits of a row only
+  // Two-model speculative sampling (Algorithm 2 of the appendix) reuses the drafting epilogue:
+  int row_base;    // added to the row number in the random streams: the drafting model's t-th single-row call draws
+                   //   with the stream of draft row t
+  int stats_only;  // 1: rows 1.. hold logits drafted elsewhere: only their filter and ln-sum-exp are computed,
+                   //   no token is drawn and no state changes (row 0 is skipped)
 };
 
 // ---- launchers (each checks nothing but launches; shapes are validated by the caller) ----

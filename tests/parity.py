@@ -223,6 +223,63 @@ def check_stats(st, n_iters, max_err, max_unstable=2, max_resyncs=0):
     assert st.unstable <= max_unstable and st.resyncs <= max_resyncs, st
 
 
+def sps_parity(gpu_t, gpu_d, om_t, om_d, slot, seq_id, prompt, n_iters, temp, seed, tol, max_len=256, top_k=0):
+    """Two-model speculative sampling (Algorithm 2), one sequence, GPU target / drafter contexts
+    against the oracle's: per iteration the drafter's logits rows and drafted tokens, the target's
+    validation logits and every decision, as in stepwise_parity (resync on an unstable difference)."""
+    st = StepStats()
+    k = getattr(gpu_t, "k_act", gpu_t.k)
+    inv_t = 1.0 if temp == 0 else 1.0 / temp
+    hist = [int(t) for t in prompt]
+    done = 0
+    while done < n_iters:
+        for g in (gpu_t, gpu_d):
+            g.prefill(slot, hist, seq_id=seq_id)
+        ot, od = om_t.sequence(max_len, seq_id=seq_id), om_d.sequence(max_len, seq_id=seq_id)
+        ot.prefill(hist)
+        od.prefill(hist)
+        it = 0
+        while done < n_iters:
+            kv0 = ot.kv_len
+            o_a, o_out, o_dl = ot.sps_iteration(od, temp, seed, top_k=top_k)
+            g_drafts, g_a, g_out = gpu_t.sps_iteration(gpu_d, [slot], [slot], temp, seed, top_k)
+            done += 1
+            st.iterations += 1
+            hist += [int(x) for x in o_out]
+            in_sync = True
+            # drafting: rows 1 .. k of the target slot's drafting logits hold the drafter's rows
+            err_d = 0.0
+            drafts = []
+            if k:
+                gl = gpu_t.get_logits(slot, 0)[1:k + 1]
+                err_d = logits_error(gl, o_dl, tol, f"drafter it={it}")
+                st.max_rel_err = max(st.max_rel_err, err_d / np.abs(o_dl).max())
+            tau = err_d * inv_t * 1.01 + (0.0 if temp == 0 else F32_ARITH)
+            for t in range(1, k + 1):
+                tok, stable = O.sample_softmax(o_dl[t - 1], temp, seed, seq_id, it, t, O.DRAFT, tau, top_k)
+                drafts.append(tok)
+                st.compared += 1
+                if stable:
+                    assert g_drafts[0, t - 1] == tok, f"drafter it={it} row {t}: gpu {g_drafts[0, t - 1]} != oracle {tok}"
+                else:
+                    st.unstable += 1
+                    in_sync &= g_drafts[0, t - 1] == tok
+                if not in_sync:
+                    break  # later drafter rows saw another token
+            if in_sync:
+                ol = np.concatenate([np.zeros((1, o_dl.shape[1]), np.float32), o_dl]) if k else np.zeros((1, gpu_t.vocab), np.float32)
+                pl, gpl = ot.logits(1), gpu_t.get_logits(slot, 1)[:k + 1]
+                in_sync = _check_verify(st, it, k, temp, seed, seq_id, tol, top_k, ol, pl, gpl, err_d, drafts, o_a, o_out,
+                                        int(g_a[0]), g_out[0])
+            if in_sync:
+                assert gpu_t.seq_len(slot)[0] == kv0 + 1 + o_a == ot.kv_len == od.kv_len == gpu_d.seq_len(slot)[0]
+            else:
+                st.resyncs += 1
+                break
+            it += 1
+    return st
+
+
 def generate_parity(gpu_tokens, oracle_tokens, oracle_acc, oracle_stable):
     """Free-running comparison.  Returns the identical prefix length; a mismatch inside an
     iteration whose decisions the oracle reports stable (and with no unstable iteration before

@@ -785,3 +785,70 @@ def test_run_iterations_stops_exactly_where_stepwise_calls_stop():
         state.append(g.seq_len(0))
         g.close()
     assert state[0] == state[1] and state[0][0] + 2 + 3 > 64
+
+
+# ---------------------------------------------------------------------------------------------
+# Algorithm 2 (appendix): two-model speculative sampling through pass_sps_iteration
+# ---------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("which", ["fp32", "mfma"])
+@pytest.mark.parametrize("temp", [0.0, 0.9])
+def test_two_model_speculative_sampling_stepwise(which, temp):
+    """A target context and a drafter context (a smaller model of the same vocabulary) against the
+    oracle's Algorithm 2: the drafter's k sequential rows and tokens, the target's validation logits,
+    accept bits, residual / extra token and both sequences' lengths, every iteration."""
+    k = 3
+    if which == "fp32":
+        shape_t, page = TINY.shape, 16
+        shape_d = synth.ModelShape(1, 128, 2, 64, 256, shape_t.vocab, dtype=synth.F32)
+    else:
+        shape_t, page = MFMA_HD128.shape, 64
+        shape_d = synth.ModelShape(1, 256, 2, 128, 512, shape_t.vocab, dtype=synth.BF16)
+    Wt = synth.make_weights(shape_t, 71, k, 5.0)
+    Wd = synth.make_weights(shape_d, 72, 1, 5.0)
+    gt = _gpu(shape_t, Wt, k, max_seq_len=256, page_size=page)
+    gd = _gpu(shape_d, Wd, 0, max_seq_len=256, page_size=page)
+    mt, md = O.Model(shape_t, Wt, k), O.Model(shape_d, Wd, 0)
+    prompt = np.random.default_rng(17).integers(0, shape_t.vocab, 41).astype(np.int32)
+    st = parity.sps_parity(gt, gd, mt, md, 0, 6, prompt, 12, temp, 2027, parity.LOGIT_TOL[shape_t.dtype])
+    print(which, temp, st)
+    parity.check_stats(st, 12, parity.ERR_F32 if which == "fp32" else parity.ERR_BF16_SMALL)
+    gt.close()
+    gd.close()
+
+
+def test_two_model_speculative_sampling_with_the_target_as_drafter_accepts_everything():
+    """The same model in both contexts: draft t is drawn from the distribution validation row t-1
+    scores it with, so every draft is accepted and each iteration adds k + 1 tokens (which also
+    exercises the extra drafter call that makes the last draft's cache row); a batch of two slot
+    pairs; greedy, where the tokens are the target's greedy decoding."""
+    w, k = TINY, 4
+    W = synth.make_weights(w.shape, 9, k, 4.0)
+    gt = _gpu(w.shape, W, k, max_slots=2, max_seq_len=256)
+    gd = _gpu(w.shape, W, 0, max_slots=2, max_seq_len=256)
+    prompts = [np.random.default_rng(i).integers(0, w.shape.vocab, n).astype(np.int32) for i, n in enumerate((12, 30))]
+    for i, p in enumerate(prompts):
+        gt.prefill(i, p, seq_id=i)
+        gd.prefill(i, p, seq_id=i)
+    toks = {0: [], 1: []}
+    for _ in range(5):
+        drafts, a, out = gt.sps_iteration(gd, [0, 1], [0, 1], 0.8, 11)
+        assert list(a) == [k, k]
+        for i in (0, 1):
+            assert np.array_equal(out[i, :k], drafts[i])
+            toks[i] += [int(x) for x in out[i]]
+    for i in (0, 1):
+        assert gt.seq_len(i)[0] == gd.seq_len(i)[0] == len(prompts[i]) - 1 + 5 * (k + 1)
+        assert np.array_equal(gt.get_tokens(i, 0, 5 * (k + 1)), toks[i])
+    # greedy: Algorithm 2's output is the target's own greedy decoding
+    m = O.Model(w.shape, W, k)
+    gt.prefill(0, prompts[0], seq_id=0)
+    gd.prefill(0, prompts[0], seq_id=0)
+    got = []
+    for _ in range(4):
+        _d, a, out = gt.sps_iteration(gd, [0], [0], 0.0, 11)
+        got += [int(x) for x in out[0, :a[0] + 1]]
+    s = m.sequence(256, seq_id=0)
+    s.prefill(prompts[0])
+    assert np.array_equal(got, s.generate_ar(len(got), 0.0, 11))
+    gt.close()
+    gd.close()
