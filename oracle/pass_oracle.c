@@ -414,6 +414,11 @@ static void rmsnorm(const orc_model *m, const double *x, const void *g, double *
 static void matmul(const orc_model *m, const double *X, const void *W, int R, int K, int N,
                    double *Y) {
   int dtype = m->c.dtype;
+  /* the rows side by side, Xt[k][r] = X[r][k]: the sums below then walk memory in order (same
+   * products, same order of additions per output as with X itself) */
+  double *Xt = (double *)malloc(sizeof(double) * (size_t)R * K);
+  for (int r = 0; r < R; ++r)
+    for (int k = 0; k < K; ++k) Xt[(size_t)k * R + r] = X[(size_t)r * K + k];
 #pragma omp parallel for schedule(static)
   for (int n = 0; n < N; ++n) {
     double acc[ORC_MAX_ROWS];
@@ -421,10 +426,12 @@ static void matmul(const orc_model *m, const double *X, const void *W, int R, in
     size_t base = (size_t)n * K;
     for (int k = 0; k < K; ++k) {
       double w = load_elem(W, dtype, base + k);
-      for (int r = 0; r < R; ++r) acc[r] += w * X[(size_t)r * K + k];
+      const double *xk = Xt + (size_t)k * R;
+      for (int r = 0; r < R; ++r) acc[r] += w * xk[r];
     }
     for (int r = 0; r < R; ++r) Y[(size_t)r * N + n] = acc[r];
   }
+  free(Xt);
 }
 
 /* rotate interleaved pairs (2i, 2i+1) of every head by pos * base^(-2i/head_dim) */
