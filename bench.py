@@ -55,7 +55,7 @@ def measured_traffic(workload_name):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
     (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel of known size); None if there is no
     summary for this workload."""
-    path = os.path.join(ROOT, "profiles", "7b_k4_gate_up_gemm_hbm_traffic.txt")
+    path = os.path.join(ROOT, "profiles", "7b_k4_gate_up_gemm_hbm_traffic.txt")  # counters cannot be read from inside the run
     if workload_name != "7b_k4_greedy" or not os.path.exists(path):
         return None
     for line in open(path):
