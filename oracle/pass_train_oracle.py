@@ -40,9 +40,12 @@ def _t(a, dtype):
     return torch.from_numpy(a.astype(np.float64))
 
 
-def forward_logits(shape, W, prefix, la):
+def forward_logits(shape, W, prefix, la, rounding=None):
     """Logits [L, V] of the look-ahead rows for the sequence prefix + L look-ahead embeddings.
-    la: [L, d] fp64 tensor (may require grad)."""
+    la: [L, d] fp64 tensor (may require grad).  rounding (tests of this file's gradient only): a list
+    that receives, per layer, what the cache's rounding added to K and V; handed in again, those
+    amounts are added as constants instead of rounding, which makes the pass a smooth function with
+    the same value and the same gradient at the point where the list was filled."""
     dt = shape.dtype
     H, hd, eps = shape.n_heads, shape.head_dim, shape.rms_eps
     x = torch.cat([_t(W["tok_emb"], dt)[torch.as_tensor(np.asarray(prefix), dtype=torch.long)], la], 0)
@@ -65,9 +68,15 @@ def forward_logits(shape, W, prefix, la):
         q = rope((n1 @ _t(W["wq"][l], dt).T).view(T, H, hd))
         k = rope((n1 @ _t(W["wk"][l], dt).T).view(T, H, hd))
         v = (n1 @ _t(W["wv"][l], dt).T).view(T, H, hd)
-        if dt == BF16:  # the cache stores bfloat16 values; the cast passes gradients through
-            k = k.to(torch.bfloat16).double()
-            v = v.to(torch.bfloat16).double()
+        if dt == BF16:  # the cache stores bfloat16 values; gradients pass the rounding unchanged (a cast
+            # node would round the gradient to bfloat16 on its way back as well)
+            if rounding is not None and len(rounding) > l:
+                dk, dv = rounding[l]
+            else:
+                dk, dv = (k.to(torch.bfloat16).double() - k).detach(), (v.to(torch.bfloat16).double() - v).detach()
+                if rounding is not None:
+                    rounding.append((dk, dv))
+            k, v = k + dk, v + dv
         s = torch.einsum("qhd,khd->hqk", q, k) / math.sqrt(hd)
         p = torch.softmax(s.masked_fill(~mask[None], -math.inf), -1)
         a = torch.einsum("hqk,khd->qhd", p, v).reshape(T, H * hd)
@@ -78,15 +87,16 @@ def forward_logits(shape, W, prefix, la):
     return norm(x, W["final_norm"])[len(prefix):] @ _t(W["lm_head"], dt).T
 
 
-def loss_and_grad(shape, W, la, prefixes, targets):
+def loss_and_grad(shape, W, la, prefixes, targets, rounding=None):
     """Mean cross-entropy over the look-ahead rows of a batch, and its gradient w.r.t. the look-ahead
     embeddings.  prefixes: list of token lists (w_1 .. w_T); targets: [B, L] tokens w_{T+2} .. w_{T+1+L}.
+    rounding: None, or one list per sequence (see forward_logits).
     Returns (loss float, grad [L, d] float64 numpy)."""
     p = torch.tensor(np.asarray(la, dtype=np.float64), requires_grad=True)
     total = 0.0
     L = p.shape[0]
-    for prefix, tg in zip(prefixes, targets):
-        lg = forward_logits(shape, W, prefix, p)
+    for b, (prefix, tg) in enumerate(zip(prefixes, targets)):
+        lg = forward_logits(shape, W, prefix, p, None if rounding is None else rounding[b])
         logp = torch.log_softmax(lg, -1)
         total = total - logp[torch.arange(L), torch.as_tensor(np.asarray(tg), dtype=torch.long)].sum()
     loss = total / (len(prefixes) * L)
