@@ -191,6 +191,45 @@ int pass_generate(pass_ctx *ctx, const int32_t *slots, int n_slots, int max_new,
 int pass_run_iterations(pass_ctx *ctx, const int32_t *slots, int n_slots, int n_iters,
                         const pass_sampling *sp, pass_stats *out_stats);
 
+/* Training of the look-ahead embeddings (Training details of the paper; Section 2.2.1): every
+ * parameter of the model is frozen, only the k x d_model look-ahead embeddings learn.  One step takes
+ * a batch of prefilled slots (slot b holds the prefix w_1 .. w_T of a training sequence, cut at a
+ * position the caller draws at random: K/V of w_1 .. w_{T-1} cached, w_T pending), runs the block
+ * (w_T, [LA]_1 .. [LA]_k) through the model, takes the mean cross-entropy of the look-ahead rows
+ * (row [LA]_i predicts targets[b * k + i - 1] = w_{T+1+i}; the row of w_T carries no loss), carries
+ * its gradient back through the frozen model to the look-ahead rows, and applies AdamW (decoupled
+ * weight decay; the paper: learning rate 0.01 after a linear warm-up, cosine schedule, batches of
+ * 8 sequences -- the schedule is the caller's: it passes each step's learning rate).  The trained
+ * values are fp32 ("master") and enter the forward pass unrounded; after every step the model's
+ * own look-ahead tensor is refreshed from them in its storage type, so pass_draft uses what was
+ * learned.  Slots are left as they were (the block's K/V rows lie beyond kv_len: dead).
+ * Training runs on the generic kernels: the context must have been loaded with option "path" = 1.
+ *   pass_train_bytes   device bytes pass_train_begin needs for this configuration (0: invalid or k = 0)
+ *   pass_train_begin   device_workspace: caller's device memory (256-byte aligned, kept alive while
+ *                      training); the embeddings start from the embedding of init_token (the paper:
+ *                      [UNK]) or, with init_token < 0, from the model's own look-ahead tensor;
+ *                      AdamW's moments and step count start at zero
+ *   pass_train_step    slots: host, n_slots prefilled slots, (1+k) * n_slots <= PASS_MAX_ROWS, at most
+ *                      8192 keys each; targets: host [n_slots * k]; *out_loss: the batch loss before
+ *                      the update (may be NULL)
+ *   pass_train_read    what = 0: the master values, 1: the gradient of the last step, 2 / 3: AdamW's first /
+ *                      second moment; out: host [k * d_model]
+ *   pass_train_resume  restores a saved training state: master values, moments (host [k * d_model] each; a
+ *                      NULL pointer leaves that part as it is) and the number of optimiser steps taken so
+ *                      far (it enters AdamW's bias correction); the model's own look-ahead tensor follows
+ *                      the master values
+ * Errors: PASS_ESTATE (matrix-core path, no pass_train_begin, look-ahead options not at their
+ * defaults), PASS_EINVAL, PASS_ECAPACITY. */
+typedef struct {
+  float lr, beta1, beta2, eps, weight_decay;
+} pass_adamw;
+size_t pass_train_bytes(const pass_config *cfg);
+int pass_train_begin(pass_ctx *ctx, void *device_workspace, size_t bytes, int32_t init_token);
+int pass_train_step(pass_ctx *ctx, const int32_t *slots, int n_slots, const int32_t *targets, const pass_adamw *opt,
+                    float *out_loss);
+int pass_train_read(pass_ctx *ctx, int what, float *out);
+int pass_train_resume(pass_ctx *ctx, const float *master, const float *m1, const float *m2, int64_t steps);
+
 /* Parity hook: fp32 logits [(1+k) * vocab] of the slot's last drafting (which = 0) or
  * validation (which = 1) call, copied to host memory. */
 int pass_get_logits(pass_ctx *ctx, int slot, int which, float *out);

@@ -18,7 +18,7 @@ MAX_K, MAX_ROWS = 15, 64
 
 SYMBOLS = ["pass_arena_bytes", "pass_create", "pass_load_weights", "pass_prefill", "pass_release",
            "pass_draft", "pass_draft_static", "pass_verify", "pass_generate", "pass_sps_iteration", "pass_run_iterations", "pass_kernel_time", "pass_plain_read", "pass_rng_uniforms", "pass_get_logits", "pass_seq_len",
-           "pass_set_option", "pass_attention_plan", "pass_get_tokens", "pass_time_step", "pass_last_error", "pass_destroy"]
+           "pass_train_bytes", "pass_train_begin", "pass_train_step", "pass_train_read", "pass_train_resume", "pass_set_option", "pass_attention_plan", "pass_get_tokens", "pass_time_step", "pass_last_error", "pass_destroy"]
 
 
 class PassConfig(C.Structure):
@@ -46,6 +46,11 @@ class PassWeights(C.Structure):
                 ("lookahead", C.c_void_p),
                 ("attn_norm", _PP), ("wq", _PP), ("wk", _PP), ("wv", _PP), ("wo", _PP),
                 ("ffn_norm", _PP), ("w_gate", _PP), ("w_up", _PP), ("w_down", _PP)]
+
+
+class PassAdamW(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float)]
 
 
 class PassError(RuntimeError):
@@ -91,6 +96,12 @@ def load_library():
     L.pass_get_logits.argtypes = [C.c_void_p, C.c_int, C.c_int, C.POINTER(C.c_float)]
     L.pass_seq_len.argtypes = [C.c_void_p, C.c_int, ip, ip]
     L.pass_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int]
+    L.pass_train_bytes.restype = C.c_size_t
+    L.pass_train_bytes.argtypes = [C.POINTER(PassConfig)]
+    L.pass_train_begin.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32]
+    L.pass_train_step.argtypes = [C.c_void_p, ip, C.c_int, ip, C.POINTER(PassAdamW), C.POINTER(C.c_float)]
+    L.pass_train_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float)]
+    L.pass_train_resume.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_int64]
     L.pass_get_tokens.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, ip]
     L.pass_attention_plan.argtypes = [C.c_int, C.c_int, ip, ip, ip]
     L.pass_time_step.argtypes = [C.c_void_p, ip, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double)]
@@ -264,6 +275,35 @@ class Pass:
         out = np.empty((self.k + 1, self.vocab), dtype=np.float32)
         self._check(self.lib.pass_get_logits(self.h, slot, which, out.ctypes.data_as(C.POINTER(C.c_float))))
         return out
+
+    def train_begin(self, init_token: int = -1):
+        """Set up look-ahead embedding training (the workspace is a torch tensor this object keeps)."""
+        nbytes = self.lib.pass_train_bytes(C.byref(self.cfg))
+        if nbytes == 0:
+            raise PassError(-1, "no look-ahead embeddings to train")
+        self.train_ws = self._torch.empty(nbytes + 256, dtype=self._torch.uint8, device="cuda")
+        self._torch.cuda.synchronize()
+        base = (self.train_ws.data_ptr() + 255) & ~255
+        self._check(self.lib.pass_train_begin(self.h, C.c_void_p(base), nbytes, init_token))
+
+    def train_step(self, slots, targets, lr: float, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01) -> float:
+        s = np.ascontiguousarray(slots, dtype=np.int32)
+        t = np.ascontiguousarray(targets, dtype=np.int32)
+        assert t.size == s.size * self.k
+        opt = PassAdamW(lr, beta1, beta2, eps, weight_decay)
+        loss = C.c_float(0)
+        self._check(self.lib.pass_train_step(self.h, _ip(s), s.size, _ip(t), C.byref(opt), C.byref(loss)))
+        return loss.value
+
+    def train_read(self, what: int) -> np.ndarray:
+        out = np.empty((self.k, self.cfg.d_model), dtype=np.float32)
+        self._check(self.lib.pass_train_read(self.h, what, out.ctypes.data_as(C.POINTER(C.c_float))))
+        return out
+
+    def train_resume(self, master=None, m1=None, m2=None, steps: int = 0):
+        keep = [None if a is None else np.ascontiguousarray(a, dtype=np.float32).reshape(self.k, self.cfg.d_model) for a in (master, m1, m2)]
+        ptr = [None if a is None else a.ctypes.data_as(C.POINTER(C.c_float)) for a in keep]
+        self._check(self.lib.pass_train_resume(self.h, ptr[0], ptr[1], ptr[2], steps))
 
     def get_tokens(self, slot: int, first: int, n: int) -> np.ndarray:
         out = np.empty(max(1, n), dtype=np.int32)

@@ -41,6 +41,20 @@ struct Slot {
   std::vector<int> pages;
 };
 
+// Workspace of the look-ahead embedding training (caller's memory, carved by carve_train)
+struct TrainWs {
+  bool on = false;
+  int64_t step = 0;  // optimiser steps taken (AdamW's bias correction)
+  float *master, *m1, *m2, *grad;                    // [k][d] fp32: trained values, AdamW moments, last gradient
+  float *save_h0, *save_h1, *save_q, *save_gu;       // per layer [L][kMaxRows][d | d | D | 2F]: what the backward pass needs
+  float *save_hl;                                    // [kMaxRows][d] residual stream before the final norm
+  float *logits;                                     // [kMaxRows][V] logits, then d loss / d logits
+  float *dh, *dxn, *dattn, *dqkv, *dact, *dgu;       // gradients of the rows' activations
+  float *part;                                       // [kTrainSplits][kMaxRows][max(d, D, F)] slice sums of a transposed projection
+  float *row_loss;                                   // [kMaxRows]
+  int32_t *targets;                                  // [kMaxRows] target token of a row, -1 = no loss
+};
+
 constexpr int kReportStride = 4 + kMaxK + kMaxK + 1 + 1;  // ... and the slot's iteration counter
 
 // Scratch of pass_draft_static: the attention partials (running maximum, sum and accumulator of
@@ -89,7 +103,9 @@ struct pass_ctx {
   int row_base = 0;  // SampleArgs::row_base of the calls issued now (pass_sps_iteration's drafting steps)
   std::map<GraphKey, hipGraphExec_t> graphs;
   int opt_kernel_timing = 0;
-  GemmTuning tuning;  // launch shapes of the decode GEMMs (captured graphs carry them: cleared when it changes)
+  GemmTuning tuning;
+  TrainWs train;
+  float *train_loss_host = nullptr;  // pinned [kMaxRows]  // launch shapes of the decode GEMMs (captured graphs carry them: cleared when it changes)
   int opt_prefill_chunk = 64;
   int opt_prefill_tiled = -1;  // -1: prompts of more than 2 * kMaxRows rows take the tiled pass; 0 never; 1 always
   Params PP;                   // P with the row buffers of the tiled prompt pass
@@ -221,6 +237,25 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
     PP.rope_cos = S2.take<float>(R * c.head_dim / 2); PP.rope_sin = S2.take<float>(R * c.head_dim / 2);
     ctx->PP = PP; ctx->pws = W;
   }
+  return (A.off + 255) & ~(size_t)255;
+}
+
+size_t carve_train(const pass_config &c, char *base, TrainWs *out) {
+  Arena A{base, 0};
+  const size_t d = c.d_model, D = (size_t)c.n_heads * c.head_dim, F = c.d_ffn, V = c.vocab, L = c.n_layers, M = kMaxRows;
+  const size_t kd = (size_t)(c.k ? c.k : 1) * d;
+  TrainWs T;
+  T.master = A.take<float>(kd); T.m1 = A.take<float>(kd); T.m2 = A.take<float>(kd); T.grad = A.take<float>(kd);
+  T.save_h0 = A.take<float>(L * M * d); T.save_h1 = A.take<float>(L * M * d);
+  T.save_q = A.take<float>(L * M * D); T.save_gu = A.take<float>(L * M * 2 * F);
+  T.save_hl = A.take<float>(M * d);
+  T.logits = A.take<float>(M * V);
+  T.dh = A.take<float>(M * d); T.dxn = A.take<float>(M * d); T.dattn = A.take<float>(M * D); T.dqkv = A.take<float>(M * 3 * D);
+  T.dact = A.take<float>(M * F); T.dgu = A.take<float>(M * 2 * F);
+  T.part = A.take<float>((size_t)kTrainSplits * M * std::max(std::max(d, D), F));
+  T.row_loss = A.take<float>(M);
+  T.targets = A.take<int32_t>(M);
+  if (out) *out = T;
   return (A.off + 255) & ~(size_t)255;
 }
 
@@ -1124,6 +1159,145 @@ int pass_get_tokens(pass_ctx *c, int slot, int first, int n, int32_t *out) {
   return PASS_OK;
 }
 
+size_t pass_train_bytes(const pass_config *cfg) {
+  if (!config_ok(cfg, nullptr) || cfg->k < 1) return 0;
+  return carve_train(*cfg, nullptr, nullptr);
+}
+
+int pass_train_begin(pass_ctx *c, void *device_workspace, size_t bytes, int32_t init_token) {
+  if (!c) return PASS_EINVAL;
+  if (!c->weights_loaded) return fail(c, PASS_ESTATE, "weights not loaded");
+  if (c->use_mfma) return fail(c, PASS_ESTATE, "training runs on the generic kernels: set the \"path\" option to 1 before pass_load_weights");
+  if (c->cfg.k < 1) return fail(c, PASS_EINVAL, "the model has no look-ahead embeddings (k = 0)");
+  if (!device_workspace || ((uintptr_t)device_workspace & 255) || bytes < carve_train(c->cfg, nullptr, nullptr))
+    return fail(c, PASS_EINVAL, "training workspace null, misaligned or smaller than pass_train_bytes");
+  if (init_token >= c->cfg.vocab) return fail(c, PASS_EINVAL, "init_token outside the vocabulary");
+  carve_train(c->cfg, (char *)device_workspace, &c->train);
+  if (!c->train_loss_host) HIP_TRY(c, hipHostMalloc((void **)&c->train_loss_host, sizeof(float) * kMaxRows, hipHostMallocDefault));
+  launch_lookahead_init(c->cfg.dtype, c->tok_emb, c->lookahead, init_token, c->cfg.k, c->P.d, c->train.master, c->train.m1,
+                        c->train.m2, c->stream);
+  HIP_TRY(c, hipGetLastError());
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  c->train.on = true;
+  c->train.step = 0;
+  return PASS_OK;
+}
+
+int pass_train_step(pass_ctx *c, const int32_t *slots, int n_slots, const int32_t *targets, const pass_adamw *opt, float *out_loss) {
+  if (!c) return PASS_EINVAL;
+  if (!c->train.on) return fail(c, PASS_ESTATE, "pass_train_begin has not been called");
+  int rc;
+  if ((rc = check_slots(c, slots, n_slots, 1))) return rc;
+  if (!targets || !opt || !(opt->lr >= 0.f) || !(opt->beta1 >= 0.f && opt->beta1 < 1.f) || !(opt->beta2 >= 0.f && opt->beta2 < 1.f) ||
+      !(opt->eps > 0.f) || !(opt->weight_decay >= 0.f))
+    return fail(c, PASS_EINVAL, "bad targets / optimiser parameters");
+  const int k = c->cfg.k, R = 1 + k, M = n_slots * R;
+  if (c->P.k_act != k || c->P.la_token >= 0)
+    return fail(c, PASS_ESTATE, "training uses all k look-ahead embeddings (\"lookahead_rows\" = k, \"lookahead_token\" = -1)");
+  int max_keys = 1;
+  std::vector<int32_t> tg(M);
+  for (int b = 0; b < n_slots; ++b) {
+    const Slot &s = c->slots[slots[b]];
+    if (s.kv_len + R > c->cfg.max_seq_len) return fail(c, PASS_ECAPACITY, "slot %d is full", slots[b]);
+    if (s.kv_len + R > kTrainMaxKeys) return fail(c, PASS_ECAPACITY, "slot %d: a training step takes at most %d keys", slots[b], kTrainMaxKeys);
+    if ((rc = ensure_pages(c, slots[b], s.kv_len + R))) return rc;
+    max_keys = std::max(max_keys, s.kv_len + R);
+    tg[b * R] = -1;  // the row of w_T predicts w_{T+1}: no loss there
+    for (int i = 0; i < k; ++i) {
+      const int32_t t = targets[b * k + i];
+      if (t < 0 || t >= c->cfg.vocab) return fail(c, PASS_EINVAL, "target %d of slot %d outside the vocabulary", i, slots[b]);
+      tg[b * R + 1 + i] = t;
+    }
+  }
+  if ((rc = set_step_slots(c, slots, n_slots))) return rc;
+  TrainWs &T = c->train;
+  const Params &P = c->P;
+  const int dt = c->cfg.dtype;
+  hipStream_t s = c->stream;
+  const size_t d = P.d, D = P.D, F = P.F, V = P.V;
+  HIP_TRY(c, hipMemcpyAsync(T.targets, tg.data(), sizeof(int32_t) * M, hipMemcpyHostToDevice, s));
+  // ---- forward: the drafting call on the generic kernels, look-ahead rows from the master values ----
+  const int S = choose_splits(c, n_slots, R, max_keys);
+  launch_assemble_train(P, dt, c->tok_emb, T.master, n_slots, R, s);
+  for (int l = 0; l < P.L; ++l) {
+    const LayerW &w = c->layers[l];
+    HIP_TRY(c, hipMemcpyAsync(T.save_h0 + (size_t)l * kMaxRows * d, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
+    launch_rmsnorm(P, dt, P.h, w.attn_norm, P.xn, M, s);
+    launch_gemm_generic(dt, P.xn, w.wqkv, P.qkv, M, 3 * P.D, P.d, 3 * P.D, nullptr, 0, s);
+    launch_rope_kv(P, dt, l, M, s);
+    HIP_TRY(c, hipMemcpy2DAsync(T.save_q + (size_t)l * kMaxRows * D, sizeof(float) * D, P.qkv, sizeof(float) * 3 * D, sizeof(float) * D, M,
+                                hipMemcpyDeviceToDevice, s));
+    launch_attention(P, dt, l, n_slots, R, S, 0, s);
+    launch_gemm_generic(dt, P.attn, w.wo, P.h, M, P.d, P.D, P.d, nullptr, 1, s);
+    HIP_TRY(c, hipMemcpyAsync(T.save_h1 + (size_t)l * kMaxRows * d, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
+    launch_rmsnorm(P, dt, P.h, w.ffn_norm, P.xn, M, s);
+    launch_gemm_generic(dt, P.xn, w.wgu, P.gu, M, 2 * P.F, P.d, 2 * P.F, nullptr, 0, s);
+    HIP_TRY(c, hipMemcpyAsync(T.save_gu + (size_t)l * kMaxRows * 2 * F, P.gu, sizeof(float) * M * 2 * F, hipMemcpyDeviceToDevice, s));
+    launch_silu_mul(P, M, s);
+    launch_gemm_generic(dt, P.act, w.wdown, P.h, M, P.d, P.F, P.d, nullptr, 1, s);
+  }
+  HIP_TRY(c, hipMemcpyAsync(T.save_hl, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
+  launch_rmsnorm(P, dt, P.h, c->final_norm, P.xn, M, s);
+  launch_gemm_generic(dt, P.xn, c->lm_head, T.logits, M, P.V, P.d, P.V, nullptr, 0, s);
+  // ---- loss on the look-ahead rows and its gradient, back through the frozen model ----
+  launch_ce_grad(T.logits, T.targets, 1.0f / (float)(n_slots * k), T.row_loss, M, P.V, s);
+  launch_gemm_t(dt, T.logits, (int)V, c->lm_head, T.part, T.dxn, (int)d, M, (int)V, (int)d, s);
+  launch_rmsnorm_bwd(P, dt, T.save_hl, c->final_norm, T.dxn, T.dh, M, 0, s);
+  for (int l = P.L - 1; l >= 0; --l) {
+    const LayerW &w = c->layers[l];
+    launch_gemm_t(dt, T.dh, (int)d, w.wdown, T.part, T.dact, (int)F, M, (int)d, (int)F, s);
+    launch_swiglu_bwd(P, T.save_gu + (size_t)l * kMaxRows * 2 * F, T.dact, T.dgu, M, s);
+    launch_gemm_t(dt, T.dgu, (int)(2 * F), w.wgu, T.part, T.dxn, (int)d, M, (int)(2 * F), (int)d, s);
+    launch_rmsnorm_bwd(P, dt, T.save_h1 + (size_t)l * kMaxRows * d, w.ffn_norm, T.dxn, T.dh, M, 1, s);
+    launch_gemm_t(dt, T.dh, (int)d, w.wo, T.part, T.dattn, (int)D, M, (int)d, (int)D, s);
+    launch_attn_bwd(P, dt, l, n_slots, R, max_keys, T.save_q + (size_t)l * kMaxRows * D, T.dattn, T.dqkv, s);
+    launch_gemm_t(dt, T.dqkv, (int)(3 * D), w.wqkv, T.part, T.dxn, (int)d, M, (int)(3 * D), (int)d, s);
+    launch_rmsnorm_bwd(P, dt, T.save_h0 + (size_t)l * kMaxRows * d, w.attn_norm, T.dxn, T.dh, M, 1, s);
+  }
+  // ---- AdamW on the look-ahead embeddings; the model's own tensor follows in its storage type ----
+  T.step += 1;
+  const float bc1 = (float)(1.0 - pow((double)opt->beta1, (double)T.step)), bc2 = (float)(1.0 - pow((double)opt->beta2, (double)T.step));
+  launch_lookahead_adamw(dt, T.dh, n_slots, R, P.d, T.grad, T.master, T.m1, T.m2, c->lookahead, opt->lr, opt->beta1, opt->beta2,
+                         opt->eps, opt->weight_decay, bc1, bc2, s);
+  HIP_TRY(c, hipGetLastError());
+  HIP_TRY(c, hipMemcpyAsync(c->train_loss_host, T.row_loss, sizeof(float) * M, hipMemcpyDeviceToHost, s));
+  HIP_TRY(c, hipStreamSynchronize(s));
+  if (out_loss) {
+    double sum = 0;
+    for (int m = 0; m < M; ++m) sum += c->train_loss_host[m];
+    *out_loss = (float)(sum / (n_slots * k));
+  }
+  return PASS_OK;
+}
+
+int pass_train_read(pass_ctx *c, int what, float *out) {
+  if (!c) return PASS_EINVAL;
+  if (!c->train.on) return fail(c, PASS_ESTATE, "pass_train_begin has not been called");
+  if (!out || what < 0 || what > 3) return fail(c, PASS_EINVAL, "bad argument");
+  const float *src[4] = {c->train.master, c->train.grad, c->train.m1, c->train.m2};
+  HIP_TRY(c, hipMemcpyAsync(out, src[what], sizeof(float) * c->cfg.k * c->P.d, hipMemcpyDeviceToHost, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  return PASS_OK;
+}
+
+int pass_train_resume(pass_ctx *c, const float *master, const float *m1, const float *m2, int64_t steps) {
+  if (!c) return PASS_EINVAL;
+  if (!c->train.on) return fail(c, PASS_ESTATE, "pass_train_begin has not been called");
+  if (steps < 0 || steps > (int64_t)1 << 40) return fail(c, PASS_EINVAL, "bad step count");
+  const size_t bytes = sizeof(float) * c->cfg.k * c->P.d;
+  const float *src[3] = {master, m1, m2};
+  float *dst[3] = {c->train.master, c->train.m1, c->train.m2};
+  for (int i = 0; i < 3; ++i)  // pageable host memory: the copy has left the caller's array when the call returns
+    if (src[i]) HIP_TRY(c, hipMemcpyAsync(dst[i], src[i], bytes, hipMemcpyHostToDevice, c->stream));
+  if (master) {
+    launch_lookahead_store(c->cfg.dtype, c->train.master, c->cfg.k, c->P.d, c->lookahead, c->stream);
+    HIP_TRY(c, hipGetLastError());
+  }
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  c->train.step = steps;
+  return PASS_OK;
+}
+
 int pass_attention_plan(int n_heads, int n_keys, int *n_splits, int *chunk_keys, int *grid_splits) {
   if (n_heads < 1 || n_keys < 1) return PASS_EINVAL;
   int ns, ch;
@@ -1271,6 +1445,7 @@ void pass_destroy(pass_ctx *c) {
   for (auto &g : c->graphs) (void)hipGraphExecDestroy(g.second);
   if (c->report_host) (void)hipHostFree(c->report_host);
   if (c->block_table_host) (void)hipHostFree(c->block_table_host);
+  if (c->train_loss_host) (void)hipHostFree(c->train_loss_host);
   delete c;
 }
 

@@ -230,4 +230,23 @@ int prefill_resid_strips(const Params &p, int M);
 
 void launch_gemm_logits(const Params &p, const GemmTuning &tn, const void *W, float *logits, int M, hipStream_t s);
 
+// ---- look-ahead embedding training (kernels_train.hip) ----
+constexpr int kTrainSplits = 32;    // row slices of a transposed projection (partial sums: kTrainSplits x M x K floats)
+constexpr int kTrainMaxKeys = 8192; // longest context a training step takes (scores of a row live in LDS)
+void launch_assemble_train(const Params &p, int dtype, const void *tok_emb, const float *master, int B, int R, hipStream_t s);
+void launch_ce_grad(float *logits, const int32_t *targets, float scale, float *row_loss, int M, int V, hipStream_t s);
+void launch_gemm_t(int dtype, const float *dY, int ldy, const void *W, float *part, float *out, int ldo, int M, int N, int K,
+                   hipStream_t s);
+void launch_rmsnorm_bwd(const Params &p, int dtype, const float *x, const void *gain, const float *dy, float *dx_acc, int M,
+                        int accumulate, hipStream_t s);
+void launch_swiglu_bwd(const Params &p, const float *gu, const float *dact, float *dgu, int M, hipStream_t s);
+void launch_attn_bwd(const Params &p, int dtype, int layer, int B, int R, int max_keys, const float *q_saved, const float *dattn,
+                     float *dqkv, hipStream_t s);
+void launch_lookahead_adamw(int dtype, const float *dh, int B, int R, int d, float *grad, float *master, float *m1, float *m2,
+                            void *model_la, float lr, float beta1, float beta2, float eps, float wd, float bc1, float bc2,
+                            hipStream_t s);
+void launch_lookahead_init(int dtype, const void *tok_emb, void *model_la, int token, int k, int d, float *master, float *m1,
+                           float *m2, hipStream_t s);
+void launch_lookahead_store(int dtype, const float *master, int k, int d, void *model_la, hipStream_t s);
+
 }  // namespace pass

@@ -1,0 +1,167 @@
+"""Look-ahead embedding training (pass_train_*) against the training oracle: loss, gradient and the
+AdamW trajectory of several steps on a batch of ragged prefixes, and the drafting call afterwards."""
+import copy
+
+import numpy as np
+import pytest
+
+import parity
+import pass_oracle as O
+import pass_train_oracle as TO
+from paper_2311_13581_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+TINY = synth.WORKLOADS["tiny_fp32_greedy"].shape
+SMALL_BF16 = synth.ModelShape(2, 256, 4, 64, 704, 512, dtype=synth.BF16)
+HD128_BF16 = synth.ModelShape(2, 256, 2, 128, 512, 384, dtype=synth.BF16)
+
+
+def _gpu(shape, W, k, max_slots, max_seq_len, page, options=None):
+    from paper_2311_13581_amd import binding
+    g = binding.Pass(binding.make_config(shape, k, max_slots, max_seq_len, page), options)
+    g.load_weights(W)
+    return g
+
+
+def _update_bound(opt, la, grad, lr, delta):
+    """How far one AdamW step may move apart when every gradient component is off by at most delta: the
+    oracle's own step taken at grad - delta, grad and grad + delta (the first steps divide a component
+    by its own magnitude, so a component within delta of zero may go either way by lr)."""
+    lo, mid, hi = (copy.deepcopy(opt).step(la, grad + s * delta, lr) for s in (-1.0, 0.0, 1.0))
+    return np.maximum(np.abs(lo - mid), np.abs(hi - mid))
+
+
+# bf16 models: the cache holds K and V in bf16 on both sides; a value that fp32 and fp64 arithmetic put on
+# different sides of a rounding boundary differs by 2^-9 of itself between them (measured: up to 8e-5 of
+# the largest gradient component, 1.5e-5 of the loss; fp32 models 5e-7 and 7e-8)
+@pytest.mark.parametrize("shape,page,lockstep,tol_loss,tol_grad",
+                         [(TINY, 16, False, 1e-6, 5e-6), (TINY, 16, True, 1e-6, 5e-6), (SMALL_BF16, 16, True, 6e-5, 4e-4),
+                          (HD128_BF16, 64, True, 6e-5, 4e-4)], ids=["fp32-free", "fp32", "bf16", "bf16-hd128"])
+def test_training_steps_match_the_oracle(shape, page, lockstep, tol_loss, tol_grad):
+    """Five AdamW steps on changing batches of three ragged prefixes (one of them longer than a page
+    and than the attention kernels' key step): the loss and the gradient of every step and the trained
+    values after it, against the fp64 oracle fed with the same weights; the embeddings start from the
+    embedding of one token, as in the paper.  "free": both sides run their own trajectory from the
+    common start; otherwise the oracle's state (values, moments, step count, rounded to fp32) is
+    written into the library before every step, so that every step is compared at the same point."""
+    k, init_token = 3, 7
+    W = synth.make_weights(shape, 13, k, 6.0)
+    g = _gpu(shape, W, k, 3, 160, page, {"path": 1})
+    g.train_begin(init_token)
+    la = TO._t(W["tok_emb"], shape.dtype)[init_token].numpy()[None, :].repeat(k, 0)
+    assert np.array_equal(g.train_read(0), la.astype(np.float32))
+    opt = TO.AdamW(la.size, 0.9, 0.999, 1e-8, 0.01)
+    rng = np.random.default_rng(3)
+    slack = np.zeros_like(la)
+    for step in range(5):
+        prefixes = [rng.integers(0, shape.vocab, n).astype(np.int32) for n in (5 + step, 21, 97 + 7 * step)]
+        targets = rng.integers(0, shape.vocab, (3, k)).astype(np.int32)
+        for i, p in enumerate(prefixes):
+            g.prefill(i, p, seq_id=i)
+        lr = 0.01 * (step + 1) / 5
+        if lockstep:
+            la = la.astype(np.float32).astype(np.float64)
+            opt.m = opt.m.astype(np.float32).astype(np.float64)
+            opt.v = opt.v.astype(np.float32).astype(np.float64)
+            g.train_resume(la, opt.m, opt.v, opt.t)
+            slack[:] = 0
+        loss = g.train_step([0, 1, 2], targets, lr)
+        o_loss, o_grad = TO.loss_and_grad(shape, W, la, [p.tolist() for p in prefixes], targets)
+        grad = g.train_read(1)
+        e_loss, e_grad, g_max = abs(loss - o_loss) / abs(o_loss), float(np.abs(grad - o_grad).max()), float(np.abs(o_grad).max())
+        print(f"step {step}: loss {loss:.6f} (oracle {o_loss:.6f}, rel {e_loss:.1e}) grad err {e_grad / g_max:.1e} of max {g_max:.3f}")
+        assert e_loss <= tol_loss, (step, loss, o_loss)
+        assert e_grad <= tol_grad * g_max, (step, e_grad, g_max)
+        slack = slack + 1.5 * _update_bound(opt, la, o_grad, lr, tol_grad * g_max) + 1e-6
+        la = opt.step(la, o_grad, lr)
+        over = float((np.abs(g.train_read(0) - la) - slack).max())
+        assert over <= 0, (step, over)
+        if lockstep:  # the moments, too
+            assert float(np.abs(g.train_read(2).ravel() - opt.m).max()) <= 0.11 * tol_grad * g_max + 1e-7
+            assert float(np.abs(g.train_read(3).ravel() - opt.v).max()) <= 0.003 * tol_grad * g_max * g_max + 1e-7
+        assert g.seq_len(0)[0] == len(prefixes[0]) - 1  # the slots are left as they were
+    g.close()
+
+
+def test_training_state_resumes():
+    """Two steps, state saved, two more steps; a fresh context resumed from the saved state takes the
+    same two steps to the same values bit for bit."""
+    shape, k = SMALL_BF16, 2
+    W = synth.make_weights(shape, 17, k, 6.0)
+    rng = np.random.default_rng(1)
+    batches = [([rng.integers(0, shape.vocab, n).astype(np.int32) for n in (9, 30)], rng.integers(0, shape.vocab, (2, k))) for _ in range(4)]
+
+    def run(g, which):
+        for prefixes, targets in which:
+            for i, p in enumerate(prefixes):
+                g.prefill(i, p, seq_id=i)
+            g.train_step([0, 1], targets, 0.01)
+
+    a = _gpu(shape, W, k, 2, 64, 16, {"path": 1})
+    a.train_begin(11)
+    run(a, batches[:2])
+    saved = [a.train_read(w) for w in (0, 2, 3)]
+    run(a, batches[2:])
+    b = _gpu(shape, W, k, 2, 64, 16, {"path": 1})
+    b.train_begin(-1)
+    b.train_resume(saved[0], saved[1], saved[2], 2)
+    run(b, batches[2:])
+    for w in (0, 2, 3):
+        assert np.array_equal(a.train_read(w), b.train_read(w)), w
+    a.close()
+    b.close()
+
+
+def test_drafting_call_uses_the_trained_embeddings_and_training_lowers_the_loss():
+    """Thirty steps on one fixed batch lower its loss; the drafting call then runs on the trained
+    embeddings: its logits equal the C oracle's with the trained values as look-ahead embeddings."""
+    shape, k = TINY, 2
+    W = synth.make_weights(shape, 21, k, 6.0)
+    g = _gpu(shape, W, k, 2, 96, 16, {"path": 1})
+    g.train_begin(-1)  # from the model's own look-ahead tensor
+    assert np.array_equal(g.train_read(0), W["lookahead"])
+    rng = np.random.default_rng(9)
+    prefixes = [rng.integers(0, shape.vocab, n).astype(np.int32) for n in (12, 40)]
+    targets = rng.integers(0, shape.vocab, (2, k)).astype(np.int32)
+    for i, p in enumerate(prefixes):
+        g.prefill(i, p, seq_id=i)
+    losses = [g.train_step([0, 1], targets, 0.01) for _ in range(30)]
+    assert losses[-1] < losses[0] - 0.3, losses
+    trained = g.train_read(0)
+    W2 = dict(W)
+    W2["lookahead"] = trained.copy()
+    s = O.Model(shape, W2, k).sequence(96, seq_id=0)
+    s.prefill(prefixes[0])
+    s.draft(0.0, 1)
+    g.draft([0], 0.0, 1)
+    parity.logits_error(g.get_logits(0, 0), s.logits(0), 1e-4, "drafting call after training")
+    g.verify([0], 0.0, 1)
+    g.close()
+
+
+def test_training_error_paths():
+    from paper_2311_13581_amd import binding
+    shape, k = SMALL_BF16, 2
+    W = synth.make_weights(shape, 5, k, 4.0)
+    g = _gpu(shape, W, k, 1, 64, 16)  # matrix-core path: no training there
+    with pytest.raises(binding.PassError) as e:
+        g.train_begin(3)
+    assert e.value.code == -2
+    g.close()
+    g = _gpu(shape, W, k, 1, 64, 16, {"path": 1})
+    g.prefill(0, [1, 2, 3])
+    with pytest.raises(binding.PassError) as e:
+        g.train_step([0], [[1, 2]], 0.01)  # before pass_train_begin
+    assert e.value.code == -2
+    g.train_begin(3)
+    with pytest.raises(binding.PassError) as e:
+        g.train_step([0], [[1, shape.vocab]], 0.01)
+    assert e.value.code == -1
+    g.set_option("lookahead_rows", 1)
+    with pytest.raises(binding.PassError) as e:
+        g.train_step([0], [[1, 2]], 0.01)
+    assert e.value.code == -2
+    g.set_option("lookahead_rows", 2)
+    assert g.train_step([0], [[1, 2]], 0.01) > 0
+    g.close()
