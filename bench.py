@@ -118,6 +118,44 @@ def cpu_baseline(w, k, W_host, prompt, n_iters=8, prompt_rows=32):
                       "excludes the prompt pass"}
 
 
+def train_report(binding, devgen, synth, torch, np, n_steps):
+    """Look-ahead embedding training (the paper's Training details: frozen model, batches of 8 sequences
+    cut at random positions, AdamW) on the 7B-shaped model: seconds per optimiser step, the prompt pass
+    of the batch's prefixes (generic kernels on this context) timed apart."""
+    w = synth.WORKLOADS["7b_b8_ragged_t1"]  # eight ragged prefixes, k = 4
+    prompts = synth.make_prompts(w)
+    g = binding.Pass(binding.make_config(w.shape, w.k, w.batch, max(len(p) for p in prompts) + 64, 64), {"path": 1})
+    g.load_weights(devgen.device_weights(w.shape, w.k, w.lm_head_scale, w.seed))
+    torch.cuda.empty_cache()
+    g.train_begin(0)
+    rng = np.random.default_rng(7)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i, p in enumerate(prompts):
+        g.prefill(i, p, seq_id=i)
+    torch.cuda.synchronize()
+    prefill_s = time.perf_counter() - t0
+    slots = list(range(w.batch))
+    losses = []
+    for _ in range(2):
+        g.train_step(slots, rng.integers(0, w.shape.vocab, (w.batch, w.k)), 0.01)
+    targets = rng.integers(0, w.shape.vocab, (w.batch, w.k))
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n_steps):
+        losses.append(g.train_step(slots, targets, 0.01))
+    torch.cuda.synchronize()
+    step_s = (time.perf_counter() - t0) / n_steps
+    g.close()
+    sh = w.shape
+    weight_bytes = 2 * (sh.n_layers * (4 * sh.d_model * sh.n_heads * sh.head_dim + 3 * sh.d_model * sh.d_ffn) + sh.vocab * sh.d_model)
+    return {"workload": w.name, "k": w.k, "batch": w.batch, "prefix_len": [len(p) for p in prompts], "steps": n_steps,
+            "ms_per_step": step_s * 1e3, "loss_first": losses[0], "loss_last": losses[-1],
+            # the frozen weights are read once forward and once backward
+            "weights_twice_GBps": 2 * weight_bytes / step_s / 1e9, "prefix_prompt_pass_ms": prefill_s * 1e3,
+            "path": "generic"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -140,6 +178,8 @@ def main():
                     help="tuning: launch shape override(s), kind*10000 + wavefronts*100 + unroll")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="tuning: a library option (pass_set_option) to set before the run")
+    ap.add_argument("--train-steps", type=int, default=0,
+                    help="also time that many look-ahead embedding training steps (a second context on the generic kernels)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (a kernel of known traffic, for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -297,6 +337,8 @@ def main():
         for _ in range(3):
             dst.copy_(src * 1)  # elementwise kernel: reads 256 MiB, writes 256 MiB (then a copy of the same size)
         torch.cuda.synchronize()
+    if args.train_steps > 0:
+        out["train"] = train_report(binding, devgen, synth, torch, np, args.train_steps)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, k, W_host, prompts[0])
     print(json.dumps(out))

@@ -435,7 +435,9 @@ __global__ __launch_bounds__(HD * Q) void attn_combine_kernel(Params p, int R, i
       l_n += sl[i] * f;
       v += sv[i][dim] * f;
     }
+    m_n = m_all;
   }
+  if (p.lse != nullptr && dim == 0) p.lse[(size_t)m * p.H + head] = dead ? 0.f : m_n + logf(l_n);
   float o = dead ? 0.f : v / l_n;
   if (OUT == 1) {
     // (hi, lo) pair in the tiled activation layout of the matrix-core GEMMs

@@ -233,137 +233,224 @@ void launch_swiglu_bwd(const Params &p, const float *gu, const float *dact, floa
 }
 
 // ---------------------------------------------------------------------------------------------
-// Attention backward for the R rows of one slot and one head.  Row r attends to keys 0 .. pos0 + r:
-//   P = softmax(scale q K^T),  O = P V,  dP_j = dO . V_j,  dS_j = P_j (dP_j - sum_i P_i dP_i),
-//   dq = scale sum_j dS_j K_j,  and for the keys that are rows of this very block (positions >= pos0)
-//   dK_j += scale dS_j q,  dV_j += P_j dO.
-// Keys before pos0 are the prompt's: nothing upstream of them is trained.  The rows are walked in
-// order, the block keys' sums kept in registers (one dimension per thread), so the result does not
-// depend on scheduling.  Scores live in LDS (`max_keys` floats, dynamic).
-// q is the rotated query kept by the forward pass; dq / dK / dV go to dqkv [M][3D] (still rotated:
-// rope_bwd_kernel turns them back).  K/V come from the cache in its storage type (a bfloat16 cache
-// holds rounded values: the gradient passes through the rounding).
+// Attention backward for the R rows of one slot, one head and one chunk of kTrainAttnChunk keys.
+// Row r attends to keys 0 .. pos0 + r.  With the forward pass's ln-sum-exp of the row (lse) and its
+// output O, a chunk of keys needs nothing from the others:
+//   P_j = exp(scale q.K_j - lse),  dP_j = dO.V_j,  D = dO.O (= sum_j P_j dP_j),  dS_j = P_j (dP_j - D),
+//   dq = scale sum_j dS_j K_j (summed over the chunks afterwards, in chunk order),
+// and for the keys that are rows of this very block (positions >= pos0; each lies in one chunk):
+//   dK_j = scale sum_r dS_rj q_r,  dV_j = sum_r P_rj dO_r.
+// Keys before pos0 are the prompt's: nothing upstream of them is trained.  K and V come from the
+// cache in its storage type (a bfloat16 cache holds rounded values: the gradient passes through
+// the rounding), in tiles of 32 keys staged in LDS as fp32, whichever way the V pages are laid out.
+// q is the rotated query kept by the forward pass; dq / dK / dV are still rotated here:
+// attn_bwd_finish_kernel adds up the chunks and turns them back.
 // ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void load8(const float *p, size_t off, float (&v)[8]) {
+  const float4 a = *(const float4 *)(p + off), b = *(const float4 *)(p + off + 4);
+  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t *p, size_t off, float (&v)[8]) {
+  const uint4 a = *(const uint4 *)(p + off);
+  const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    v[2 * e] = __uint_as_float(w[e] << 16);
+    v[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+  }
+}
+
 template <typename T, int HD>
-__global__ __launch_bounds__(256) void attn_bwd_kernel(Params p, int layer, int R, const float *q_saved, const float *dattn,
-                                                       float *dqkv) {
-  extern __shared__ float sc[];  // scores -> exponentials -> dS of the row in hand
-  __shared__ float red[4];
-  __shared__ float pblk[kMaxK + 1];
-  constexpr int PARTS = 256 / HD;
-  __shared__ float comb[PARTS][HD];
-  const int head = blockIdx.x, b = blockIdx.y;
+__global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer, int R, const float *q_saved, int ldq,
+                                                             const float *o_f32, const uint16_t *o_x, const float *lse,
+                                                             const float *dattn, float *dq_part, float *dqkv) {
+  constexpr int TK = 32, LD = HD + 4, RMAX = kMaxK + 1, PARTS = 256 / HD;
+  __shared__ __align__(16) float tiles[2][TK][LD];  // K tile, V tile; at the end the parts' dq
+  __shared__ __align__(16) float qs[RMAX][HD], dos[RMAX][HD];
+  __shared__ float lse_s[RMAX], D_s[RMAX];
+  __shared__ float ds_s[RMAX][TK], p_s[RMAX][TK];
+  static_assert(PARTS * RMAX * HD <= 2 * TK * LD, "the parts' dq must fit the tiles");
+  const int split = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
   const int m0 = b * R;
   const int slot = p.row_slot[m0], pos0 = p.row_pos[m0];
+  const int n_keys = pos0 + R;
+  const int k_lo = split * kTrainAttnChunk;
+  if (slot < 0 || k_lo >= n_keys) return;  // uniform over the workgroup
+  const int k_hi = min(n_keys, k_lo + kTrainAttnChunk);
   const T *kpool = (const T *)p.k_pool, *vpool = (const T *)p.v_pool;
   const float scale = rsqrtf((float)HD);
-  const int dim = threadIdx.x % HD, part = threadIdx.x / HD;
-  float dk_acc[kMaxK + 1], dv_acc[kMaxK + 1];
-#pragma unroll
-  for (int j = 0; j <= kMaxK; ++j) dk_acc[j] = dv_acc[j] = 0.f;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  for (int r = 0; r < R; ++r) {
-    const int n_keys = pos0 + r + 1;
-    const float *qr = q_saved + (size_t)(m0 + r) * p.D + head * HD;
-    const float *dor = dattn + (size_t)(m0 + r) * p.D + head * HD;
-    __syncthreads();  // the previous row's scores have been consumed
-    // scores
-    float mx = -INFINITY;
-    for (int j = threadIdx.x; j < n_keys; j += 256) {
-      const size_t off = kv_offset(p, layer, slot, j, head);
-      float s = 0.f;
-      for (int i = 0; i < HD; ++i) s = fmaf(qr[i], load_f(kpool, off + i), s);
-      s *= scale;
-      sc[j] = s;
-      mx = fmaxf(mx, s);
-    }
-    mx = block_max_256(mx, red);
-    float se = 0.f;
-    for (int j = threadIdx.x; j < n_keys; j += 256) {
-      const float e = expf(sc[j] - mx);
-      sc[j] = e;
-      se += e;
-    }
-    se = block_sum_256(se, red);
-    const float inv = 1.f / se;
-    // D = sum_j P_j (dO . V_j)
-    float dsum = 0.f;
-    for (int j = threadIdx.x; j < n_keys; j += 256) {
-      const size_t off = kv_offset(p, layer, slot, j, head);
-      float dp = 0.f;
-      for (int i = 0; i < HD; ++i) dp = fmaf(dor[i], load_f(vpool, off + i), dp);
-      dsum += sc[j] * inv * dp;
-    }
-    dsum = block_sum_256(dsum, red);
-    // dS_j in place; P of the block's own keys kept aside
-    for (int j = threadIdx.x; j < n_keys; j += 256) {
-      const size_t off = kv_offset(p, layer, slot, j, head);
-      float dp = 0.f;
-      for (int i = 0; i < HD; ++i) dp = fmaf(dor[i], load_f(vpool, off + i), dp);
-      const float pj = sc[j] * inv;
-      if (j >= pos0) pblk[j - pos0] = pj;
-      sc[j] = pj * (dp - dsum);
-    }
-    __syncthreads();
-    // dq: thread (part, dim) sums the keys j = part, part + PARTS, ...; the parts are added in order
-    float dq = 0.f;
-    for (int j = part; j < n_keys; j += PARTS) dq = fmaf(sc[j], load_f(kpool, kv_offset(p, layer, slot, j, head) + dim), dq);
-    comb[part][dim] = dq;
-    __syncthreads();
-    if (part == 0) {
-      float t = comb[0][dim];
-#pragma unroll
-      for (int q2 = 1; q2 < PARTS; ++q2) t += comb[q2][dim];
-      dqkv[(size_t)(m0 + r) * 3 * p.D + head * HD + dim] = t * scale;
-      const float qd = qr[dim], dod = dor[dim];
-#pragma unroll
-      for (int jj = 0; jj <= kMaxK; ++jj)
-        if (jj <= r) {
-          dk_acc[jj] = fmaf(sc[pos0 + jj] * scale, qd, dk_acc[jj]);
-          dv_acc[jj] = fmaf(pblk[jj], dod, dv_acc[jj]);
-        }
-    }
+  for (int idx = tid; idx < R * HD; idx += 256) {
+    const int r = idx / HD, dm = idx % HD;
+    qs[r][dm] = q_saved[(size_t)(m0 + r) * ldq + head * HD + dm];
+    dos[r][dm] = dattn[(size_t)(m0 + r) * p.D + head * HD + dm];
   }
-  if (part == 0) {
-#pragma unroll
-    for (int jj = 0; jj <= kMaxK; ++jj)
-      if (jj < R) {
-        dqkv[(size_t)(m0 + jj) * 3 * p.D + p.D + head * HD + dim] = dk_acc[jj];
-        dqkv[(size_t)(m0 + jj) * 3 * p.D + 2 * p.D + head * HD + dim] = dv_acc[jj];
+  __syncthreads();
+  for (int r = wave; r < R; r += 4) {  // D of row r: one wavefront, lanes over the dimensions
+    float acc = 0.f;
+    for (int dm = lane; dm < HD; dm += 64) {
+      float o;
+      if (o_f32) {
+        o = o_f32[(size_t)(m0 + r) * p.D + head * HD + dm];
+      } else {
+        const uint16_t *x = o_x + xs_index(m0 + r, p.D, head * HD + dm);
+        o = bf16_to_f32(x[0]) + bf16_to_f32(x[kXsLoOffset]);
       }
+      acc = fmaf(dos[r][dm], o, acc);
+    }
+#pragma unroll
+    for (int o2 = 32; o2 > 0; o2 >>= 1) acc += __shfl_xor(acc, o2);
+    if (lane == 0) {
+      D_s[r] = acc;
+      lse_s[r] = lse[(size_t)(m0 + r) * p.H + head];
+    }
+  }
+
+  const int dim = tid % HD, part = tid / HD;
+  float dq[RMAX];
+#pragma unroll
+  for (int r = 0; r < RMAX; ++r) dq[r] = 0.f;
+
+  for (int t0 = k_lo; t0 < k_hi; t0 += TK) {
+    __syncthreads();  // the previous tile has been consumed (first trip: D_s and lse_s are in place)
+    for (int c = tid; c < TK * HD / 8; c += 256) {
+      const int key = c / (HD / 8), d0 = (c % (HD / 8)) * 8, j = t0 + key;
+      float kv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, vv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      if (j < k_hi) {
+        const size_t off = kv_offset(p, layer, slot, j, head) + d0;
+        load8(kpool, off, kv);
+        if (!p.v_transposed) load8(vpool, off, vv);
+      }
+      *(float4 *)&tiles[0][key][d0] = make_float4(kv[0], kv[1], kv[2], kv[3]);
+      *(float4 *)&tiles[0][key][d0 + 4] = make_float4(kv[4], kv[5], kv[6], kv[7]);
+      if (!p.v_transposed) {
+        *(float4 *)&tiles[1][key][d0] = make_float4(vv[0], vv[1], vv[2], vv[3]);
+        *(float4 *)&tiles[1][key][d0 + 4] = make_float4(vv[4], vv[5], vv[6], vv[7]);
+      }
+    }
+    if (p.v_transposed) {
+      // pages hold [head][dim][page_size]: eight consecutive keys of one dimension per load (a tile
+      // starts at a multiple of 32 keys and a page holds a multiple of 32, so they share a page)
+      for (int c = tid; c < HD * (TK / 8); c += 256) {
+        const int dv = c / (TK / 8), key0 = (c % (TK / 8)) * 8, j0 = t0 + key0;
+        float vv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if (j0 < k_hi) {
+          const int page = p.block_table[(size_t)slot * p.pages_per_seq + (j0 >> p.page_shift)];
+          const size_t off = ((((size_t)layer * p.n_pages + page) * p.H + head) * p.hd + dv) * p.page_size + (j0 & (p.page_size - 1));
+          load8(vpool, off, vv);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tiles[1][key0 + e][dv] = (j0 + e < k_hi) ? vv[e] : 0.f;  // unwritten positions hold anything
+      }
+    }
+    __syncthreads();
+    {  // scores, probabilities, dS: thread = (key, row r = rs, rs + 8)
+      const int key = tid & 31, rs = tid >> 5, j = t0 + key;
+      for (int r = rs; r < R; r += 8) {
+        float sc = 0.f, dp = 0.f;
+#pragma unroll 8
+        for (int d4 = 0; d4 < HD; d4 += 4) {
+          const float4 kq = *(const float4 *)&tiles[0][key][d4], vq = *(const float4 *)&tiles[1][key][d4];
+          const float4 qq = *(const float4 *)&qs[r][d4], dd = *(const float4 *)&dos[r][d4];
+          sc = fmaf(qq.x, kq.x, sc); sc = fmaf(qq.y, kq.y, sc); sc = fmaf(qq.z, kq.z, sc); sc = fmaf(qq.w, kq.w, sc);
+          dp = fmaf(dd.x, vq.x, dp); dp = fmaf(dd.y, vq.y, dp); dp = fmaf(dd.z, vq.z, dp); dp = fmaf(dd.w, vq.w, dp);
+        }
+        const bool ok = j < k_hi && j <= pos0 + r;
+        const float pj = ok ? expf(sc * scale - lse_s[r]) : 0.f;
+        p_s[r][key] = pj;
+        ds_s[r][key] = ok ? pj * (dp - D_s[r]) : 0.f;
+      }
+    }
+    __syncthreads();
+    // dq: thread (part, dim) takes the keys part, part + PARTS, ...
+    for (int key = part; key < TK; key += PARTS) {
+      const float kd = tiles[0][key][dim];
+#pragma unroll
+      for (int r = 0; r < RMAX; ++r)
+        if (r < R) dq[r] = fmaf(ds_s[r][key], kd, dq[r]);
+    }
+    // the block's own keys in this tile
+    for (int j = max(t0, pos0) + part; j < min(t0 + TK, k_hi); j += PARTS) {
+      const int key = j - t0, jj = j - pos0;
+      float dk = 0.f, dvv = 0.f;
+      for (int r = jj; r < R; ++r) {
+        dk = fmaf(ds_s[r][key], qs[r][dim], dk);
+        dvv = fmaf(p_s[r][key], dos[r][dim], dvv);
+      }
+      dqkv[(size_t)(m0 + jj) * 3 * p.D + p.D + head * HD + dim] = dk * scale;
+      dqkv[(size_t)(m0 + jj) * 3 * p.D + 2 * p.D + head * HD + dim] = dvv;
+    }
+  }
+  __syncthreads();
+  float *comb = &tiles[0][0][0];  // [PARTS][RMAX][HD]
+#pragma unroll
+  for (int r = 0; r < RMAX; ++r)
+    if (r < R) comb[(part * RMAX + r) * HD + dim] = dq[r];
+  __syncthreads();
+  if (part == 0) {
+    for (int r = 0; r < R; ++r) {
+      float t = comb[r * HD + dim];
+#pragma unroll
+      for (int q2 = 1; q2 < PARTS; ++q2) t += comb[(q2 * RMAX + r) * HD + dim];
+      dq_part[((size_t)split * kMaxRows + m0 + r) * p.D + head * HD + dim] = t * scale;
+    }
   }
 }
 
-// dq and dk back through the rotary embedding: the transpose of a rotation is the opposite rotation
-__global__ __launch_bounds__(256) void rope_bwd_kernel(Params p, float *dqkv) {
+// The chunks' dq added in chunk order; dq and dK back through the rotary embedding (the transpose of a
+// rotation is the opposite rotation); the row of dqkv as fp32 in place or as (hi, lo) tiles for the
+// matrix-core projection that follows.  Four consecutive features (two rotary pairs) per thread.
+__global__ __launch_bounds__(256) void attn_bwd_finish_kernel(Params p, int R, const float *dq_part, float *dqkv,
+                                                              uint16_t *dqkv_x) {
   const int m = blockIdx.x, half = p.hd / 2;
-  for (int idx = threadIdx.x; idx < 2 * p.H * half; idx += 256) {
-    const int which = idx / (p.H * half), rem = idx % (p.H * half);
-    const int h = rem / half, i = rem % half;
-    const float cs = p.rope_cos[(size_t)m * half + i], sn = p.rope_sin[(size_t)m * half + i];
-    float *v = dqkv + (size_t)m * 3 * p.D + (size_t)which * p.D + h * p.hd + 2 * i;
-    const float a = v[0], b2 = v[1];
-    v[0] = a * cs + b2 * sn;
-    v[1] = -a * sn + b2 * cs;
+  if (p.row_slot[m] < 0) return;
+  const int n_splits = (p.row_pos[(m / R) * R] + R + kTrainAttnChunk - 1) / kTrainAttnChunk;
+  for (int idx = threadIdx.x; idx < 3 * p.D / 4; idx += 256) {
+    const int col = idx * 4, which = col / p.D, c = col - which * p.D;
+    float t[4];
+    if (which == 0) {
+      t[0] = t[1] = t[2] = t[3] = 0.f;
+      for (int s = 0; s < n_splits; ++s) {
+        const float4 v = *(const float4 *)(dq_part + ((size_t)s * kMaxRows + m) * p.D + c);
+        t[0] += v.x; t[1] += v.y; t[2] += v.z; t[3] += v.w;
+      }
+    } else {
+      const float4 v = *(const float4 *)(dqkv + (size_t)m * 3 * p.D + col);
+      t[0] = v.x; t[1] = v.y; t[2] = v.z; t[3] = v.w;
+    }
+    if (which < 2) {
+      const int i = (c % p.hd) / 2;
+      const float *cs = p.rope_cos + (size_t)m * half + i, *sn = p.rope_sin + (size_t)m * half + i;
+      const float a0 = t[0], b0 = t[1], a1 = t[2], b1 = t[3];
+      t[0] = a0 * cs[0] + b0 * sn[0];
+      t[1] = -a0 * sn[0] + b0 * cs[0];
+      t[2] = a1 * cs[1] + b1 * sn[1];
+      t[3] = -a1 * sn[1] + b1 * cs[1];
+    }
+    if (dqkv_x)
+      store_split4(dqkv_x, m, 3 * p.D, col, t);
+    else
+      *(float4 *)(dqkv + (size_t)m * 3 * p.D + col) = make_float4(t[0], t[1], t[2], t[3]);
   }
 }
 
-void launch_attn_bwd(const Params &p, int dtype, int layer, int B, int R, int max_keys, const float *q_saved, const float *dattn,
-                     float *dqkv, hipStream_t s) {
-  dim3 grid(p.H, B);
-  const size_t lds = (size_t)max_keys * sizeof(float);
+void launch_attn_bwd(const Params &p, int dtype, int layer, int B, int R, int max_keys, const float *q_saved, int ldq,
+                     const float *o, const uint16_t *o_x, const float *lse, const float *dattn, float *dq_part, float *dqkv,
+                     uint16_t *dqkv_x, hipStream_t s) {
+  dim3 grid((max_keys + kTrainAttnChunk - 1) / kTrainAttnChunk, p.H, B);
   if (p.hd == 128) {
     if (dtype == PASS_F32)
-      attn_bwd_kernel<float, 128><<<grid, 256, lds, s>>>(p, layer, R, q_saved, dattn, dqkv);
+      attn_bwd_split_kernel<float, 128><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, dq_part, dqkv);
     else
-      attn_bwd_kernel<bf16_t, 128><<<grid, 256, lds, s>>>(p, layer, R, q_saved, dattn, dqkv);
+      attn_bwd_split_kernel<bf16_t, 128><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, dq_part, dqkv);
   } else {
     if (dtype == PASS_F32)
-      attn_bwd_kernel<float, 64><<<grid, 256, lds, s>>>(p, layer, R, q_saved, dattn, dqkv);
+      attn_bwd_split_kernel<float, 64><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, dq_part, dqkv);
     else
-      attn_bwd_kernel<bf16_t, 64><<<grid, 256, lds, s>>>(p, layer, R, q_saved, dattn, dqkv);
+      attn_bwd_split_kernel<bf16_t, 64><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, dq_part, dqkv);
   }
-  rope_bwd_kernel<<<B * R, 256, 0, s>>>(p, dqkv);
+  attn_bwd_finish_kernel<<<B * R, 256, 0, s>>>(p, R, dq_part, dqkv, dqkv_x);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -46,11 +46,16 @@ struct TrainWs {
   bool on = false;
   int64_t step = 0;  // optimiser steps taken (AdamW's bias correction)
   float *master, *m1, *m2, *grad;                    // [k][d] fp32: trained values, AdamW moments, last gradient
-  float *save_h0, *save_h1, *save_q, *save_gu;       // per layer [L][kMaxRows][d | d | D | 2F]: what the backward pass needs
+  // what the backward pass needs of every layer, [L][kMaxRows][..]: the residual stream before the two norms (d each),
+  // the layer's q | k | v workspace (3D; the rotated queries are what is used), the attention output (D) and the
+  // ln-sum-exp of its rows (H), the gate | up pre-activations (2F).  The forward pass writes them in place: its
+  // workspace pointers are set to the layer's area.
+  float *save_h0, *save_h1, *save_qkv, *save_attn, *save_lse, *save_gu;
   float *save_hl;                                    // [kMaxRows][d] residual stream before the final norm
   float *logits;                                     // [kMaxRows][V] logits, then d loss / d logits
   float *dh, *dxn, *dattn, *dqkv, *dact, *dgu;       // gradients of the rows' activations
   float *part;                                       // [kTrainSplits][kMaxRows][max(d, D, F)] slice sums of a transposed projection
+  float *dq_part;                                    // [kTrainAttnSplits][kMaxRows][D] the key chunks' shares of dq
   float *row_loss;                                   // [kMaxRows]
   int32_t *targets;                                  // [kMaxRows] target token of a row, -1 = no loss
 };
@@ -247,12 +252,14 @@ size_t carve_train(const pass_config &c, char *base, TrainWs *out) {
   TrainWs T;
   T.master = A.take<float>(kd); T.m1 = A.take<float>(kd); T.m2 = A.take<float>(kd); T.grad = A.take<float>(kd);
   T.save_h0 = A.take<float>(L * M * d); T.save_h1 = A.take<float>(L * M * d);
-  T.save_q = A.take<float>(L * M * D); T.save_gu = A.take<float>(L * M * 2 * F);
+  T.save_qkv = A.take<float>(L * M * 3 * D); T.save_attn = A.take<float>(L * M * D); T.save_lse = A.take<float>(L * M * c.n_heads);
+  T.save_gu = A.take<float>(L * M * 2 * F);
   T.save_hl = A.take<float>(M * d);
   T.logits = A.take<float>(M * V);
   T.dh = A.take<float>(M * d); T.dxn = A.take<float>(M * d); T.dattn = A.take<float>(M * D); T.dqkv = A.take<float>(M * 3 * D);
   T.dact = A.take<float>(M * F); T.dgu = A.take<float>(M * 2 * F);
   T.part = A.take<float>((size_t)kTrainSplits * M * std::max(std::max(d, D), F));
+  T.dq_part = A.take<float>((size_t)kTrainAttnSplits * M * D);
   T.row_loss = A.take<float>(M);
   T.targets = A.take<int32_t>(M);
   if (out) *out = T;
@@ -1211,28 +1218,30 @@ int pass_train_step(pass_ctx *c, const int32_t *slots, int n_slots, const int32_
   }
   if ((rc = set_step_slots(c, slots, n_slots))) return rc;
   TrainWs &T = c->train;
-  const Params &P = c->P;
+  Params P = c->P;
   const int dt = c->cfg.dtype;
   hipStream_t s = c->stream;
-  const size_t d = P.d, D = P.D, F = P.F, V = P.V;
+  const size_t d = P.d, D = P.D, F = P.F, V = P.V, H = P.H;
   HIP_TRY(c, hipMemcpyAsync(T.targets, tg.data(), sizeof(int32_t) * M, hipMemcpyHostToDevice, s));
-  // ---- forward: the drafting call on the generic kernels, look-ahead rows from the master values ----
+  // ---- forward: the drafting call on the generic kernels, look-ahead rows from the master values; each layer
+  // works in its own area of the workspace, so what the backward pass needs is simply left there ----
   const int S = choose_splits(c, n_slots, R, max_keys);
   launch_assemble_train(P, dt, c->tok_emb, T.master, n_slots, R, s);
   for (int l = 0; l < P.L; ++l) {
     const LayerW &w = c->layers[l];
+    P.qkv = T.save_qkv + (size_t)l * kMaxRows * 3 * D;
+    P.attn = T.save_attn + (size_t)l * kMaxRows * D;
+    P.lse = T.save_lse + (size_t)l * kMaxRows * H;
+    P.gu = T.save_gu + (size_t)l * kMaxRows * 2 * F;
     HIP_TRY(c, hipMemcpyAsync(T.save_h0 + (size_t)l * kMaxRows * d, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
     launch_rmsnorm(P, dt, P.h, w.attn_norm, P.xn, M, s);
     launch_gemm_generic(dt, P.xn, w.wqkv, P.qkv, M, 3 * P.D, P.d, 3 * P.D, nullptr, 0, s);
     launch_rope_kv(P, dt, l, M, s);
-    HIP_TRY(c, hipMemcpy2DAsync(T.save_q + (size_t)l * kMaxRows * D, sizeof(float) * D, P.qkv, sizeof(float) * 3 * D, sizeof(float) * D, M,
-                                hipMemcpyDeviceToDevice, s));
     launch_attention(P, dt, l, n_slots, R, S, 0, s);
     launch_gemm_generic(dt, P.attn, w.wo, P.h, M, P.d, P.D, P.d, nullptr, 1, s);
     HIP_TRY(c, hipMemcpyAsync(T.save_h1 + (size_t)l * kMaxRows * d, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
     launch_rmsnorm(P, dt, P.h, w.ffn_norm, P.xn, M, s);
     launch_gemm_generic(dt, P.xn, w.wgu, P.gu, M, 2 * P.F, P.d, 2 * P.F, nullptr, 0, s);
-    HIP_TRY(c, hipMemcpyAsync(T.save_gu + (size_t)l * kMaxRows * 2 * F, P.gu, sizeof(float) * M * 2 * F, hipMemcpyDeviceToDevice, s));
     launch_silu_mul(P, M, s);
     launch_gemm_generic(dt, P.act, w.wdown, P.h, M, P.d, P.F, P.d, nullptr, 1, s);
   }
@@ -1250,7 +1259,9 @@ int pass_train_step(pass_ctx *c, const int32_t *slots, int n_slots, const int32_
     launch_gemm_t(dt, T.dgu, (int)(2 * F), w.wgu, T.part, T.dxn, (int)d, M, (int)(2 * F), (int)d, s);
     launch_rmsnorm_bwd(P, dt, T.save_h1 + (size_t)l * kMaxRows * d, w.ffn_norm, T.dxn, T.dh, M, 1, s);
     launch_gemm_t(dt, T.dh, (int)d, w.wo, T.part, T.dattn, (int)D, M, (int)d, (int)D, s);
-    launch_attn_bwd(P, dt, l, n_slots, R, max_keys, T.save_q + (size_t)l * kMaxRows * D, T.dattn, T.dqkv, s);
+    launch_attn_bwd(P, dt, l, n_slots, R, max_keys, T.save_qkv + (size_t)l * kMaxRows * 3 * D, (int)(3 * D),
+                    T.save_attn + (size_t)l * kMaxRows * D, nullptr, T.save_lse + (size_t)l * kMaxRows * H, T.dattn, T.dq_part,
+                    T.dqkv, nullptr, s);
     launch_gemm_t(dt, T.dqkv, (int)(3 * D), w.wqkv, T.part, T.dxn, (int)d, M, (int)(3 * D), (int)d, s);
     launch_rmsnorm_bwd(P, dt, T.save_h0 + (size_t)l * kMaxRows * d, w.attn_norm, T.dxn, T.dh, M, 1, s);
   }

@@ -110,6 +110,7 @@ struct Params {
   uint16_t *xg;      // K = d  h * gain of the next norm
   float *ssq;           // [d/16][kMaxRows] per-strip partial sums of h^2
   float *part_acc, *part_m, *part_l;  // attention partials [M][H][S][hd], [M][H][S]
+  float *lse;  // [M][H], or null: where the attention combine also leaves ln sum exp of the row's scaled scores (training)
   // K/V pools: [layer][page][head][page_size][hd] in the model's storage type
   void *k_pool, *v_pool;
 };
@@ -232,7 +233,9 @@ void launch_gemm_logits(const Params &p, const GemmTuning &tn, const void *W, fl
 
 // ---- look-ahead embedding training (kernels_train.hip) ----
 constexpr int kTrainSplits = 32;    // row slices of a transposed projection (partial sums: kTrainSplits x M x K floats)
-constexpr int kTrainMaxKeys = 8192; // longest context a training step takes (scores of a row live in LDS)
+constexpr int kTrainMaxKeys = 8192; // longest context a training step takes
+constexpr int kTrainAttnChunk = 256; // keys per workgroup of the attention backward
+constexpr int kTrainAttnSplits = kTrainMaxKeys / kTrainAttnChunk;  // its partial dq: [kTrainAttnSplits][kMaxRows][D] floats
 void launch_assemble_train(const Params &p, int dtype, const void *tok_emb, const float *master, int B, int R, hipStream_t s);
 void launch_ce_grad(float *logits, const int32_t *targets, float scale, float *row_loss, int M, int V, hipStream_t s);
 void launch_gemm_t(int dtype, const float *dY, int ldy, const void *W, float *part, float *out, int ldo, int M, int N, int K,
@@ -240,8 +243,12 @@ void launch_gemm_t(int dtype, const float *dY, int ldy, const void *W, float *pa
 void launch_rmsnorm_bwd(const Params &p, int dtype, const float *x, const void *gain, const float *dy, float *dx_acc, int M,
                         int accumulate, hipStream_t s);
 void launch_swiglu_bwd(const Params &p, const float *gu, const float *dact, float *dgu, int M, hipStream_t s);
-void launch_attn_bwd(const Params &p, int dtype, int layer, int B, int R, int max_keys, const float *q_saved, const float *dattn,
-                     float *dqkv, hipStream_t s);
+// q_saved [M][ldq] rotated queries; o / o_x: the forward pass's attention output as fp32 [M][D] or as (hi, lo) tiles
+// (one of them null); lse [M][H]; dattn [M][D]; dq_part: workspace; result: dqkv [M][3D] fp32, or, with dqkv_x not
+// null, (hi, lo) tiles of it (dqkv still serves as workspace)
+void launch_attn_bwd(const Params &p, int dtype, int layer, int B, int R, int max_keys, const float *q_saved, int ldq,
+                     const float *o, const uint16_t *o_x, const float *lse, const float *dattn, float *dq_part, float *dqkv,
+                     uint16_t *dqkv_x, hipStream_t s);
 void launch_lookahead_adamw(int dtype, const float *dh, int B, int R, int d, float *grad, float *master, float *m1, float *m2,
                             void *model_la, float lr, float beta1, float beta2, float eps, float wd, float bc1, float bc2,
                             hipStream_t s);
