@@ -118,13 +118,13 @@ def cpu_baseline(w, k, W_host, prompt, n_iters=8, prompt_rows=32):
                       "excludes the prompt pass"}
 
 
-def train_report(binding, devgen, synth, torch, np, n_steps):
+def train_report(binding, devgen, synth, torch, np, n_steps, path):
     """Look-ahead embedding training (the paper's Training details: frozen model, batches of 8 sequences
     cut at random positions, AdamW) on the 7B-shaped model: seconds per optimiser step, the prompt pass
-    of the batch's prefixes (generic kernels on this context) timed apart."""
+    of the batch's prefixes timed apart."""
     w = synth.WORKLOADS["7b_b8_ragged_t1"]  # eight ragged prefixes, k = 4
     prompts = synth.make_prompts(w)
-    g = binding.Pass(binding.make_config(w.shape, w.k, w.batch, max(len(p) for p in prompts) + 64, 64), {"path": 1})
+    g = binding.Pass(binding.make_config(w.shape, w.k, w.batch, max(len(p) for p in prompts) + 64, 64), {"path": path})
     g.load_weights(devgen.device_weights(w.shape, w.k, w.lm_head_scale, w.seed))
     torch.cuda.empty_cache()
     g.train_begin(0)
@@ -153,7 +153,7 @@ def train_report(binding, devgen, synth, torch, np, n_steps):
             "ms_per_step": step_s * 1e3, "loss_first": losses[0], "loss_last": losses[-1],
             # the frozen weights are read once forward and once backward
             "weights_twice_GBps": 2 * weight_bytes / step_s / 1e9, "prefix_prompt_pass_ms": prefill_s * 1e3,
-            "path": "generic"}
+            "path": "generic" if path else "auto"}
 
 
 def main():
@@ -179,7 +179,7 @@ def main():
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="tuning: a library option (pass_set_option) to set before the run")
     ap.add_argument("--train-steps", type=int, default=0,
-                    help="also time that many look-ahead embedding training steps (a second context on the generic kernels)")
+                    help="also time that many look-ahead embedding training steps (on a context of their own)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (a kernel of known traffic, for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
@@ -338,7 +338,7 @@ def main():
             dst.copy_(src * 1)  # elementwise kernel: reads 256 MiB, writes 256 MiB (then a copy of the same size)
         torch.cuda.synchronize()
     if args.train_steps > 0:
-        out["train"] = train_report(binding, devgen, synth, torch, np, args.train_steps)
+        out["train"] = train_report(binding, devgen, synth, torch, np, args.train_steps, args.path)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, k, W_host, prompts[0])
     print(json.dumps(out))

@@ -223,7 +223,7 @@ int pass_run_iterations(pass_ctx *ctx, const int32_t *slots, int n_slots, int n_
 typedef struct {
   float lr, beta1, beta2, eps, weight_decay;
 } pass_adamw;
-size_t pass_train_bytes(const pass_config *cfg);
+size_t pass_train_bytes(pass_ctx *ctx);
 int pass_train_begin(pass_ctx *ctx, void *device_workspace, size_t bytes, int32_t init_token);
 int pass_train_step(pass_ctx *ctx, const int32_t *slots, int n_slots, const int32_t *targets, const pass_adamw *opt,
                     float *out_loss);

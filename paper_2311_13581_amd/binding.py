@@ -97,7 +97,7 @@ def load_library():
     L.pass_seq_len.argtypes = [C.c_void_p, C.c_int, ip, ip]
     L.pass_set_option.argtypes = [C.c_void_p, C.c_char_p, C.c_int]
     L.pass_train_bytes.restype = C.c_size_t
-    L.pass_train_bytes.argtypes = [C.POINTER(PassConfig)]
+    L.pass_train_bytes.argtypes = [C.c_void_p]
     L.pass_train_begin.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int32]
     L.pass_train_step.argtypes = [C.c_void_p, ip, C.c_int, ip, C.POINTER(PassAdamW), C.POINTER(C.c_float)]
     L.pass_train_read.argtypes = [C.c_void_p, C.c_int, C.POINTER(C.c_float)]
@@ -278,7 +278,7 @@ class Pass:
 
     def train_begin(self, init_token: int = -1):
         """Set up look-ahead embedding training (the workspace is a torch tensor this object keeps)."""
-        nbytes = self.lib.pass_train_bytes(C.byref(self.cfg))
+        nbytes = self.lib.pass_train_bytes(self.h)
         if nbytes == 0:
             raise PassError(-1, "no look-ahead embeddings to train")
         self.train_ws = self._torch.empty(nbytes + 256, dtype=self._torch.uint8, device="cuda")

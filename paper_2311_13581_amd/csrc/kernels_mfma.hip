@@ -160,7 +160,7 @@ void launch_assemble_prefill(const Params &p, const void *tok_emb, const void *g
 // ---------------------------------------------------------------------------------------------
 // The streaming GEMM
 // ---------------------------------------------------------------------------------------------
-enum { EPI_QKV = 0, EPI_RESID = 1, EPI_GATEUP = 2, EPI_LOGITS = 3, EPI_PARTIAL = 4 };
+enum { EPI_QKV = 0, EPI_RESID = 1, EPI_GATEUP = 2, EPI_LOGITS = 3, EPI_PARTIAL = 4, EPI_GATEUP_SAVE = 5 };
 
 struct GemmArgs {
   const u32x4 *W;             // packed weight tiles
@@ -172,6 +172,8 @@ struct GemmArgs {
   int kt_split;               // PARTIAL: k-tiles per workgroup row (blockIdx.y picks the slice of K); else 0
   float *partial;             // PARTIAL: [gridDim.y][kMaxRows][N] sums over the slice of K
   int n_strips;               // strips of the matrix (NB = 3: the last workgroup may own fewer blocks)
+  int ldy;                    // PARTIAL: features per row of `partial`
+  float *gu_save;             // GATEUP_SAVE: [M][2F] gate | up before the activation (what its derivative needs)
 };
 
 // MT = number of 8-row groups (one MFMA column block each); NB = output blocks per workgroup (a
@@ -181,7 +183,8 @@ struct GemmArgs {
 template <int MT, int EPI, int WAVES, int U, int NB>
 __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArgs a) {
   constexpr int kGemmWaves = WAVES;
-  constexpr int PER = (EPI == EPI_GATEUP) ? 2 : 1;  // strips per block
+  constexpr bool GU = (EPI == EPI_GATEUP || EPI == EPI_GATEUP_SAVE);
+  constexpr int PER = GU ? 2 : 1;  // strips per block
   constexpr int NS = NB * PER;
   constexpr bool NORM = (EPI != EPI_RESID && EPI != EPI_PARTIAL);
   static_assert(WAVES * NS <= 32 && NB <= WAVES, "reduction buffer must fit the static LDS limit");
@@ -347,7 +350,7 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
         float *o = a.logits + (size_t)p.row_out[m] * p.V + strip * 16 + 4 * g;
         *(floatx4 *)o = y[0] * inv;
       }
-    } else if constexpr (EPI == EPI_GATEUP) {
+    } else if constexpr (GU) {
       if (live) {
         // strips 2b (gate) and 2b+1 (up) of the interleaved matrix both belong to features 16b..16b+15
         int f0 = (blockIdx.x * NB + blk) * 16 + 4 * g;
@@ -358,11 +361,15 @@ __global__ __launch_bounds__(WAVES * 64) void gemm_mfma_kernel(Params p, GemmArg
           t[r] = gt / (1.0f + __expf(-gt)) * up;
         }
         store_split4(p.act_x, m, p.F, f0, t);
+        if constexpr (EPI == EPI_GATEUP_SAVE) {
+          *(floatx4 *)(a.gu_save + (size_t)m * 2 * p.F + f0) = y[0] * inv;
+          *(floatx4 *)(a.gu_save + (size_t)m * 2 * p.F + p.F + f0) = y[1] * inv;
+        }
       }
     } else if constexpr (EPI == EPI_PARTIAL) {
       // sums over this workgroup's slice of K; the slices are added up by resid_reduce_kernel
       if (live)
-        *(floatx4 *)(a.partial + ((size_t)blockIdx.y * kMaxRows + m) * p.d + strip * 16 + 4 * g) = y[0];
+        *(floatx4 *)(a.partial + ((size_t)blockIdx.y * kMaxRows + m) * a.ldy + strip * 16 + 4 * g) = y[0];
     } else if constexpr (EPI == EPI_RESID) {
       int n = strip * 16 + 4 * g;
       float ss = 0.f;
@@ -468,7 +475,7 @@ static void launch_one(const Params &p, const GemmArgs &a, int grid, hipStream_t
 
 template <int EPI, int W, int NB>
 static void launch_big(const Params &p, const GemmArgs &a, int n_blocks, int mt, hipStream_t s) {
-  constexpr int PER = (EPI == EPI_GATEUP) ? 2 : 1;
+  constexpr int PER = (EPI == EPI_GATEUP || EPI == EPI_GATEUP_SAVE) ? 2 : 1;
   if constexpr (W * NB * PER > 32) {
     launch_big<EPI, 8, 1>(p, a, n_blocks, mt, s);
   } else {
@@ -583,6 +590,7 @@ static bool launch_resid_split(const Params &p, const GemmTuning &tn, const Gemm
   GemmArgs a = a0;
   a.kt_split = KT / KS;
   a.partial = p.gu;
+  a.ldy = p.d;
   dim3 grid(n_strips / kSplitBlocks, KS);
   constexpr int T = kSplitWaves * 64;
   switch (mt) {
@@ -615,6 +623,83 @@ void launch_gemm_gateup(const Params &p, const GemmTuning &tn, const void *W, in
 void launch_gemm_logits(const Params &p, const GemmTuning &tn, const void *W, float *logits, int M, hipStream_t s) {
   GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, logits, 0, nullptr, p.V / 16};
   launch_gemm_epi<EPI_LOGITS>(p, tn, a, p.V / 16, s);
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// What the training of the look-ahead embeddings adds (kernels_train.hip has the rest).
+// ---------------------------------------------------------------------------------------------
+// The gate/up GEMM that also keeps gate | up before the activation, in the decode call's launch shapes.
+void launch_gemm_gateup_save(const Params &p, const void *W, float *gu_save, int M, hipStream_t s) {
+  GemmArgs a{(const u32x4 *)W, p.xg, M, p.d, 0, nullptr, nullptr, 0, nullptr, 2 * p.F / 16, 0, gu_save};
+  const int n_blocks = p.F / 16, mt = (M + 7) / 8;
+  if (mt == 1)
+    launch_one<EPI_GATEUP_SAVE, 4, 1>(p, a, n_blocks, s);
+  else if (mt <= 5)
+    launch_big<EPI_GATEUP_SAVE, 4, 3>(p, a, n_blocks, mt, s);
+  else if (n_blocks % 2 == 0)  // three blocks of more than 40 rows do not fit the register file
+    launch_big<EPI_GATEUP_SAVE, 4, 2>(p, a, n_blocks, mt, s);
+  else
+    launch_big<EPI_GATEUP_SAVE, 4, 1>(p, a, n_blocks, mt, s);
+}
+
+// Plain product Y = X W^T on packed tiles: X as (hi, lo) tiles of K features, W packed [N][K], Y fp32.
+// K is cut into KS slices across workgroups of 8 wavefronts that own 4 strips each; slice ks leaves its
+// sums in part[ks][kMaxRows][N] and the consumer adds the slices in order.  Needs N % 64 == 0 and
+// (K / 32) % KS == 0; returns the KS it used (plain_gemm_slices: what the consumer must add up).
+int plain_gemm_slices(int N, int K) {
+  const int KT = K / 32, wgs = N / 64;
+  int best = 1;
+  for (int ks = 1; ks <= 8; ks *= 2) {
+    if (KT % ks != 0 || KT / ks < 8) break;
+    best = ks;
+    if (wgs * ks >= 512) break;
+  }
+  return best;
+}
+int launch_gemm_plain(const Params &p, const void *W, const uint16_t *X, int M, int N, int K, float *part, hipStream_t s) {
+  const int KS = plain_gemm_slices(N, K);
+  GemmArgs a{(const u32x4 *)W, X, M, K, 0, nullptr, nullptr, (K / 32) / KS, part, N / 16, N, nullptr};
+  dim3 grid(N / 64, KS);
+  constexpr int T = kSplitWaves * 64;
+  switch ((M + 7) / 8) {
+    case 1: gemm_mfma_kernel<1, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    case 2: gemm_mfma_kernel<2, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    case 3: gemm_mfma_kernel<3, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    case 4: gemm_mfma_kernel<4, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    case 5: gemm_mfma_kernel<5, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    case 6: gemm_mfma_kernel<6, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    case 7: gemm_mfma_kernel<7, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+    default: gemm_mfma_kernel<8, EPI_PARTIAL, kSplitWaves, 1, kSplitBlocks><<<grid, T, 0, s>>>(p, a); break;
+  }
+  return KS;
+}
+
+// Packed tiles of W [N][K] -> packed tiles of its transpose [K][N] (the backward pass multiplies by
+// W^T with the same kernels).  One 16-byte chunk of the destination per thread: row k of W^T, eight
+// consecutive n.  Run once when training is set up.
+__global__ __launch_bounds__(256) void transpose_packed_kernel(const uint16_t *src, uint16_t *dst, int N, int K) {
+  const int KT = K / 32, NT = N / 32;  // k-tiles of the source, of the destination
+  const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x, total = (size_t)(K / 16) * NT * 64;
+  if (idx >= total) return;
+  const int lane = (int)(idx & 63);
+  const size_t tile = idx >> 6;
+  const int nt = (int)(tile % NT), ks = (int)(tile / NT);  // destination k-tile (over n), strip (over k)
+  const int k = ks * 16 + (lane & 15), n0 = nt * 32 + (lane >> 4) * 8;
+  uint16_t v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int n = n0 + e;
+    v[e] = src[((((size_t)(n >> 4) * KT + (k >> 5)) * 64 + ((k >> 3) & 3) * 16 + (n & 15)) << 3) + (k & 7)];
+  }
+  uint4 o;
+  o.x = v[0] | (uint32_t)v[1] << 16; o.y = v[2] | (uint32_t)v[3] << 16;
+  o.z = v[4] | (uint32_t)v[5] << 16; o.w = v[6] | (uint32_t)v[7] << 16;
+  *(uint4 *)(dst + idx * 8) = o;
+}
+void launch_transpose_packed(const void *src, void *dst, int N, int K, hipStream_t s) {
+  const size_t total = (size_t)(K / 16) * (N / 32) * 64;
+  transpose_packed_kernel<<<(unsigned)((total + 255) / 256), 256, 0, s>>>((const uint16_t *)src, (uint16_t *)dst, N, K);
 }
 
 }  // namespace pass

@@ -71,18 +71,67 @@ void launch_assemble_train(const Params &p, int dtype, const void *tok_emb, cons
     assemble_train_kernel<bf16_t><<<B * R, 256, 0, s>>>(p, (const bf16_t *)tok_emb, master, R);
 }
 
+// The same rows for the matrix-core path (bf16 models): besides h, the (hi, lo) tiles of h * gain of the
+// first norm and the partial sums of h^2 its consumer expects (partial 0 carries the whole row).
+__global__ __launch_bounds__(256) void assemble_train_mfma_kernel(Params p, const bf16_t *tok_emb, const float *master,
+                                                                  const bf16_t *gain0, int R) {
+  __shared__ float red[4];
+  const int m = blockIdx.x, b = m / R, r = m % R;
+  const int slot = p.step_slots[b];
+  const int pos = p.kv_len[slot] + r;
+  const bf16_t *tok = tok_emb + (size_t)clamp_token(p, p.pending[slot]) * p.d;
+  const float *la = master + (size_t)(r > 0 ? r - 1 : 0) * p.d;
+  float ss = 0.f;
+  for (int c0 = threadIdx.x * 4; c0 < p.d; c0 += 1024) {
+    float v[4], x[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[e] = r == 0 ? load_f(tok, c0 + e) : la[c0 + e];
+      x[e] = v[e] * load_f(gain0, c0 + e);
+      ss += v[e] * v[e];
+    }
+    *(float4 *)(p.h + (size_t)m * p.d + c0) = make_float4(v[0], v[1], v[2], v[3]);
+    store_split4(p.xg, m, p.d, c0, x);
+  }
+  ss = block_sum_256(ss, red);
+  for (int i = threadIdx.x; i < p.d / 16; i += 256) p.ssq[(size_t)i * kMaxRows + m] = (i == 0) ? ss : 0.f;
+  const int half = p.hd / 2;
+  for (int i = threadIdx.x; i < half; i += 256) {
+    double sn, cs;
+    sincos((double)pos * p.rope_theta[i], &sn, &cs);
+    p.rope_cos[(size_t)m * half + i] = (float)cs;
+    p.rope_sin[(size_t)m * half + i] = (float)sn;
+  }
+  if (threadIdx.x == 0) {
+    p.row_pos[m] = pos;
+    p.row_slot[m] = slot;
+    p.row_out[m] = m;
+  }
+}
+
+void launch_assemble_train_mfma(const Params &p, const void *tok_emb, const float *master, const void *gain0, int B, int R,
+                                hipStream_t s) {
+  assemble_train_mfma_kernel<<<B * R, 256, 0, s>>>(p, (const bf16_t *)tok_emb, master, (const bf16_t *)gain0, R);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Cross-entropy of the look-ahead rows: loss of a row = ln sum exp(logits) - logit[target];
 // logits are overwritten by d loss / d logits = (softmax - onehot) * scale (rows without a target,
-// i.e. each slot's row 0, get zeros).  One workgroup per row.
+// i.e. each slot's row 0, get zeros).  One workgroup per row.  With x_out not null the gradient goes there as
+// (hi, lo) tiles of V features instead (input of the matrix-core product with the LM head's transpose).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void ce_grad_kernel(float *logits, const int32_t *targets, float scale, float *row_loss, int V) {
+__global__ __launch_bounds__(256) void ce_grad_kernel(float *logits, const int32_t *targets, float scale, float *row_loss, int V,
+                                                      uint16_t *x_out) {
   __shared__ float red[4];
   const int m = blockIdx.x;
   float *lg = logits + (size_t)m * V;
   const int tg = targets[m];
   if (tg < 0) {
-    for (int j = threadIdx.x; j < V; j += 256) lg[j] = 0.f;
+    const float z[4] = {0.f, 0.f, 0.f, 0.f};
+    if (x_out)
+      for (int j = threadIdx.x * 4; j < V; j += 1024) store_split4(x_out, m, V, j, z);
+    else
+      for (int j = threadIdx.x; j < V; j += 256) lg[j] = 0.f;
     if (threadIdx.x == 0) row_loss[m] = 0.f;
     return;
   }
@@ -95,11 +144,21 @@ __global__ __launch_bounds__(256) void ce_grad_kernel(float *logits, const int32
   const float lse = mx + logf(se), inv = 1.f / se;
   if (threadIdx.x == 0) row_loss[m] = lse - lg[tg];
   __syncthreads();
-  for (int j = threadIdx.x; j < V; j += 256) lg[j] = (expf(lg[j] - mx) * inv - (j == tg ? 1.f : 0.f)) * scale;
+  if (x_out) {
+    for (int j = threadIdx.x * 4; j < V; j += 1024) {
+      float t[4];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) t[e] = (expf(lg[j + e] - mx) * inv - (j + e == tg ? 1.f : 0.f)) * scale;
+      store_split4(x_out, m, V, j, t);
+    }
+  } else {
+    for (int j = threadIdx.x; j < V; j += 256) lg[j] = (expf(lg[j] - mx) * inv - (j == tg ? 1.f : 0.f)) * scale;
+  }
 }
 
-void launch_ce_grad(float *logits, const int32_t *targets, float scale, float *row_loss, int M, int V, hipStream_t s) {
-  ce_grad_kernel<<<M, 256, 0, s>>>(logits, targets, scale, row_loss, V);
+void launch_ce_grad(float *logits, const int32_t *targets, float scale, float *row_loss, int M, int V, uint16_t *x_out,
+                    hipStream_t s) {
+  ce_grad_kernel<<<M, 256, 0, s>>>(logits, targets, scale, row_loss, V, x_out);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -189,33 +248,47 @@ void launch_gemm_t(int dtype, const float *dY, int ldy, const void *W, float *pa
 // y = x * rsqrt(mean(x^2) + eps) * g  ==>  dx = g dy r - x r^3 (sum_i g_i dy_i x_i) / d,  r = rsqrt(..)
 // dx is added to `dx_acc` (the gradient of the residual stream).  One workgroup per row.
 // ---------------------------------------------------------------------------------------------
+// dy may come as KS slices (sums over slices of the contraction, `slice_stride` floats apart), added in
+// order; with dx_x not null the updated gradient row also goes there as (hi, lo) tiles.
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const float *x, const T *gain, const float *dy, float *dx_acc, int d,
-                                                          float eps, int accumulate) {
+__global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const float *x, const T *gain, const float *dy, int KS, size_t slice_stride,
+                                                          float *dx_acc, int d, float eps, int accumulate, uint16_t *dx_x) {
   __shared__ float red[4];
-  const size_t base = (size_t)blockIdx.x * d;
+  const int m = blockIdx.x;
+  const size_t base = (size_t)m * d;
   float ss = 0.f, c = 0.f;
   for (int i = threadIdx.x; i < d; i += 256) {
     const float xv = x[base + i];
+    float dyv = dy[base + i];
+    for (int ks = 1; ks < KS; ++ks) dyv += dy[ks * slice_stride + base + i];
     ss += xv * xv;
-    c += load_f(gain, i) * dy[base + i] * xv;
+    c += load_f(gain, i) * dyv * xv;
   }
   ss = block_sum_256(ss, red);
   c = block_sum_256(c, red);
   const float r = 1.0f / sqrtf(ss / (float)d + eps);
   const float k3 = r * r * r * c / (float)d;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    const float v = load_f(gain, i) * dy[base + i] * r - x[base + i] * k3;
-    dx_acc[base + i] = accumulate ? dx_acc[base + i] + v : v;
+  for (int i0 = threadIdx.x * 4; i0 < d; i0 += 1024) {
+    float t[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int i = i0 + e;
+      float dyv = dy[base + i];
+      for (int ks = 1; ks < KS; ++ks) dyv += dy[ks * slice_stride + base + i];
+      const float v = load_f(gain, i) * dyv * r - x[base + i] * k3;
+      t[e] = accumulate ? dx_acc[base + i] + v : v;
+      dx_acc[base + i] = t[e];
+    }
+    if (dx_x) store_split4(dx_x, m, d, i0, t);
   }
 }
 
-void launch_rmsnorm_bwd(const Params &p, int dtype, const float *x, const void *gain, const float *dy, float *dx_acc, int M,
-                        int accumulate, hipStream_t s) {
+void launch_rmsnorm_bwd(const Params &p, int dtype, const float *x, const void *gain, const float *dy, int KS, size_t slice_stride,
+                        float *dx_acc, int M, int accumulate, uint16_t *dx_x, hipStream_t s) {
   if (dtype == PASS_F32)
-    rmsnorm_bwd_kernel<float><<<M, 256, 0, s>>>(x, (const float *)gain, dy, dx_acc, p.d, p.eps, accumulate);
+    rmsnorm_bwd_kernel<float><<<M, 256, 0, s>>>(x, (const float *)gain, dy, KS, slice_stride, dx_acc, p.d, p.eps, accumulate, dx_x);
   else
-    rmsnorm_bwd_kernel<bf16_t><<<M, 256, 0, s>>>(x, (const bf16_t *)gain, dy, dx_acc, p.d, p.eps, accumulate);
+    rmsnorm_bwd_kernel<bf16_t><<<M, 256, 0, s>>>(x, (const bf16_t *)gain, dy, KS, slice_stride, dx_acc, p.d, p.eps, accumulate, dx_x);
 }
 
 // act = silu(gate) * up:  dgate = dact up s (1 + gate (1 - s)),  dup = dact gate s,  s = sigmoid(gate)
@@ -227,9 +300,34 @@ __global__ __launch_bounds__(256) void swiglu_bwd_kernel(const float *gu, const 
   dgu[(size_t)m * 2 * F + f] = da * u * sg * (1.0f + g * (1.0f - sg));
   dgu[(size_t)m * 2 * F + F + f] = da * g * sg;
 }
+// The same for the matrix-core path: dact comes as KS slices; dgate and dup leave as (hi, lo) tiles of 2F
+// features in the row order of the packed gate/up matrix (strips of 16 gate rows and 16 up rows alternate),
+// which is the order its transpose contracts over.  Four consecutive features per thread.
+__global__ __launch_bounds__(256) void swiglu_bwd_tiles_kernel(const float *gu, const float *dact, int KS, size_t slice_stride,
+                                                               uint16_t *dgu_x, int F) {
+  const int m = blockIdx.y, f = (blockIdx.x * 256 + threadIdx.x) * 4;
+  if (f >= F) return;
+  float dg[4], du[4];
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float g = gu[(size_t)m * 2 * F + f + e], u = gu[(size_t)m * 2 * F + F + f + e];
+    float da = dact[(size_t)m * F + f + e];
+    for (int ks = 1; ks < KS; ++ks) da += dact[ks * slice_stride + (size_t)m * F + f + e];
+    const float sg = 1.0f / (1.0f + expf(-g));
+    dg[e] = da * u * sg * (1.0f + g * (1.0f - sg));
+    du[e] = da * g * sg;
+  }
+  const int row = (f >> 4) * 32 + (f & 15);  // packed row of gate feature f; its up row is 16 further
+  store_split4(dgu_x, m, 2 * F, row, dg);
+  store_split4(dgu_x, m, 2 * F, row + 16, du);
+}
 
 void launch_swiglu_bwd(const Params &p, const float *gu, const float *dact, float *dgu, int M, hipStream_t s) {
   swiglu_bwd_kernel<<<dim3((p.F + 255) / 256, M), 256, 0, s>>>(gu, dact, dgu, p.F);
+}
+void launch_swiglu_bwd_tiles(const Params &p, const float *gu, const float *dact, int KS, size_t slice_stride, uint16_t *dgu_x,
+                             int M, hipStream_t s) {
+  swiglu_bwd_tiles_kernel<<<dim3((p.F / 4 + 255) / 256, M), 256, 0, s>>>(gu, dact, KS, slice_stride, dgu_x, p.F);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -263,7 +361,8 @@ __device__ __forceinline__ void load8(const bf16_t *p, size_t off, float (&v)[8]
 template <typename T, int HD>
 __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer, int R, const float *q_saved, int ldq,
                                                              const float *o_f32, const uint16_t *o_x, const float *lse,
-                                                             const float *dattn, float *dq_part, float *dqkv) {
+                                                             const float *dattn, int KS, size_t slice_stride, float *dq_part,
+                                                             float *dqkv) {
   constexpr int TK = 32, LD = HD + 4, RMAX = kMaxK + 1, PARTS = 256 / HD;
   __shared__ __align__(16) float tiles[2][TK][LD];  // K tile, V tile; at the end the parts' dq
   __shared__ __align__(16) float qs[RMAX][HD], dos[RMAX][HD];
@@ -284,7 +383,9 @@ __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer
   for (int idx = tid; idx < R * HD; idx += 256) {
     const int r = idx / HD, dm = idx % HD;
     qs[r][dm] = q_saved[(size_t)(m0 + r) * ldq + head * HD + dm];
-    dos[r][dm] = dattn[(size_t)(m0 + r) * p.D + head * HD + dm];
+    float dv = dattn[(size_t)(m0 + r) * p.D + head * HD + dm];
+    for (int ks = 1; ks < KS; ++ks) dv += dattn[ks * slice_stride + (size_t)(m0 + r) * p.D + head * HD + dm];  // slices, in order
+    dos[r][dm] = dv;
   }
   __syncthreads();
   for (int r = wave; r < R; r += 4) {  // D of row r: one wavefront, lanes over the dimensions
@@ -436,19 +537,19 @@ __global__ __launch_bounds__(256) void attn_bwd_finish_kernel(Params p, int R, c
 }
 
 void launch_attn_bwd(const Params &p, int dtype, int layer, int B, int R, int max_keys, const float *q_saved, int ldq,
-                     const float *o, const uint16_t *o_x, const float *lse, const float *dattn, float *dq_part, float *dqkv,
-                     uint16_t *dqkv_x, hipStream_t s) {
+                     const float *o, const uint16_t *o_x, const float *lse, const float *dattn, int KS, size_t slice_stride,
+                     float *dq_part, float *dqkv, uint16_t *dqkv_x, hipStream_t s) {
   dim3 grid((max_keys + kTrainAttnChunk - 1) / kTrainAttnChunk, p.H, B);
   if (p.hd == 128) {
     if (dtype == PASS_F32)
-      attn_bwd_split_kernel<float, 128><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, dq_part, dqkv);
+      attn_bwd_split_kernel<float, 128><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv);
     else
-      attn_bwd_split_kernel<bf16_t, 128><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, dq_part, dqkv);
+      attn_bwd_split_kernel<bf16_t, 128><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv);
   } else {
     if (dtype == PASS_F32)
-      attn_bwd_split_kernel<float, 64><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, dq_part, dqkv);
+      attn_bwd_split_kernel<float, 64><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv);
     else
-      attn_bwd_split_kernel<bf16_t, 64><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, dq_part, dqkv);
+      attn_bwd_split_kernel<bf16_t, 64><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv);
   }
   attn_bwd_finish_kernel<<<B * R, 256, 0, s>>>(p, R, dq_part, dqkv, dqkv_x);
 }

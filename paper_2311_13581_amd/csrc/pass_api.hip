@@ -44,7 +44,8 @@ struct Slot {
 // Workspace of the look-ahead embedding training (caller's memory, carved by carve_train)
 struct TrainWs {
   bool on = false;
-  int64_t step = 0;  // optimiser steps taken (AdamW's bias correction)
+  bool mfma = false;  // the context runs on the matrix-core path: packed transposes of the weights, gradients as tiles
+  int64_t step = 0;   // optimiser steps taken (AdamW's bias correction)
   float *master, *m1, *m2, *grad;                    // [k][d] fp32: trained values, AdamW moments, last gradient
   // what the backward pass needs of every layer, [L][kMaxRows][..]: the residual stream before the two norms (d each),
   // the layer's q | k | v workspace (3D; the rotated queries are what is used), the attention output (D) and the
@@ -56,6 +57,11 @@ struct TrainWs {
   float *dh, *dxn, *dattn, *dqkv, *dact, *dgu;       // gradients of the rows' activations
   float *part;                                       // [kTrainSplits][kMaxRows][max(d, D, F)] slice sums of a transposed projection
   float *dq_part;                                    // [kTrainAttnSplits][kMaxRows][D] the key chunks' shares of dq
+  // matrix-core path: the weights' transposes in packed tiles (dx = W^T dy is then the forward pass's own product),
+  // and the (hi, lo) tiles of the gradient that is the next product's input [2 * kMaxRows * max(V, 2F, 3D, d)]
+  void *lm_head_t = nullptr;
+  std::vector<LayerW> layers_t;  // wqkv, wo, wgu, wdown: the transposes; the norm gains are unused
+  uint16_t *x = nullptr;
   float *row_loss;                                   // [kMaxRows]
   int32_t *targets;                                  // [kMaxRows] target token of a row, -1 = no loss
 };
@@ -245,7 +251,7 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   return (A.off + 255) & ~(size_t)255;
 }
 
-size_t carve_train(const pass_config &c, char *base, TrainWs *out) {
+size_t carve_train(const pass_config &c, bool mfma, char *base, TrainWs *out) {
   Arena A{base, 0};
   const size_t d = c.d_model, D = (size_t)c.n_heads * c.head_dim, F = c.d_ffn, V = c.vocab, L = c.n_layers, M = kMaxRows;
   const size_t kd = (size_t)(c.k ? c.k : 1) * d;
@@ -262,6 +268,17 @@ size_t carve_train(const pass_config &c, char *base, TrainWs *out) {
   T.dq_part = A.take<float>((size_t)kTrainAttnSplits * M * D);
   T.row_loss = A.take<float>(M);
   T.targets = A.take<int32_t>(M);
+  T.mfma = mfma;
+  if (mfma) {
+    T.x = A.take<uint16_t>(2 * M * std::max(std::max(V, 2 * F), std::max(3 * D, d)));
+    T.lm_head_t = A.take<uint16_t>(V * d);
+    T.layers_t.resize(L);
+    for (auto &l : T.layers_t) {
+      l.attn_norm = l.ffn_norm = nullptr;
+      l.wqkv = A.take<uint16_t>(3 * D * d); l.wo = A.take<uint16_t>(d * D);
+      l.wgu = A.take<uint16_t>(2 * F * d); l.wdown = A.take<uint16_t>(d * F);
+    }
+  }
   if (out) *out = T;
   return (A.off + 255) & ~(size_t)255;
 }
@@ -1166,20 +1183,34 @@ int pass_get_tokens(pass_ctx *c, int slot, int first, int n, int32_t *out) {
   return PASS_OK;
 }
 
-size_t pass_train_bytes(const pass_config *cfg) {
-  if (!config_ok(cfg, nullptr) || cfg->k < 1) return 0;
-  return carve_train(*cfg, nullptr, nullptr);
+size_t pass_train_bytes(pass_ctx *c) {
+  if (!c || !c->weights_loaded || c->cfg.k < 1) return 0;
+  return carve_train(c->cfg, c->use_mfma, nullptr, nullptr);
 }
 
 int pass_train_begin(pass_ctx *c, void *device_workspace, size_t bytes, int32_t init_token) {
   if (!c) return PASS_EINVAL;
   if (!c->weights_loaded) return fail(c, PASS_ESTATE, "weights not loaded");
-  if (c->use_mfma) return fail(c, PASS_ESTATE, "training runs on the generic kernels: set the \"path\" option to 1 before pass_load_weights");
+  if (c->use_mfma && (c->P.d % 64 || c->P.D % 64 || c->P.F % 64 || c->P.V % 32))
+    return fail(c, PASS_ESTATE, "training on the matrix-core path needs d_model, n_heads * head_dim and d_ffn in multiples of 64 and the "
+                                "vocabulary in multiples of 32: load the model with the \"path\" option at 1");
   if (c->cfg.k < 1) return fail(c, PASS_EINVAL, "the model has no look-ahead embeddings (k = 0)");
-  if (!device_workspace || ((uintptr_t)device_workspace & 255) || bytes < carve_train(c->cfg, nullptr, nullptr))
+  if (!device_workspace || ((uintptr_t)device_workspace & 255) || bytes < carve_train(c->cfg, c->use_mfma, nullptr, nullptr))
     return fail(c, PASS_EINVAL, "training workspace null, misaligned or smaller than pass_train_bytes");
   if (init_token >= c->cfg.vocab) return fail(c, PASS_EINVAL, "init_token outside the vocabulary");
-  carve_train(c->cfg, (char *)device_workspace, &c->train);
+  carve_train(c->cfg, c->use_mfma, (char *)device_workspace, &c->train);
+  if (c->use_mfma) {
+    const int d = c->P.d, D = c->P.D, F = c->P.F, V = c->P.V;
+    launch_transpose_packed(c->lm_head, c->train.lm_head_t, V, d, c->stream);
+    for (int l = 0; l < c->P.L; ++l) {
+      const LayerW &w = c->layers[l], &t = c->train.layers_t[l];
+      launch_transpose_packed(w.wqkv, t.wqkv, 3 * D, d, c->stream);
+      launch_transpose_packed(w.wo, t.wo, d, D, c->stream);
+      launch_transpose_packed(w.wgu, t.wgu, 2 * F, d, c->stream);
+      launch_transpose_packed(w.wdown, t.wdown, d, F, c->stream);
+    }
+    HIP_TRY(c, hipGetLastError());
+  }
   if (!c->train_loss_host) HIP_TRY(c, hipHostMalloc((void **)&c->train_loss_host, sizeof(float) * kMaxRows, hipHostMallocDefault));
   launch_lookahead_init(c->cfg.dtype, c->tok_emb, c->lookahead, init_token, c->cfg.k, c->P.d, c->train.master, c->train.m1,
                         c->train.m2, c->stream);
@@ -1223,47 +1254,88 @@ int pass_train_step(pass_ctx *c, const int32_t *slots, int n_slots, const int32_
   hipStream_t s = c->stream;
   const size_t d = P.d, D = P.D, F = P.F, V = P.V, H = P.H;
   HIP_TRY(c, hipMemcpyAsync(T.targets, tg.data(), sizeof(int32_t) * M, hipMemcpyHostToDevice, s));
-  // ---- forward: the drafting call on the generic kernels, look-ahead rows from the master values; each layer
-  // works in its own area of the workspace, so what the backward pass needs is simply left there ----
   const int S = choose_splits(c, n_slots, R, max_keys);
-  launch_assemble_train(P, dt, c->tok_emb, T.master, n_slots, R, s);
-  for (int l = 0; l < P.L; ++l) {
-    const LayerW &w = c->layers[l];
-    P.qkv = T.save_qkv + (size_t)l * kMaxRows * 3 * D;
-    P.attn = T.save_attn + (size_t)l * kMaxRows * D;
-    P.lse = T.save_lse + (size_t)l * kMaxRows * H;
-    P.gu = T.save_gu + (size_t)l * kMaxRows * 2 * F;
-    HIP_TRY(c, hipMemcpyAsync(T.save_h0 + (size_t)l * kMaxRows * d, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
-    launch_rmsnorm(P, dt, P.h, w.attn_norm, P.xn, M, s);
-    launch_gemm_generic(dt, P.xn, w.wqkv, P.qkv, M, 3 * P.D, P.d, 3 * P.D, nullptr, 0, s);
-    launch_rope_kv(P, dt, l, M, s);
-    launch_attention(P, dt, l, n_slots, R, S, 0, s);
-    launch_gemm_generic(dt, P.attn, w.wo, P.h, M, P.d, P.D, P.d, nullptr, 1, s);
-    HIP_TRY(c, hipMemcpyAsync(T.save_h1 + (size_t)l * kMaxRows * d, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
-    launch_rmsnorm(P, dt, P.h, w.ffn_norm, P.xn, M, s);
-    launch_gemm_generic(dt, P.xn, w.wgu, P.gu, M, 2 * P.F, P.d, 2 * P.F, nullptr, 0, s);
-    launch_silu_mul(P, M, s);
-    launch_gemm_generic(dt, P.act, w.wdown, P.h, M, P.d, P.F, P.d, nullptr, 1, s);
-  }
-  HIP_TRY(c, hipMemcpyAsync(T.save_hl, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
-  launch_rmsnorm(P, dt, P.h, c->final_norm, P.xn, M, s);
-  launch_gemm_generic(dt, P.xn, c->lm_head, T.logits, M, P.V, P.d, P.V, nullptr, 0, s);
-  // ---- loss on the look-ahead rows and its gradient, back through the frozen model ----
-  launch_ce_grad(T.logits, T.targets, 1.0f / (float)(n_slots * k), T.row_loss, M, P.V, s);
-  launch_gemm_t(dt, T.logits, (int)V, c->lm_head, T.part, T.dxn, (int)d, M, (int)V, (int)d, s);
-  launch_rmsnorm_bwd(P, dt, T.save_hl, c->final_norm, T.dxn, T.dh, M, 0, s);
-  for (int l = P.L - 1; l >= 0; --l) {
-    const LayerW &w = c->layers[l];
-    launch_gemm_t(dt, T.dh, (int)d, w.wdown, T.part, T.dact, (int)F, M, (int)d, (int)F, s);
-    launch_swiglu_bwd(P, T.save_gu + (size_t)l * kMaxRows * 2 * F, T.dact, T.dgu, M, s);
-    launch_gemm_t(dt, T.dgu, (int)(2 * F), w.wgu, T.part, T.dxn, (int)d, M, (int)(2 * F), (int)d, s);
-    launch_rmsnorm_bwd(P, dt, T.save_h1 + (size_t)l * kMaxRows * d, w.ffn_norm, T.dxn, T.dh, M, 1, s);
-    launch_gemm_t(dt, T.dh, (int)d, w.wo, T.part, T.dattn, (int)D, M, (int)d, (int)D, s);
-    launch_attn_bwd(P, dt, l, n_slots, R, max_keys, T.save_qkv + (size_t)l * kMaxRows * 3 * D, (int)(3 * D),
-                    T.save_attn + (size_t)l * kMaxRows * D, nullptr, T.save_lse + (size_t)l * kMaxRows * H, T.dattn, T.dq_part,
-                    T.dqkv, nullptr, s);
-    launch_gemm_t(dt, T.dqkv, (int)(3 * D), w.wqkv, T.part, T.dxn, (int)d, M, (int)(3 * D), (int)d, s);
-    launch_rmsnorm_bwd(P, dt, T.save_h0 + (size_t)l * kMaxRows * d, w.attn_norm, T.dxn, T.dh, M, 1, s);
+  const float loss_scale = 1.0f / (float)(n_slots * k);
+  if (T.mfma) {
+    // ---- forward: the drafting call's own kernels (the gate/up product also keeps its pre-activations); each
+    // layer's q, attention output and ln-sum-exp land in that layer's area ----
+    launch_assemble_train_mfma(P, c->tok_emb, T.master, c->layers[0].attn_norm, n_slots, R, s);
+    for (int l = 0; l < P.L; ++l) {
+      const LayerW &w = c->layers[l];
+      P.qkv = T.save_qkv + (size_t)l * kMaxRows * 3 * D;
+      P.attn_x = (uint16_t *)(T.save_attn + (size_t)l * kMaxRows * D);
+      P.lse = T.save_lse + (size_t)l * kMaxRows * H;
+      HIP_TRY(c, hipMemcpyAsync(T.save_h0 + (size_t)l * kMaxRows * d, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
+      launch_gemm_qkv(P, c->tuning, w.wqkv, l, M, s);
+      launch_attention(P, dt, l, n_slots, R, S, 1, s);
+      launch_gemm_resid(P, c->tuning, w.wo, P.attn_x, P.D, w.ffn_norm, M, s);
+      HIP_TRY(c, hipMemcpyAsync(T.save_h1 + (size_t)l * kMaxRows * d, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
+      launch_gemm_gateup_save(P, w.wgu, T.save_gu + (size_t)l * kMaxRows * 2 * F, M, s);
+      launch_gemm_resid(P, c->tuning, w.wdown, P.act_x, P.F, l + 1 < P.L ? c->layers[l + 1].attn_norm : c->final_norm, M, s);
+    }
+    HIP_TRY(c, hipMemcpyAsync(T.save_hl, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
+    launch_gemm_logits(P, c->tuning, c->lm_head, T.logits, M, s);
+    // ---- backward: every dx = W^T dy is a matrix-core product with the packed transpose; its input travels as
+    // (hi, lo) tiles (T.x), its output as slices over the contraction (T.part) that the consumer adds up ----
+    const size_t rows = kMaxRows;
+    launch_ce_grad(T.logits, T.targets, loss_scale, T.row_loss, M, P.V, T.x, s);
+    int KS = launch_gemm_plain(P, T.lm_head_t, T.x, M, (int)d, (int)V, T.part, s);
+    launch_rmsnorm_bwd(P, dt, T.save_hl, c->final_norm, T.part, KS, rows * d, T.dh, M, 0, T.x, s);
+    for (int l = P.L - 1; l >= 0; --l) {
+      const LayerW &w = c->layers[l], &t = T.layers_t[l];
+      KS = launch_gemm_plain(P, t.wdown, T.x, M, (int)F, (int)d, T.part, s);
+      launch_swiglu_bwd_tiles(P, T.save_gu + (size_t)l * kMaxRows * 2 * F, T.part, KS, rows * F, T.x, M, s);
+      KS = launch_gemm_plain(P, t.wgu, T.x, M, (int)d, (int)(2 * F), T.part, s);
+      launch_rmsnorm_bwd(P, dt, T.save_h1 + (size_t)l * kMaxRows * d, w.ffn_norm, T.part, KS, rows * d, T.dh, M, 1, T.x, s);
+      KS = launch_gemm_plain(P, t.wo, T.x, M, (int)D, (int)d, T.part, s);
+      launch_attn_bwd(P, dt, l, n_slots, R, max_keys, T.save_qkv + (size_t)l * kMaxRows * 3 * D, (int)(3 * D), nullptr,
+                      (const uint16_t *)(T.save_attn + (size_t)l * kMaxRows * D), T.save_lse + (size_t)l * kMaxRows * H, T.part, KS,
+                      rows * D, T.dq_part, T.dqkv, T.x, s);
+      KS = launch_gemm_plain(P, t.wqkv, T.x, M, (int)d, (int)(3 * D), T.part, s);
+      launch_rmsnorm_bwd(P, dt, T.save_h0 + (size_t)l * kMaxRows * d, w.attn_norm, T.part, KS, rows * d, T.dh, M, 1, T.x, s);
+    }
+  } else {
+    // ---- forward: the drafting call on the generic kernels, look-ahead rows from the master values; each layer
+    // works in its own area of the workspace, so what the backward pass needs is simply left there ----
+    launch_assemble_train(P, dt, c->tok_emb, T.master, n_slots, R, s);
+    for (int l = 0; l < P.L; ++l) {
+      const LayerW &w = c->layers[l];
+      P.qkv = T.save_qkv + (size_t)l * kMaxRows * 3 * D;
+      P.attn = T.save_attn + (size_t)l * kMaxRows * D;
+      P.lse = T.save_lse + (size_t)l * kMaxRows * H;
+      P.gu = T.save_gu + (size_t)l * kMaxRows * 2 * F;
+      HIP_TRY(c, hipMemcpyAsync(T.save_h0 + (size_t)l * kMaxRows * d, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
+      launch_rmsnorm(P, dt, P.h, w.attn_norm, P.xn, M, s);
+      launch_gemm_generic(dt, P.xn, w.wqkv, P.qkv, M, 3 * P.D, P.d, 3 * P.D, nullptr, 0, s);
+      launch_rope_kv(P, dt, l, M, s);
+      launch_attention(P, dt, l, n_slots, R, S, 0, s);
+      launch_gemm_generic(dt, P.attn, w.wo, P.h, M, P.d, P.D, P.d, nullptr, 1, s);
+      HIP_TRY(c, hipMemcpyAsync(T.save_h1 + (size_t)l * kMaxRows * d, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
+      launch_rmsnorm(P, dt, P.h, w.ffn_norm, P.xn, M, s);
+      launch_gemm_generic(dt, P.xn, w.wgu, P.gu, M, 2 * P.F, P.d, 2 * P.F, nullptr, 0, s);
+      launch_silu_mul(P, M, s);
+      launch_gemm_generic(dt, P.act, w.wdown, P.h, M, P.d, P.F, P.d, nullptr, 1, s);
+    }
+    HIP_TRY(c, hipMemcpyAsync(T.save_hl, P.h, sizeof(float) * M * d, hipMemcpyDeviceToDevice, s));
+    launch_rmsnorm(P, dt, P.h, c->final_norm, P.xn, M, s);
+    launch_gemm_generic(dt, P.xn, c->lm_head, T.logits, M, P.V, P.d, P.V, nullptr, 0, s);
+    // ---- loss on the look-ahead rows and its gradient, back through the frozen model ----
+    launch_ce_grad(T.logits, T.targets, loss_scale, T.row_loss, M, P.V, nullptr, s);
+    launch_gemm_t(dt, T.logits, (int)V, c->lm_head, T.part, T.dxn, (int)d, M, (int)V, (int)d, s);
+    launch_rmsnorm_bwd(P, dt, T.save_hl, c->final_norm, T.dxn, 1, 0, T.dh, M, 0, nullptr, s);
+    for (int l = P.L - 1; l >= 0; --l) {
+      const LayerW &w = c->layers[l];
+      launch_gemm_t(dt, T.dh, (int)d, w.wdown, T.part, T.dact, (int)F, M, (int)d, (int)F, s);
+      launch_swiglu_bwd(P, T.save_gu + (size_t)l * kMaxRows * 2 * F, T.dact, T.dgu, M, s);
+      launch_gemm_t(dt, T.dgu, (int)(2 * F), w.wgu, T.part, T.dxn, (int)d, M, (int)(2 * F), (int)d, s);
+      launch_rmsnorm_bwd(P, dt, T.save_h1 + (size_t)l * kMaxRows * d, w.ffn_norm, T.dxn, 1, 0, T.dh, M, 1, nullptr, s);
+      launch_gemm_t(dt, T.dh, (int)d, w.wo, T.part, T.dattn, (int)D, M, (int)d, (int)D, s);
+      launch_attn_bwd(P, dt, l, n_slots, R, max_keys, T.save_qkv + (size_t)l * kMaxRows * 3 * D, (int)(3 * D),
+                      T.save_attn + (size_t)l * kMaxRows * D, nullptr, T.save_lse + (size_t)l * kMaxRows * H, T.dattn, 1, 0,
+                      T.dq_part, T.dqkv, nullptr, s);
+      launch_gemm_t(dt, T.dqkv, (int)(3 * D), w.wqkv, T.part, T.dxn, (int)d, M, (int)(3 * D), (int)d, s);
+      launch_rmsnorm_bwd(P, dt, T.save_h0 + (size_t)l * kMaxRows * d, w.attn_norm, T.dxn, 1, 0, T.dh, M, 1, nullptr, s);
+    }
   }
   // ---- AdamW on the look-ahead embeddings; the model's own tensor follows in its storage type ----
   T.step += 1;

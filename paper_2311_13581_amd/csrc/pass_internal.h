@@ -231,24 +231,37 @@ int prefill_resid_strips(const Params &p, int M);
 
 void launch_gemm_logits(const Params &p, const GemmTuning &tn, const void *W, float *logits, int M, hipStream_t s);
 
+// ---- look-ahead embedding training: matrix-core pieces (kernels_mfma.hip) ----
+void launch_gemm_gateup_save(const Params &p, const void *W, float *gu_save, int M, hipStream_t s);
+int plain_gemm_slices(int N, int K);
+int launch_gemm_plain(const Params &p, const void *W, const uint16_t *X, int M, int N, int K, float *part, hipStream_t s);
+void launch_transpose_packed(const void *src, void *dst, int N, int K, hipStream_t s);
 // ---- look-ahead embedding training (kernels_train.hip) ----
 constexpr int kTrainSplits = 32;    // row slices of a transposed projection (partial sums: kTrainSplits x M x K floats)
 constexpr int kTrainMaxKeys = 8192; // longest context a training step takes
 constexpr int kTrainAttnChunk = 256; // keys per workgroup of the attention backward
 constexpr int kTrainAttnSplits = kTrainMaxKeys / kTrainAttnChunk;  // its partial dq: [kTrainAttnSplits][kMaxRows][D] floats
 void launch_assemble_train(const Params &p, int dtype, const void *tok_emb, const float *master, int B, int R, hipStream_t s);
-void launch_ce_grad(float *logits, const int32_t *targets, float scale, float *row_loss, int M, int V, hipStream_t s);
+void launch_assemble_train_mfma(const Params &p, const void *tok_emb, const float *master, const void *gain0, int B, int R,
+                                hipStream_t s);
+// x_out not null: the gradient leaves as (hi, lo) tiles of V features instead of in place
+void launch_ce_grad(float *logits, const int32_t *targets, float scale, float *row_loss, int M, int V, uint16_t *x_out,
+                    hipStream_t s);
 void launch_gemm_t(int dtype, const float *dY, int ldy, const void *W, float *part, float *out, int ldo, int M, int N, int K,
                    hipStream_t s);
-void launch_rmsnorm_bwd(const Params &p, int dtype, const float *x, const void *gain, const float *dy, float *dx_acc, int M,
-                        int accumulate, hipStream_t s);
+// gradients that come out of a matrix-core product arrive as KS slices, `slice_stride` floats apart, which the
+// consumer adds in order (KS = 1: a plain array); *_x outputs: (hi, lo) tiles for the next matrix-core product
+void launch_rmsnorm_bwd(const Params &p, int dtype, const float *x, const void *gain, const float *dy, int KS, size_t slice_stride,
+                        float *dx_acc, int M, int accumulate, uint16_t *dx_x, hipStream_t s);
 void launch_swiglu_bwd(const Params &p, const float *gu, const float *dact, float *dgu, int M, hipStream_t s);
+void launch_swiglu_bwd_tiles(const Params &p, const float *gu, const float *dact, int KS, size_t slice_stride, uint16_t *dgu_x,
+                             int M, hipStream_t s);
 // q_saved [M][ldq] rotated queries; o / o_x: the forward pass's attention output as fp32 [M][D] or as (hi, lo) tiles
 // (one of them null); lse [M][H]; dattn [M][D]; dq_part: workspace; result: dqkv [M][3D] fp32, or, with dqkv_x not
 // null, (hi, lo) tiles of it (dqkv still serves as workspace)
 void launch_attn_bwd(const Params &p, int dtype, int layer, int B, int R, int max_keys, const float *q_saved, int ldq,
-                     const float *o, const uint16_t *o_x, const float *lse, const float *dattn, float *dq_part, float *dqkv,
-                     uint16_t *dqkv_x, hipStream_t s);
+                     const float *o, const uint16_t *o_x, const float *lse, const float *dattn, int KS, size_t slice_stride,
+                     float *dq_part, float *dqkv, uint16_t *dqkv_x, hipStream_t s);
 void launch_lookahead_adamw(int dtype, const float *dh, int B, int R, int d, float *grad, float *master, float *m1, float *m2,
                             void *model_la, float lr, float beta1, float beta2, float eps, float wd, float bc1, float bc2,
                             hipStream_t s);
