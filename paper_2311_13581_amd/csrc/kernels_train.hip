@@ -254,32 +254,43 @@ template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const float *x, const T *gain, const float *dy, int KS, size_t slice_stride,
                                                           float *dx_acc, int d, float eps, int accumulate, uint16_t *dx_x) {
   __shared__ float red[4];
+  constexpr int CH = 8;  // chunks of four features a thread keeps in registers (rows of up to 8192 features)
   const int m = blockIdx.x;
   const size_t base = (size_t)m * d;
+  float4 xv[CH], gy[CH];  // x, and gain * dy with the slices added up
   float ss = 0.f, c = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    const float xv = x[base + i];
-    float dyv = dy[base + i];
-    for (int ks = 1; ks < KS; ++ks) dyv += dy[ks * slice_stride + base + i];
-    ss += xv * xv;
-    c += load_f(gain, i) * dyv * xv;
+#pragma unroll
+  for (int ch = 0; ch < CH; ++ch) {
+    const int i0 = (ch * 256 + threadIdx.x) * 4;
+    xv[ch] = gy[ch] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (i0 < d) {
+      xv[ch] = *(const float4 *)(x + base + i0);
+      float4 dv = *(const float4 *)(dy + base + i0);
+      for (int ks = 1; ks < KS; ++ks) {
+        const float4 t = *(const float4 *)(dy + ks * slice_stride + base + i0);
+        dv.x += t.x; dv.y += t.y; dv.z += t.z; dv.w += t.w;
+      }
+      gy[ch] = make_float4(load_f(gain, i0) * dv.x, load_f(gain, i0 + 1) * dv.y, load_f(gain, i0 + 2) * dv.z, load_f(gain, i0 + 3) * dv.w);
+      ss += xv[ch].x * xv[ch].x + xv[ch].y * xv[ch].y + xv[ch].z * xv[ch].z + xv[ch].w * xv[ch].w;
+      c += gy[ch].x * xv[ch].x + gy[ch].y * xv[ch].y + gy[ch].z * xv[ch].z + gy[ch].w * xv[ch].w;
+    }
   }
   ss = block_sum_256(ss, red);
   c = block_sum_256(c, red);
   const float r = 1.0f / sqrtf(ss / (float)d + eps);
   const float k3 = r * r * r * c / (float)d;
-  for (int i0 = threadIdx.x * 4; i0 < d; i0 += 1024) {
-    float t[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int i = i0 + e;
-      float dyv = dy[base + i];
-      for (int ks = 1; ks < KS; ++ks) dyv += dy[ks * slice_stride + base + i];
-      const float v = load_f(gain, i) * dyv * r - x[base + i] * k3;
-      t[e] = accumulate ? dx_acc[base + i] + v : v;
-      dx_acc[base + i] = t[e];
+  for (int ch = 0; ch < CH; ++ch) {
+    const int i0 = (ch * 256 + threadIdx.x) * 4;
+    if (i0 < d) {
+      float t[4] = {gy[ch].x * r - xv[ch].x * k3, gy[ch].y * r - xv[ch].y * k3, gy[ch].z * r - xv[ch].z * k3, gy[ch].w * r - xv[ch].w * k3};
+      if (accumulate) {
+        const float4 a = *(const float4 *)(dx_acc + base + i0);
+        t[0] += a.x; t[1] += a.y; t[2] += a.z; t[3] += a.w;
+      }
+      *(float4 *)(dx_acc + base + i0) = make_float4(t[0], t[1], t[2], t[3]);
+      if (dx_x) store_split4(dx_x, m, d, i0, t);
     }
-    if (dx_x) store_split4(dx_x, m, d, i0, t);
   }
 }
 
@@ -367,7 +378,7 @@ __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer
   __shared__ __align__(16) float tiles[2][TK][LD];  // K tile, V tile; at the end the parts' dq
   __shared__ __align__(16) float qs[RMAX][HD], dos[RMAX][HD];
   __shared__ float lse_s[RMAX], D_s[RMAX];
-  __shared__ float ds_s[RMAX][TK], p_s[RMAX][TK];
+  __shared__ __align__(16) float ds_s[RMAX][TK], p_s[RMAX][TK];
   static_assert(PARTS * RMAX * HD <= 2 * TK * LD, "the parts' dq must fit the tiles");
   const int split = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
   const int m0 = b * R;
@@ -446,30 +457,52 @@ __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer
       }
     }
     __syncthreads();
-    {  // scores, probabilities, dS: thread = (key, row r = rs, rs + 8)
-      const int key = tid & 31, rs = tid >> 5, j = t0 + key;
-      for (int r = rs; r < R; r += 8) {
+    {  // scores, probabilities, dS: eight adjacent lanes share a key, each with an eighth of the dimensions in
+       // registers for all rows (every K and V value leaves LDS once); the eighths meet through lane exchanges
+      constexpr int DPT = HD / 8;
+      const int key = tid >> 3, part8 = tid & 7, j = t0 + key;
+      float kk[DPT], vv[DPT];
+#pragma unroll
+      for (int i4 = 0; i4 < DPT; i4 += 4) {
+        const float4 kq = *(const float4 *)&tiles[0][key][part8 * DPT + i4], vq = *(const float4 *)&tiles[1][key][part8 * DPT + i4];
+        kk[i4] = kq.x; kk[i4 + 1] = kq.y; kk[i4 + 2] = kq.z; kk[i4 + 3] = kq.w;
+        vv[i4] = vq.x; vv[i4 + 1] = vq.y; vv[i4 + 2] = vq.z; vv[i4 + 3] = vq.w;
+      }
+      for (int r = 0; r < R; ++r) {
         float sc = 0.f, dp = 0.f;
-#pragma unroll 8
-        for (int d4 = 0; d4 < HD; d4 += 4) {
-          const float4 kq = *(const float4 *)&tiles[0][key][d4], vq = *(const float4 *)&tiles[1][key][d4];
-          const float4 qq = *(const float4 *)&qs[r][d4], dd = *(const float4 *)&dos[r][d4];
-          sc = fmaf(qq.x, kq.x, sc); sc = fmaf(qq.y, kq.y, sc); sc = fmaf(qq.z, kq.z, sc); sc = fmaf(qq.w, kq.w, sc);
-          dp = fmaf(dd.x, vq.x, dp); dp = fmaf(dd.y, vq.y, dp); dp = fmaf(dd.z, vq.z, dp); dp = fmaf(dd.w, vq.w, dp);
+#pragma unroll
+        for (int i4 = 0; i4 < DPT; i4 += 4) {
+          const float4 qq = *(const float4 *)&qs[r][part8 * DPT + i4], dd = *(const float4 *)&dos[r][part8 * DPT + i4];
+          sc = fmaf(qq.x, kk[i4], sc); sc = fmaf(qq.y, kk[i4 + 1], sc); sc = fmaf(qq.z, kk[i4 + 2], sc); sc = fmaf(qq.w, kk[i4 + 3], sc);
+          dp = fmaf(dd.x, vv[i4], dp); dp = fmaf(dd.y, vv[i4 + 1], dp); dp = fmaf(dd.z, vv[i4 + 2], dp); dp = fmaf(dd.w, vv[i4 + 3], dp);
         }
-        const bool ok = j < k_hi && j <= pos0 + r;
-        const float pj = ok ? expf(sc * scale - lse_s[r]) : 0.f;
-        p_s[r][key] = pj;
-        ds_s[r][key] = ok ? pj * (dp - D_s[r]) : 0.f;
+        sc += __shfl_xor(sc, 1); dp += __shfl_xor(dp, 1);
+        sc += __shfl_xor(sc, 2); dp += __shfl_xor(dp, 2);
+        sc += __shfl_xor(sc, 4); dp += __shfl_xor(dp, 4);
+        if (part8 == 0) {
+          const bool ok = j < k_hi && j <= pos0 + r;
+          const float pj = ok ? expf(sc * scale - lse_s[r]) : 0.f;
+          p_s[r][key] = pj;
+          ds_s[r][key] = ok ? pj * (dp - D_s[r]) : 0.f;
+        }
       }
     }
     __syncthreads();
-    // dq: thread (part, dim) takes the keys part, part + PARTS, ...
-    for (int key = part; key < TK; key += PARTS) {
-      const float kd = tiles[0][key][dim];
+    // dq: thread (part, dim) takes a run of TK / PARTS keys, four at a time
+    {
+      constexpr int KPP = TK / PARTS;
+      const int key0 = part * KPP;
 #pragma unroll
-      for (int r = 0; r < RMAX; ++r)
-        if (r < R) dq[r] = fmaf(ds_s[r][key], kd, dq[r]);
+      for (int kb = 0; kb < KPP; kb += 4) {
+        const float k0 = tiles[0][key0 + kb][dim], k1 = tiles[0][key0 + kb + 1][dim], k2 = tiles[0][key0 + kb + 2][dim],
+                    k3 = tiles[0][key0 + kb + 3][dim];
+#pragma unroll
+        for (int r = 0; r < RMAX; ++r)
+          if (r < R) {
+            const float4 d4 = *(const float4 *)&ds_s[r][key0 + kb];
+            dq[r] = fmaf(d4.x, k0, dq[r]); dq[r] = fmaf(d4.y, k1, dq[r]); dq[r] = fmaf(d4.z, k2, dq[r]); dq[r] = fmaf(d4.w, k3, dq[r]);
+          }
+      }
     }
     // the block's own keys in this tile
     for (int j = max(t0, pos0) + part; j < min(t0 + TK, k_hi); j += PARTS) {

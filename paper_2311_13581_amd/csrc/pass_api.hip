@@ -1195,6 +1195,7 @@ int pass_train_begin(pass_ctx *c, void *device_workspace, size_t bytes, int32_t 
     return fail(c, PASS_ESTATE, "training on the matrix-core path needs d_model, n_heads * head_dim and d_ffn in multiples of 64 and the "
                                 "vocabulary in multiples of 32: load the model with the \"path\" option at 1");
   if (c->cfg.k < 1) return fail(c, PASS_EINVAL, "the model has no look-ahead embeddings (k = 0)");
+  if (c->P.d > 8192 || c->P.d % 4) return fail(c, PASS_ESTATE, "training takes models of d_model up to 8192, in multiples of 4");
   if (!device_workspace || ((uintptr_t)device_workspace & 255) || bytes < carve_train(c->cfg, c->use_mfma, nullptr, nullptr))
     return fail(c, PASS_EINVAL, "training workspace null, misaligned or smaller than pass_train_bytes");
   if (init_token >= c->cfg.vocab) return fail(c, PASS_EINVAL, "init_token outside the vocabulary");
