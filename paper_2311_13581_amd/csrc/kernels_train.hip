@@ -355,6 +355,40 @@ void launch_swiglu_bwd_tiles(const Params &p, const float *gu, const float *dact
 // q is the rotated query kept by the forward pass; dq / dK / dV are still rotated here:
 // attn_bwd_finish_kernel adds up the chunks and turns them back.
 // ---------------------------------------------------------------------------------------------
+// eight consecutive cache values as loaded, untouched until they are needed (so that the loads stay in flight)
+template <typename T>
+struct Raw8;
+template <>
+struct Raw8<float> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const float *p, size_t off, bool in) {
+    a = b = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (in) {
+      a = *(const float4 *)(p + off);
+      b = *(const float4 *)(p + off + 4);
+    }
+  }
+  __device__ __forceinline__ void get(float (&v)[8]) const {
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
+};
+template <>
+struct Raw8<bf16_t> {
+  uint4 a;
+  __device__ __forceinline__ void load(const bf16_t *p, size_t off, bool in) {
+    a = make_uint4(0u, 0u, 0u, 0u);
+    if (in) a = *(const uint4 *)(p + off);
+  }
+  __device__ __forceinline__ void get(float (&v)[8]) const {
+    const uint32_t w[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[2 * e] = __uint_as_float(w[e] << 16);
+      v[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
+    }
+  }
+};
+
 __device__ __forceinline__ void load8(const float *p, size_t off, float (&v)[8]) {
   const float4 a = *(const float4 *)(p + off), b = *(const float4 *)(p + off + 4);
   v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
@@ -369,16 +403,31 @@ __device__ __forceinline__ void load8(const bf16_t *p, size_t off, float (&v)[8]
   }
 }
 
-template <typename T, int HD>
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+// sum over each aligned group of 8 lanes; every lane of the group ends with the total
+__device__ __forceinline__ float group_sum8(float v) {
+  v += dpp_move<0x141>(v);  // row_half_mirror: lane i <-> 7 - i
+  v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]
+  return v;
+}
+
+// RB: compile-time bound of the rows (R <= RB; the rows beyond R are carried as zeros), so that the loops over the
+// rows unroll and their LDS reads are requested together instead of one round trip after the other.
+template <typename T, int HD, int RB>
 __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer, int R, const float *q_saved, int ldq,
                                                              const float *o_f32, const uint16_t *o_x, const float *lse,
                                                              const float *dattn, int KS, size_t slice_stride, float *dq_part,
                                                              float *dqkv) {
-  constexpr int TK = 32, LD = HD + 4, RMAX = kMaxK + 1, PARTS = 256 / HD;
+  constexpr int TK = 32, LD = HD + 4, RMAX = RB, PARTS = 256 / HD;
   __shared__ __align__(16) float tiles[2][TK][LD];  // K tile, V tile; at the end the parts' dq
-  __shared__ __align__(16) float qs[RMAX][HD], dos[RMAX][HD];
+  __shared__ __align__(16) float qs[RB][HD], dos[RB][HD];   // the rows' q and dO
+  __shared__ __align__(16) float ds_s[RB][TK], p_s[RB][TK];  // dS and P of the tile in hand
   __shared__ float lse_s[RMAX], D_s[RMAX];
-  __shared__ __align__(16) float ds_s[RMAX][TK], p_s[RMAX][TK];
+  __shared__ int pages_s[kTrainAttnChunk / 16 + 1];  // pages hold at least 16 positions
   static_assert(PARTS * RMAX * HD <= 2 * TK * LD, "the parts' dq must fit the tiles");
   const int split = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
   const int m0 = b * R;
@@ -391,11 +440,15 @@ __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer
   const float scale = rsqrtf((float)HD);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
 
-  for (int idx = tid; idx < R * HD; idx += 256) {
+  for (int idx = tid; idx < RB * HD; idx += 256) {
     const int r = idx / HD, dm = idx % HD;
-    qs[r][dm] = q_saved[(size_t)(m0 + r) * ldq + head * HD + dm];
-    float dv = dattn[(size_t)(m0 + r) * p.D + head * HD + dm];
-    for (int ks = 1; ks < KS; ++ks) dv += dattn[ks * slice_stride + (size_t)(m0 + r) * p.D + head * HD + dm];  // slices, in order
+    float qv = 0.f, dv = 0.f;
+    if (r < R) {
+      qv = q_saved[(size_t)(m0 + r) * ldq + head * HD + dm];
+      dv = dattn[(size_t)(m0 + r) * p.D + head * HD + dm];
+      for (int ks = 1; ks < KS; ++ks) dv += dattn[ks * slice_stride + (size_t)(m0 + r) * p.D + head * HD + dm];  // slices, in order
+    }
+    qs[r][dm] = qv;
     dos[r][dm] = dv;
   }
   __syncthreads();
@@ -418,45 +471,72 @@ __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer
       lse_s[r] = lse[(size_t)(m0 + r) * p.H + head];
     }
   }
+  if (tid >= R && tid < RB) D_s[tid] = lse_s[tid] = 0.f;
+
+  // the chunk's pages, looked up once
+  const int page_lo = k_lo >> p.page_shift;
+  for (int i = tid; i <= ((k_hi - 1) >> p.page_shift) - page_lo; i += 256)
+    pages_s[i] = p.block_table[(size_t)slot * p.pages_per_seq + page_lo + i];
+  __syncthreads();  // pages_s, D_s and lse_s are in place
 
   const int dim = tid % HD, part = tid / HD;
   float dq[RMAX];
 #pragma unroll
   for (int r = 0; r < RMAX; ++r) dq[r] = 0.f;
 
-  for (int t0 = k_lo; t0 < k_hi; t0 += TK) {
-    __syncthreads();  // the previous tile has been consumed (first trip: D_s and lse_s are in place)
-    for (int c = tid; c < TK * HD / 8; c += 256) {
-      const int key = c / (HD / 8), d0 = (c % (HD / 8)) * 8, j = t0 + key;
-      float kv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}, vv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-      if (j < k_hi) {
-        const size_t off = kv_offset(p, layer, slot, j, head) + d0;
-        load8(kpool, off, kv);
-        if (!p.v_transposed) load8(vpool, off, vv);
+  // The next tile's K and V travel from memory into registers while the tile in hand is worked on; a thread
+  // carries NCH chunks of eight values of each.  K: chunk = (key, eight dimensions).  V: the same when its pages
+  // hold [position][dim]; when they hold [dim][position] (matrix-core attention), chunk = (dimension, eight
+  // consecutive keys: a tile starts at a multiple of 32 keys and a page holds a multiple of 32, so they share a page).
+  constexpr int NCH = TK * HD / 8 / 256;
+  Raw8<T> kraw[NCH], vraw[NCH];
+  auto fetch = [&](int t0) {
+#pragma unroll
+    for (int u = 0; u < NCH; ++u) {
+      const int c = u * 256 + tid;
+      {
+        const int key = c / (HD / 8), d0 = (c % (HD / 8)) * 8, j = t0 + key;
+        const bool in = j < k_hi;
+        const size_t off =
+            in ? ((((size_t)layer * p.n_pages + pages_s[(j >> p.page_shift) - page_lo]) * p.H + head) * p.page_size + (j & (p.page_size - 1))) * HD + d0 : 0;
+        kraw[u].load(kpool, off, in);
+        if (!p.v_transposed) vraw[u].load(vpool, off, in);
       }
+      if (p.v_transposed) {
+        const int dv = c / (TK / 8), j0 = t0 + (c % (TK / 8)) * 8;
+        const bool in = j0 < k_hi;
+        const size_t off =
+            in ? ((((size_t)layer * p.n_pages + pages_s[(j0 >> p.page_shift) - page_lo]) * p.H + head) * HD + dv) * p.page_size + (j0 & (p.page_size - 1)) : 0;
+        vraw[u].load(vpool, off, in);
+      }
+    }
+  };
+  auto stash = [&](int t0) {
+#pragma unroll
+    for (int u = 0; u < NCH; ++u) {
+      const int c = u * 256 + tid;
+      float kv[8], vv[8];
+      kraw[u].get(kv);
+      vraw[u].get(vv);
+      const int key = c / (HD / 8), d0 = (c % (HD / 8)) * 8;
       *(float4 *)&tiles[0][key][d0] = make_float4(kv[0], kv[1], kv[2], kv[3]);
       *(float4 *)&tiles[0][key][d0 + 4] = make_float4(kv[4], kv[5], kv[6], kv[7]);
       if (!p.v_transposed) {
         *(float4 *)&tiles[1][key][d0] = make_float4(vv[0], vv[1], vv[2], vv[3]);
         *(float4 *)&tiles[1][key][d0 + 4] = make_float4(vv[4], vv[5], vv[6], vv[7]);
-      }
-    }
-    if (p.v_transposed) {
-      // pages hold [head][dim][page_size]: eight consecutive keys of one dimension per load (a tile
-      // starts at a multiple of 32 keys and a page holds a multiple of 32, so they share a page)
-      for (int c = tid; c < HD * (TK / 8); c += 256) {
-        const int dv = c / (TK / 8), key0 = (c % (TK / 8)) * 8, j0 = t0 + key0;
-        float vv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        if (j0 < k_hi) {
-          const int page = p.block_table[(size_t)slot * p.pages_per_seq + (j0 >> p.page_shift)];
-          const size_t off = ((((size_t)layer * p.n_pages + page) * p.H + head) * p.hd + dv) * p.page_size + (j0 & (p.page_size - 1));
-          load8(vpool, off, vv);
-        }
+      } else {
+        const int dv = c / (TK / 8), key0 = (c % (TK / 8)) * 8;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) tiles[1][key0 + e][dv] = (j0 + e < k_hi) ? vv[e] : 0.f;  // unwritten positions hold anything
+        for (int e = 0; e < 8; ++e) tiles[1][key0 + e][dv] = (t0 + key0 + e < k_hi) ? vv[e] : 0.f;  // unwritten positions hold anything
       }
     }
+  };
+  fetch(k_lo);
+  for (int t0 = k_lo; t0 < k_hi; t0 += TK) {
+    __syncthreads();  // the previous tile has been consumed
+    stash(t0);
     __syncthreads();
+    if (t0 + TK < k_hi) fetch(t0 + TK);
     {  // scores, probabilities, dS: eight adjacent lanes share a key, each with an eighth of the dimensions in
        // registers for all rows (every K and V value leaves LDS once); the eighths meet through lane exchanges
       constexpr int DPT = HD / 8;
@@ -468,7 +548,8 @@ __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer
         kk[i4] = kq.x; kk[i4 + 1] = kq.y; kk[i4 + 2] = kq.z; kk[i4 + 3] = kq.w;
         vv[i4] = vq.x; vv[i4 + 1] = vq.y; vv[i4 + 2] = vq.z; vv[i4 + 3] = vq.w;
       }
-      for (int r = 0; r < R; ++r) {
+#pragma unroll
+      for (int r = 0; r < RB; ++r) {
         float sc = 0.f, dp = 0.f;
 #pragma unroll
         for (int i4 = 0; i4 < DPT; i4 += 4) {
@@ -476,11 +557,10 @@ __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer
           sc = fmaf(qq.x, kk[i4], sc); sc = fmaf(qq.y, kk[i4 + 1], sc); sc = fmaf(qq.z, kk[i4 + 2], sc); sc = fmaf(qq.w, kk[i4 + 3], sc);
           dp = fmaf(dd.x, vv[i4], dp); dp = fmaf(dd.y, vv[i4 + 1], dp); dp = fmaf(dd.z, vv[i4 + 2], dp); dp = fmaf(dd.w, vv[i4 + 3], dp);
         }
-        sc += __shfl_xor(sc, 1); dp += __shfl_xor(dp, 1);
-        sc += __shfl_xor(sc, 2); dp += __shfl_xor(dp, 2);
-        sc += __shfl_xor(sc, 4); dp += __shfl_xor(dp, 4);
+        sc = group_sum8(sc);
+        dp = group_sum8(dp);
         if (part8 == 0) {
-          const bool ok = j < k_hi && j <= pos0 + r;
+          const bool ok = r < R && j < k_hi && j <= pos0 + r;
           const float pj = ok ? expf(sc * scale - lse_s[r]) : 0.f;
           p_s[r][key] = pj;
           ds_s[r][key] = ok ? pj * (dp - D_s[r]) : 0.f;
@@ -497,11 +577,10 @@ __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer
         const float k0 = tiles[0][key0 + kb][dim], k1 = tiles[0][key0 + kb + 1][dim], k2 = tiles[0][key0 + kb + 2][dim],
                     k3 = tiles[0][key0 + kb + 3][dim];
 #pragma unroll
-        for (int r = 0; r < RMAX; ++r)
-          if (r < R) {
-            const float4 d4 = *(const float4 *)&ds_s[r][key0 + kb];
-            dq[r] = fmaf(d4.x, k0, dq[r]); dq[r] = fmaf(d4.y, k1, dq[r]); dq[r] = fmaf(d4.z, k2, dq[r]); dq[r] = fmaf(d4.w, k3, dq[r]);
-          }
+        for (int r = 0; r < RMAX; ++r) {  // rows beyond R carry dS = 0
+          const float4 d4 = *(const float4 *)&ds_s[r][key0 + kb];
+          dq[r] = fmaf(d4.x, k0, dq[r]); dq[r] = fmaf(d4.y, k1, dq[r]); dq[r] = fmaf(d4.z, k2, dq[r]); dq[r] = fmaf(d4.w, k3, dq[r]);
+        }
       }
     }
     // the block's own keys in this tile
@@ -519,8 +598,7 @@ __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer
   __syncthreads();
   float *comb = &tiles[0][0][0];  // [PARTS][RMAX][HD]
 #pragma unroll
-  for (int r = 0; r < RMAX; ++r)
-    if (r < R) comb[(part * RMAX + r) * HD + dim] = dq[r];
+  for (int r = 0; r < RMAX; ++r) comb[(part * RMAX + r) * HD + dim] = dq[r];
   __syncthreads();
   if (part == 0) {
     for (int r = 0; r < R; ++r) {
@@ -569,20 +647,36 @@ __global__ __launch_bounds__(256) void attn_bwd_finish_kernel(Params p, int R, c
   }
 }
 
+template <typename T, int HD>
+static void attn_bwd_dispatch(const Params &p, dim3 grid, int layer, int R, const float *q_saved, int ldq, const float *o,
+                              const uint16_t *o_x, const float *lse, const float *dattn, int KS, size_t slice_stride, float *dq_part,
+                              float *dqkv, hipStream_t s) {
+#define PASS_ATTN_BWD(RB) \
+  attn_bwd_split_kernel<T, HD, RB><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv)
+  if (R <= 2) PASS_ATTN_BWD(2);
+  else if (R <= 3) PASS_ATTN_BWD(3);
+  else if (R <= 4) PASS_ATTN_BWD(4);
+  else if (R <= 5) PASS_ATTN_BWD(5);
+  else if (R <= 6) PASS_ATTN_BWD(6);
+  else if (R <= 8) PASS_ATTN_BWD(8);
+  else PASS_ATTN_BWD(kMaxK + 1);
+#undef PASS_ATTN_BWD
+}
+
 void launch_attn_bwd(const Params &p, int dtype, int layer, int B, int R, int max_keys, const float *q_saved, int ldq,
                      const float *o, const uint16_t *o_x, const float *lse, const float *dattn, int KS, size_t slice_stride,
                      float *dq_part, float *dqkv, uint16_t *dqkv_x, hipStream_t s) {
   dim3 grid((max_keys + kTrainAttnChunk - 1) / kTrainAttnChunk, p.H, B);
   if (p.hd == 128) {
     if (dtype == PASS_F32)
-      attn_bwd_split_kernel<float, 128><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv);
+      attn_bwd_dispatch<float, 128>(p, grid, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv, s);
     else
-      attn_bwd_split_kernel<bf16_t, 128><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv);
+      attn_bwd_dispatch<bf16_t, 128>(p, grid, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv, s);
   } else {
     if (dtype == PASS_F32)
-      attn_bwd_split_kernel<float, 64><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv);
+      attn_bwd_dispatch<float, 64>(p, grid, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv, s);
     else
-      attn_bwd_split_kernel<bf16_t, 64><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv);
+      attn_bwd_dispatch<bf16_t, 64>(p, grid, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv, s);
   }
   attn_bwd_finish_kernel<<<B * R, 256, 0, s>>>(p, R, dq_part, dqkv, dqkv_x);
 }
