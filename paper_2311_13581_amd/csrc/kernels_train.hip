@@ -265,11 +265,13 @@ __global__ __launch_bounds__(256) void rmsnorm_bwd_kernel(const float *x, const 
     xv[ch] = gy[ch] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (i0 < d) {
       xv[ch] = *(const float4 *)(x + base + i0);
-      float4 dv = *(const float4 *)(dy + base + i0);
-      for (int ks = 1; ks < KS; ++ks) {
-        const float4 t = *(const float4 *)(dy + ks * slice_stride + base + i0);
-        dv.x += t.x; dv.y += t.y; dv.z += t.z; dv.w += t.w;
-      }
+      float4 sl[8];  // up to eight slices, requested together (index clamped, surplus dropped), added in order
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) sl[ks] = *(const float4 *)(dy + (size_t)min(ks, KS - 1) * slice_stride + base + i0);
+      float4 dv = sl[0];
+#pragma unroll
+      for (int ks = 1; ks < 8; ++ks)
+        if (ks < KS) { dv.x += sl[ks].x; dv.y += sl[ks].y; dv.z += sl[ks].z; dv.w += sl[ks].w; }
       gy[ch] = make_float4(load_f(gain, i0) * dv.x, load_f(gain, i0 + 1) * dv.y, load_f(gain, i0 + 2) * dv.z, load_f(gain, i0 + 3) * dv.w);
       ss += xv[ch].x * xv[ch].x + xv[ch].y * xv[ch].y + xv[ch].z * xv[ch].z + xv[ch].w * xv[ch].w;
       c += gy[ch].x * xv[ch].x + gy[ch].y * xv[ch].y + gy[ch].z * xv[ch].z + gy[ch].w * xv[ch].w;
@@ -615,11 +617,11 @@ __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer
 // matrix-core projection that follows.  Four consecutive features (two rotary pairs) per thread.
 __global__ __launch_bounds__(256) void attn_bwd_finish_kernel(Params p, int R, const float *dq_part, float *dqkv,
                                                               uint16_t *dqkv_x) {
-  const int m = blockIdx.x, half = p.hd / 2;
+  const int m = blockIdx.x, which = blockIdx.y, half = p.hd / 2;  // which: 0 q, 1 k, 2 v
   if (p.row_slot[m] < 0) return;
   const int n_splits = (p.row_pos[(m / R) * R] + R + kTrainAttnChunk - 1) / kTrainAttnChunk;
-  for (int idx = threadIdx.x; idx < 3 * p.D / 4; idx += 256) {
-    const int col = idx * 4, which = col / p.D, c = col - which * p.D;
+  for (int c = threadIdx.x * 4; c < p.D; c += 1024) {
+    const int col = which * p.D + c;
     float t[4];
     if (which == 0) {
       t[0] = t[1] = t[2] = t[3] = 0.f;
@@ -678,7 +680,7 @@ void launch_attn_bwd(const Params &p, int dtype, int layer, int B, int R, int ma
     else
       attn_bwd_dispatch<bf16_t, 64>(p, grid, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv, s);
   }
-  attn_bwd_finish_kernel<<<B * R, 256, 0, s>>>(p, R, dq_part, dqkv, dqkv_x);
+  attn_bwd_finish_kernel<<<dim3(B * R, 3), 256, 0, s>>>(p, R, dq_part, dqkv, dqkv_x);
 }
 
 // ---------------------------------------------------------------------------------------------
