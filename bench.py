@@ -148,11 +148,16 @@ def train_report(binding, devgen, synth, torch, np, n_steps, path):
     step_s = (time.perf_counter() - t0) / n_steps
     g.close()
     sh = w.shape
+    kv_bytes = sum(len(p) - 1 + w.k + 1 for p in prompts) * sh.n_layers * 2 * sh.n_heads * sh.head_dim * 2
     weight_bytes = 2 * (sh.n_layers * (4 * sh.d_model * sh.n_heads * sh.head_dim + 3 * sh.d_model * sh.d_ffn) + sh.vocab * sh.d_model)
     return {"workload": w.name, "k": w.k, "batch": w.batch, "prefix_len": [len(p) for p in prompts], "steps": n_steps,
             "ms_per_step": step_s * 1e3, "loss_first": losses[0], "loss_last": losses[-1],
-            # the frozen weights are read once forward and once backward
-            "weights_twice_GBps": 2 * weight_bytes / step_s / 1e9, "prefix_prompt_pass_ms": prefill_s * 1e3,
+            # algorithmic bytes of a step: the frozen weights once forward and once backward (the packed
+            # transposes), the batch's cached K/V once by the forward and once by the backward attention
+            "algorithmic_bytes_per_step": 2 * weight_bytes + 2 * kv_bytes,
+            "achieved_GBps": (2 * weight_bytes + 2 * kv_bytes) / step_s / 1e9,
+            "frac_of_peak": (2 * weight_bytes + 2 * kv_bytes) / step_s / 1e9 / HBM_PEAK_GBS,
+            "prefix_prompt_pass_ms": prefill_s * 1e3,
             "path": "generic" if path else "auto"}
 
 

@@ -203,23 +203,28 @@ int pass_run_iterations(pass_ctx *ctx, const int32_t *slots, int n_slots, int n_
  * values are fp32 ("master") and enter the forward pass unrounded; after every step the model's
  * own look-ahead tensor is refreshed from them in its storage type, so pass_draft uses what was
  * learned.  Slots are left as they were (the block's K/V rows lie beyond kv_len: dead).
- * Training runs on the generic kernels: the context must have been loaded with option "path" = 1.
- *   pass_train_bytes   device bytes pass_train_begin needs for this configuration (0: invalid or k = 0)
+ * Both kernel paths train.  On the matrix-core path (bf16 models, the default) the forward pass is
+ * the drafting call's and every backward product runs on a packed transpose of its weight matrix,
+ * which pass_train_begin builds inside the workspace: the workspace then holds a second copy of
+ * the model's matrices, and d_model, n_heads * head_dim and d_ffn must be multiples of 64, the
+ * vocabulary a multiple of 32 (else PASS_ESTATE: load such a model with option "path" = 1).
+ *   pass_train_bytes   device bytes pass_train_begin needs for this context, after pass_load_weights
+ *                      (0: no context, no weights, or k = 0)
  *   pass_train_begin   device_workspace: caller's device memory (256-byte aligned, kept alive while
  *                      training); the embeddings start from the embedding of init_token (the paper:
  *                      [UNK]) or, with init_token < 0, from the model's own look-ahead tensor;
  *                      AdamW's moments and step count start at zero
  *   pass_train_step    slots: host, n_slots prefilled slots, (1+k) * n_slots <= PASS_MAX_ROWS, at most
  *                      8192 keys each; targets: host [n_slots * k]; *out_loss: the batch loss before
- *                      the update (may be NULL)
+ *                      the update (may be NULL).  Returns when the step is done.
  *   pass_train_read    what = 0: the master values, 1: the gradient of the last step, 2 / 3: AdamW's first /
  *                      second moment; out: host [k * d_model]
  *   pass_train_resume  restores a saved training state: master values, moments (host [k * d_model] each; a
  *                      NULL pointer leaves that part as it is) and the number of optimiser steps taken so
  *                      far (it enters AdamW's bias correction); the model's own look-ahead tensor follows
  *                      the master values
- * Errors: PASS_ESTATE (matrix-core path, no pass_train_begin, look-ahead options not at their
- * defaults), PASS_EINVAL, PASS_ECAPACITY. */
+ * Errors: PASS_ESTATE (no pass_train_begin, look-ahead options not at their defaults, a shape the
+ * path cannot train, d_model above 8192), PASS_EINVAL, PASS_ECAPACITY. */
 typedef struct {
   float lr, beta1, beta2, eps, weight_decay;
 } pass_adamw;

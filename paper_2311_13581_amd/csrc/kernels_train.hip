@@ -2,15 +2,19 @@
 // frozen, only the L x d_model look-ahead embeddings learn, and the loss is taken on the outputs of
 // the look-ahead rows of the block (w_T, [LA]_1 .. [LA]_L): row [LA]_i predicts token w_{T+1+i}.
 //
-// The forward pass of a training step is the drafting call on the generic kernels (fp32
-// activations, plain weight layout) with the look-ahead rows taken from fp32 master values; the
-// host keeps a copy of what the backward pass needs of every layer (the residual stream before
-// each norm, the rotated queries, the gate / up pre-activations).  This file holds what is new:
-// the backward kernels for M <= 64 rows, and AdamW.
-//
-// Nothing here needs a weight gradient, so the only activations kept are those a non-linearity
-// needs (norms, softmax, SwiGLU); a projection y = W x is differentiated as dx = W^T dy by
-// gemm_t_*: the weights are streamed once more, row by row.
+// The forward pass of a training step is the drafting call with the look-ahead rows taken from fp32
+// master values, each layer working in an area of its own so that what the backward pass needs stays
+// behind: the residual stream before each norm, the rotated queries, the attention output and the
+// ln-sum-exp of its rows, the gate / up pre-activations.  Nothing here needs a weight gradient, so
+// those are the only activations kept (norms, softmax, SwiGLU); a projection y = W x is
+// differentiated as dx = W^T dy.
+//   matrix-core path (bf16 models): the forward kernels are the decode step's; dx = W^T dy is the same
+//     streaming GEMM on a packed transpose of W (built once), its input dy travels as (hi, lo) tiles
+//     written by the kernel that produces it, its output as slices over the contraction that the
+//     consumer adds in order.  This file holds the elementwise backward kernels in that form.
+//   generic path (fp32 models, or "path" = 1): fp32 arrays throughout, dx = W^T dy by gemm_t_*, which
+//     streams the plain weights once more, row by row.
+// Attention backward (both paths) is split over chunks of the keys like the forward pass.
 #include "pass_internal.h"
 
 namespace pass {
