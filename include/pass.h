@@ -119,6 +119,19 @@ int pass_load_weights(pass_ctx *ctx, const pass_weights *w, int on_device);
  * plus one call's rows exceed max_seq_len, or the page pool is exhausted). */
 int pass_prefill(pass_ctx *ctx, int slot, uint32_t seq_id, const int32_t *prompt, int n);
 
+/* pass_prefill for several sequences at once (Algorithm 1's "initial prompt sequence" of a batch; the prefixes
+ * of a training batch): slots[n_slots] distinct, seq_ids[n_slots], lens[n_slots] >= 1, prompts: the prompts one
+ * after the other (host, sum of lens tokens).  The state afterwards is what n_slots calls of pass_prefill
+ * leave.  Where the tiled kernels apply (matrix-core path, more than 2 * PASS_MAX_ROWS rows in all), rows of
+ * several sequences share a pass over the weights: every sequence starts on a block of 128 rows of the pass, a
+ * prompt that does not fit goes on in the next pass, attention runs per sequence.  A row's arithmetic is that of
+ * pass_prefill up to the grouping of the RMSNorm's partial sums, which follows the pass's row count (logits
+ * agree to rounding, not bit for bit).  Elsewhere the prompts go one by one.  Returns when the caches are filled.
+ * Errors as pass_prefill, and PASS_EINVAL for a slot listed twice; slots before the failing one may already
+ * have been restarted. */
+int pass_prefill_batch(pass_ctx *ctx, const int32_t *slots, const uint32_t *seq_ids, const int32_t *prompts,
+                       const int32_t *lens, int n_slots);
+
 /* Release a slot's pages. */
 int pass_release(pass_ctx *ctx, int slot);
 

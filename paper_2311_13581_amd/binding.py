@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libpass_hip.so")
 PASS_F32, PASS_BF16 = 0, 1
 MAX_K, MAX_ROWS = 15, 64
 
-SYMBOLS = ["pass_arena_bytes", "pass_create", "pass_load_weights", "pass_prefill", "pass_release",
+SYMBOLS = ["pass_arena_bytes", "pass_create", "pass_load_weights", "pass_prefill", "pass_prefill_batch", "pass_release",
            "pass_draft", "pass_draft_static", "pass_verify", "pass_generate", "pass_sps_iteration", "pass_run_iterations", "pass_kernel_time", "pass_plain_read", "pass_rng_uniforms", "pass_get_logits", "pass_seq_len",
            "pass_train_bytes", "pass_train_begin", "pass_train_step", "pass_train_read", "pass_train_resume", "pass_set_option", "pass_attention_plan", "pass_get_tokens", "pass_time_step", "pass_last_error", "pass_destroy"]
 
@@ -82,6 +82,7 @@ def load_library():
     L.pass_create.argtypes = [C.POINTER(PassConfig), C.c_void_p, C.c_void_p, C.c_size_t, C.POINTER(C.c_void_p)]
     L.pass_load_weights.argtypes = [C.c_void_p, C.POINTER(PassWeights), C.c_int]
     L.pass_prefill.argtypes = [C.c_void_p, C.c_int, C.c_uint32, ip, C.c_int]
+    L.pass_prefill_batch.argtypes = [C.c_void_p, ip, C.POINTER(C.c_uint32), ip, ip, C.c_int]
     L.pass_release.argtypes = [C.c_void_p, C.c_int]
     L.pass_draft.argtypes = [C.c_void_p, ip, C.c_int, C.POINTER(PassSampling), ip, ip]
     L.pass_draft_static.argtypes = [C.c_void_p, ip, C.c_int, C.POINTER(PassSampling), ip, ip]
@@ -204,6 +205,14 @@ class Pass:
     def prefill(self, slot: int, prompt, seq_id: int = 0):
         p = np.ascontiguousarray(prompt, dtype=np.int32)
         self._check(self.lib.pass_prefill(self.h, slot, seq_id, _ip(p), p.size))
+
+    def prefill_batch(self, slots, prompts, seq_ids=None):
+        s = np.ascontiguousarray(slots, dtype=np.int32)
+        ps = [np.ascontiguousarray(p, dtype=np.int32) for p in prompts]
+        lens = np.array([p.size for p in ps], dtype=np.int32)
+        cat = np.ascontiguousarray(np.concatenate(ps), dtype=np.int32)
+        ids = np.ascontiguousarray(s if seq_ids is None else seq_ids, dtype=np.uint32)
+        self._check(self.lib.pass_prefill_batch(self.h, _ip(s), ids.ctypes.data_as(C.POINTER(C.c_uint32)), _ip(cat), _ip(lens), s.size))
 
     def release(self, slot: int):
         self._check(self.lib.pass_release(self.h, slot))

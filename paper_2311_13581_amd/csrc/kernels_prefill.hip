@@ -50,7 +50,7 @@ struct TileArgs {
   int M, K, n_strips;
   int layer;
   const uint16_t *gain_next;  // RESID: gain of the norm that follows
-  int slot, pos0;             // QKV: the sequence and the position of row 0
+  PrefillSegs segs;           // QKV: whose rows these are (K/V go to that sequence's pages)
   int tiles_m, tiles_n;
   int blk_n, blk_m, blocks_m, n_blocks;  // blocks of tiles, one per die at a time
 };
@@ -286,8 +286,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
               *(floatx4 *)(w.q + (size_t)m * p.D + c) = v;
             } else {
               // K rows [page][head][pos][dim], V pages transposed [page][head][dim][pos]; bf16 storage
-              const int pos = a.pos0 + m;
-              const int page = p.block_table[(size_t)a.slot * p.pages_per_seq + (pos >> p.page_shift)];
+              // (the eight rows of a group share a block: the index is uniform over the wavefront)
+              const int sb = __builtin_amdgcn_readfirstlane(m / kPrefillBlockRows), sr = m % kPrefillBlockRows;
+              if (sr >= a.segs.rows[sb]) continue;  // a padding row: nothing to cache
+              const int pos = a.segs.pos[sb] + sr;
+              const int page = p.block_table[(size_t)a.segs.slot[sb] * p.pages_per_seq + (pos >> p.page_shift)];
               const size_t hbase = ((size_t)a.layer * p.n_pages + page) * p.H + head;
               const int off = pos & (p.page_size - 1);
               if (which == 1) {
@@ -767,18 +770,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // must know.
 int prefill_resid_strips(const Params &p, int M) { return tile_strips(p.d / 16, M, 1); }
 
-void launch_prefill_qkv(const Params &p, const PrefillWs &w, const void *W, int layer, int slot, int pos0, int M,
+void launch_prefill_qkv(const Params &p, const PrefillWs &w, const void *W, int layer, const PrefillSegs &segs, int M,
                         hipStream_t s) {
-  TileArgs a{(const u32x4 *)W, p.xg, M, p.d, 3 * p.D / 16, layer, nullptr, slot, pos0, 0, 0, 0, 0, 0, 0};
+  TileArgs a{(const u32x4 *)W, p.xg, M, p.d, 3 * p.D / 16, layer, nullptr, segs, 0, 0, 0, 0, 0, 0};
   launch_tile<TILE_QKV>(p, w, a, w.resid_strips_opt ? w.resid_strips_opt : tile_strips(a.n_strips, M, 1), s);
 }
 void launch_prefill_resid(const Params &p, const PrefillWs &w, const void *W, const uint16_t *X, int K,
                           const void *gain_next, int M, hipStream_t s) {
-  TileArgs a{(const u32x4 *)W, X, M, K, p.d / 16, 0, (const uint16_t *)gain_next, 0, 0, 0, 0, 0, 0, 0, 0};
+  TileArgs a{(const u32x4 *)W, X, M, K, p.d / 16, 0, (const uint16_t *)gain_next, PrefillSegs{}, 0, 0, 0, 0, 0, 0};
   launch_tile<TILE_RESID>(p, w, a, w.resid_strips, s);
 }
 void launch_prefill_gateup(const Params &p, const PrefillWs &w, const void *W, int M, hipStream_t s) {
-  TileArgs a{(const u32x4 *)W, p.xg, M, p.d, 2 * p.F / 16, 0, nullptr, 0, 0, 0, 0, 0, 0, 0, 0};
+  TileArgs a{(const u32x4 *)W, p.xg, M, p.d, 2 * p.F / 16, 0, nullptr, PrefillSegs{}, 0, 0, 0, 0, 0, 0};
   launch_tile<TILE_GATEUP>(p, w, a, w.resid_strips_opt > 1 ? w.resid_strips_opt : tile_strips(a.n_strips, M, 2), s);
 }
 void launch_prefill_attention(const Params &p, const PrefillWs &w, int layer, int slot, int pos0, int R,
@@ -795,6 +798,57 @@ void launch_prefill_attention(const Params &p, const PrefillWs &w, int layer, in
     dim3 grid((R + 31) / 32, p.H);
     attn_prefill_kernel<2><<<grid, 256, 0, s>>>(p, w, layer, slot, pos0, R);
   }
+}
+
+// Row assembly of a tiled pass that carries rows of several sequences (see PrefillSegs): h (fp32), (hi, lo) of
+// h * gain of the first norm, partial sums of h^2 (partial 0 carries the whole row), rotary table at the row's
+// own position.  Padding rows are assembled like any other (their token is whatever `p.prefill_ids` holds for
+// them, position 0): rows are independent, and nothing of a padding row is ever cached or read.
+__global__ __launch_bounds__(256) void assemble_prefill_segs_kernel(Params p, const uint16_t *tok_emb, const uint16_t *gain0,
+                                                                    PrefillSegs segs, int ssq_parts, int ssq_stride) {
+  __shared__ float red[4];
+  const int m = blockIdx.x, sb = m / kPrefillBlockRows, sr = m % kPrefillBlockRows;
+  const int pos = sr < segs.rows[sb] ? segs.pos[sb] + sr : 0;
+  const uint16_t *src = tok_emb + (size_t)clamp_token(p, p.prefill_ids[m]) * p.d;
+  float ss = 0.f;
+  for (int c0 = threadIdx.x * 8; c0 < p.d; c0 += 256 * 8) {
+    const uint4 sv = *(const uint4 *)(src + c0), gv = *(const uint4 *)(gain0 + c0);
+    const uint32_t sw[4] = {sv.x, sv.y, sv.z, sv.w}, gw[4] = {gv.x, gv.y, gv.z, gv.w};
+    float v[8], x[8];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      v[2 * e] = __uint_as_float(sw[e] << 16);
+      v[2 * e + 1] = __uint_as_float(sw[e] & 0xffff0000u);
+      x[2 * e] = v[2 * e] * __uint_as_float(gw[e] << 16);
+      x[2 * e + 1] = v[2 * e + 1] * __uint_as_float(gw[e] & 0xffff0000u);
+    }
+    float4 *hp = (float4 *)(p.h + (size_t)m * p.d + c0);
+    hp[0] = make_float4(v[0], v[1], v[2], v[3]);
+    hp[1] = make_float4(v[4], v[5], v[6], v[7]);
+    const float x0[4] = {x[0], x[1], x[2], x[3]}, x1[4] = {x[4], x[5], x[6], x[7]};
+    store_split4(p.xg, m, p.d, c0, x0);
+    store_split4(p.xg, m, p.d, c0 + 4, x1);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ss += v[e] * v[e];
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  for (int i = threadIdx.x; i < ssq_parts; i += 256)
+    p.ssq[(size_t)i * ssq_stride + m] = (i == 0) ? (red[0] + red[1] + red[2] + red[3]) : 0.f;
+  const int half = p.hd / 2;
+  for (int i = threadIdx.x; i < half; i += 256) {
+    double sn, cs;
+    sincos((double)pos * p.rope_theta[i], &sn, &cs);
+    p.rope_cos[(size_t)m * half + i] = (float)cs;
+    p.rope_sin[(size_t)m * half + i] = (float)sn;
+  }
+}
+
+void launch_assemble_prefill_segs(const Params &p, const void *tok_emb, const void *gain0, const PrefillSegs &segs, int M,
+                                  int ssq_parts, int ssq_stride, hipStream_t s) {
+  assemble_prefill_segs_kernel<<<M, 256, 0, s>>>(p, (const uint16_t *)tok_emb, (const uint16_t *)gain0, segs, ssq_parts, ssq_stride);
 }
 
 }  // namespace pass

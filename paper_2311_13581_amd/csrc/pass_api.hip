@@ -211,7 +211,7 @@ size_t carve(const pass_config &c, char *base, pass_ctx *ctx) {
   P.part_m = A.take<float>(M * c.n_heads * kMaxSplits); P.part_l = A.take<float>(M * c.n_heads * kMaxSplits);
   size_t pool_elems = (size_t)c.n_layers * np * c.n_heads * c.page_size * c.head_dim;
   P.k_pool = A.take<char>(pool_elems * esz); P.v_pool = A.take<char>(pool_elems * esz);
-  int32_t *prompt_buf = A.take<int32_t>(c.max_seq_len);
+  int32_t *prompt_buf = A.take<int32_t>(std::max(c.max_seq_len, kPrefillRows));
 
   void *tok_emb = A.take<char>(V * d * esz), *lm_head = A.take<char>(V * d * esz);
   void *final_norm = A.take<char>(d * esz), *lookahead = A.take<char>((size_t)(c.k ? c.k : 1) * d * esz);
@@ -422,29 +422,53 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
   return PASS_OK;
 }
 
-// Prompt rows [pos0, pos0 + R) of one slot through all layers, R <= pws.rows, tiled kernels.
+// One tiled pass over the weights: the rows `segs` describes (M rows including padding, M <= pws.rows), token
+// ids of all M rows at `ids` (device).  Attention runs per sequence on its own rows of the pass (row_base:
+// multiples of 128, so a sequence's rows are whole 8-row groups of the (hi, lo) tiles).
 // No LM head: the last prompt token stays pending and goes through the first draft call.
-int run_prefill_tiled(pass_ctx *c, int slot, int pos0, int R, const int32_t *ids) {
+struct PassSeg { int slot, pos0, rows, row_base; };
+int run_prefill_pass(pass_ctx *c, const std::vector<PassSeg> &parts, int M, const int32_t *ids) {
   Params P = c->P;
   const Params &B = c->PP;
   P.h = B.h; P.xg = B.xg; P.attn_x = B.attn_x; P.act_x = B.act_x; P.ssq = B.ssq;
   P.rope_cos = B.rope_cos; P.rope_sin = B.rope_sin;
   P.prefill_ids = const_cast<int32_t *>(ids);
   PrefillWs W = c->pws;
-  W.resid_strips = W.resid_strips_opt ? W.resid_strips_opt : prefill_resid_strips(P, R);
+  W.resid_strips = W.resid_strips_opt ? W.resid_strips_opt : prefill_resid_strips(P, M);
   W.np = (P.d / 16 + W.resid_strips - 1) / W.resid_strips;
+  PrefillSegs segs;
+  memset(&segs, 0, sizeof segs);
+  segs.n_blocks = (M + kPrefillBlockRows - 1) / kPrefillBlockRows;
+  for (const PassSeg &g : parts)
+    for (int done = 0; done < g.rows; done += kPrefillBlockRows) {
+      const int b = (g.row_base + done) / kPrefillBlockRows;
+      segs.slot[b] = g.slot;
+      segs.pos[b] = g.pos0 + done;
+      segs.rows[b] = std::min(kPrefillBlockRows, g.rows - done);
+    }
   hipStream_t s = c->stream;
-  launch_assemble_prefill(P, c->tok_emb, c->layers[0].attn_norm, R, W.np, W.rows, s);
+  launch_assemble_prefill_segs(P, c->tok_emb, c->layers[0].attn_norm, segs, M, W.np, W.rows, s);
   for (int l = 0; l < P.L; ++l) {
     const LayerW &w = c->layers[l];
-    launch_prefill_qkv(P, W, w.wqkv, l, slot, pos0, R, s);
-    launch_prefill_attention(P, W, l, slot, pos0, R, s);
-    launch_prefill_resid(P, W, w.wo, P.attn_x, P.D, w.ffn_norm, R, s);
-    launch_prefill_gateup(P, W, w.wgu, R, s);
-    launch_prefill_resid(P, W, w.wdown, P.act_x, P.F, l + 1 < P.L ? c->layers[l + 1].attn_norm : c->final_norm, R, s);
+    launch_prefill_qkv(P, W, w.wqkv, l, segs, M, s);
+    for (const PassSeg &g : parts) {
+      Params Pg = P;
+      PrefillWs Wg = W;
+      Pg.attn_x = P.attn_x + (size_t)g.row_base * 2 * P.D;  // 8-row groups of 16 * D elements
+      Wg.q = W.q + (size_t)g.row_base * P.D;
+      launch_prefill_attention(Pg, Wg, l, g.slot, g.pos0, g.rows, s);
+    }
+    launch_prefill_resid(P, W, w.wo, P.attn_x, P.D, w.ffn_norm, M, s);
+    launch_prefill_gateup(P, W, w.wgu, M, s);
+    launch_prefill_resid(P, W, w.wdown, P.act_x, P.F, l + 1 < P.L ? c->layers[l + 1].attn_norm : c->final_norm, M, s);
   }
   HIP_TRY(c, hipGetLastError());
   return PASS_OK;
+}
+
+// Prompt rows [pos0, pos0 + R) of one slot, R <= pws.rows
+int run_prefill_tiled(pass_ctx *c, int slot, int pos0, int R, const int32_t *ids) {
+  return run_prefill_pass(c, {PassSeg{slot, pos0, R, 0}}, R, ids);
 }
 
 int check_slots(pass_ctx *c, const int32_t *slots, int n_slots, int want_state) {
@@ -725,9 +749,8 @@ int pass_release(pass_ctx *c, int slot) {
   return PASS_OK;
 }
 
-int pass_prefill(pass_ctx *c, int slot, uint32_t seq_id, const int32_t *prompt, int n) {
-  if (!c) return PASS_EINVAL;
-  if (!c->weights_loaded) return fail(c, PASS_ESTATE, "weights not loaded");
+// what pass_prefill does before and after the prompt's rows go through the model
+static int prefill_begin(pass_ctx *c, int slot, uint32_t seq_id, const int32_t *prompt, int n) {
   if (slot < 0 || slot >= c->cfg.max_slots) return fail(c, PASS_EINVAL, "slot %d out of range", slot);
   if (!prompt || n < 1) return fail(c, PASS_EINVAL, "prompt must hold at least one token");
   for (int i = 0; i < n; ++i)
@@ -736,13 +759,30 @@ int pass_prefill(pass_ctx *c, int slot, uint32_t seq_id, const int32_t *prompt, 
   int rc = pass_release(c, slot);
   if (rc) return rc;
   if ((rc = ensure_pages(c, slot, n - 1 + 1 + c->cfg.k))) return rc;
-  Slot &s = c->slots[slot];
-  s.seq_id = seq_id;
+  c->slots[slot].seq_id = seq_id;
   const Params &P = c->P;
   std::vector<int32_t *> ptrs = {P.kv_len + slot, P.pending + slot, P.n_gen + slot, (int32_t *)P.iter + slot,
-                                 (int32_t *)P.seq_id + slot, P.gen_limit + slot, P.frozen + slot, P.n_acc + slot,
-                                 P.step_slots};
-  std::vector<int32_t> vals = {0, prompt[n - 1], 0, 0, (int32_t)seq_id, INT_MAX, 0, 0, slot};
+                                 (int32_t *)P.seq_id + slot, P.gen_limit + slot, P.frozen + slot, P.n_acc + slot};
+  std::vector<int32_t> vals = {0, prompt[n - 1], 0, 0, (int32_t)seq_id, INT_MAX, 0, 0};
+  return poke(c, ptrs, vals);
+}
+static int prefill_end(pass_ctx *c, int slot, int n) {  // after the stream has been synchronised
+  Slot &s = c->slots[slot];
+  s.kv_len = n - 1;
+  s.n_gen = 0;
+  s.iteration = 0;
+  s.state = 1;
+  return PASS_OK;
+}
+
+int pass_prefill(pass_ctx *c, int slot, uint32_t seq_id, const int32_t *prompt, int n) {
+  if (!c) return PASS_EINVAL;
+  if (!c->weights_loaded) return fail(c, PASS_ESTATE, "weights not loaded");
+  int rc = prefill_begin(c, slot, seq_id, prompt, n);
+  if (rc) return rc;
+  const Params &P = c->P;
+  std::vector<int32_t *> ptrs = {P.step_slots};
+  std::vector<int32_t> vals = {slot};
   if ((rc = poke(c, ptrs, vals))) return rc;
   if (n > 1) {
     HIP_TRY(c, hipMemcpyAsync(c->prompt_buf, prompt, sizeof(int32_t) * (n - 1), hipMemcpyHostToDevice, c->stream));
@@ -769,10 +809,79 @@ int pass_prefill(pass_ctx *c, int slot, uint32_t seq_id, const int32_t *prompt, 
     if ((rc = poke(c, ptrs, vals))) return rc;
   }
   HIP_TRY(c, hipStreamSynchronize(c->stream));
-  s.kv_len = n - 1;
-  s.n_gen = 0;
-  s.iteration = 0;
-  s.state = 1;
+  return prefill_end(c, slot, n);
+}
+
+int pass_prefill_batch(pass_ctx *c, const int32_t *slots, const uint32_t *seq_ids, const int32_t *prompts, const int32_t *lens,
+                       int n_slots) {
+  if (!c) return PASS_EINVAL;
+  if (!c->weights_loaded) return fail(c, PASS_ESTATE, "weights not loaded");
+  if (!slots || !seq_ids || !prompts || !lens || n_slots < 1 || n_slots > c->cfg.max_slots) return fail(c, PASS_EINVAL, "bad slot list");
+  long total = 0;
+  for (int b = 0; b < n_slots; ++b) {
+    for (int j = 0; j < b; ++j)
+      if (slots[j] == slots[b]) return fail(c, PASS_EINVAL, "slot %d listed twice", slots[b]);
+    if (lens[b] < 1) return fail(c, PASS_EINVAL, "prompt must hold at least one token");
+    total += lens[b] - 1;
+  }
+  // the tiled kernels take rows of several sequences through one pass over the weights; where they do not
+  // apply (generic path, untransposed V pages, switched off, or too few rows to pay for a tiled pass) the
+  // prompts go one by one
+  const bool tiled = c->use_mfma && c->P.v_transposed &&
+                     (c->opt_prefill_tiled == 1 || (c->opt_prefill_tiled < 0 && total > 2 * kMaxRows));
+  int rc;
+  if (!tiled) {
+    const int32_t *pr = prompts;
+    for (int b = 0; b < n_slots; pr += lens[b], ++b)
+      if ((rc = pass_prefill(c, slots[b], seq_ids[b], pr, lens[b]))) return rc;
+    return PASS_OK;
+  }
+  {
+    const int32_t *pr = prompts;
+    for (int b = 0; b < n_slots; pr += lens[b], ++b)
+      if ((rc = prefill_begin(c, slots[b], seq_ids[b], pr, lens[b]))) return rc;
+  }
+  // passes: a sequence's rows start on a block of 128 rows; a prompt that does not fit goes on in the next pass
+  const int cap = c->pws.rows;
+  std::vector<std::vector<int32_t>> keep;  // the passes' token ids, alive until the stream has been synchronised
+  std::vector<PassSeg> parts;
+  std::vector<int32_t> ids;
+  int cur = 0;
+  auto flush = [&]() -> int {
+    if (parts.empty()) return PASS_OK;
+    const int M = parts.back().row_base + parts.back().rows;
+    ids.resize(M, 0);
+    keep.push_back(ids);
+    HIP_TRY(c, hipMemcpyAsync(c->prompt_buf, keep.back().data(), sizeof(int32_t) * M, hipMemcpyHostToDevice, c->stream));
+    int r = run_prefill_pass(c, parts, M, c->prompt_buf);
+    parts.clear();
+    ids.clear();
+    cur = 0;
+    return r;
+  };
+  const int32_t *pr = prompts;
+  for (int b = 0; b < n_slots; pr += lens[b], ++b) {
+    const int rows = lens[b] - 1;
+    for (int done = 0; done < rows;) {
+      if (cur >= cap && (rc = flush())) return rc;
+      const int take = std::min(rows - done, cap - cur);
+      parts.push_back(PassSeg{slots[b], done, take, cur});
+      ids.resize(cur, 0);  // padding rows carry token 0
+      ids.insert(ids.end(), pr + done, pr + done + take);
+      done += take;
+      cur = (cur + take + kPrefillBlockRows - 1) / kPrefillBlockRows * kPrefillBlockRows;
+    }
+  }
+  if ((rc = flush())) return rc;
+  std::vector<int32_t *> ptrs;
+  std::vector<int32_t> vals;
+  for (int b = 0; b < n_slots; ++b) {
+    ptrs.push_back(c->P.kv_len + slots[b]);
+    vals.push_back(lens[b] - 1);
+  }
+  if ((rc = poke(c, ptrs, vals))) return rc;
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (int b = 0; b < n_slots; ++b) prefill_end(c, slots[b], lens[b]);
   return PASS_OK;
 }
 

@@ -218,9 +218,20 @@ struct PrefillWs {
   int attn_rows;  // query rows of an attention workgroup: 16, 32 or 128 (0 = 128 for passes of more than 512 rows, else 32)
   float *q;       // [rows][D] rotated queries
 };
+// Whose rows a tiled pass carries: the pass is cut into blocks of 128 rows, block i holds `rows[i]` prompt rows
+// (0 .. 128, the rest of the block is padding) of sequence `slot[i]` starting at position `pos[i]`.  A prompt
+// longer than a block fills consecutive blocks; several prompts share a pass, each starting on a block.
+constexpr int kPrefillBlockRows = 128;
+struct PrefillSegs {
+  int n_blocks;
+  int slot[kPrefillRows / kPrefillBlockRows], pos[kPrefillRows / kPrefillBlockRows], rows[kPrefillRows / kPrefillBlockRows];
+};
 void launch_assemble_prefill(const Params &p, const void *tok_emb, const void *gain0, int R, int ssq_parts,
                              int ssq_stride, hipStream_t s);
-void launch_prefill_qkv(const Params &p, const PrefillWs &w, const void *W, int layer, int slot, int pos0, int M,
+// the same for a pass described by `segs` (ids: one token per row of the pass, padding rows any valid token)
+void launch_assemble_prefill_segs(const Params &p, const void *tok_emb, const void *gain0, const PrefillSegs &segs, int M,
+                                  int ssq_parts, int ssq_stride, hipStream_t s);
+void launch_prefill_qkv(const Params &p, const PrefillWs &w, const void *W, int layer, const PrefillSegs &segs, int M,
                         hipStream_t s);
 void launch_prefill_attention(const Params &p, const PrefillWs &w, int layer, int slot, int pos0, int R,
                               hipStream_t s);

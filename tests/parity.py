@@ -130,16 +130,20 @@ def _one_iteration(gpu, oseq, slot, seq_id, it, temp, seed, tol, st, top_k=0):
     return added, True
 
 
-def batch_parity(gpu, omodel, slots, seq_ids, prompts, sampled, n_iters, temp, seed, tol, max_len, top_k=0):
+def batch_parity(gpu, omodel, slots, seq_ids, prompts, sampled, n_iters, temp, seed, tol, max_len, top_k=0, one_call=False):
     """A batch of slots through draft / verify calls that carry every slot (the launch shapes of the
     batch), with the sequences of the `sampled` slots run alone through the oracle: a sequence's
     result does not depend on what shares its calls.  Every call's logits and decisions of the
     sampled slots are compared as in stepwise_parity.  A sampled slot that parts ways on an
     unstable decision is dropped from the comparison from then on (counted in `resyncs`).
+    one_call: the prompts go through pass_prefill_batch instead of one pass_prefill each.
     Returns {slot: StepStats}."""
     k = getattr(gpu, "k_act", gpu.k)
-    for sl, sid, p in zip(slots, seq_ids, prompts):
-        gpu.prefill(sl, p, seq_id=sid)
+    if one_call:
+        gpu.prefill_batch(slots, prompts, seq_ids)
+    else:
+        for sl, sid, p in zip(slots, seq_ids, prompts):
+            gpu.prefill(sl, p, seq_id=sid)
     oseqs, stats, live = {}, {}, set(sampled)
     for sl in sampled:
         i = list(slots).index(sl)

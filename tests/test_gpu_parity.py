@@ -355,6 +355,56 @@ def test_tiled_prompt_pass(plen, attn_rows, rows, strips, block):
     g.close()
 
 
+@pytest.mark.parametrize("rows,lens", [(384, (37, 300, 129, 2, 1, 260)), (128, (200, 5, 131)), (256, (129, 128, 127, 1, 64, 65))])
+def test_prompt_pass_over_several_slots(rows, lens):
+    """pass_prefill_batch: ragged prompts of several sequences share tiled passes over the weights (every
+    sequence starts on a block of 128 rows; prompts that spill into the next pass, that end exactly on a
+    block, one-token prompts with nothing to cache, more blocks than one pass holds).  Every slot is then
+    followed by the oracle through three iterations of calls that carry the whole batch, and its
+    state equals what pass_prefill leaves."""
+    w = MFMA_HD128
+    W = synth.make_weights(w.shape, w.seed, w.k, w.lm_head_scale)
+    m = O.Model(w.shape, W, w.k)
+    rng = np.random.default_rng(rows)
+    prompts = [rng.integers(0, w.shape.vocab, n).astype(np.int32) for n in lens]
+    slots = list(range(len(lens)))[::-1]  # slots in another order than the prompts
+    seq_ids = [20 + i for i in range(len(lens))]
+    g = _gpu(w.shape, W, w.k, max_slots=len(lens), max_seq_len=384, page_size=64,
+             options={"prefill_tiled": 1, "tune.prefill_rows": rows})
+    stats = parity.batch_parity(g, m, slots, seq_ids, prompts, slots, 3, 0.9, 777, parity.LOGIT_TOL[synth.BF16], max_len=384,
+                                one_call=True)
+    for sl in slots:
+        print(sl, stats[sl])
+        parity.check_stats(stats[sl], 3, parity.ERR_BF16_SMALL)
+    # against one pass_prefill per slot: same lengths, and the next call's logits agree to rounding
+    g.prefill_batch(slots, prompts, seq_ids)
+    assert [g.seq_len(sl) for sl in slots] == [(n - 1, 0) for n in lens]
+    g.draft(slots, 0.0, 1)
+    a = [g.get_logits(sl, 0).copy() for sl in slots]
+    for sl, sid, p in zip(slots, seq_ids, prompts):
+        g.prefill(sl, p, seq_id=sid)
+    g.draft(slots, 0.0, 1)
+    for i, sl in enumerate(slots):
+        b = g.get_logits(sl, 0)
+        assert np.abs(a[i] - b).max() <= 1e-3 * np.abs(b).max(), (sl, np.abs(a[i] - b).max() / np.abs(b).max())
+    with pytest.raises(Exception):
+        g.prefill_batch([0, 0], prompts[:2], [1, 2])
+    g.close()
+
+
+def test_prompt_pass_over_several_slots_on_the_generic_path():
+    """pass_prefill_batch where the tiled kernels do not apply: the prompts go one by one, same results."""
+    w = TINY
+    g, m, _ = _both(w, w.k, max_slots=3, max_seq_len=128)
+    rng = np.random.default_rng(4)
+    prompts = [rng.integers(0, w.shape.vocab, n).astype(np.int32) for n in (9, 1, 70)]
+    stats = parity.batch_parity(g, m, [2, 0, 1], [5, 6, 7], prompts, [2, 0, 1], 3, 0.9, 11, parity.LOGIT_TOL[synth.F32], max_len=128,
+                                one_call=True)
+    for sl in stats:
+        parity.check_stats(stats[sl], 3, parity.ERR_F32)
+    g.close()
+
+
 def test_tiled_and_chunked_prompt_passes_fill_the_same_cache():
     """Same prompt through the tiled pass and through the decode kernels in 64-row chunks: the logits
     of the next call agree to rounding (different summation orders, same bf16 cache up to the last
