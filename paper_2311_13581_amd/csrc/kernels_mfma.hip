@@ -149,13 +149,6 @@ void launch_assemble_mfma(const Params &p, const void *tok_emb, const void *look
   assemble_mfma_kernel<<<B * R, 256, 0, s>>>(p, (const uint16_t *)tok_emb, (const uint16_t *)lookahead,
                                              (const uint16_t *)gain0, mode, R, p.d / 16, kMaxRows, 1);
 }
-// the same rows for the tiled prefill: `ssq_parts` partial sums per row with row stride `ssq_stride`,
-// no row tables (one slot, consecutive positions)
-void launch_assemble_prefill(const Params &p, const void *tok_emb, const void *gain0, int R, int ssq_parts,
-                             int ssq_stride, hipStream_t s) {
-  assemble_mfma_kernel<<<R, 256, 0, s>>>(p, (const uint16_t *)tok_emb, nullptr, (const uint16_t *)gain0, MODE_PREFILL,
-                                         R, ssq_parts, ssq_stride, 0);
-}
 
 // ---------------------------------------------------------------------------------------------
 // The streaming GEMM

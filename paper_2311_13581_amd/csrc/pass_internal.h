@@ -226,9 +226,7 @@ struct PrefillSegs {
   int n_blocks;
   int slot[kPrefillRows / kPrefillBlockRows], pos[kPrefillRows / kPrefillBlockRows], rows[kPrefillRows / kPrefillBlockRows];
 };
-void launch_assemble_prefill(const Params &p, const void *tok_emb, const void *gain0, int R, int ssq_parts,
-                             int ssq_stride, hipStream_t s);
-// the same for a pass described by `segs` (ids: one token per row of the pass, padding rows any valid token)
+// row assembly of a pass described by `segs` (p.prefill_ids: one token per row of the pass, padding rows any valid token)
 void launch_assemble_prefill_segs(const Params &p, const void *tok_emb, const void *gain0, const PrefillSegs &segs, int M,
                                   int ssq_parts, int ssq_stride, hipStream_t s);
 void launch_prefill_qkv(const Params &p, const PrefillWs &w, const void *W, int layer, const PrefillSegs &segs, int M,

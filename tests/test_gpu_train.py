@@ -86,6 +86,31 @@ def test_training_steps_match_the_oracle(shape, page, path, lockstep, tol_loss, 
     g.close()
 
 
+@pytest.mark.parametrize("k", [1, 5, 7, 8, 15])
+@pytest.mark.parametrize("shape,page,path", [(TINY, 16, 1), (SMALL_BF16, 16, 0), (HD128_BF16, 64, 0)], ids=["fp32", "bf16", "bf16-hd128"])
+def test_one_training_step_for_every_row_bound(shape, page, path, k):
+    """One step for look-ahead counts that select each compile-time row bound of the attention backward
+    (2, 6, 8 and 16 rows per slot; 3, 4 and 5 are the other tests'), two slots, the second prefix
+    longer than one chunk of keys."""
+    W = synth.make_weights(shape, 31 + k, k, 6.0)
+    g = _gpu(shape, W, k, 2, 320, page, {"path": path})
+    g.train_begin(-1)
+    la = TO._t(W["lookahead"], shape.dtype).numpy()
+    rng = np.random.default_rng(k)
+    prefixes = [rng.integers(0, shape.vocab, n).astype(np.int32) for n in (3, 270 + k)]
+    targets = rng.integers(0, shape.vocab, (2, k)).astype(np.int32)
+    for i, p in enumerate(prefixes):
+        g.prefill(i, p, seq_id=i)
+    loss = g.train_step([0, 1], targets, 0.01)
+    o_loss, o_grad = TO.loss_and_grad(shape, W, la, [p.tolist() for p in prefixes], targets)
+    grad = g.train_read(1)
+    e_loss, e_grad, g_max = abs(loss - o_loss) / abs(o_loss), float(np.abs(grad - o_grad).max()), float(np.abs(o_grad).max())
+    print(f"k={k}: loss rel {e_loss:.1e} grad err {e_grad / g_max:.1e} of max {g_max:.3f}")
+    fp32 = shape.dtype == synth.F32
+    assert e_loss <= (1e-6 if fp32 else 6e-5) and e_grad <= (5e-6 if fp32 else 4e-4) * g_max
+    g.close()
+
+
 _ORACLE_7B = {}
 
 
