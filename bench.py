@@ -183,8 +183,8 @@ def main():
                     help="tuning: launch shape override(s), kind*10000 + wavefronts*100 + unroll")
     ap.add_argument("--option", action="append", default=[], metavar="NAME=VALUE",
                     help="tuning: a library option (pass_set_option) to set before the run")
-    ap.add_argument("--train-steps", type=int, default=0,
-                    help="also time that many look-ahead embedding training steps (on a context of their own)")
+    ap.add_argument("--train-steps", type=int, default=4,
+                    help="also time that many look-ahead embedding training steps (on a context of their own; 0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (a kernel of known traffic, for scaling rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE readings)")
