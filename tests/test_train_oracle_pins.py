@@ -104,6 +104,27 @@ def test_adamw_first_steps_closed_form():
     assert np.allclose(t2, t1 - 0.01 * (m_hat / (np.sqrt(v_hat) + 1e-8) + 0.1 * t1), rtol=0, atol=1e-15)
 
 
+def test_adamw_equals_the_library_optimiser():
+    """Twelve steps with random gradients and a changing learning rate against torch.optim.AdamW in fp64
+    (decoupled weight decay, bias-corrected moments, epsilon added to the root of the second moment)."""
+    import torch
+    rng = np.random.default_rng(8)
+    th0 = rng.standard_normal(40)
+    ref = torch.tensor(th0, dtype=torch.float64, requires_grad=True)
+    lib = torch.optim.AdamW([ref], lr=0.01, betas=(0.85, 0.97), eps=1e-7, weight_decay=0.05)
+    opt = TO.AdamW(40, 0.85, 0.97, 1e-7, 0.05)
+    th = th0.copy()
+    for step in range(12):
+        g = rng.standard_normal(40) * (10.0 ** rng.integers(-3, 2))
+        lr = 0.01 * (step + 1) / 12
+        for grp in lib.param_groups:
+            grp["lr"] = lr
+        ref.grad = torch.tensor(g, dtype=torch.float64)
+        lib.step()
+        th = opt.step(th, g, lr)
+        assert np.allclose(th, ref.detach().numpy(), rtol=1e-12, atol=1e-14), step
+
+
 def test_learning_rate_schedule():
     """Linear warm-up over 2000 steps to 0.01, cosine to zero at step 10000."""
     assert TO.learning_rate(0) == pytest.approx(0.01 / 2000)
