@@ -616,6 +616,207 @@ __global__ __launch_bounds__(256) void attn_bwd_split_kernel(Params p, int layer
   }
 }
 
+// The same for bfloat16 caches and up to eight rows per slot, with the two contractions over the head
+// dimension on the matrix core: the K and V tiles stay in LDS as cached ([key][dim] bf16, whichever way the V
+// pages are laid out), and are the A operand of v_mfma_f32_16x16x32_bf16; q (scaled) and dO are the B operand as
+// (hi, lo) column pairs like every activation of the matrix-core path (columns 0..7 the hi halves of the rows,
+// 8..15 the lo halves, added afterwards), so nothing but the cache is rounded.  Wavefront w takes the scores
+// (w < 2) or dP (w >= 2) of 16 of the tile's 32 keys; probabilities and dS are then formed by one thread per
+// (row, key), and dq, dK, dV as in the kernel above.
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+template <int HD, int RB>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void attn_bwd_mfma_kernel(Params p, int layer, int R, const float *q_saved, int ldq,
+                                                            const float *o_f32, const uint16_t *o_x, const float *lse,
+                                                            const float *dattn, int KS, size_t slice_stride, float *dq_part,
+                                                            float *dqkv) {
+  constexpr int TK = 32, LDK = HD + 8, PARTS = 256 / HD, KT = HD / 32, RQ = 8;
+  static_assert(RB <= RQ, "one (hi, lo) column group");
+  __shared__ __align__(16) uint16_t kv_s[2][TK][LDK];        // K tile, V tile: [key][dim] bf16
+  __shared__ __align__(16) float qs[RQ][HD], dos[RQ][HD];    // the rows' q and dO (rows beyond R: zeros)
+  __shared__ __align__(16) float sp_s[RQ][TK], dd_s[RQ][TK];  // scores, then P; dP, then dS
+  __shared__ __align__(16) float comb[PARTS][RB][HD];
+  __shared__ float lse_s[RQ], D_s[RQ];
+  __shared__ int pages_s[kTrainAttnChunk / 16 + 1];
+  const int split = blockIdx.x, head = blockIdx.y, b = blockIdx.z;
+  const int m0 = b * R;
+  const int slot = p.row_slot[m0], pos0 = p.row_pos[m0];
+  const int n_keys = pos0 + R;
+  const int k_lo = split * kTrainAttnChunk;
+  if (slot < 0 || k_lo >= n_keys) return;  // uniform over the workgroup
+  const int k_hi = min(n_keys, k_lo + kTrainAttnChunk);
+  const bf16_t *kpool = (const bf16_t *)p.k_pool, *vpool = (const bf16_t *)p.v_pool;
+  const float scale = rsqrtf((float)HD);
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+
+  for (int idx = tid; idx < RQ * HD; idx += 256) {
+    const int r = idx / HD, dm = idx % HD;
+    float qv = 0.f, dv = 0.f;
+    if (r < R) {
+      qv = q_saved[(size_t)(m0 + r) * ldq + head * HD + dm];
+      dv = dattn[(size_t)(m0 + r) * p.D + head * HD + dm];
+      for (int ks = 1; ks < KS; ++ks) dv += dattn[ks * slice_stride + (size_t)(m0 + r) * p.D + head * HD + dm];  // slices, in order
+    }
+    qs[r][dm] = qv;
+    dos[r][dm] = dv;
+  }
+  __syncthreads();
+  for (int r = wave; r < R; r += 4) {  // D of row r: one wavefront, lanes over the dimensions
+    float acc = 0.f;
+    for (int dm = lane; dm < HD; dm += 64) {
+      float o;
+      if (o_f32) {
+        o = o_f32[(size_t)(m0 + r) * p.D + head * HD + dm];
+      } else {
+        const uint16_t *x = o_x + xs_index(m0 + r, p.D, head * HD + dm);
+        o = bf16_to_f32(x[0]) + bf16_to_f32(x[kXsLoOffset]);
+      }
+      acc = fmaf(dos[r][dm], o, acc);
+    }
+#pragma unroll
+    for (int o2 = 32; o2 > 0; o2 >>= 1) acc += __shfl_xor(acc, o2);
+    if (lane == 0) {
+      D_s[r] = acc;
+      lse_s[r] = lse[(size_t)(m0 + r) * p.H + head];
+    }
+  }
+  if (tid >= R && tid < RQ) D_s[tid] = lse_s[tid] = 0.f;
+  const int page_lo = k_lo >> p.page_shift;
+  for (int i = tid; i <= ((k_hi - 1) >> p.page_shift) - page_lo; i += 256)
+    pages_s[i] = p.block_table[(size_t)slot * p.pages_per_seq + page_lo + i];
+
+  // this wavefront's B operand: q * scale (scores) or dO (dP), column c = hi (c < 8) or lo half of row c & 7
+  const int c = lane & 15, g = lane >> 4;
+  const int which = wave >> 1, kb = wave & 1;
+  u32x4_t frag[KT];
+  {
+    const float(*src)[HD] = which ? dos : qs;
+    const float f = which ? 1.f : scale;
+    const bool hi = c < 8;
+#pragma unroll
+    for (int j = 0; j < KT; ++j) {
+      const float4 x0 = *(const float4 *)&src[c & 7][j * 32 + g * 8], x1 = *(const float4 *)&src[c & 7][j * 32 + g * 8 + 4];
+      frag[j][0] = split2_bf16(x0.x * f, x0.y * f, hi);
+      frag[j][1] = split2_bf16(x0.z * f, x0.w * f, hi);
+      frag[j][2] = split2_bf16(x1.x * f, x1.y * f, hi);
+      frag[j][3] = split2_bf16(x1.z * f, x1.w * f, hi);
+    }
+  }
+  __syncthreads();  // pages_s, D_s and lse_s are in place
+
+  const int dim = tid % HD, part = tid / HD;
+  float dq[RB];
+#pragma unroll
+  for (int r = 0; r < RB; ++r) dq[r] = 0.f;
+
+  // next tile's K and V in flight while the tile in hand is worked on (chunks as in the kernel above)
+  constexpr int NCH = TK * HD / 8 / 256;
+  Raw8<bf16_t> kraw[NCH], vraw[NCH];
+  auto fetch = [&](int t0) {
+#pragma unroll
+    for (int u = 0; u < NCH; ++u) {
+      const int ch = u * 256 + tid;
+      {
+        const int key = ch / (HD / 8), d0 = (ch % (HD / 8)) * 8, j = t0 + key;
+        const bool in = j < k_hi;
+        const size_t off =
+            in ? ((((size_t)layer * p.n_pages + pages_s[(j >> p.page_shift) - page_lo]) * p.H + head) * p.page_size + (j & (p.page_size - 1))) * HD + d0 : 0;
+        kraw[u].load(kpool, off, in);
+        if (!p.v_transposed) vraw[u].load(vpool, off, in);
+      }
+      if (p.v_transposed) {
+        const int dv = ch / (TK / 8), j0 = t0 + (ch % (TK / 8)) * 8;
+        const bool in = j0 < k_hi;
+        const size_t off =
+            in ? ((((size_t)layer * p.n_pages + pages_s[(j0 >> p.page_shift) - page_lo]) * p.H + head) * HD + dv) * p.page_size + (j0 & (p.page_size - 1)) : 0;
+        vraw[u].load(vpool, off, in);
+      }
+    }
+  };
+  auto stash = [&](int t0) {
+#pragma unroll
+    for (int u = 0; u < NCH; ++u) {
+      const int ch = u * 256 + tid;
+      const int key = ch / (HD / 8), d0 = (ch % (HD / 8)) * 8;
+      *(uint4 *)&kv_s[0][key][d0] = kraw[u].a;
+      if (!p.v_transposed) {
+        *(uint4 *)&kv_s[1][key][d0] = vraw[u].a;
+      } else {
+        const int dv = ch / (TK / 8), key0 = (ch % (TK / 8)) * 8;
+        const uint32_t w[4] = {vraw[u].a.x, vraw[u].a.y, vraw[u].a.z, vraw[u].a.w};
+#pragma unroll
+        for (int e = 0; e < 8; ++e)  // unwritten positions hold anything
+          kv_s[1][key0 + e][dv] = (t0 + key0 + e < k_hi) ? (uint16_t)(w[e >> 1] >> ((e & 1) * 16)) : (uint16_t)0;
+      }
+    }
+  };
+  fetch(k_lo);
+  for (int t0 = k_lo; t0 < k_hi; t0 += TK) {
+    __syncthreads();  // the previous tile has been consumed
+    stash(t0);
+    __syncthreads();
+    if (t0 + TK < k_hi) fetch(t0 + TK);
+    {  // scores or dP of this wavefront's 16 keys x 8 rows
+      floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+      const uint16_t *row = &kv_s[which][kb * 16 + c][g * 8];
+#pragma unroll
+      for (int j = 0; j < KT; ++j)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(*(const bf16x8_t *)(row + j * 32), __builtin_bit_cast(bf16x8_t, frag[j]), acc, 0, 0, 0);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) acc[r] += dpp_move<0x128>(acc[r]);  // row_ror 8: the lo column onto its hi column
+      if (c < 8) *(floatx4_t *)&(which ? dd_s : sp_s)[c][kb * 16 + 4 * g] = acc;  // lane (c, g): keys 4g .. 4g+3 of row c
+    }
+    __syncthreads();
+    {  // probabilities and dS: one thread per (row, key)
+      const int key = tid & 31, r = tid >> 5, j = t0 + key;
+      const bool ok = r < R && j < k_hi && j <= pos0 + r;
+      const float pj = ok ? expf(sp_s[r][key] - lse_s[r]) : 0.f;
+      const float dsj = ok ? pj * (dd_s[r][key] - D_s[r]) : 0.f;
+      sp_s[r][key] = pj;
+      dd_s[r][key] = dsj;
+    }
+    __syncthreads();
+    {  // dq: thread (part, dim) takes a run of TK / PARTS keys, four at a time
+      constexpr int KPP = TK / PARTS;
+      const int key0 = part * KPP;
+#pragma unroll 2
+      for (int kq = 0; kq < KPP; kq += 4) {
+        const float k0 = bf16_to_f32(kv_s[0][key0 + kq][dim]), k1 = bf16_to_f32(kv_s[0][key0 + kq + 1][dim]),
+                    k2 = bf16_to_f32(kv_s[0][key0 + kq + 2][dim]), k3 = bf16_to_f32(kv_s[0][key0 + kq + 3][dim]);
+#pragma unroll
+        for (int r = 0; r < RB; ++r) {  // rows beyond R carry dS = 0
+          const float4 d4 = *(const float4 *)&dd_s[r][key0 + kq];
+          dq[r] = fmaf(d4.x, k0, dq[r]); dq[r] = fmaf(d4.y, k1, dq[r]); dq[r] = fmaf(d4.z, k2, dq[r]); dq[r] = fmaf(d4.w, k3, dq[r]);
+        }
+      }
+    }
+    // the block's own keys in this tile
+    for (int j = max(t0, pos0) + part; j < min(t0 + TK, k_hi); j += PARTS) {
+      const int key = j - t0, jj = j - pos0;
+      float dk = 0.f, dvv = 0.f;
+      for (int r = jj; r < R; ++r) {
+        dk = fmaf(dd_s[r][key], qs[r][dim], dk);
+        dvv = fmaf(sp_s[r][key], dos[r][dim], dvv);
+      }
+      dqkv[(size_t)(m0 + jj) * 3 * p.D + p.D + head * HD + dim] = dk * scale;
+      dqkv[(size_t)(m0 + jj) * 3 * p.D + 2 * p.D + head * HD + dim] = dvv;
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < RB; ++r) comb[part][r][dim] = dq[r];
+  __syncthreads();
+  if (part == 0) {
+    for (int r = 0; r < R; ++r) {
+      float t = comb[0][r][dim];
+#pragma unroll
+      for (int q2 = 1; q2 < PARTS; ++q2) t += comb[q2][r][dim];
+      dq_part[((size_t)split * kMaxRows + m0 + r) * p.D + head * HD + dim] = t * scale;
+    }
+  }
+}
+
 // The chunks' dq added in chunk order; dq and dK back through the rotary embedding (the transpose of a
 // rotation is the opposite rotation); the row of dqkv as fp32 in place or as (hi, lo) tiles for the
 // matrix-core projection that follows.  Four consecutive features (two rotary pairs) per thread.
@@ -657,6 +858,20 @@ template <typename T, int HD>
 static void attn_bwd_dispatch(const Params &p, dim3 grid, int layer, int R, const float *q_saved, int ldq, const float *o,
                               const uint16_t *o_x, const float *lse, const float *dattn, int KS, size_t slice_stride, float *dq_part,
                               float *dqkv, hipStream_t s) {
+  if constexpr (sizeof(T) == 2) {  // bfloat16 cache, one column group of rows: the matrix-core kernel
+#define PASS_ATTN_BWD_MFMA(RB) \
+  attn_bwd_mfma_kernel<HD, RB><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv)
+    if (R <= 8) {
+      if (R <= 2) PASS_ATTN_BWD_MFMA(2);
+      else if (R <= 3) PASS_ATTN_BWD_MFMA(3);
+      else if (R <= 4) PASS_ATTN_BWD_MFMA(4);
+      else if (R <= 5) PASS_ATTN_BWD_MFMA(5);
+      else if (R <= 6) PASS_ATTN_BWD_MFMA(6);
+      else PASS_ATTN_BWD_MFMA(8);
+      return;
+    }
+#undef PASS_ATTN_BWD_MFMA
+  }
 #define PASS_ATTN_BWD(RB) \
   attn_bwd_split_kernel<T, HD, RB><<<grid, 256, 0, s>>>(p, layer, R, q_saved, ldq, o, o_x, lse, dattn, KS, slice_stride, dq_part, dqkv)
   if (R <= 2) PASS_ATTN_BWD(2);
