@@ -646,7 +646,7 @@ int plain_gemm_slices(int N, int K) {
   for (int ks = 1; ks <= 8; ks *= 2) {
     if (KT % ks != 0 || KT / ks < 8) break;
     best = ks;
-    if (wgs * ks >= 512) break;
+    if (wgs * ks >= 256) break;  // one workgroup per compute unit: each pulls its slice of the rows once
   }
   return best;
 }
