@@ -395,20 +395,6 @@ struct Raw8<bf16_t> {
   }
 };
 
-__device__ __forceinline__ void load8(const float *p, size_t off, float (&v)[8]) {
-  const float4 a = *(const float4 *)(p + off), b = *(const float4 *)(p + off + 4);
-  v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-}
-__device__ __forceinline__ void load8(const bf16_t *p, size_t off, float (&v)[8]) {
-  const uint4 a = *(const uint4 *)(p + off);
-  const uint32_t w[4] = {a.x, a.y, a.z, a.w};
-#pragma unroll
-  for (int e = 0; e < 4; ++e) {
-    v[2 * e] = __uint_as_float(w[e] << 16);
-    v[2 * e + 1] = __uint_as_float(w[e] & 0xffff0000u);
-  }
-}
-
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float v) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
