@@ -226,7 +226,7 @@ int pass_run_iterations(pass_ctx *ctx, const int32_t *slots, int n_slots, int n_
  *   pass_train_begin   device_workspace: caller's device memory (256-byte aligned, kept alive while
  *                      training); the embeddings start from the embedding of init_token (the paper:
  *                      [UNK]) or, with init_token < 0, from the model's own look-ahead tensor;
- *                      AdamW's moments and step count start at zero
+ *                      AdamW's moments and step count start at zero; pass_load_weights ends the set-up
  *   pass_train_step    slots: host, n_slots prefilled slots, (1+k) * n_slots <= PASS_MAX_ROWS, at most
  *                      8192 keys each; targets: host [n_slots * k]; *out_loss: the batch loss before
  *                      the update (may be NULL).  Returns when the step is done.
@@ -280,6 +280,13 @@ int pass_get_tokens(pass_ctx *ctx, int slot, int first, int n, int32_t *out);
  * the host launches for calls whose longest group has at most n_keys keys (never less than any
  * shorter group's split count).  Any output pointer may be NULL.  PASS_EINVAL: n_keys or n_heads < 1. */
 int pass_attention_plan(int n_heads, int n_keys, int *n_splits, int *chunk_keys, int *grid_splits);
+
+/* Introspection hook for pass_prefill_batch (no context, no GPU): how prompts of lens[n] tokens are packed into
+ * tiled passes of at most rows_per_pass rows (a multiple of 128).  Prompt b has lens[b] - 1 rows to cache.  Writes
+ * *n_segs and, for each segment in launch order, five values to out_segs: pass, prompt, first row of the prompt,
+ * rows, first row in the pass (a multiple of 128).  PASS_EINVAL: bad arguments; PASS_ECAPACITY: more than max_segs
+ * segments (*n_segs is still written; max_segs = 0 just counts). */
+int pass_prefill_plan(int rows_per_pass, const int32_t *lens, int n, int max_segs, int32_t *out_segs, int *n_segs);
 
 /* kv_len and number of generated tokens of a slot (either pointer may be NULL). */
 int pass_seq_len(pass_ctx *ctx, int slot, int32_t *kv_len, int32_t *n_generated);

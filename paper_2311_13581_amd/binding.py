@@ -18,7 +18,7 @@ MAX_K, MAX_ROWS = 15, 64
 
 SYMBOLS = ["pass_arena_bytes", "pass_create", "pass_load_weights", "pass_prefill", "pass_prefill_batch", "pass_release",
            "pass_draft", "pass_draft_static", "pass_verify", "pass_generate", "pass_sps_iteration", "pass_run_iterations", "pass_kernel_time", "pass_plain_read", "pass_rng_uniforms", "pass_get_logits", "pass_seq_len",
-           "pass_train_bytes", "pass_train_begin", "pass_train_step", "pass_train_read", "pass_train_resume", "pass_set_option", "pass_attention_plan", "pass_get_tokens", "pass_time_step", "pass_last_error", "pass_destroy"]
+           "pass_train_bytes", "pass_train_begin", "pass_train_step", "pass_train_read", "pass_train_resume", "pass_set_option", "pass_attention_plan", "pass_prefill_plan", "pass_get_tokens", "pass_time_step", "pass_last_error", "pass_destroy"]
 
 
 class PassConfig(C.Structure):
@@ -105,6 +105,7 @@ def load_library():
     L.pass_train_resume.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.POINTER(C.c_float), C.POINTER(C.c_float), C.c_int64]
     L.pass_get_tokens.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, ip]
     L.pass_attention_plan.argtypes = [C.c_int, C.c_int, ip, ip, ip]
+    L.pass_prefill_plan.argtypes = [C.c_int, ip, C.c_int, C.c_int, ip, ip]
     L.pass_time_step.argtypes = [C.c_void_p, ip, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double)]
     L.pass_last_error.restype = C.c_char_p
     L.pass_last_error.argtypes = [C.c_void_p]

@@ -427,6 +427,26 @@ int run_step(pass_ctx *c, int mode, int B, int R, float *logits_base, int max_ke
 // multiples of 128, so a sequence's rows are whole 8-row groups of the (hi, lo) tiles).
 // No LM head: the last prompt token stays pending and goes through the first draft call.
 struct PassSeg { int slot, pos0, rows, row_base; };
+
+// How pass_prefill_batch packs prompts into tiled passes of at most `cap` rows (a multiple of 128): prompt b has
+// lens[b] - 1 rows to cache; its rows start on a block of 128 rows of a pass; what does not fit goes on in the next
+// pass.  Segments come out in launch order: rows [pos0, pos0 + rows) of `prompt` at rows row_base .. of pass `pass`.
+struct PlanSeg { int pass, prompt, pos0, rows, row_base; };
+std::vector<PlanSeg> plan_prefill(int cap, const int32_t *lens, int n) {
+  std::vector<PlanSeg> out;
+  int pass = 0, cur = 0;
+  for (int b = 0; b < n; ++b) {
+    const int rows = lens[b] - 1;
+    for (int done = 0; done < rows;) {
+      if (cur >= cap) { ++pass; cur = 0; }
+      const int take = std::min(rows - done, cap - cur);
+      out.push_back(PlanSeg{pass, b, done, take, cur});
+      done += take;
+      cur = (cur + take + kPrefillBlockRows - 1) / kPrefillBlockRows * kPrefillBlockRows;
+    }
+  }
+  return out;
+}
 int run_prefill_pass(pass_ctx *c, const std::vector<PassSeg> &parts, int M, const int32_t *ids) {
   Params P = c->P;
   const Params &B = c->PP;
@@ -674,6 +694,7 @@ int pass_load_weights(pass_ctx *c, const pass_weights *w, int on_device) {
       !w->wq || !w->wk || !w->wv || !w->wo || !w->ffn_norm || !w->w_gate || !w->w_up || !w->w_down)
     return fail(c, PASS_EINVAL, "null weight pointer");
   const size_t e = c->esz, d = c->P.d, D = c->P.D, F = c->P.F, V = c->P.V;
+  c->train.on = false;  // a training set-up belongs to the weights it was made from (their packed transposes)
   const hipMemcpyKind kind = on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice;
   auto cp = [&](void *dst, const void *src, size_t elems) -> int {
     if (!src) return fail(c, PASS_EINVAL, "null weight pointer");
@@ -842,37 +863,26 @@ int pass_prefill_batch(pass_ctx *c, const int32_t *slots, const uint32_t *seq_id
       if ((rc = prefill_begin(c, slots[b], seq_ids[b], pr, lens[b]))) return rc;
   }
   // passes: a sequence's rows start on a block of 128 rows; a prompt that does not fit goes on in the next pass
-  const int cap = c->pws.rows;
+  const std::vector<PlanSeg> plan = plan_prefill(c->pws.rows, lens, n_slots);
+  std::vector<size_t> first_token(n_slots, 0);  // where prompt b starts in `prompts`
+  for (int b = 1; b < n_slots; ++b) first_token[b] = first_token[b - 1] + lens[b - 1];
   std::vector<std::vector<int32_t>> keep;  // the passes' token ids, alive until the stream has been synchronised
-  std::vector<PassSeg> parts;
-  std::vector<int32_t> ids;
-  int cur = 0;
-  auto flush = [&]() -> int {
-    if (parts.empty()) return PASS_OK;
-    const int M = parts.back().row_base + parts.back().rows;
-    ids.resize(M, 0);
-    keep.push_back(ids);
-    HIP_TRY(c, hipMemcpyAsync(c->prompt_buf, keep.back().data(), sizeof(int32_t) * M, hipMemcpyHostToDevice, c->stream));
-    int r = run_prefill_pass(c, parts, M, c->prompt_buf);
-    parts.clear();
-    ids.clear();
-    cur = 0;
-    return r;
-  };
-  const int32_t *pr = prompts;
-  for (int b = 0; b < n_slots; pr += lens[b], ++b) {
-    const int rows = lens[b] - 1;
-    for (int done = 0; done < rows;) {
-      if (cur >= cap && (rc = flush())) return rc;
-      const int take = std::min(rows - done, cap - cur);
-      parts.push_back(PassSeg{slots[b], done, take, cur});
-      ids.resize(cur, 0);  // padding rows carry token 0
-      ids.insert(ids.end(), pr + done, pr + done + take);
-      done += take;
-      cur = (cur + take + kPrefillBlockRows - 1) / kPrefillBlockRows * kPrefillBlockRows;
+  for (size_t i0 = 0; i0 < plan.size();) {
+    size_t i1 = i0;
+    while (i1 < plan.size() && plan[i1].pass == plan[i0].pass) ++i1;
+    const int M = plan[i1 - 1].row_base + plan[i1 - 1].rows;
+    std::vector<PassSeg> parts;
+    std::vector<int32_t> ids(M, 0);  // padding rows carry token 0
+    for (size_t i = i0; i < i1; ++i) {
+      const PlanSeg &g = plan[i];
+      parts.push_back(PassSeg{slots[g.prompt], g.pos0, g.rows, g.row_base});
+      std::copy(prompts + first_token[g.prompt] + g.pos0, prompts + first_token[g.prompt] + g.pos0 + g.rows, ids.begin() + g.row_base);
     }
+    keep.push_back(std::move(ids));
+    HIP_TRY(c, hipMemcpyAsync(c->prompt_buf, keep.back().data(), sizeof(int32_t) * M, hipMemcpyHostToDevice, c->stream));
+    if ((rc = run_prefill_pass(c, parts, M, c->prompt_buf))) return rc;
+    i0 = i1;
   }
-  if ((rc = flush())) return rc;
   std::vector<int32_t *> ptrs;
   std::vector<int32_t> vals;
   for (int b = 0; b < n_slots; ++b) {
@@ -1488,6 +1498,21 @@ int pass_train_resume(pass_ctx *c, const float *master, const float *m1, const f
   }
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   c->train.step = steps;
+  return PASS_OK;
+}
+
+int pass_prefill_plan(int rows_per_pass, const int32_t *lens, int n, int max_segs, int32_t *out_segs, int *n_segs) {
+  if (rows_per_pass < kPrefillBlockRows || rows_per_pass % kPrefillBlockRows || !lens || n < 1 || !n_segs || (max_segs > 0 && !out_segs))
+    return PASS_EINVAL;
+  for (int b = 0; b < n; ++b)
+    if (lens[b] < 1) return PASS_EINVAL;
+  const std::vector<PlanSeg> plan = plan_prefill(rows_per_pass, lens, n);
+  *n_segs = (int)plan.size();
+  if ((int)plan.size() > max_segs) return PASS_ECAPACITY;
+  for (size_t i = 0; i < plan.size(); ++i) {
+    int32_t *o = out_segs + 5 * i;
+    o[0] = plan[i].pass; o[1] = plan[i].prompt; o[2] = plan[i].pos0; o[3] = plan[i].rows; o[4] = plan[i].row_base;
+  }
   return PASS_OK;
 }
 

@@ -67,3 +67,39 @@ def test_attention_grid_covers_every_shorter_group():
             assert plans[2432 - 1] == 19 and plans[2433 - 1] == 10
     assert lib.pass_attention_plan(0, 5, None, None, None) == -1
     assert lib.pass_attention_plan(4, 0, None, None, None) == -1
+
+
+def test_prompt_packing_plan_covers_every_row_once():
+    """How pass_prefill_batch packs prompts into tiled passes: every row of every prompt lies in exactly one
+    segment, a prompt's segments follow each other in position order (a later pass reads what an earlier
+    one cached), segments start on blocks of 128 rows, never overlap inside a pass, never exceed it, and
+    passes are filled in order (a new pass only when the block cursor has reached the pass's end)."""
+    import numpy as np
+    lib = binding.load_library()
+    rng = np.random.default_rng(0)
+    ip = lambda a: a.ctypes.data_as(C.POINTER(C.c_int32))
+    cases = [(2048, [170, 1075, 1235, 968, 773, 1159, 474, 1774]), (128, [1, 2, 129, 130, 500]), (256, [257, 257, 1, 128, 129])]
+    cases += [(int(cap), rng.integers(1, 3000, int(n)).tolist()) for cap, n in zip(rng.choice([128, 384, 1024, 2048], 40), rng.integers(1, 12, 40))]
+    for cap, lens in cases:
+        lens_a = np.array(lens, dtype=np.int32)
+        n_segs = C.c_int32()
+        assert lib.pass_prefill_plan(cap, ip(lens_a), len(lens), 0, None, C.byref(n_segs)) in (0, -3)
+        segs = np.zeros((max(1, n_segs.value), 5), dtype=np.int32)
+        assert lib.pass_prefill_plan(cap, ip(lens_a), len(lens), n_segs.value, ip(segs), C.byref(n_segs)) == 0
+        segs = segs[:n_segs.value]
+        covered = [0] * len(lens)
+        last_pass, used = -1, {}
+        for ps, prompt, pos0, rows, base in segs.tolist():
+            assert rows >= 1 and base % 128 == 0 and base + rows <= cap
+            assert pos0 == covered[prompt]  # in position order, nothing skipped
+            covered[prompt] += rows
+            assert ps in (last_pass, last_pass + 1)
+            if ps != last_pass:
+                assert last_pass < 0 or used[last_pass] >= cap  # the previous pass was full (in whole blocks)
+                last_pass, used[ps] = ps, 0
+            assert base == used[ps]  # next free block: no overlap, no hole
+            used[ps] = (base + rows + 127) // 128 * 128
+        assert covered == [n - 1 for n in lens]
+    one = np.array([5], dtype=np.int32)
+    assert lib.pass_prefill_plan(100, ip(one), 1, 0, None, C.byref(n_segs)) == -1  # not a multiple of 128
+    assert lib.pass_prefill_plan(128, ip(np.array([0], dtype=np.int32)), 1, 0, None, C.byref(n_segs)) == -1
