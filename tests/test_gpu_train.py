@@ -111,6 +111,31 @@ def test_one_training_step_for_every_row_bound(shape, page, path, k):
     g.close()
 
 
+def test_training_step_at_13b_width_vs_oracle():
+    """One step at the 13B model's width (one layer, full vocabulary, bf16: d_model 5120, 40 heads of
+    128, d_ffn 13824 -- 320 and 864 strips, 160 and 432 k-tiles, none a power of two), k = 4, four ragged
+    prefixes, matrix-core path."""
+    import time
+    w = synth.scaled(synth.WORKLOADS["13b_k4_t0.8"], n_layers=1)
+    k = 4
+    W = synth.make_weights(w.shape, w.seed, k, w.lm_head_scale)
+    g = _gpu(w.shape, W, k, 4, 448, 64)
+    g.train_begin(-1)
+    la = TO._t(W["lookahead"], w.shape.dtype).numpy()
+    rng = np.random.default_rng(12)
+    prefixes = [rng.integers(0, w.shape.vocab, n).astype(np.int32) for n in (19, 258, 77, 385)]
+    targets = rng.integers(0, w.shape.vocab, (4, k)).astype(np.int32)
+    g.prefill_batch([0, 1, 2, 3], prefixes)
+    loss = g.train_step([0, 1, 2, 3], targets, 0.01)
+    grad = g.train_read(1)
+    t0 = time.time()
+    o_loss, o_grad = TO.loss_and_grad(w.shape, W, la, [p.tolist() for p in prefixes], targets)
+    e_loss, e_grad, g_max = abs(loss - o_loss) / abs(o_loss), float(np.abs(grad - o_grad).max()), float(np.abs(o_grad).max())
+    print(f"13B width: oracle {time.time() - t0:.0f} s; loss {loss:.6f} (oracle {o_loss:.6f}, rel {e_loss:.1e}) grad err {e_grad / g_max:.1e} of max {g_max:.3f}", flush=True)
+    assert e_loss <= 1e-4 and e_grad <= 1.5e-3 * g_max
+    g.close()
+
+
 _ORACLE_7B = {}
 
 
