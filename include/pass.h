@@ -4,7 +4,10 @@
  * The library runs the (1+k)-row decode step that the method calls twice per iteration
  * (Section 2.2 of the paper): a drafting call on the last token plus k look-ahead embeddings
  * (Section 2.2.1), and a validation call on the drafted block followed by the accept / reject
- * chain of Algorithm 1.  Every step of that path runs in HIP kernels; there is no CPU fallback.
+ * chain of Algorithm 1.  Around it: the prompt pass that fills the cache, two-model speculative
+ * sampling (the appendix's Algorithm 2) on the same validation call, and the training of the
+ * look-ahead embeddings against the frozen model (Training details).  Every step of these paths
+ * runs in HIP kernels; there is no CPU fallback.
  *
  * Conventions
  *   - Every function returns PASS_OK (0) or a negative pass_status; nothing throws or aborts.
@@ -13,7 +16,9 @@
  *     the duration of the call only, except the arena given to pass_create, which the caller
  *     owns and must keep alive (and not touch) until pass_destroy.
  *   - The library allocates no device memory: K/V pages, packed weights, workspaces and
- *     per-slot state all live in the caller's arena (pass_arena_bytes tells how large).
+ *     per-slot state all live in the caller's arena (pass_arena_bytes tells how large); what
+ *     training the look-ahead embeddings needs lives in a second workspace of the caller's
+ *     (pass_train_bytes, pass_train_begin).
  *   - All work is issued on the HIP stream given to pass_create.  Calls that return results to
  *     host memory synchronise that stream before returning.
  *   - One context may be used from one thread at a time.
