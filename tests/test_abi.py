@@ -42,6 +42,19 @@ def test_struct_layouts_match_header_sizes():
     assert C.sizeof(binding.PassSampling) == 16
     assert C.sizeof(binding.PassStats) == 48
     assert C.sizeof(binding.PassWeights) == 13 * 8
+    assert C.sizeof(binding.PassAdamW) == 5 * 4
+
+
+def test_calls_without_a_context_are_rejected():
+    """The entry points added for training and the batched prompt pass return PASS_EINVAL for a null context
+    (or 0 bytes) before they touch the device."""
+    lib = binding.load_library()
+    assert lib.pass_train_bytes(None) == 0
+    assert lib.pass_train_begin(None, None, 0, 0) == -1
+    assert lib.pass_train_step(None, None, 0, None, None, None) == -1
+    assert lib.pass_train_read(None, 0, None) == -1
+    assert lib.pass_train_resume(None, None, None, None, 0) == -1
+    assert lib.pass_prefill_batch(None, None, None, None, None, 0) == -1
 
 
 def test_attention_grid_covers_every_shorter_group():
