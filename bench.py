@@ -339,7 +339,10 @@ def main():
             dst.copy_(src * 1)  # elementwise kernel: reads 256 MiB, writes 256 MiB (then a copy of the same size)
         torch.cuda.synchronize()
     if args.train_steps > 0:
-        out["train"] = train_report(binding, devgen, synth, torch, np, args.train_steps, args.path)
+        try:  # a side figure: its failure must not take the line's main figures with it
+            out["train"] = train_report(binding, devgen, synth, torch, np, args.train_steps, args.path)
+        except Exception as e:  # noqa: BLE001
+            out["train"] = {"error": repr(e)}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, k, W_host, prompts[0])
     print(json.dumps(out))
