@@ -136,6 +136,30 @@ def test_training_step_at_13b_width_vs_oracle():
     g.close()
 
 
+@pytest.mark.parametrize("shape,page,path", [(SMALL_BF16, 16, 0), (HD128_BF16, 64, 0), (TINY, 16, 1)], ids=["bf16", "bf16-hd128", "fp32"])
+def test_training_step_with_the_most_rows_and_a_long_prefix(shape, page, path):
+    """Four slots of sixteen rows (the 64 rows a call can carry: eight row groups in every GEMM, two
+    column groups in the forward attention, the vector-ALU attention backward), one prefix of 2100
+    tokens (nine chunks of keys, the forward attention's split plan beyond eight splits)."""
+    k = 15
+    W = synth.make_weights(shape, 77, k, 6.0)
+    g = _gpu(shape, W, k, 4, 2176, page, {"path": path})
+    g.train_begin(-1)
+    la = TO._t(W["lookahead"], shape.dtype).numpy()
+    rng = np.random.default_rng(5)
+    prefixes = [rng.integers(0, shape.vocab, n).astype(np.int32) for n in (2100, 1, 300, 64)]
+    targets = rng.integers(0, shape.vocab, (4, k)).astype(np.int32)
+    g.prefill_batch([0, 1, 2, 3], prefixes)
+    loss = g.train_step([0, 1, 2, 3], targets, 0.01)
+    o_loss, o_grad = TO.loss_and_grad(shape, W, la, [p.tolist() for p in prefixes], targets)
+    grad = g.train_read(1)
+    e_loss, e_grad, g_max = abs(loss - o_loss) / abs(o_loss), float(np.abs(grad - o_grad).max()), float(np.abs(o_grad).max())
+    print(f"64 rows: loss rel {e_loss:.1e} grad err {e_grad / g_max:.1e} of max {g_max:.3f}")
+    fp32 = shape.dtype == synth.F32
+    assert e_loss <= (1e-6 if fp32 else 6e-5) and e_grad <= (5e-6 if fp32 else 4e-4) * g_max
+    g.close()
+
+
 _ORACLE_7B = {}
 
 
